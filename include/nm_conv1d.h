@@ -1,0 +1,122 @@
+/*
+ * nm_conv1d.h -- C ABI of the MI355X (gfx950) conv1d sub-block library.
+ *
+ * The operation is the 1D time-convolution sub-block of the Jasper-style acoustic
+ * encoder that the paper's ASR collection trains (Section 4.1.1: JasperEncoder
+ * consumes a [batch, feature, time] spectrogram), in the three passes a training
+ * step needs (Section 3: a trainable module computes its outputs and its gradient
+ * flows).  Operands are low precision and accumulation is float32, following the
+ * paper's mixed-precision contract (Section 3.3).  The paper prints no formula; the
+ * definition used is the standard one:
+ *
+ *   T_out      = floor((T + 2*pad - dilation*(K-1) - 1)/stride) + 1
+ *   tau(t,k)   = t*stride - pad + k*dilation              (cross-correlation, no flip)
+ *   z[b,co,t]  = sum_ci sum_k w[co,ci,k] * x[b,ci,tau(t,k)],   x == 0 outside [0,T)
+ *   y          = relu?( scale[co]*z + shift[co] + residual[b,co,t] )
+ *   m = [y>0] (1 without ReLU);  dres = dy*m;  dz = dy*m*scale[co]
+ *   dx[b,ci,s] = sum over (co,t,k) with tau(t,k)==s of w[co,ci,k]*dz[b,co,t]
+ *   dw[co,ci,k]= sum_b sum_t dz[b,co,t] * x[b,ci,tau(t,k)]
+ *
+ * Conventions common to every entry point
+ *  - Tensor pointers are DEVICE pointers to dense row-major buffers with the last
+ *    listed dimension innermost: activations [B][C][T], weights [Cout][Cin][K].
+ *    The caller owns them; the library never allocates, frees or keeps them.
+ *  - `dtype` selects the storage type of x, w, residual, y, dy, dx, dres
+ *    (NM_BF16: bfloat16, NM_F32: float).  scale, shift and dw are always float.
+ *    Accumulation is float32 in both modes.
+ *  - `workspace` is caller-provided device memory of at least
+ *    nm_conv1d_workspace_bytes(op, ...) bytes, 256-byte aligned (may be NULL when
+ *    that size is 0).  Its contents are scratch: undefined before and after a call.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on that stream; they never synchronise the host.
+ *  - Return value: an nm_status.  Argument errors are detected before any device
+ *    call, so they are reported identically on a host without a GPU.  No exception,
+ *    abort or message crosses the boundary.
+ *  - Outputs must not overlap inputs or the workspace.  Results are deterministic:
+ *    identical inputs give bit-identical outputs.
+ *  - Each tensor must hold fewer than 2^31 elements.
+ */
+#ifndef NM_CONV1D_H
+#define NM_CONV1D_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NM_OK = 0,
+    NM_ERR_BAD_ARG = -1,     /* NULL required pointer, non-positive size, unknown flag/dtype, T_out <= 0 */
+    NM_ERR_UNSUPPORTED = -2, /* valid request this build cannot serve (e.g. a tensor of 2^31 elements or more) */
+    NM_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned or smaller than required */
+    NM_ERR_DEVICE = -4       /* the HIP runtime refused a launch */
+} nm_status;
+
+typedef enum { NM_BF16 = 0, NM_F32 = 1 } nm_dtype;
+
+/* flags */
+enum {
+    NM_RELU = 1u,        /* forward: apply max(.,0); backward: mask with [y > 0] (y required) */
+    NM_ACCUM_DW = 2u,    /* bwd_weight: dw += result instead of dw = result (gradient
+                            accumulation over several batches, paper Section 3.3) */
+    NM_FORCE_DIRECT = 4u /* use the plain one-thread-per-output kernels instead of the
+                            matrix-core kernels (always used for NM_F32) */
+};
+
+enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2 };
+
+/* T_out of the convolution (formula above), or NM_ERR_BAD_ARG (<0) if any argument is
+ * out of range or no output position exists.  Host only. */
+int nm_conv1d_out_len(int T, int K, int stride, int dilation, int pad);
+
+/* Bytes of device workspace that operation `op` (NM_OP_*) needs for this geometry,
+ * dtype and flags.  Returns 0 for invalid arguments (the operation itself then
+ * reports NM_ERR_BAD_ARG).  Host only. */
+size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K, int stride,
+                                 int dilation, int pad, int dtype, unsigned flags);
+
+/* Static, NUL-terminated description of a status code. */
+const char *nm_strerror(int status);
+
+/* Block forward (conv + folded-BatchNorm affine + optional residual + optional ReLU).
+ *   x        [B][Cin][T]        in,  dtype
+ *   w        [Cout][Cin][K]     in,  dtype
+ *   scale    [Cout] float       in,  NULL means 1
+ *   shift    [Cout] float       in,  NULL means 0
+ *   residual [B][Cout][T_out]   in,  dtype, NULL means none; added before the ReLU
+ *   y        [B][Cout][T_out]   out, dtype (float32 result rounded to nearest even)
+ */
+int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                        const void *x, const void *w, const float *scale, const float *shift,
+                        const void *residual, void *y, unsigned flags, int dtype,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Input gradient of the block.
+ *   dy    [B][Cout][T_out]  in,  dtype: gradient with respect to the block output y
+ *   y     [B][Cout][T_out]  in,  dtype: saved forward output; required iff NM_RELU
+ *   scale [Cout] float      in,  NULL means 1
+ *   w     [Cout][Cin][K]    in,  dtype
+ *   dx    [B][Cin][T]       out, dtype
+ *   dres  [B][Cout][T_out]  out, dtype, or NULL: gradient with respect to the residual
+ * In NM_BF16 mode dz = dy*m*scale is rounded to bfloat16 before it is contracted.
+ */
+int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                       const void *dy, const void *y, const float *scale, const void *w,
+                       void *dx, void *dres, unsigned flags, int dtype,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Weight gradient of the block.
+ *   x     [B][Cin][T]       in,  dtype
+ *   dy, y, scale            as for nm_conv1d_bwd_data
+ *   dw    [Cout][Cin][K]    out, float (in/out with NM_ACCUM_DW)
+ */
+int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                         const void *x, const void *dy, const void *y, const float *scale,
+                         float *dw, unsigned flags, int dtype,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_CONV1D_H */

@@ -1,0 +1,183 @@
+"""Thin ctypes binding of libnmconv1d.so (C ABI: include/nm_conv1d.h).
+
+Only argument marshalling happens here: tensors are torch device tensors whose
+``data_ptr()`` is handed to the library, the stream is torch's current HIP stream,
+and outputs / workspace are ``torch.empty`` buffers when the caller passes none.
+Every arithmetic step runs inside the library's kernels.  If the library has not
+been built, loading raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnmconv1d.so")
+
+NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE = 0, -1, -2, -3, -4
+NM_BF16, NM_F32 = 0, 1
+NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
+NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT = 0, 1, 2
+
+EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
+           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight")
+
+_lib = None
+
+
+class NmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({strerror(status)})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library (raises FileNotFoundError if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = ctypes.CDLL(LIB_PATH)
+        i, u, vp, sz = ctypes.c_int, ctypes.c_uint, ctypes.c_void_p, ctypes.c_size_t
+        L.nm_conv1d_out_len.argtypes = [i] * 5
+        L.nm_conv1d_out_len.restype = i
+        L.nm_conv1d_workspace_bytes.argtypes = [i] * 9 + [i, u]
+        L.nm_conv1d_workspace_bytes.restype = sz
+        L.nm_strerror.argtypes = [i]
+        L.nm_strerror.restype = ctypes.c_char_p
+        L.nm_conv1d_block_fwd.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp, sz, vp]
+        L.nm_conv1d_block_fwd.restype = i
+        L.nm_conv1d_bwd_data.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd_data.restype = i
+        L.nm_conv1d_bwd_weight.argtypes = [i] * 8 + [vp] * 5 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd_weight.restype = i
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().nm_strerror(int(status)).decode()
+
+
+def nm_conv1d_out_len(T: int, K: int, stride: int = 1, dilation: int = 1, pad: int = 0) -> int:
+    return int(lib().nm_conv1d_out_len(T, K, stride, dilation, pad))
+
+
+def nm_conv1d_workspace_bytes(op: int, B, Cin, Cout, T, K, stride=1, dilation=1, pad=0, dtype=NM_BF16,
+                              flags=0) -> int:
+    return int(lib().nm_conv1d_workspace_bytes(op, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags))
+
+
+# ---- tensor marshalling -----------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.bfloat16:
+        return NM_BF16
+    if t.dtype == torch.float32:
+        return NM_F32
+    raise TypeError(f"unsupported storage dtype {t.dtype}")
+
+
+def _ptr(t, dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(op, dims, dtype_code, flags, workspace, device):
+    torch = _torch()
+    need = nm_conv1d_workspace_bytes(op, *dims, dtype_code, flags)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, stride=1, dilation=1,
+                        pad=0, relu=False, force_direct=False, workspace=None, stream=None):
+    """y = relu?(scale*conv1d(x,w)+shift+residual); returns y (allocated if not given)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = nm_conv1d_out_len(T, K, stride, dilation, pad)
+    if To <= 0:
+        raise NmError(NM_ERR_BAD_ARG, "nm_conv1d_block_fwd")
+    code = _dtype_code(x)
+    if y is None:
+        y = torch.empty((B, Cout, To), dtype=x.dtype, device=x.device)
+    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_FWD, dims, code, flags, workspace, x.device)
+    st = lib().nm_conv1d_block_fwd(
+        *dims, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(shift, torch.float32, (Cout,), "shift"),
+        _ptr(residual, x.dtype, (B, Cout, To), "residual"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+        flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_block_fwd")
+    return y
+
+
+def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stride=1, dilation=1, pad=0,
+                       relu=False, want_dres=False, force_direct=False, workspace=None, stream=None):
+    """dx (and optionally dres) from the upstream gradient dy; returns (dx, dres)."""
+    torch = _torch()
+    B, Cout, To = dy.shape
+    _, Cin, K = w.shape
+    code = _dtype_code(dy)
+    if dx is None:
+        dx = torch.empty((B, Cin, T), dtype=dy.dtype, device=dy.device)
+    if dres is None and want_dres:
+        dres = torch.empty_like(dy)
+    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD_DATA, dims, code, flags, workspace, dy.device)
+    st = lib().nm_conv1d_bwd_data(
+        *dims, _ptr(dy, name="dy"), _ptr(y, dy.dtype, (B, Cout, To), "y"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(w, dy.dtype, (Cout, Cin, K), "w"),
+        _ptr(dx, dy.dtype, (B, Cin, T), "dx"), _ptr(dres, dy.dtype, (B, Cout, To), "dres"),
+        flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bwd_data")
+    return dx, dres
+
+
+def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dilation=1, pad=0,
+                         relu=False, accumulate=False, force_direct=False, workspace=None, stream=None):
+    """dw [Cout,Cin,K] float32 from x and the upstream gradient dy; returns dw."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    _, Cout, To = dy.shape
+    code = _dtype_code(x)
+    if dw is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dw")
+        dw = torch.empty((Cout, Cin, K), dtype=torch.float32, device=x.device)
+    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD_WEIGHT, dims, code, flags, workspace, x.device)
+    st = lib().nm_conv1d_bwd_weight(
+        *dims, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(dw, torch.float32, (Cout, Cin, K), "dw"),
+        flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bwd_weight")
+    return dw

@@ -1,0 +1,71 @@
+// Internal declarations shared by the translation units of the conv1d library.
+// Nothing here is part of the public C ABI (that is include/nm_conv1d.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace nm {
+
+// Geometry of one conv1d sub-block; To is T_out.
+struct Geom {
+    int B, Cin, Cout, T, K, stride, dil, pad, To;
+};
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// float -> bfloat16, round to nearest, ties to even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_as_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_as_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_from_f32(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_from_f32(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+// Value a stored element will read back as (identity for float, bf16 rounding otherwise).
+__device__ __forceinline__ float round_to_storage(float v, const float *) { return v; }
+__device__ __forceinline__ float round_to_storage(float v, const bf16_t *) { return bf16_to_f32(f32_to_bf16(v)); }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- plain kernels (direct_kernels.hip); is_bf16 selects the storage type ---------------
+hipError_t launch_direct_fwd(const Geom &g, bool is_bf16, const void *x, const void *w,
+                             const float *scale, const float *shift, const void *res, void *y,
+                             bool relu, hipStream_t s);
+// dz = dy*[y>0]*scale (any of dz/dres may be NULL); y may be NULL when !relu.
+hipError_t launch_epilogue_bwd(const Geom &g, bool is_bf16, const void *dy, const void *y,
+                               const float *scale, bool relu, void *dz, void *dres, hipStream_t s);
+hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx,
+                               hipStream_t s);
+hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, float *dw,
+                               bool accumulate, hipStream_t s);
+
+// ---- matrix-core kernels (mfma_*.hip), bf16 storage only -------------------------------
+// Each *_supported says whether the matrix-core path can serve the geometry; the
+// *_workspace functions give its scratch need; launches return hipSuccess or the error.
+bool mfma_fwd_supported(const Geom &g);
+size_t mfma_fwd_workspace(const Geom &g);
+hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const float *scale,
+                           const float *shift, const void *res, void *y, bool relu, void *ws,
+                           hipStream_t s);
+
+bool mfma_dgrad_supported(const Geom &g);
+size_t mfma_dgrad_workspace(const Geom &g);
+hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale,
+                             const void *w, void *dx, void *dres, bool relu, void *ws, hipStream_t s);
+
+bool mfma_wgrad_supported(const Geom &g);
+size_t mfma_wgrad_workspace(const Geom &g, bool need_dz);
+hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y,
+                             const float *scale, float *dw, bool relu, bool accumulate, void *ws,
+                             hipStream_t s);
+
+}  // namespace nm

@@ -1,0 +1,216 @@
+// Host side of the C ABI declared in include/nm_conv1d.h: argument validation,
+// choice between the matrix-core kernels and the plain kernels, workspace carving,
+// launches.  Validation never touches the HIP runtime, so it behaves the same on a
+// host without a device.
+#include "../../include/nm_conv1d.h"
+#include "nm_common.h"
+
+using namespace nm;
+
+namespace {
+
+constexpr unsigned kAllFlags = NM_RELU | NM_ACCUM_DW | NM_FORCE_DIRECT;
+constexpr size_t kWsAlign = 256;
+constexpr long long kMaxElems = (1LL << 31) - 1;
+
+int out_len(int T, int K, int stride, int dil, int pad)
+{
+    if (T <= 0 || K <= 0 || stride <= 0 || dil <= 0 || pad < 0) return NM_ERR_BAD_ARG;
+    const long long span = (long long)T + 2LL * pad - (long long)dil * (K - 1) - 1;
+    if (span < 0) return NM_ERR_BAD_ARG;
+    const long long to = span / stride + 1;
+    if (to > kMaxElems) return NM_ERR_BAD_ARG;
+    return (int)to;
+}
+
+// Fills g; returns NM_OK or the status to hand back.
+int check_geometry(int B, int Cin, int Cout, int T, int K, int stride, int dil, int pad, int dtype,
+                   unsigned flags, unsigned allowed_flags, Geom *g)
+{
+    if (B <= 0 || Cin <= 0 || Cout <= 0) return NM_ERR_BAD_ARG;
+    const int to = out_len(T, K, stride, dil, pad);
+    if (to <= 0) return NM_ERR_BAD_ARG;
+    if (dtype != NM_BF16 && dtype != NM_F32) return NM_ERR_BAD_ARG;
+    if (flags & ~allowed_flags) return NM_ERR_BAD_ARG;
+    if ((long long)B * Cin * T > kMaxElems || (long long)B * Cout * to > kMaxElems ||
+        (long long)Cout * Cin * K > kMaxElems)
+        return NM_ERR_UNSUPPORTED;
+    if (B > 65535 || Cout > 65535 || Cin > 65535) return NM_ERR_UNSUPPORTED;  // grid y/z limits
+    if ((long long)pad + (long long)dil * K > (1 << 28) || stride > (1 << 20)) return NM_ERR_UNSUPPORTED;
+    g->B = B; g->Cin = Cin; g->Cout = Cout; g->T = T; g->K = K;
+    g->stride = stride; g->dil = dil; g->pad = pad; g->To = to;
+    return NM_OK;
+}
+
+bool overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b) return false;
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+size_t elt(int dtype) { return dtype == NM_BF16 ? 2 : 4; }
+
+bool use_mfma(int op, const Geom &g, int dtype, unsigned flags)
+{
+    if (dtype != NM_BF16 || (flags & NM_FORCE_DIRECT)) return false;
+    switch (op) {
+    case NM_OP_FWD: return mfma_fwd_supported(g);
+    case NM_OP_BWD_DATA: return mfma_dgrad_supported(g);
+    case NM_OP_BWD_WEIGHT: return mfma_wgrad_supported(g);
+    default: return false;
+    }
+}
+
+// Whether dz differs from dy (then backward passes on the plain path materialise it).
+bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || scale != nullptr; }
+
+size_t workspace_for(int op, const Geom &g, int dtype, unsigned flags, bool scale_or_relu)
+{
+    const size_t dz_bytes = align_up((size_t)g.B * g.Cout * g.To * elt(dtype), kWsAlign);
+    if (use_mfma(op, g, dtype, flags)) {
+        if (op == NM_OP_FWD) return mfma_fwd_workspace(g);
+        if (op == NM_OP_BWD_DATA) return mfma_dgrad_workspace(g);
+        return mfma_wgrad_workspace(g, scale_or_relu);
+    }
+    if (op == NM_OP_FWD) return 0;
+    return scale_or_relu ? dz_bytes : 0;
+}
+
+int check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return NM_OK;
+    if (!ws || have < need || ((uintptr_t)ws % kWsAlign) != 0) return NM_ERR_WORKSPACE;
+    return NM_OK;
+}
+
+int dev(hipError_t e) { return e == hipSuccess ? NM_OK : NM_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+int nm_conv1d_out_len(int T, int K, int stride, int dilation, int pad)
+{
+    return out_len(T, K, stride, dilation, pad);
+}
+
+size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K, int stride, int dilation,
+                                 int pad, int dtype, unsigned flags)
+{
+    Geom g;
+    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT) return 0;
+    if (check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g) != NM_OK)
+        return 0;
+    // The query cannot see whether scale is NULL; it sizes for the larger case.
+    return workspace_for(op, g, dtype, flags, true);
+}
+
+const char *nm_strerror(int status)
+{
+    switch (status) {
+    case NM_OK: return "ok";
+    case NM_ERR_BAD_ARG: return "invalid argument";
+    case NM_ERR_UNSUPPORTED: return "unsupported size";
+    case NM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case NM_ERR_DEVICE: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                        const void *x, const void *w, const float *scale, const float *shift,
+                        const void *residual, void *y, unsigned flags, int dtype, void *workspace,
+                        size_t workspace_bytes, void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
+                            NM_RELU | NM_FORCE_DIRECT, &g);
+    if (st != NM_OK) return st;
+    if (!x || !w || !y) return NM_ERR_BAD_ARG;
+    const size_t e = elt(dtype);
+    const size_t ny = (size_t)g.B * g.Cout * g.To * e;
+    if (overlap(y, ny, x, (size_t)g.B * g.Cin * g.T * e) || overlap(y, ny, w, (size_t)g.Cout * g.Cin * g.K * e) ||
+        overlap(y, ny, residual, ny))
+        return NM_ERR_BAD_ARG;
+    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags);
+    const size_t need = workspace_for(NM_OP_FWD, g, dtype, flags, true);
+    st = check_workspace(workspace, workspace_bytes, need);
+    if (st != NM_OK) return st;
+    if (overlap(y, ny, workspace, need)) return NM_ERR_BAD_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const bool relu = (flags & NM_RELU) != 0;
+    if (mfma) return dev(launch_mfma_fwd(g, x, w, scale, shift, residual, y, relu, workspace, s));
+    return dev(launch_direct_fwd(g, dtype == NM_BF16, x, w, scale, shift, residual, y, relu, s));
+}
+
+int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                       const void *dy, const void *y, const float *scale, const void *w, void *dx,
+                       void *dres, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                       void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
+                            NM_RELU | NM_FORCE_DIRECT, &g);
+    if (st != NM_OK) return st;
+    if (!dy || !w || !dx) return NM_ERR_BAD_ARG;
+    const bool relu = (flags & NM_RELU) != 0;
+    if (relu && !y) return NM_ERR_BAD_ARG;
+    const size_t e = elt(dtype);
+    const size_t ndy = (size_t)g.B * g.Cout * g.To * e, ndx = (size_t)g.B * g.Cin * g.T * e;
+    if (overlap(dx, ndx, dy, ndy) || overlap(dx, ndx, y, ndy) || overlap(dx, ndx, w, (size_t)g.Cout * g.Cin * g.K * e) ||
+        overlap(dx, ndx, dres, ndy) || overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy))
+        return NM_ERR_BAD_ARG;
+    const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags);
+    const bool dzneeded = needs_dz(flags, scale);
+    const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, flags, dzneeded);
+    st = check_workspace(workspace, workspace_bytes, need);
+    if (st != NM_OK) return st;
+    if (overlap(dx, ndx, workspace, need) || overlap(dres, ndy, workspace, need)) return NM_ERR_BAD_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (mfma) return dev(launch_mfma_dgrad(g, dy, y, scale, w, dx, dres, relu, workspace, s));
+    const bool bf = dtype == NM_BF16;
+    const void *dz = dy;
+    if (dzneeded || dres) {
+        hipError_t err = launch_epilogue_bwd(g, bf, dy, y, scale, relu, dzneeded ? workspace : nullptr, dres, s);
+        if (err != hipSuccess) return NM_ERR_DEVICE;
+        if (dzneeded) dz = workspace;
+    }
+    return dev(launch_direct_dgrad(g, bf, dz, w, dx, s));
+}
+
+int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                         const void *x, const void *dy, const void *y, const float *scale, float *dw,
+                         unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                         void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
+    if (st != NM_OK) return st;
+    if (!x || !dy || !dw) return NM_ERR_BAD_ARG;
+    const bool relu = (flags & NM_RELU) != 0;
+    if (relu && !y) return NM_ERR_BAD_ARG;
+    const size_t e = elt(dtype);
+    const size_t ndy = (size_t)g.B * g.Cout * g.To * e, ndw = (size_t)g.Cout * g.Cin * g.K * sizeof(float);
+    if (overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, (size_t)g.B * g.Cin * g.T * e))
+        return NM_ERR_BAD_ARG;
+    const bool mfma = use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags);
+    const bool dzneeded = needs_dz(flags, scale);
+    const size_t need = workspace_for(NM_OP_BWD_WEIGHT, g, dtype, flags, dzneeded);
+    st = check_workspace(workspace, workspace_bytes, need);
+    if (st != NM_OK) return st;
+    if (overlap(dw, ndw, workspace, need)) return NM_ERR_BAD_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const bool accum = (flags & NM_ACCUM_DW) != 0;
+    if (mfma) return dev(launch_mfma_wgrad(g, x, dy, y, scale, dw, relu, accum, workspace, s));
+    const bool bf = dtype == NM_BF16;
+    const void *dz = dy;
+    if (dzneeded) {
+        hipError_t err = launch_epilogue_bwd(g, bf, dy, y, scale, relu, workspace, nullptr, s);
+        if (err != hipSuccess) return NM_ERR_DEVICE;
+        dz = workspace;
+    }
+    return dev(launch_direct_wgrad(g, bf, x, dz, dw, accum, s));
+}
+
+}  // extern "C"

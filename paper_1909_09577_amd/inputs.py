@@ -7,8 +7,10 @@ needed to hand identical bits to every consumer.  It depends on numpy only.
 Recipe.  With ``rng = numpy.random.default_rng(seed)`` the tensors are drawn in
 float32 in this fixed order: x ~ N(0,1) [B,Cin,T]; w ~ N(0, variance 1/(Cin*K))
 [Cout,Cin,K]; scale ~ U(0.5,1.5) [Cout]; shift ~ N(0, std 0.1) [Cout];
-residual ~ N(0,1) [B,Cout,T_out]; dy ~ N(0,1) [B,Cout,T_out].  All six are always
-drawn (so the stream does not depend on which are used).  For the bf16 workloads x,
+residual ~ N(0,1) [B,Cout,T_out]; dy ~ N(0,1) [B,Cout,T_out]; and last a stand-in for
+a saved forward output, y_saved = max(N(0,1), 0) [B,Cout,T_out] (about half zeros, like
+a post-ReLU activation), used by backward-only checks.  All seven are always drawn (so
+the stream does not depend on which are used).  For the bf16 workloads x,
 w, residual and dy are then rounded to bf16 (round to nearest even) and it is those
 rounded values that every consumer sees; scale and shift stay float32.  The
 activations stand in for the spectrogram-derived feature maps of the paper's
@@ -123,10 +125,10 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 def make_inputs(cfg: LayerCfg, dtype: str = "bf16", seed: Optional[int] = None) -> Dict[str, np.ndarray]:
     """Draw the six tensors of one layer.
 
-    Returns float32 arrays under "x","w","scale","shift","residual","dy" holding the
+    Returns float32 arrays under "x","w","scale","shift","residual","dy","y_saved" holding the
     values every consumer must use (already bf16-representable when dtype == "bf16"),
     plus, for bf16, the uint16 bit patterns under "x_bits", "w_bits", "residual_bits",
-    "dy_bits".  Tensors a layer does not use are still returned; the caller drops them.
+    "dy_bits", "y_saved_bits".  Tensors a layer does not use are still returned; the caller drops them.
     """
     if dtype not in ("bf16", "f32"):
         raise ValueError("dtype must be 'bf16' or 'f32'")
@@ -140,8 +142,9 @@ def make_inputs(cfg: LayerCfg, dtype: str = "bf16", seed: Optional[int] = None) 
     out["shift"] = (rng.standard_normal(cfg.Cout, dtype=np.float32) * np.float32(0.1))
     out["residual"] = rng.standard_normal((cfg.B, cfg.Cout, To), dtype=np.float32)
     out["dy"] = rng.standard_normal((cfg.B, cfg.Cout, To), dtype=np.float32)
+    out["y_saved"] = np.maximum(rng.standard_normal((cfg.B, cfg.Cout, To), dtype=np.float32), np.float32(0))
     if dtype == "bf16":
-        for name in ("x", "w", "residual", "dy"):
+        for name in ("x", "w", "residual", "dy", "y_saved"):
             bits = f32_to_bf16_bits(out[name])
             out[name + "_bits"] = bits
             out[name] = bf16_bits_to_f32(bits)

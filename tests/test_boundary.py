@@ -1,0 +1,128 @@
+"""CPU-only tests of the C boundary: the library loads, exports what the header declares,
+and reports every argument error before touching the device (no compute call is made)."""
+import ctypes
+import itertools
+import os
+import re
+
+import pytest
+
+from oracle import conv1d_oracle as orc
+from paper_1909_09577_amd import binding as nm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)        # never dereferenced: every call below fails validation first
+FAKE2 = ctypes.c_void_p(0x7F0000000000)
+FAKE3 = ctypes.c_void_p(0x7E0000000000)
+FAKE4 = ctypes.c_void_p(0x7D0000000000)
+
+
+def declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = nm.lib()
+    names = declared_functions()
+    assert set(nm.EXPORTS) <= names and len(names) >= 6
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_strerror():
+    msgs = {nm.strerror(s) for s in (0, -1, -2, -3, -4)}
+    assert len(msgs) == 5 and nm.strerror(-99) == "unknown status"
+
+
+def test_out_len_matches_oracle_brute_force_range():
+    for T, K, s, d, pad in itertools.product(range(0, 14), range(0, 6), range(0, 4), range(0, 4), range(-1, 7)):
+        got = nm.nm_conv1d_out_len(T, K, s, d, pad)
+        if T <= 0 or K <= 0 or s <= 0 or d <= 0 or pad < 0:
+            assert got < 0
+        else:
+            exp = orc.out_len(T, K, s, d, pad)
+            assert got == exp or (exp < 0 and got < 0), (T, K, s, d, pad, got, exp)
+    assert nm.nm_conv1d_out_len(1600, 11, 2, 1, 5) == 800
+    assert nm.nm_conv1d_out_len(800, 29, 1, 2, 28) == 800
+
+
+GOOD = dict(B=2, Cin=4, Cout=4, T=16, K=3, stride=1, dilation=1, pad=1)
+
+
+def fwd(dims=None, x=FAKE2, w=FAKE3, y=FAKE4, flags=0, dtype=0, ws=None, ws_bytes=0, res=None):
+    d = dict(GOOD, **(dims or {}))
+    return nm.lib().nm_conv1d_block_fwd(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"],
+                                        d["pad"], x, w, None, None, res, y, flags, dtype, ws, ws_bytes, None)
+
+
+def bwd_data(dims=None, dy=FAKE2, yv=None, w=FAKE3, dx=FAKE4, flags=0, dtype=0):
+    d = dict(GOOD, **(dims or {}))
+    return nm.lib().nm_conv1d_bwd_data(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"],
+                                       d["pad"], dy, yv, None, w, dx, None, flags, dtype, None, 0, None)
+
+
+def bwd_weight(dims=None, x=FAKE2, dy=FAKE3, yv=None, dw=FAKE4, flags=0, dtype=0):
+    d = dict(GOOD, **(dims or {}))
+    return nm.lib().nm_conv1d_bwd_weight(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"],
+                                         d["pad"], x, dy, yv, None, dw, flags, dtype, None, 0, None)
+
+
+@pytest.mark.parametrize("call", [fwd, bwd_data, bwd_weight])
+def test_bad_geometry_is_rejected(call):
+    for bad in (dict(B=0), dict(Cin=0), dict(Cout=-1), dict(T=0), dict(K=0), dict(stride=0), dict(dilation=0),
+                dict(pad=-1), dict(T=2, K=5, pad=0)):
+        assert call(bad) == nm.NM_ERR_BAD_ARG, bad
+    assert call(dtype=7) == nm.NM_ERR_BAD_ARG
+    assert call(flags=1 << 9) == nm.NM_ERR_BAD_ARG
+    assert call(dict(B=60000, Cin=60000, T=60000)) == nm.NM_ERR_UNSUPPORTED
+    assert call(dict(B=70000, T=4)) == nm.NM_ERR_UNSUPPORTED
+
+
+def test_null_pointers_are_rejected():
+    assert fwd(x=None) == nm.NM_ERR_BAD_ARG
+    assert fwd(w=None) == nm.NM_ERR_BAD_ARG
+    assert fwd(y=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_data(dy=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_data(w=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_data(dx=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_data(flags=nm.NM_RELU, yv=None) == nm.NM_ERR_BAD_ARG      # ReLU mask needs y
+    assert bwd_weight(x=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_weight(dy=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_weight(dw=None) == nm.NM_ERR_BAD_ARG
+    assert bwd_weight(flags=nm.NM_RELU, yv=None) == nm.NM_ERR_BAD_ARG
+    assert fwd(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG                # flag of another entry point
+    assert bwd_data(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG
+
+
+def test_aliasing_is_rejected():
+    assert fwd(x=FAKE2, y=FAKE2) == nm.NM_ERR_BAD_ARG
+    assert fwd(w=FAKE3, y=FAKE3) == nm.NM_ERR_BAD_ARG
+    assert fwd(res=FAKE4, y=FAKE4) == nm.NM_ERR_BAD_ARG
+    assert bwd_data(dy=FAKE2, dx=FAKE2) == nm.NM_ERR_BAD_ARG
+    assert bwd_weight(x=FAKE2, dw=ctypes.c_void_p(FAKE2.value + 8)) == nm.NM_ERR_BAD_ARG
+
+
+def test_workspace_is_checked_before_any_launch():
+    # backward with a ReLU mask on the plain path needs room for dz
+    need = nm.nm_conv1d_workspace_bytes(nm.NM_OP_BWD_DATA, 2, 4, 4, 16, 3, 1, 1, 1, nm.NM_BF16, nm.NM_RELU | nm.NM_FORCE_DIRECT)
+    assert need >= 2 * 4 * 16 * 2 and need % 256 == 0
+    assert bwd_data(flags=nm.NM_RELU | nm.NM_FORCE_DIRECT, yv=FAKE) == nm.NM_ERR_WORKSPACE
+    assert bwd_weight(flags=nm.NM_RELU | nm.NM_FORCE_DIRECT, yv=FAKE) == nm.NM_ERR_WORKSPACE
+    assert nm.nm_conv1d_workspace_bytes(99, 2, 4, 4, 16, 3) == 0
+    assert nm.nm_conv1d_workspace_bytes(nm.NM_OP_FWD, 0, 4, 4, 16, 3) == 0
+    for op in (nm.NM_OP_FWD, nm.NM_OP_BWD_DATA, nm.NM_OP_BWD_WEIGHT):
+        for dims in ((32, 512, 512, 800, 17, 1, 1, 8), (32, 768, 896, 800, 29, 1, 2, 28), (2, 64, 256, 200, 11, 1, 1, 5)):
+            n = nm.nm_conv1d_workspace_bytes(op, *dims, nm.NM_BF16, 0)
+            assert n % 256 == 0 and n < (1 << 31)
+            # a misaligned or short workspace is refused (when one is needed at all)
+            if n:
+                d = dict(zip(("B", "Cin", "Cout", "T", "K", "stride", "dilation", "pad"), dims))
+                if op == nm.NM_OP_FWD:
+                    assert fwd(d, ws=ctypes.c_void_p(0x10000100), ws_bytes=n - 1) == nm.NM_ERR_WORKSPACE
+                    assert fwd(d, ws=ctypes.c_void_p(0x10000104), ws_bytes=n) == nm.NM_ERR_WORKSPACE

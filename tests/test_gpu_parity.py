@@ -1,0 +1,257 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the fp64 oracle on the
+same seeded inputs.
+
+Small and medium geometries are compared element by element over whole tensors (sizes span
+several tiles of the matrix-core kernels plus ragged tails); the full-size Jasper-shaped
+workloads are compared on sampled output elements the oracle evaluates one by one.  Gate:
+max |g-o|/(|o|+rms(o)) <= 1e-2 for bf16 storage (float32 accumulation), <= 1e-5 for float32
+storage; bf16 results must also have a relative RMS error <= 3e-3.
+
+Backward checks take the saved forward output from the input recipe (or from the oracle's own
+forward, rounded to the storage type on the host), never from the GPU.
+"""
+import numpy as np
+import pytest
+
+import _util as U
+from oracle import conv1d_oracle as orc
+from paper_1909_09577_amd import binding as nm
+from paper_1909_09577_amd import inputs as syn
+from paper_1909_09577_amd.inputs import LayerCfg
+
+pytestmark = pytest.mark.gpu
+
+
+def run_fwd(cfg, inp, dtype, force_direct):
+    y = nm.nm_conv1d_block_fwd(
+        U.to_dev(inp, "x", dtype), U.to_dev(inp, "w", dtype),
+        U.to_dev(inp, "scale", dtype) if cfg.affine else None,
+        U.to_dev(inp, "shift", dtype) if cfg.affine else None,
+        U.to_dev(inp, "residual", dtype) if cfg.residual else None,
+        relu=cfg.relu, force_direct=force_direct, **U.geom_kw(cfg))
+    return y
+
+
+def run_bwd(cfg, inp, dtype, force_direct, y_saved_dev):
+    scale = U.to_dev(inp, "scale", dtype) if cfg.affine else None
+    dy, w, x = U.to_dev(inp, "dy", dtype), U.to_dev(inp, "w", dtype), U.to_dev(inp, "x", dtype)
+    ysv = y_saved_dev if cfg.relu else None
+    dx, dres = nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, relu=cfg.relu, want_dres=True,
+                                     force_direct=force_direct, **U.geom_kw(cfg))
+    dw = nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=ysv, scale=scale, relu=cfg.relu, force_direct=force_direct,
+                                 **U.geom_kw(cfg))
+    return dx, dw, dres
+
+
+def L(name, B, Cin, Cout, T, K, stride=1, dilation=1, pad=0, affine=True, relu=True, residual=False, seed=11):
+    return LayerCfg(name, B, Cin, Cout, T, K, stride, dilation, pad, affine, relu, residual, seed)
+
+
+# Odd shapes: ragged channel counts and lengths, strides, dilations, pad 0 / larger than needed,
+# K = 1 and even K, every epilogue combination.
+SMALL = [
+    L("s_basic", 2, 8, 8, 40, 3, pad=1, residual=True),
+    L("s_noepi", 1, 5, 7, 33, 5, pad=2, affine=False, relu=False),
+    L("s_k1", 3, 16, 29, 50, 1),
+    L("s_k2_even", 2, 6, 10, 37, 2, pad=1),
+    L("s_stride2", 2, 12, 20, 101, 11, stride=2, pad=5),
+    L("s_stride3_d2", 1, 7, 9, 64, 4, stride=3, dilation=2, pad=3, residual=True),
+    L("s_dil3_pad0", 2, 9, 5, 70, 5, dilation=3, pad=0),
+    L("s_bigpad", 1, 4, 6, 20, 3, pad=7, relu=False, residual=True),
+    L("s_t1", 2, 3, 4, 1, 1),
+    L("s_affine_only", 2, 10, 12, 45, 7, pad=3, relu=False),
+]
+
+# Medium: several 64x160 tiles with ragged tails in every dimension (oracle: a few seconds each).
+MEDIUM = [
+    L("m_ragged", 3, 72, 100, 333, 11, pad=5, residual=True),
+    L("m_two_tiles", 2, 128, 192, 320, 17, pad=8, residual=True),
+    L("m_dil2", 2, 96, 80, 250, 9, dilation=2, pad=8),
+    L("m_k1_wide", 2, 200, 29, 400, 1, affine=False, relu=False),
+    L("m_stride2_prolog", 2, 64, 96, 400, 11, stride=2, pad=5),
+    L("m_cin_small", 2, 16, 64, 480, 5, pad=2),
+]
+
+
+def check_layer(cfg, dtype, force_direct):
+    inp = syn.make_inputs(cfg, dtype)
+    y = run_fwd(cfg, inp, dtype, force_direct)
+    y_ref = U.oracle_fwd(cfg, inp)
+    U.assert_close(U.to_host_f64(y), y_ref, dtype, f"{cfg.name} y")
+    # backward: saved output = the oracle's forward rounded to storage on the host
+    y_saved = U.round_to_storage(y_ref, dtype)
+    dx, dw, dres = run_bwd(cfg, inp, dtype, force_direct, U.arr_to_dev(y_saved, dtype))
+    dx_ref, dw_ref, dres_ref = U.oracle_bwd(cfg, inp, y_saved.astype(np.float64))
+    U.assert_close(U.to_host_f64(dx), dx_ref, dtype, f"{cfg.name} dx")
+    U.assert_close(U.to_host_f64(dw), dw_ref, dtype, f"{cfg.name} dw", rms_bound=U.RMS_DW_BF16)
+    # dres = dy*[y>0] is exact in any precision
+    np.testing.assert_array_equal(U.to_host_f64(dres), dres_ref)
+
+
+@pytest.mark.parametrize("force_direct", [False, True], ids=["auto", "direct"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_small_shapes_full_tensor(cfg, dtype, force_direct):
+    if dtype == "f32" and not force_direct:
+        pytest.skip("float32 storage always takes the plain kernels")
+    check_layer(cfg, dtype, force_direct)
+
+
+@pytest.mark.parametrize("force_direct", [False, True], ids=["auto", "direct"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("cfg", MEDIUM + [syn.TINY], ids=lambda c: c.name)
+def test_medium_shapes_full_tensor(cfg, dtype, force_direct):
+    if dtype == "f32" and not force_direct:
+        pytest.skip("float32 storage always takes the plain kernels")
+    check_layer(cfg, dtype, force_direct)
+
+
+def sample_indices(n_total, n, rng, extra=()):
+    idx = rng.choice(n_total, size=min(n, n_total), replace=False)
+    return np.unique(np.concatenate([idx, np.asarray(list(extra), dtype=np.int64)])).astype(np.int64)
+
+
+def edge_indices(shape):
+    """Flat indices of corners and tile-boundary positions of a 3-d tensor."""
+    d0, d1, d2 = shape
+    picks = []
+    for a in {0, d0 - 1}:
+        for b in {0, min(63, d1 - 1), min(64, d1 - 1), d1 - 1}:
+            for c in {0, 1, min(159, d2 - 1), min(160, d2 - 1), d2 - 2 if d2 > 1 else 0, d2 - 1}:
+                picks.append((a * d1 + b) * d2 + c)
+    return picks
+
+
+FULL = [syn.JASPER_B1, syn.JASPER_B3, syn.EPILOG_A, syn.EPILOG_B, syn.EPILOG_C]
+
+
+@pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
+def test_full_size_workloads_sampled(cfg):
+    """Full-size bf16 workloads in the launch configuration the benchmark times; the oracle
+    evaluates 4096 sampled elements (plus corners and tile edges) of each output tensor."""
+    dtype = "bf16"
+    rng = np.random.default_rng(99)
+    inp = syn.make_inputs(cfg, dtype)
+    x64, w64 = inp["x"].astype(np.float64), inp["w"].astype(np.float64)
+    scale = inp["scale"] if cfg.affine else None
+    shift = inp["shift"] if cfg.affine else None
+    res = inp["residual"] if cfg.residual else None
+    kw = U.geom_kw(cfg)
+    To = cfg.T_out
+
+    y = U.to_host_f64(run_fwd(cfg, inp, dtype, False)).reshape(-1)
+    idx = sample_indices(y.size, 4096, rng, edge_indices((cfg.B, cfg.Cout, To)))
+    y_ref = orc.block_fwd_at(x64, w64, idx, scale, shift, res, cfg.relu, **kw)
+    # rms of the whole output is estimated from the sample (the sample is uniform)
+    U.assert_close(y[idx], y_ref, dtype, f"{cfg.name} y (sampled)")
+    if cfg.relu:
+        assert np.mean(y == 0) > 0.05 and np.mean(y > 0) > 0.05
+
+    ysv = U.to_dev(inp, "y_saved", dtype)
+    dx, dw, dres = run_bwd(cfg, inp, dtype, False, ysv)
+    dz, dres_ref = orc.epilogue_bwd(inp["dy"], inp["y_saved"] if cfg.relu else None, scale, cfg.relu)
+    np.testing.assert_array_equal(U.to_host_f64(dres), dres_ref)
+    dx = U.to_host_f64(dx).reshape(-1)
+    idx = sample_indices(dx.size, 4096, rng, edge_indices((cfg.B, cfg.Cin, cfg.T)))
+    U.assert_close(dx[idx], orc.bwd_data_at(dz, w64, cfg.T, idx, **kw), dtype, f"{cfg.name} dx (sampled)")
+    dw = U.to_host_f64(dw).reshape(-1)
+    idx = sample_indices(dw.size, 2048, rng, [0, dw.size - 1, cfg.K - 1, cfg.Cin * cfg.K - 1])
+    U.assert_close(dw[idx], orc.bwd_weight_at(x64, dz, cfg.K, idx, **kw), dtype, f"{cfg.name} dw (sampled)",
+                   rms_bound=U.RMS_DW_BF16)
+
+
+def test_full_size_f32_mode_sampled():
+    """float32 storage at the B1 shape (smaller batch keeps the plain kernels quick)."""
+    cfg = syn.shrink(syn.JASPER_B1, B=4)
+    dtype = "f32"
+    rng = np.random.default_rng(5)
+    inp = syn.make_inputs(cfg, dtype)
+    x64, w64 = inp["x"].astype(np.float64), inp["w"].astype(np.float64)
+    kw = U.geom_kw(cfg)
+    y = U.to_host_f64(run_fwd(cfg, inp, dtype, True)).reshape(-1)
+    idx = sample_indices(y.size, 4096, rng)
+    U.assert_close(y[idx], orc.block_fwd_at(x64, w64, idx, inp["scale"], inp["shift"], inp["residual"], True, **kw),
+                   dtype, "f32 y")
+    dx, dw, dres = run_bwd(cfg, inp, dtype, True, U.to_dev(inp, "y_saved", dtype))
+    dz, dres_ref = orc.epilogue_bwd(inp["dy"], inp["y_saved"], inp["scale"], True)
+    dx = U.to_host_f64(dx).reshape(-1)
+    idx = sample_indices(dx.size, 4096, rng)
+    U.assert_close(dx[idx], orc.bwd_data_at(dz, w64, cfg.T, idx, **kw), dtype, "f32 dx")
+    dw = U.to_host_f64(dw).reshape(-1)
+    idx = sample_indices(dw.size, 2048, rng)
+    U.assert_close(dw[idx], orc.bwd_weight_at(x64, dz, cfg.K, idx, **kw), dtype, "f32 dw")
+
+
+def test_pure_gradients_without_epilogue_and_accumulate():
+    """y=NULL, scale=NULL: the backward entry points are plain convolution gradients;
+    NM_ACCUM_DW adds into dw."""
+    import torch
+    cfg = L("pure", 2, 24, 40, 170, 7, pad=3, affine=False, relu=False)
+    for dtype, fd in (("bf16", False), ("bf16", True), ("f32", True)):
+        inp = syn.make_inputs(cfg, dtype)
+        dx, dw, dres = run_bwd(cfg, inp, dtype, fd, None)
+        dx_ref, dw_ref, dres_ref = U.oracle_bwd(cfg, inp, None)
+        U.assert_close(U.to_host_f64(dx), dx_ref, dtype, "pure dx")
+        U.assert_close(U.to_host_f64(dw), dw_ref, dtype, "pure dw")
+        np.testing.assert_array_equal(U.to_host_f64(dres), inp["dy"].astype(np.float64))
+        base = torch.full_like(dw, 0.5)
+        acc = nm.nm_conv1d_bwd_weight(U.to_dev(inp, "x", dtype), U.to_dev(inp, "dy", dtype), cfg.K, dw=base.clone(),
+                                      accumulate=True, force_direct=fd, **U.geom_kw(cfg))
+        U.assert_close(U.to_host_f64(acc), dw_ref + 0.5, dtype, "accumulated dw")
+
+
+def test_impulse_recovers_weights_on_gpu():
+    """Completeness of the index set on the GPU path itself: a unit impulse must return every
+    weight exactly (bf16 weights are exact in float32, no other term contributes)."""
+    import torch
+    cfg = L("impulse", 2, 70, 90, 200, 17, pad=8, affine=False, relu=False)
+    inp = syn.make_inputs(cfg, "bf16")
+    for ci0, t0 in ((0, 0), (33, 97), (69, 199), (64, 160), (31, 159)):
+        x = np.zeros((cfg.B, cfg.Cin, cfg.T), dtype=np.float32)
+        x[1, ci0, t0] = 1.0
+        y = nm.nm_conv1d_block_fwd(U.arr_to_dev(x, "bf16"), U.to_dev(inp, "w", "bf16"), pad=cfg.pad)
+        y = U.to_host_f64(y)
+        expect = np.zeros_like(y)
+        for t in range(cfg.T_out):
+            k = t0 - (t - cfg.pad)
+            if 0 <= k < cfg.K:
+                expect[1, :, t] = inp["w"][:, ci0, k]
+        np.testing.assert_array_equal(y, expect)
+
+
+def test_determinism_and_guard_bands():
+    """Two runs give identical bits; nothing is written outside the output tensors; inputs
+    are left untouched."""
+    import torch
+    cfg = L("guard", 2, 72, 100, 333, 11, pad=5, residual=True)
+    dtype = "bf16"
+    inp = syn.make_inputs(cfg, dtype)
+    To = cfg.T_out
+    guard = 4096
+
+    def guarded(n, tdtype):
+        buf = torch.full((n + 2 * guard,), 7.0, dtype=tdtype, device="cuda")
+        return buf, buf[guard:guard + n]
+
+    x, w = U.to_dev(inp, "x", dtype), U.to_dev(inp, "w", dtype)
+    x0, w0 = x.clone(), w.clone()
+    scale, shift, res = U.to_dev(inp, "scale", dtype), U.to_dev(inp, "shift", dtype), U.to_dev(inp, "residual", dtype)
+    dy, ysv = U.to_dev(inp, "dy", dtype), U.to_dev(inp, "y_saved", dtype)
+    outs = []
+    for _ in range(2):
+        ybuf, yv = guarded(cfg.B * cfg.Cout * To, torch.bfloat16)
+        dxbuf, dxv = guarded(cfg.B * cfg.Cin * cfg.T, torch.bfloat16)
+        drbuf, drv = guarded(cfg.B * cfg.Cout * To, torch.bfloat16)
+        dwbuf, dwv = guarded(cfg.Cout * cfg.Cin * cfg.K, torch.float32)
+        kw = U.geom_kw(cfg)
+        nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=yv.view(cfg.B, cfg.Cout, To), relu=True, **kw)
+        nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, dx=dxv.view(cfg.B, cfg.Cin, cfg.T),
+                              dres=drv.view(cfg.B, cfg.Cout, To), relu=True, **kw)
+        nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=ysv, scale=scale, dw=dwv.view(cfg.Cout, cfg.Cin, cfg.K), relu=True, **kw)
+        torch.cuda.synchronize()
+        for buf in (ybuf, dxbuf, drbuf, dwbuf):
+            assert (buf[:guard] == 7.0).all() and (buf[-guard:] == 7.0).all(), "write outside the output"
+        outs.append([t.clone() for t in (yv, dxv, drv, dwv)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b), "results differ between two identical calls"
+    assert torch.equal(x, x0) and torch.equal(w, w0)
