@@ -1,0 +1,548 @@
+// Matrix-core implicit-GEMM engine for the forward pass and the input gradient.
+//
+// Both passes are the same contraction
+//     out[b, m, t] = sum_r sum_k  W'[m, r, k] * in[b, r, t*stride - padL + k*dil]
+// with (m, r) = (co, ci), W' = w, padL = pad for the forward pass and, for the input gradient
+// of a stride-1 convolution, (m, r) = (ci, co), W'[ci,co,k] = w[co,ci,K-1-k],
+// padL = dil*(K-1) - pad, in = dz = dy*[y>0]*scale (formed while the tile is staged).
+//
+// Work decomposition (one workgroup = 4 wavefronts of 64 lanes, one workgroup per CU,
+// persistent over output tiles):
+//   * an output tile is 64 channels x NT*32 time steps of one batch item;
+//   * the four wavefronts split the reduction channels in chunks of 32 (wave w takes chunks
+//     w, w+4, ...), each accumulating the whole tile in 2*NT 32x32 MFMA accumulators, so the
+//     main loop needs no workgroup barrier; the four partial tiles are summed through LDS
+//     at the end of the tile and each wavefront finishes a quarter of the rows;
+//   * the activation window of a chunk (32 channels x all time steps the K taps touch) is
+//     read from HBM once with 16-byte loads along T and written to the wavefront's private LDS
+//     region transposed to [time][channel], so that every tap is a row offset and each MFMA
+//     B fragment (8 consecutive channels of one time step) is one aligned 16-byte LDS read;
+//   * weights are prepacked once per call into MFMA A-fragment order and stream from L2
+//     straight into registers (each lane reads 16 contiguous bytes, a wavefront 1 KiB).
+//   * tiles are numbered channel-tile fastest, so the workgroups that the hardware places on
+//     one XCD (blockIdx mod 8) keep reusing the same slice of the packed weights in that L2.
+#include "nm_common.h"
+
+namespace nm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTileM = 64;       // output channels per tile
+constexpr int kChunk = 32;       // reduction channels per staged chunk
+constexpr int kRowBytes = 80;    // LDS row: 32 channels * 2 B + 16 B pad (bank-conflict-free 16 B reads)
+constexpr int kRowDwords = kRowBytes / 4;
+constexpr int kMaxLds = 160 * 1024;
+
+enum { MODE_FWD = 0, MODE_DGRAD = 1 };
+
+struct ConvGemmParams {
+    int B, M, R, Tin, Tout, K, dil, padL;
+    int nmt, nch, ntt, num_tiles;
+    int NR;          // rows of one staged window that are read (multiple of 8)
+    int buf_bytes;   // bytes of one staging buffer: nitems*32 rows of kRowBytes
+    int nitems;      // staging items per lane and chunk = ceil(NR/8 * 16 / 64)
+    int relu;
+    const bf16_t *in;       // [B][R][Tin]
+    const bf16_t *ysaved;   // DGRAD: saved forward output (ReLU mask) or NULL
+    const float *in_scale;  // DGRAD: per reduction channel scale or NULL
+    const bf16x8 *wp;       // packed weights
+    const float *scale;     // FWD epilogue (may be NULL)
+    const float *shift;     // FWD epilogue (may be NULL)
+    const bf16_t *res;      // FWD epilogue (may be NULL)
+    bf16_t *out;            // [B][M][Tout]
+};
+
+__device__ __forceinline__ int floor_div8(int v) { return v >> 3; }  // arithmetic shift: floor
+
+// Eight consecutive time steps of one channel row (16-byte aligned) as 4 packed dwords; zero
+// when the row or the time range is outside the tensor.  The address is clamped, so the load
+// itself is always in bounds and the code stays branch-free.
+__device__ __forceinline__ u32x4 load_row8(const bf16_t *base, size_t row_off, int t, int Tin, bool row_ok)
+{
+    const bool ok = row_ok && t >= 0 && t + 8 <= Tin;
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(base + (ok ? row_off + (size_t)t : (size_t)0));
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    return ok ? v : z;
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// dz = dy * [y>0] * scale for 8 packed elements.
+__device__ __forceinline__ u32x4 make_dz8(u32x4 dy, u32x4 y, float scale, bool relu)
+{
+    u32x4 r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float g0 = __uint_as_float(dy[j] << 16), g1 = __uint_as_float(dy[j] & 0xffff0000u);
+        if (relu) {
+            const float y0 = __uint_as_float(y[j] << 16), y1 = __uint_as_float(y[j] & 0xffff0000u);
+            g0 = (y0 > 0.f) ? g0 : 0.f;
+            g1 = (y1 > 0.f) ? g1 : 0.f;
+        }
+        r[j] = pack2(g0 * scale, g1 * scale);
+    }
+    return r;
+}
+
+struct StageRegs {
+    u32x4 a, b;  // channel rows 2pp and 2pp+1, 8 time steps each
+};
+
+// One staging item: channel pair pp = item & 15 of the chunk x time group q = item >> 4.
+template <int MODE>
+__device__ __forceinline__ void stage_load(const ConvGemmParams &p, int b, int c, int ws_al, int item, StageRegs &s)
+{
+    const int pp = item & 15, q = item >> 4;
+    const int ch = c * kChunk + 2 * pp;
+    const int t = ws_al + 8 * q;
+    const size_t row = ((size_t)b * p.R + ch) * p.Tin;
+    const bool ok_a = ch < p.R, ok_b = ch + 1 < p.R;
+    s.a = load_row8(p.in, row, t, p.Tin, ok_a);
+    s.b = load_row8(p.in, row + p.Tin, t, p.Tin, ok_b);
+    if (MODE == MODE_DGRAD) {
+        if (p.relu || p.in_scale) {
+            u32x4 ya = {0u, 0u, 0u, 0u}, yb = ya;
+            if (p.relu) {
+                ya = load_row8(p.ysaved, row, t, p.Tin, ok_a);
+                yb = load_row8(p.ysaved, row + p.Tin, t, p.Tin, ok_b);
+            }
+            float sa = 1.f, sb = 1.f;
+            if (p.in_scale) {
+                sa = p.in_scale[ok_a ? ch : 0];
+                sb = p.in_scale[ok_b ? ch + 1 : 0];
+            }
+            s.a = make_dz8(s.a, ya, sa, p.relu != 0);
+            s.b = make_dz8(s.b, yb, sb, p.relu != 0);
+        }
+    }
+}
+
+// Transposing write: one dword (channel pair) per time step.  The buffer has room for every
+// item of every lane, so no bounds test is needed.
+__device__ __forceinline__ void stage_write(uint32_t *buf, int item, const StageRegs &s)
+{
+    const int pp = item & 15, q = item >> 4;
+    uint32_t *dst = buf + (q * 8) * kRowDwords + pp;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        dst[(2 * j) * kRowDwords] = (s.a[j] & 0xffffu) | (s.b[j] << 16);
+        dst[(2 * j + 1) * kRowDwords] = (s.a[j] >> 16) | (s.b[j] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wavefront execute in order; this only stops the compiler from
+    // moving LDS accesses across the point where other lanes' data must be visible.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int NT, int STRIDE, int MODE>
+__global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int kTiles = 2 * NT;
+    constexpr int TN = NT * 32;
+
+    unsigned char *wbuf0 = smem + (size_t)wave * 2 * p.buf_bytes;
+    const int nitems = p.nitems;                           // staging items per lane and chunk
+    const int nmy = (p.nch - wave + kWaves - 1) / kWaves;  // chunks of this wavefront (may be 0)
+    const int K = p.K;
+
+    for (int tile = blockIdx.x; tile < p.num_tiles; tile += gridDim.x) {
+        const int mt = tile % p.nmt;
+        const int ntile = tile / p.nmt;
+        const int b = ntile / p.ntt;
+        const int t0 = (ntile % p.ntt) * TN;
+        const int ws = t0 * STRIDE - p.padL;
+        const int ws_al = floor_div8(ws) * 8;
+        const int off0 = ws - ws_al;
+
+        f32x16 acc[2][NT];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+        if (nmy > 0) {
+            // ---- first chunk of the tile: nothing to overlap with; three items in flight
+            {
+                uint32_t *buf = reinterpret_cast<uint32_t *>(wbuf0);
+                for (int it = 0; it < nitems; it += 3) {
+                    StageRegs s0, s1, s2;
+                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * it, s0);
+                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * min(it + 1, nitems - 1), s1);
+                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * min(it + 2, nitems - 1), s2);
+                    stage_write(buf, lane + 64 * it, s0);
+                    stage_write(buf, lane + 64 * min(it + 1, nitems - 1), s1);
+                    stage_write(buf, lane + 64 * min(it + 2, nitems - 1), s2);
+                }
+            }
+            // ---- weight fragment stream: taps are handled in pairs and the fragments of a
+            // pair are fetched one pair (40 MFMAs) before they are used.  The stream runs on
+            // over this wave's chunks; past the end it re-reads the last pair (valid memory).
+            const size_t chunk_stride = (size_t)K * 256;  // bf16x8 per (tile, chunk)
+            const bf16x8 *wchunk = p.wp + ((size_t)mt * p.nch + wave) * chunk_stride + lane;
+            const int P = (K + 1) >> 1;  // tap pairs per chunk (the last may hold one tap)
+            int pslot = 0, pi = 0;
+            bf16x8 afA[8], afB[8];
+            auto fetch_pair = [&](bf16x8(&dst)[8]) {
+                const bf16x8 *s0 = wchunk + (size_t)(2 * pslot) * 256;
+                const bf16x8 *s1 = wchunk + (size_t)min(2 * pslot + 1, K - 1) * 256;
+#pragma unroll
+                for (int f = 0; f < 4; ++f) {
+                    dst[f] = s0[f * 64];
+                    dst[4 + f] = s1[f * 64];
+                }
+                ++pslot;
+                if (pslot == P) {
+                    if (pi + 1 < nmy) {
+                        ++pi;
+                        pslot = 0;
+                        wchunk += kWaves * chunk_stride;
+                    } else {
+                        pslot = P - 1;
+                    }
+                }
+            };
+            fetch_pair(afA);
+
+            for (int i = 0; i < nmy; ++i) {
+                const bool has_next = (i + 1 < nmy);
+                const int c_next = wave + kWaves * (i + 1);
+                const unsigned char *cur = wbuf0 + (size_t)(i & 1) * p.buf_bytes;
+                uint32_t *nxt = reinterpret_cast<uint32_t *>(wbuf0 + (size_t)((i + 1) & 1) * p.buf_bytes);
+                wave_lds_fence();
+                // per-lane base of the B fragment reads: row (lane%32)*STRIDE + off0, 16 B half lane/32
+                const unsigned char *bbase = cur + ((lane & 31) * STRIDE + off0) * kRowBytes + (lane >> 5) * 16;
+                const int tap_bytes = p.dil * kRowBytes;
+
+                bf16x8 b0[NT], b1[NT];
+                auto read_b = [&](bf16x8(&dst)[NT], int k, int ks) {
+                    const unsigned char *brow = bbase + (size_t)k * tap_bytes + ks * 32;
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni)
+                        dst[ni] = *reinterpret_cast<const bf16x8 *>(brow + ni * 32 * STRIDE * kRowBytes);
+                };
+                auto mma = [&](const bf16x8 *af, const bf16x8(&bf)[NT]) {
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+                };
+                read_b(b0, 0, 0);
+
+                // one pair of taps = 4 k-steps of 16 channels, 2*NT MFMAs each; B fragments are
+                // read one k-step ahead of their use
+                auto tap_pair = [&](int k) {
+                    fetch_pair(afB);
+                    read_b(b1, k, 1);
+                    mma(&afA[0], b0);
+                    read_b(b0, k + 1, 0);
+                    mma(&afA[2], b1);
+                    read_b(b1, k + 1, 1);
+                    mma(&afA[4], b0);
+                    read_b(b0, min(k + 2, K - 1), 0);
+                    mma(&afA[6], b1);
+#pragma unroll
+                    for (int f = 0; f < 8; ++f) afA[f] = afB[f];
+                };
+                // the last tap of an odd-length kernel
+                auto tap_single = [&](int k) {
+                    fetch_pair(afB);
+                    read_b(b1, k, 1);
+                    mma(&afA[0], b0);
+                    mma(&afA[2], b1);
+#pragma unroll
+                    for (int f = 0; f < 8; ++f) afA[f] = afB[f];
+                };
+
+                const int nst = has_next ? nitems : 0;
+                int k = 0, it = 0;
+                for (; k + 1 < K; k += 2, ++it) {
+                    const bool st = it < nst;  // this pair also stages one item of the next chunk
+                    StageRegs s;
+                    if (st) stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
+                    tap_pair(k);
+                    if (st) stage_write(nxt, lane + 64 * it, s);
+                }
+                for (; k < K; ++k, ++it) {
+                    const bool st = it < nst;
+                    StageRegs s;
+                    if (st) stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
+                    tap_single(k);
+                    if (st) stage_write(nxt, lane + 64 * it, s);
+                }
+                for (; it < nst; ++it) {  // more items than tap pairs (short kernels)
+                    StageRegs s;
+                    stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
+                    stage_write(nxt, lane + 64 * it, s);
+                }
+            }
+        }
+
+        // ---- sum the four partial tiles: wave g finishes accumulator rows [4g, 4g+4) of every
+        // 32x32 block; every wave hands the other three quarters over through LDS.
+        __syncthreads();
+        f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+#pragma unroll
+        for (int g = 0; g < kWaves; ++g) {
+            if (g != wave) {
+                const int slot = wave < g ? wave : wave - 1;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) {
+                        f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
+                                   acc[mi][ni][4 * g + 3]};
+                        red[((g * 3 + slot) * kTiles + mi * NT + ni) * 64 + lane] = v;
+                    }
+            }
+        }
+        __syncthreads();
+        f32x4 own[kTiles];
+#pragma unroll
+        for (int g = 0; g < kWaves; ++g) {
+            if (g == wave) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni)
+                        own[mi * NT + ni] = f32x4{acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
+                                                  acc[mi][ni][4 * g + 3]};
+            }
+        }
+#pragma unroll
+        for (int slot = 0; slot < 3; ++slot)
+#pragma unroll
+            for (int tl = 0; tl < kTiles; ++tl) own[tl] += red[((wave * 3 + slot) * kTiles + tl) * 64 + lane];
+        __syncthreads();  // the staging buffers of the next tile alias `red`
+
+        // ---- epilogue on the rows this wave owns
+        const int tcol = lane & 31;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = mt * kTileM + mi * 32 + 8 * wave + 4 * (lane >> 5) + j;
+                if (m >= p.M) continue;
+                float sc = 1.f, sh = 0.f;
+                if (MODE == MODE_FWD) {
+                    if (p.scale) sc = p.scale[m];
+                    if (p.shift) sh = p.shift[m];
+                }
+                const size_t orow = ((size_t)b * p.M + m) * p.Tout;
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) {
+                    const int t = t0 + ni * 32 + tcol;
+                    if (t >= p.Tout) continue;
+                    float v = own[mi * NT + ni][j];
+                    if (MODE == MODE_FWD) {
+                        v = v * sc + sh;
+                        if (p.res) v += bf16_to_f32(p.res[orow + t]);
+                        if (p.relu) v = v > 0.f ? v : 0.f;
+                    }
+                    p.out[orow + t] = f32_to_bf16(v);
+                }
+            }
+        }
+    }
+}
+
+// Packed weights: [mt][chunk][tap][ks][mi][lane][8]; element (lane, j) of fragment (ks, mi) is
+// W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside.
+// W'[m][r][k] = w[m*sm + r*sr + (flip ? K-1-k : k)].
+__global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp,
+                                                      int M, int R, int K, int nmt, int nch, long sm, long sr,
+                                                      int flip)
+{
+    const size_t total = (size_t)nmt * nch * K * 256;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int lane = idx & 63;
+    const int f = (idx >> 6) & 3;
+    const size_t rest = idx >> 8;
+    const int k = (int)(rest % K);
+    const int c = (int)((rest / K) % nch);
+    const int mt = (int)(rest / ((size_t)K * nch));
+    const int m = mt * kTileM + (f & 1) * 32 + (lane & 31);
+    const int r0 = c * kChunk + (f >> 1) * 16 + 8 * (lane >> 5);
+    const int kk = flip ? K - 1 - k : k;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (m < M) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = r0 + j;
+            uint32_t v = (r < R) ? (uint32_t)w[(size_t)m * sm + (size_t)r * sr + kk] : 0u;
+            out[j >> 1] |= v << ((j & 1) * 16);
+        }
+    }
+    wp[idx] = out;
+}
+
+struct Plan {
+    bool ok;
+    int nt;      // NT template value (5 or 2)
+    int stride;  // 1 or 2
+    int NR;      // window rows that are read
+    int nitems;  // staging items per lane; the buffer holds nitems*32 rows
+    size_t lds;
+};
+
+// Tin: length of the rows that are staged; they must be 16-byte aligned (Tin % 8 == 0).
+Plan make_plan(int Tin, int Tout, int K, int stride, int dil)
+{
+    Plan pl = {false, 0, stride, 0, 0, 0};
+    if (stride != 1 && stride != 2) return pl;
+    if (Tin % 8 != 0) return pl;
+    const int cands[2] = {5, 2};
+    for (int ci = 0; ci < 2; ++ci) {
+        const int nt = cands[ci];
+        if (ci == 0 && Tout <= 64) continue;  // short sequences: the narrow tile wastes less
+        const long rows = (long)(nt * 32 - 1) * stride + (long)(K - 1) * dil + 1 + 7;
+        const long NR = (rows + 7) / 8 * 8;
+        const long nitems = (NR / 8 * 16 + 63) / 64;
+        const size_t stage = (size_t)kWaves * 2 * (nitems * 32) * kRowBytes;
+        const size_t red = (size_t)kWaves * 3 * (2 * nt) * 64 * sizeof(f32x4);
+        const size_t lds = stage > red ? stage : red;
+        if (lds <= (size_t)kMaxLds) {
+            pl.ok = true;
+            pl.nt = nt;
+            pl.NR = (int)NR;
+            pl.nitems = (int)nitems;
+            pl.lds = lds;
+            return pl;
+        }
+    }
+    return pl;
+}
+
+size_t packed_bytes(int M, int R, int K)
+{
+    const size_t nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
+    return align_up(nmt * nch * K * 256 * sizeof(u32x4), 256);
+}
+
+template <int NT, int STRIDE, int MODE>
+hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
+{
+    auto kern = conv_gemm_kernel<NT, STRIDE, MODE>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    }
+    const int grid = p.num_tiles < cus ? p.num_tiles : cus;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_mode(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
+{
+    if (pl.nt == 5 && pl.stride == 1) return launch_t<5, 1, MODE>(p, pl.lds, s);
+    if (pl.nt == 2 && pl.stride == 1) return launch_t<2, 1, MODE>(p, pl.lds, s);
+    if (MODE == MODE_FWD) {
+        if (pl.nt == 5 && pl.stride == 2) return launch_t<5, 2, MODE_FWD>(p, pl.lds, s);
+        if (pl.nt == 2 && pl.stride == 2) return launch_t<2, 2, MODE_FWD>(p, pl.lds, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, long sm, long sr, bool flip, hipStream_t s)
+{
+    const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
+    const size_t total = (size_t)nmt * nch * K * 256;
+    hipLaunchKernelGGL(prepack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)w,
+                       (u32x4 *)wp, M, R, K, nmt, nch, sm, sr, flip ? 1 : 0);
+    return hipGetLastError();
+}
+
+void fill_common(ConvGemmParams &p, const Plan &pl, int B, int M, int R, int Tin, int Tout, int K, int dil, int padL,
+                 const void *)
+{
+    p.B = B; p.M = M; p.R = R; p.Tin = Tin; p.Tout = Tout; p.K = K; p.dil = dil; p.padL = padL;
+    p.nmt = (M + kTileM - 1) / kTileM;
+    p.nch = (R + kChunk - 1) / kChunk;
+    p.ntt = (Tout + pl.nt * 32 - 1) / (pl.nt * 32);
+    p.num_tiles = p.nmt * p.ntt * B;
+    p.NR = pl.NR;
+    p.nitems = pl.nitems;
+    p.buf_bytes = pl.nitems * 32 * kRowBytes;
+}
+
+}  // namespace
+
+// ---- forward ---------------------------------------------------------------------------
+bool mfma_fwd_supported(const Geom &g) { return make_plan(g.T, g.To, g.K, g.stride, g.dil).ok; }
+
+size_t mfma_fwd_workspace(const Geom &g) { return packed_bytes(g.Cout, g.Cin, g.K); }
+
+hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const float *scale, const float *shift,
+                           const void *res, void *y, bool relu, void *ws, hipStream_t s)
+{
+    const Plan pl = make_plan(g.T, g.To, g.K, g.stride, g.dil);
+    if (!pl.ok) return hipErrorInvalidValue;
+    hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, (long)g.Cin * g.K, g.K, false, s);
+    if (e != hipSuccess) return e;
+    ConvGemmParams p = {};
+    fill_common(p, pl, g.B, g.Cout, g.Cin, g.T, g.To, g.K, g.dil, g.pad, x);
+    p.relu = relu ? 1 : 0;
+    p.in = (const bf16_t *)x;
+    p.wp = (const bf16x8 *)ws;
+    p.scale = scale; p.shift = shift; p.res = (const bf16_t *)res;
+    p.out = (bf16_t *)y;
+    return launch_mode<MODE_FWD>(pl, p, s);
+}
+
+// ---- input gradient (stride 1 only; other strides use the plain kernels) ----------------
+bool mfma_dgrad_supported(const Geom &g)
+{
+    if (g.stride != 1) return false;
+    return make_plan(g.To, g.T, g.K, 1, g.dil).ok;
+}
+
+size_t mfma_dgrad_workspace(const Geom &g) { return packed_bytes(g.Cin, g.Cout, g.K); }
+
+hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
+                             void *dx, void *dres, bool relu, void *ws, hipStream_t s)
+{
+    const Plan pl = make_plan(g.To, g.T, g.K, 1, g.dil);
+    if (!pl.ok) return hipErrorInvalidValue;
+    hipError_t e = run_prepack(w, ws, g.Cin, g.Cout, g.K, g.K, (long)g.Cin * g.K, true, s);
+    if (e != hipSuccess) return e;
+    if (dres) {
+        e = launch_epilogue_bwd(g, true, dy, y, nullptr, relu, nullptr, dres, s);
+        if (e != hipSuccess) return e;
+    }
+    ConvGemmParams p = {};
+    fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad, dy);
+    p.relu = relu ? 1 : 0;
+    p.in = (const bf16_t *)dy;
+    p.ysaved = (const bf16_t *)y;
+    p.in_scale = scale;
+    p.wp = (const bf16x8 *)ws;
+    p.out = (bf16_t *)dx;
+    return launch_mode<MODE_DGRAD>(pl, p, s);
+}
+
+}  // namespace nm

@@ -1,0 +1,510 @@
+// Matrix-core weight gradient with a wavefront-level split over time.
+//
+//   dw[co, ci, k] = sum_b sum_t dz[b, co, t] * x[b, ci, t*stride - pad + k*dil]
+//
+// is, for each tap k, a GEMM with M = co, N = ci and the reduction over (b, t).  An output
+// tile is 64 output channels x 32 input channels x a group of up to KT taps (2*KT 32x32 MFMA
+// accumulators per wavefront).  The reduction is cut into units of one batch item x TCH time
+// steps; the 4*S wavefronts that share an output tile (4 per workgroup, S workgroups) each
+// take every (4*S)-th unit and accumulate privately, so the main loop has no workgroup
+// barrier.  The four partial tiles of a workgroup are summed through LDS, the S workgroup
+// results go to a float32 scratch laid out [S][K][Cout][Cin] (coalesced along ci) and a small
+// kernel adds them in a fixed order and writes dw[co][ci][k]: the result is deterministic.
+//
+// Operand staging (private to each wavefront, double buffered):
+//   * dz rows are copied to LDS as they are ([co][t]); an A fragment (8 consecutive t of one
+//     co) is one aligned 16-byte read;
+//   * x is written transposed to [time][channel] exactly as in the forward kernel, so a tap is
+//     a row offset; a B fragment needs 8 consecutive *time steps* of one channel, i.e. a column
+//     of that layout, which the gfx950 transposing LDS read (ds_read_b64_tr_b16: 16 lanes read a
+//     4x16 block, lane i receives column i) delivers in two reads.
+// dz itself (dy * [y>0] * scale, rounded to bf16) is materialised once per call by a
+// vectorised elementwise kernel when it differs from dy.
+#include "nm_common.h"
+
+namespace nm {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTileCo = 64;
+constexpr int kTileCi = 32;
+constexpr int kXRowBytes = 80;  // 32 channels * 2 B + 16 B pad
+constexpr int kXRowDwords = kXRowBytes / 4;
+constexpr int kMaxLds = 160 * 1024;
+constexpr int kMaxKT = 6;
+
+struct WgradParams {
+    int B, Cin, Cout, T, To, K, stride, dil, pad;
+    int ncot, ncit, ntg, KTg;  // tiles per dimension; taps per group
+    int S;                     // workgroups sharing one output tile
+    int TCH, nchunk, units;    // time steps per unit, units per batch row, total units
+    int NRX;                   // rows of the staged x window that are read (multiple of 8)
+    int n_dz, n_x, ips;        // staging items per lane (dz, x) and items riding on one MFMA step
+    int dz_row_bytes, dz_bytes, x_bytes, buf_bytes;
+    int total, per_xcd, CL;    // work-item numbering (CL == 0: plain order)
+    const bf16_t *x;           // [B][Cin][T]
+    const bf16_t *dz;          // [B][Cout][To]
+    float *part;               // [S][K][Cout][Cin]
+};
+
+// Eight consecutive time steps of one 16-byte aligned channel row as 4 packed dwords; zero when
+// the row or the time range lies outside the tensor (the address is clamped: no branch).
+__device__ __forceinline__ u32x4 load_row8(const bf16_t *base, size_t row_off, int t, int Tlen, bool row_ok)
+{
+    const bool ok = row_ok && t >= 0 && t + 8 <= Tlen;
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(base + (ok ? row_off + (size_t)t : (size_t)0));
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    return ok ? v : z;
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wavefront execute in order; this only keeps the compiler from
+    // moving LDS accesses across the point where other lanes' data must be visible.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Staging of one unit: n_dz dz items then n_x x items per lane.
+//  dz item idx: row = lane/4 + 16*(idx&3), time group = lane%4 + 4*(idx>>2) (8 steps each);
+//               groups past the chunk land in the row's spare columns and are never read.
+//  x item idx:  channel pair pp = item & 15, time group q = item >> 4, item = lane + 64*idx.
+struct StageSlot {
+    u32x4 a, b;
+};
+
+__device__ __forceinline__ void stage_load(const WgradParams &p, int co0, int ci0, int b, int tbase, int xs_al,
+                                           int idx, int lane, StageSlot &s)
+{
+    if (idx < p.n_dz) {
+        const int row = (lane >> 2) + 16 * (idx & 3);
+        const int grp = (lane & 3) + 4 * (idx >> 2);
+        const int co = co0 + row;
+        s.a = load_row8(p.dz, ((size_t)b * p.Cout + co) * p.To, tbase + 8 * grp, p.To, co < p.Cout);
+        s.b = s.a;
+    } else {
+        const int item = lane + 64 * (idx - p.n_dz);
+        const int pp = item & 15, q = item >> 4;
+        const int ci = ci0 + 2 * pp;
+        const int t = xs_al + 8 * q;
+        const size_t row = ((size_t)b * p.Cin + ci) * p.T;
+        s.a = load_row8(p.x, row, t, p.T, ci < p.Cin);
+        s.b = load_row8(p.x, row + p.T, t, p.T, ci + 1 < p.Cin);
+    }
+}
+
+__device__ __forceinline__ void stage_write(const WgradParams &p, unsigned char *buf, int idx, int lane,
+                                            const StageSlot &s)
+{
+    if (idx < p.n_dz) {
+        const int row = (lane >> 2) + 16 * (idx & 3);
+        const int grp = (lane & 3) + 4 * (idx >> 2);
+        *reinterpret_cast<u32x4 *>(buf + row * p.dz_row_bytes + grp * 16) = s.a;
+    } else {
+        const int item = lane + 64 * (idx - p.n_dz);
+        const int pp = item & 15, q = item >> 4;
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + p.dz_bytes) + (q * 8) * kXRowDwords + pp;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dst[(2 * j) * kXRowDwords] = (s.a[j] & 0xffffu) | (s.b[j] << 16);
+            dst[(2 * j + 1) * kXRowDwords] = (s.a[j] >> 16) | (s.b[j] & 0xffff0000u);
+        }
+    }
+}
+
+constexpr int kStagePerStep = 4;  // at most this many staging items ride on one MFMA step
+
+template <int KT>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    // ---- which (split, tile) this workgroup owns: work items are numbered so that the
+    // workgroups the hardware places on one XCD (blockIdx mod 8) form a contiguous range
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int v = xcd * p.per_xcd + j;
+    if (j >= p.per_xcd || v >= p.total) return;
+    int sp, tg, cot, cit;
+    if (p.CL > 0) {
+        // digits, slowest to fastest: sp, cot_hi, tg, cot_lo, cit
+        int r = v;
+        cit = r % p.ncit; r /= p.ncit;
+        const int cot_lo = r % p.CL; r /= p.CL;
+        tg = r % p.ntg; r /= p.ntg;
+        const int nhi = p.ncot / p.CL;
+        const int cot_hi = r % nhi; r /= nhi;
+        sp = r;
+        cot = cot_hi * p.CL + cot_lo;
+    } else {
+        int r = v;
+        cit = r % p.ncit; r /= p.ncit;
+        cot = r % p.ncot; r /= p.ncot;
+        tg = r % p.ntg; r /= p.ntg;
+        sp = r;
+    }
+    const int k0 = tg * p.KTg;
+    const int kt = min(p.KTg, p.K - k0);
+    const int co0 = cot * kTileCo, ci0 = cit * kTileCi;
+
+    f32x16 acc[2][KT];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int kk = 0; kk < KT; ++kk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][kk][r] = 0.f;
+
+    unsigned char *wbuf0 = smem + (size_t)wave * 2 * p.buf_bytes;
+    const int nitems = p.n_dz + p.n_x;
+    const int nsteps = p.TCH >> 4;
+    const int slot_id = sp * kWaves + wave;
+    const int slots = p.S * kWaves;
+
+    auto unit_coords = [&](int u, int &b, int &tbase, int &xs_al, int &off0) {
+        b = u / p.nchunk;
+        tbase = (u - b * p.nchunk) * p.TCH;
+        const int xs = tbase * p.stride - p.pad + k0 * p.dil;
+        xs_al = (xs >> 3) * 8;
+        off0 = xs - xs_al;
+    };
+
+    // fragment addressing that does not depend on the unit
+    const int a_lane_off = (lane & 31) * p.dz_row_bytes + (lane >> 5) * 16;  // row lane%32, t half lane/32
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const int trow = 8 * (g4 >> 1) + (i16 >> 2);   // time row this lane addresses in a transposing read
+    const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);  // first of the 4 channels it addresses
+    const int x_step_bytes = 16 * p.stride * kXRowBytes;
+    const int x_half_bytes = 4 * p.stride * kXRowBytes;
+    const int x_tap_bytes = p.dil * kXRowBytes;
+
+    int u = slot_id;
+    if (u < p.units) {
+        int b, tbase, xs_al, off0;
+        unit_coords(u, b, tbase, xs_al, off0);
+        // first unit of this wavefront: nothing to overlap with; four items in flight
+        for (int it = 0; it < nitems; it += 4) {
+            StageSlot s[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) stage_load(p, co0, ci0, b, tbase, xs_al, min(it + q, nitems - 1), lane, s[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) stage_write(p, wbuf0, min(it + q, nitems - 1), lane, s[q]);
+        }
+        int parity = 0;
+        for (; u < p.units; u += slots, parity ^= 1) {
+            unit_coords(u, b, tbase, xs_al, off0);
+            const int un = u + slots;
+            const bool has_next = un < p.units;
+            int bn = 0, tbn = 0, xsn = 0, offn = 0;
+            if (has_next) unit_coords(un, bn, tbn, xsn, offn);
+            const unsigned char *cur = wbuf0 + (size_t)parity * p.buf_bytes;
+            unsigned char *nxt = wbuf0 + (size_t)(parity ^ 1) * p.buf_bytes;
+            wave_lds_fence();
+            const unsigned char *abase = cur + a_lane_off;
+            const unsigned char *xbase = cur + p.dz_bytes + (size_t)(trow * p.stride + off0) * kXRowBytes + tcol * 2;
+
+            auto read_frags = [&](int st, bf16x8(&af)[2], bf16x8(&bfr)[KT]) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+                    af[mi] = *reinterpret_cast<const bf16x8 *>(abase + mi * 32 * p.dz_row_bytes + st * 32);
+                const unsigned char *xst = xbase + (size_t)st * x_step_bytes;
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk) {
+                    // taps past the group read the last valid tap again (never used)
+                    const unsigned char *xa = xst + (size_t)min(kk, kt - 1) * x_tap_bytes;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa + x_half_bytes));
+                    union {
+                        s16x4 h[2];
+                        bf16x8 v;
+                    } cvt;
+                    cvt.h[0] = lo;
+                    cvt.h[1] = hi;
+                    bfr[kk] = cvt.v;
+                }
+            };
+
+            bf16x8 a0[2], a1[2], b0[KT], b1[KT];
+            read_frags(0, a0, b0);
+            // the next unit's items ride on this unit's MFMA steps
+            const int ips = has_next ? p.ips : 0;
+            int it = 0;
+            for (int st = 0; st < nsteps; ++st) {
+                StageSlot s[kStagePerStep];
+#pragma unroll
+                for (int q = 0; q < kStagePerStep; ++q)
+                    if (q < ips && it + q < nitems) stage_load(p, co0, ci0, bn, tbn, xsn, it + q, lane, s[q]);
+                read_frags(min(st + 1, nsteps - 1), a1, b1);
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk) {
+                    if (kk < kt) {
+#pragma unroll
+                        for (int mi = 0; mi < 2; ++mi)
+                            acc[mi][kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mi], b0[kk], acc[mi][kk], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < kStagePerStep; ++q)
+                    if (q < ips && it + q < nitems) stage_write(p, nxt, it + q, lane, s[q]);
+                it += ips;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) a0[mi] = a1[mi];
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk) b0[kk] = b1[kk];
+            }
+        }
+    }
+
+    // ---- sum the four wavefronts' partial tiles through LDS (wave g finishes rows [4g,4g+4)
+    // of every 32x32 block), then write this workgroup's tile to the scratch.
+    constexpr int kTiles = 2 * KT;
+    __syncthreads();
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+#pragma unroll
+    for (int g = 0; g < kWaves; ++g) {
+        if (g != wave) {
+            const int slot = wave < g ? wave : wave - 1;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk) {
+                    f32x4 val = {acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
+                                 acc[mi][kk][4 * g + 3]};
+                    red[((g * 3 + slot) * kTiles + mi * KT + kk) * 64 + lane] = val;
+                }
+        }
+    }
+    __syncthreads();
+    f32x4 own[kTiles];
+#pragma unroll
+    for (int g = 0; g < kWaves; ++g) {
+        if (g == wave) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk)
+                    own[mi * KT + kk] = f32x4{acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
+                                              acc[mi][kk][4 * g + 3]};
+        }
+    }
+#pragma unroll
+    for (int slot = 0; slot < 3; ++slot)
+#pragma unroll
+        for (int tl = 0; tl < kTiles; ++tl) own[tl] += red[((wave * 3 + slot) * kTiles + tl) * 64 + lane];
+
+    const int ci = ci0 + (lane & 31);
+    if (ci < p.Cin) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int kk = 0; kk < KT; ++kk) {
+                if (kk >= kt) continue;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int co = co0 + mi * 32 + 8 * wave + 4 * (lane >> 5) + jj;
+                    if (co < p.Cout)
+                        p.part[(((size_t)sp * p.K + k0 + kk) * p.Cout + co) * p.Cin + ci] = own[mi * KT + kk][jj];
+                }
+            }
+    }
+}
+
+// dw[co][ci][k] = (accumulate ? dw : 0) + sum_s part[s][k][co][ci]; one block per (co, 64 ci).
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw,
+                                                           int S, int K, int Cout, int Cin, int accumulate)
+{
+    extern __shared__ float tile[];  // [64][K+1]
+    const int co = blockIdx.y;
+    const int ci0 = blockIdx.x * 64;
+    const int l = threadIdx.x & 63, kq = threadIdx.x >> 6;
+    const int ci = ci0 + l;
+    const size_t plane = (size_t)Cout * Cin;
+    for (int k = kq; k < K; k += 4) {
+        float s = 0.f;
+        if (ci < Cin) {
+            const float *src = part + ((size_t)k * Cout + co) * Cin + ci;
+            for (int sp = 0; sp < S; ++sp) s += src[(size_t)sp * K * plane];
+        }
+        tile[l * (K + 1) + k] = s;
+    }
+    __syncthreads();
+    const int nci = min(64, Cin - ci0);
+    const int n = nci * K;
+    float *dst = dw + ((size_t)co * Cin + ci0) * K;
+    for (int e = threadIdx.x; e < n; e += 256) {
+        const int c = e / K, k = e - c * K;
+        const float val = tile[c * (K + 1) + k];
+        dst[e] = accumulate ? dst[e] + val : val;
+    }
+}
+
+// dz = dy*[y>0]*scale in bf16, 8 elements per thread (To % 8 == 0, 16-byte aligned rows).
+__global__ __launch_bounds__(256) void dz_vec8_kernel(size_t n8, int Cout, int To8, const u32x4 *__restrict__ dy,
+                                                      const u32x4 *__restrict__ y, const float *__restrict__ scale,
+                                                      int relu, u32x4 *__restrict__ dz)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const int co = (int)((i / (size_t)To8) % (size_t)Cout);
+    const float sc = scale ? scale[co] : 1.f;
+    const u32x4 g = dy[i];
+    u32x4 yv = {0u, 0u, 0u, 0u};
+    if (relu) yv = y[i];
+    u32x4 r;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        float g0 = __uint_as_float(g[jj] << 16), g1 = __uint_as_float(g[jj] & 0xffff0000u);
+        if (relu) {
+            if (!(__uint_as_float(yv[jj] << 16) > 0.f)) g0 = 0.f;
+            if (!(__uint_as_float(yv[jj] & 0xffff0000u) > 0.f)) g1 = 0.f;
+        }
+        r[jj] = (uint32_t)f32_to_bf16(g0 * sc) | ((uint32_t)f32_to_bf16(g1 * sc) << 16);
+    }
+    dz[i] = r;
+}
+
+struct WPlan {
+    bool ok;
+    int KTg, ntg, TCH, NRX, S;
+    int n_dz, n_x, ips;
+    int dz_row_bytes, dz_bytes, x_bytes, buf_bytes;
+    size_t lds;
+};
+
+// Needs 16-byte aligned rows of both operands (T % 8 == 0 and To % 8 == 0).
+WPlan make_wplan(const Geom &g)
+{
+    WPlan w = {};
+    if (g.T % 8 != 0 || g.To % 8 != 0) return w;
+    const int ntg = (g.K + kMaxKT - 1) / kMaxKT;
+    const int KTg = (g.K + ntg - 1) / ntg;
+    w.ntg = (g.K + KTg - 1) / KTg;
+    w.KTg = KTg;
+    const int cands[4] = {80, 64, 48, 32};
+    const size_t red = (size_t)kWaves * 3 * (2 * KTg) * 64 * sizeof(f32x4);
+    for (int c = 0; c < 4; ++c) {
+        const int tch = cands[c];
+        if (c < 3 && g.To <= cands[c + 1]) continue;  // do not stage far beyond a short row
+        const long rows = (long)(tch - 1) * g.stride + (long)(KTg - 1) * g.dil + 1 + 7;
+        const long nrx = (rows + 7) / 8 * 8;
+        const long n_x = (nrx / 8 * 16 + 63) / 64;
+        const long gpr4 = (tch / 8 + 3) / 4 * 4;       // time groups per dz row, padded to 4
+        const long n_dz = gpr4;                         // 4 row blocks x gpr4/4 group blocks
+        const long dzrow = gpr4 * 16 + 16;
+        const long dzb = kTileCo * dzrow, xb = n_x * 32 * kXRowBytes;
+        const long nsteps = tch / 16;
+        const long ips = (n_dz + n_x + nsteps - 1) / nsteps;
+        const size_t stage = (size_t)kWaves * 2 * (dzb + xb);
+        const size_t lds = stage > red ? stage : red;
+        if (lds <= (size_t)kMaxLds && ips <= kStagePerStep) {
+            w.ok = true;
+            w.TCH = tch; w.NRX = (int)nrx;
+            w.n_dz = (int)n_dz; w.n_x = (int)n_x; w.ips = (int)ips;
+            w.dz_row_bytes = (int)dzrow; w.dz_bytes = (int)dzb; w.x_bytes = (int)xb; w.buf_bytes = (int)(dzb + xb);
+            w.lds = lds;
+            break;
+        }
+    }
+    if (!w.ok) return w;
+    const int ncot = (g.Cout + kTileCo - 1) / kTileCo, ncit = (g.Cin + kTileCi - 1) / kTileCi;
+    const long ntiles = (long)ncot * ncit * w.ntg;
+    const long units = (long)g.B * ((g.To + w.TCH - 1) / w.TCH);
+    long S = (512 + ntiles - 1) / ntiles;
+    if (S > 8) S = 8;
+    if (S > units / kWaves) S = units / kWaves;
+    if (S < 1) S = 1;
+    w.S = (int)S;
+    return w;
+}
+
+size_t part_bytes(const Geom &g, int S) { return align_up((size_t)S * g.K * g.Cout * g.Cin * sizeof(float), 256); }
+size_t dz_buf_bytes(const Geom &g) { return align_up((size_t)g.B * g.Cout * g.To * sizeof(bf16_t), 256); }
+
+template <int KT>
+hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
+{
+    auto kern = wgrad_kernel<KT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_wgrad_supported(const Geom &g) { return make_wplan(g).ok; }
+
+size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
+{
+    const WPlan w = make_wplan(g);
+    if (!w.ok) return 0;
+    return part_bytes(g, w.S) + (need_dz ? dz_buf_bytes(g) : 0);
+}
+
+hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y, const float *scale,
+                             float *dw, bool relu, bool accumulate, void *ws, hipStream_t s)
+{
+    const WPlan w = make_wplan(g);
+    if (!w.ok) return hipErrorInvalidValue;
+    float *part = (float *)ws;
+    const void *dz = dy;
+    if (relu || scale) {
+        void *dzbuf = (unsigned char *)ws + part_bytes(g, w.S);
+        // rows are 16-byte aligned here: To % 8 == 0 and the caller checked the pointers
+        const size_t n8 = (size_t)g.B * g.Cout * g.To / 8;
+        hipLaunchKernelGGL(dz_vec8_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, n8, g.Cout,
+                           g.To / 8, (const u32x4 *)dy, (const u32x4 *)y, scale, relu ? 1 : 0, (u32x4 *)dzbuf);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        dz = dzbuf;
+    }
+    WgradParams p = {};
+    p.B = g.B; p.Cin = g.Cin; p.Cout = g.Cout; p.T = g.T; p.To = g.To; p.K = g.K;
+    p.stride = g.stride; p.dil = g.dil; p.pad = g.pad;
+    p.ncot = (g.Cout + kTileCo - 1) / kTileCo;
+    p.ncit = (g.Cin + kTileCi - 1) / kTileCi;
+    p.ntg = w.ntg; p.KTg = w.KTg; p.S = w.S;
+    p.TCH = w.TCH; p.nchunk = (g.To + w.TCH - 1) / w.TCH; p.units = g.B * p.nchunk;
+    p.NRX = w.NRX;
+    p.n_dz = w.n_dz; p.n_x = w.n_x; p.ips = w.ips;
+    p.dz_row_bytes = w.dz_row_bytes; p.dz_bytes = w.dz_bytes; p.x_bytes = w.x_bytes; p.buf_bytes = w.buf_bytes;
+    p.total = p.ncot * p.ncit * p.ntg * p.S;
+    p.per_xcd = (p.total + 7) / 8;
+    p.CL = 0;
+    if (p.total % 8 == 0) {
+        const int denom = p.ntg * p.ncit;
+        if (p.per_xcd % denom == 0) {
+            const int cl = p.per_xcd / denom;
+            if (cl >= 1 && p.ncot % cl == 0) p.CL = cl;
+        }
+    }
+    p.x = (const bf16_t *)x; p.dz = (const bf16_t *)dz; p.part = part;
+    const int grid = p.per_xcd * 8;
+    hipError_t e;
+    switch (w.KTg) {
+    case 1: e = launch_kt<1>(p, w.lds, grid, s); break;
+    case 2: e = launch_kt<2>(p, w.lds, grid, s); break;
+    case 3: e = launch_kt<3>(p, w.lds, grid, s); break;
+    case 4: e = launch_kt<4>(p, w.lds, grid, s); break;
+    case 5: e = launch_kt<5>(p, w.lds, grid, s); break;
+    default: e = launch_kt<6>(p, w.lds, grid, s); break;
+    }
+    if (e != hipSuccess) return e;
+    dim3 rgrid((g.Cin + 63) / 64, g.Cout);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, w.S, g.K,
+                       g.Cout, g.Cin, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace nm

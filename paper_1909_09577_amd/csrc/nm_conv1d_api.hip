@@ -65,16 +65,18 @@ bool use_mfma(int op, const Geom &g, int dtype, unsigned flags)
 // Whether dz differs from dy (then backward passes on the plain path materialise it).
 bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || scale != nullptr; }
 
-size_t workspace_for(int op, const Geom &g, int dtype, unsigned flags, bool scale_or_relu)
+bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
+
+// Scratch need of one operation on one path (mfma: matrix-core kernels, else plain kernels).
+size_t workspace_for(int op, const Geom &g, int dtype, bool mfma, bool scale_or_relu)
 {
-    const size_t dz_bytes = align_up((size_t)g.B * g.Cout * g.To * elt(dtype), kWsAlign);
-    if (use_mfma(op, g, dtype, flags)) {
+    if (mfma) {
         if (op == NM_OP_FWD) return mfma_fwd_workspace(g);
         if (op == NM_OP_BWD_DATA) return mfma_dgrad_workspace(g);
         return mfma_wgrad_workspace(g, scale_or_relu);
     }
     if (op == NM_OP_FWD) return 0;
-    return scale_or_relu ? dz_bytes : 0;
+    return scale_or_relu ? align_up((size_t)g.B * g.Cout * g.To * elt(dtype), kWsAlign) : 0;
 }
 
 int check_workspace(const void *ws, size_t have, size_t need)
@@ -102,8 +104,11 @@ size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K,
     if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT) return 0;
     if (check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g) != NM_OK)
         return 0;
-    // The query cannot see whether scale is NULL; it sizes for the larger case.
-    return workspace_for(op, g, dtype, flags, true);
+    // The query sees neither the scale pointer nor the alignment of the tensors (misaligned
+    // tensors take the plain kernels); it sizes for the larger of the cases.
+    const size_t plain = workspace_for(op, g, dtype, false, true);
+    const size_t fast = use_mfma(op, g, dtype, flags) ? workspace_for(op, g, dtype, true, true) : 0;
+    return plain > fast ? plain : fast;
 }
 
 const char *nm_strerror(int status)
@@ -133,8 +138,8 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
     if (overlap(y, ny, x, (size_t)g.B * g.Cin * g.T * e) || overlap(y, ny, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(y, ny, residual, ny))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags);
-    const size_t need = workspace_for(NM_OP_FWD, g, dtype, flags, true);
+    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags) && aligned16(x);
+    const size_t need = workspace_for(NM_OP_FWD, g, dtype, mfma, true);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
     if (overlap(y, ny, workspace, need)) return NM_ERR_BAD_ARG;
@@ -161,9 +166,9 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
     if (overlap(dx, ndx, dy, ndy) || overlap(dx, ndx, y, ndy) || overlap(dx, ndx, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(dx, ndx, dres, ndy) || overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags);
+    const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && aligned16(dy) && (!relu || aligned16(y));
     const bool dzneeded = needs_dz(flags, scale);
-    const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, flags, dzneeded);
+    const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
     if (overlap(dx, ndx, workspace, need) || overlap(dres, ndy, workspace, need)) return NM_ERR_BAD_ARG;
@@ -194,9 +199,10 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
     const size_t ndy = (size_t)g.B * g.Cout * g.To * e, ndw = (size_t)g.Cout * g.Cin * g.K * sizeof(float);
     if (overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, (size_t)g.B * g.Cin * g.T * e))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags);
+    const bool mfma = use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) && aligned16(x) && aligned16(dy) &&
+                      (!relu || aligned16(y));
     const bool dzneeded = needs_dz(flags, scale);
-    const size_t need = workspace_for(NM_OP_BWD_WEIGHT, g, dtype, flags, dzneeded);
+    const size_t need = workspace_for(NM_OP_BWD_WEIGHT, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
     if (overlap(dw, ndw, workspace, need)) return NM_ERR_BAD_ARG;
