@@ -42,7 +42,7 @@ constexpr int kMaxLds = 160 * 1024;
 enum { MODE_FWD = 0, MODE_DGRAD = 1 };
 
 struct ConvGemmParams {
-    int B, M, R, Tin, Tout, K, dil, padL;
+    int B, M, R, Tin, Tout, K, Kp, dil, padL;  // Kp: K rounded up to even (packed weights)
     int nmt, nch, ntt, num_tiles;
     int NR;          // rows of one staged window that are read (multiple of 8)
     int buf_bytes;   // bytes of one staging buffer: nitems*32 rows of kRowBytes
@@ -60,15 +60,13 @@ struct ConvGemmParams {
 
 __device__ __forceinline__ int floor_div8(int v) { return v >> 3; }  // arithmetic shift: floor
 
-// Eight consecutive time steps of one channel row (16-byte aligned) as 4 packed dwords; zero
-// when the row or the time range is outside the tensor.  The address is clamped, so the load
-// itself is always in bounds and the code stays branch-free.
-__device__ __forceinline__ u32x4 load_row8(const bf16_t *base, size_t row_off, int t, int Tin, bool row_ok)
+// Eight consecutive time steps of one 16-byte aligned channel row as 4 packed dwords.  The
+// address is clamped to a valid one when the row or the time range lies outside the tensor;
+// the caller zeroes such data when it consumes it (not here: a select placed right after the
+// load would make the wavefront wait for the load at once).
+__device__ __forceinline__ u32x4 load_row8(const bf16_t *base, size_t row_off, int t, bool ok)
 {
-    const bool ok = row_ok && t >= 0 && t + 8 <= Tin;
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(base + (ok ? row_off + (size_t)t : (size_t)0));
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    return ok ? v : z;
+    return *reinterpret_cast<const u32x4 *>(base + (ok ? row_off + (size_t)t : (size_t)0));
 }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -93,49 +91,71 @@ __device__ __forceinline__ u32x4 make_dz8(u32x4 dy, u32x4 y, float scale, bool r
     return r;
 }
 
-struct StageRegs {
-    u32x4 a, b;  // channel rows 2pp and 2pp+1, 8 time steps each
+// Registers of one staging item in flight: channel rows 2pp and 2pp+1, 8 time steps each.
+template <int MODE>
+struct StageRegs;
+template <>
+struct StageRegs<MODE_FWD> {
+    u32x4 a, b;
+    bool oka, okb;
+};
+template <>
+struct StageRegs<MODE_DGRAD> {
+    u32x4 a, b, ya, yb;
+    float sa, sb;
+    bool oka, okb;
 };
 
 // One staging item: channel pair pp = item & 15 of the chunk x time group q = item >> 4.
+// stage_load only issues the loads; stage_write consumes them.
 template <int MODE>
-__device__ __forceinline__ void stage_load(const ConvGemmParams &p, int b, int c, int ws_al, int item, StageRegs &s)
+__device__ __forceinline__ void stage_load(const ConvGemmParams &p, int b, int c, int ws_al, int item,
+                                           StageRegs<MODE> &s)
 {
     const int pp = item & 15, q = item >> 4;
     const int ch = c * kChunk + 2 * pp;
     const int t = ws_al + 8 * q;
     const size_t row = ((size_t)b * p.R + ch) * p.Tin;
-    const bool ok_a = ch < p.R, ok_b = ch + 1 < p.R;
-    s.a = load_row8(p.in, row, t, p.Tin, ok_a);
-    s.b = load_row8(p.in, row + p.Tin, t, p.Tin, ok_b);
-    if (MODE == MODE_DGRAD) {
-        if (p.relu || p.in_scale) {
-            u32x4 ya = {0u, 0u, 0u, 0u}, yb = ya;
-            if (p.relu) {
-                ya = load_row8(p.ysaved, row, t, p.Tin, ok_a);
-                yb = load_row8(p.ysaved, row + p.Tin, t, p.Tin, ok_b);
-            }
-            float sa = 1.f, sb = 1.f;
-            if (p.in_scale) {
-                sa = p.in_scale[ok_a ? ch : 0];
-                sb = p.in_scale[ok_b ? ch + 1 : 0];
-            }
-            s.a = make_dz8(s.a, ya, sa, p.relu != 0);
-            s.b = make_dz8(s.b, yb, sb, p.relu != 0);
+    const bool t_ok = t >= 0 && t + 8 <= p.Tin;
+    s.oka = t_ok && ch < p.R;
+    s.okb = t_ok && ch + 1 < p.R;
+    s.a = load_row8(p.in, row, t, s.oka);
+    s.b = load_row8(p.in, row + p.Tin, t, s.okb);
+    if constexpr (MODE == MODE_DGRAD) {
+        if (p.relu) {
+            s.ya = load_row8(p.ysaved, row, t, s.oka);
+            s.yb = load_row8(p.ysaved, row + p.Tin, t, s.okb);
+        }
+        s.sa = 1.f;
+        s.sb = 1.f;
+        if (p.in_scale) {
+            s.sa = p.in_scale[ch < p.R ? ch : 0];
+            s.sb = p.in_scale[ch + 1 < p.R ? ch + 1 : 0];
         }
     }
 }
 
 // Transposing write: one dword (channel pair) per time step.  The buffer has room for every
 // item of every lane, so no bounds test is needed.
-__device__ __forceinline__ void stage_write(uint32_t *buf, int item, const StageRegs &s)
+template <int MODE>
+__device__ __forceinline__ void stage_write(const ConvGemmParams &p, uint32_t *buf, int item, const StageRegs<MODE> &s)
 {
     const int pp = item & 15, q = item >> 4;
     uint32_t *dst = buf + (q * 8) * kRowDwords + pp;
+    u32x4 a = s.a, b = s.b;
+    if constexpr (MODE == MODE_DGRAD) {
+        if (p.relu || p.in_scale) {
+            a = make_dz8(s.a, s.ya, s.sa, p.relu != 0);
+            b = make_dz8(s.b, s.yb, s.sb, p.relu != 0);
+        }
+    }
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    a = s.oka ? a : z;
+    b = s.okb ? b : z;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        dst[(2 * j) * kRowDwords] = (s.a[j] & 0xffffu) | (s.b[j] << 16);
-        dst[(2 * j + 1) * kRowDwords] = (s.a[j] >> 16) | (s.b[j] & 0xffff0000u);
+        dst[(2 * j) * kRowDwords] = (a[j] & 0xffffu) | (b[j] << 16);
+        dst[(2 * j + 1) * kRowDwords] = (a[j] >> 16) | (b[j] & 0xffff0000u);
     }
 }
 
@@ -160,7 +180,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     unsigned char *wbuf0 = smem + (size_t)wave * 2 * p.buf_bytes;
     const int nitems = p.nitems;                           // staging items per lane and chunk
     const int nmy = (p.nch - wave + kWaves - 1) / kWaves;  // chunks of this wavefront (may be 0)
-    const int K = p.K;
 
     for (int tile = blockIdx.x; tile < p.num_tiles; tile += gridDim.x) {
         const int mt = tile % p.nmt;
@@ -171,6 +190,22 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         const int ws_al = floor_div8(ws) * 8;
         const int off0 = ws - ws_al;
 
+        // ---- first chunk of the tile: nothing to overlap with, so the items are put in flight
+        // in batches before any is written (the accumulators are not live yet)
+        if (nmy > 0) {
+            uint32_t *buf = reinterpret_cast<uint32_t *>(wbuf0);
+            constexpr int kBatch = (MODE == MODE_DGRAD) ? 3 : 6;
+            for (int it0 = 0; it0 < nitems; it0 += kBatch) {
+                StageRegs<MODE> s[kBatch];
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q)
+                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * min(it0 + q, nitems - 1), s[q]);
+#pragma unroll
+                for (int q = 0; q < kBatch; ++q)
+                    stage_write<MODE>(p, buf, lane + 64 * min(it0 + q, nitems - 1), s[q]);
+            }
+        }
+
         f32x16 acc[2][NT];
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
@@ -180,35 +215,21 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
         if (nmy > 0) {
-            // ---- first chunk of the tile: nothing to overlap with; three items in flight
-            {
-                uint32_t *buf = reinterpret_cast<uint32_t *>(wbuf0);
-                for (int it = 0; it < nitems; it += 3) {
-                    StageRegs s0, s1, s2;
-                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * it, s0);
-                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * min(it + 1, nitems - 1), s1);
-                    stage_load<MODE>(p, b, wave, ws_al, lane + 64 * min(it + 2, nitems - 1), s2);
-                    stage_write(buf, lane + 64 * it, s0);
-                    stage_write(buf, lane + 64 * min(it + 1, nitems - 1), s1);
-                    stage_write(buf, lane + 64 * min(it + 2, nitems - 1), s2);
-                }
-            }
-            // ---- weight fragment stream: taps are handled in pairs and the fragments of a
-            // pair are fetched one pair (40 MFMAs) before they are used.  The stream runs on
-            // over this wave's chunks; past the end it re-reads the last pair (valid memory).
-            const size_t chunk_stride = (size_t)K * 256;  // bf16x8 per (tile, chunk)
+            // ---- main loop over (chunk, tap pair).  Taps are handled in pairs (the packed
+            // weights pad an odd K with one zero tap), 4 k-steps of 16 channels = 8*NT MFMAs per
+            // pair.  The weight fragments of a pair are fetched one pair before they are used
+            // (the stream runs on over this wave's chunks and, past the end, re-reads the last
+            // pair); B fragments are read one k-step ahead; one staging item of the next chunk
+            // rides on each pair.  All MFMAs sit in this single loop.
+            const int P = p.Kp >> 1;                      // tap pairs per chunk
+            const size_t chunk_stride = (size_t)p.Kp * 256;  // bf16x8 per (tile, chunk)
             const bf16x8 *wchunk = p.wp + ((size_t)mt * p.nch + wave) * chunk_stride + lane;
-            const int P = (K + 1) >> 1;  // tap pairs per chunk (the last may hold one tap)
             int pslot = 0, pi = 0;
             bf16x8 afA[8], afB[8];
             auto fetch_pair = [&](bf16x8(&dst)[8]) {
-                const bf16x8 *s0 = wchunk + (size_t)(2 * pslot) * 256;
-                const bf16x8 *s1 = wchunk + (size_t)min(2 * pslot + 1, K - 1) * 256;
+                const bf16x8 *s0 = wchunk + (size_t)pslot * 512;
 #pragma unroll
-                for (int f = 0; f < 4; ++f) {
-                    dst[f] = s0[f * 64];
-                    dst[4 + f] = s1[f * 64];
-                }
+                for (int f = 0; f < 8; ++f) dst[f] = s0[f * 64];
                 ++pslot;
                 if (pslot == P) {
                     if (pi + 1 < nmy) {
@@ -222,77 +243,66 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             };
             fetch_pair(afA);
 
-            for (int i = 0; i < nmy; ++i) {
-                const bool has_next = (i + 1 < nmy);
-                const int c_next = wave + kWaves * (i + 1);
-                const unsigned char *cur = wbuf0 + (size_t)(i & 1) * p.buf_bytes;
-                uint32_t *nxt = reinterpret_cast<uint32_t *>(wbuf0 + (size_t)((i + 1) & 1) * p.buf_bytes);
-                wave_lds_fence();
-                // per-lane base of the B fragment reads: row (lane%32)*STRIDE + off0, 16 B half lane/32
-                const unsigned char *bbase = cur + ((lane & 31) * STRIDE + off0) * kRowBytes + (lane >> 5) * 16;
-                const int tap_bytes = p.dil * kRowBytes;
-
-                bf16x8 b0[NT], b1[NT];
-                auto read_b = [&](bf16x8(&dst)[NT], int k, int ks) {
-                    const unsigned char *brow = bbase + (size_t)k * tap_bytes + ks * 32;
+            const int tap_bytes = p.dil * kRowBytes;
+            const int lane_off = ((lane & 31) * STRIDE + off0) * kRowBytes + (lane >> 5) * 16;
+            int ci_ord = 0, pr = 0;
+            bool has_next = nmy > 1;
+            int c_next = wave + kWaves;
+            const unsigned char *bbase = wbuf0 + lane_off;
+            uint32_t *nxt = reinterpret_cast<uint32_t *>(wbuf0 + p.buf_bytes);
+            bf16x8 b0[NT], b1[NT];
+            auto read_b = [&](bf16x8(&dst)[NT], int k, int ks) {
+                const unsigned char *brow = bbase + (size_t)k * tap_bytes + ks * 32;
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni)
+                    dst[ni] = *reinterpret_cast<const bf16x8 *>(brow + ni * 32 * STRIDE * kRowBytes);
+            };
+            auto mma = [&](const bf16x8 *af, const bf16x8(&bf)[NT]) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                     for (int ni = 0; ni < NT; ++ni)
-                        dst[ni] = *reinterpret_cast<const bf16x8 *>(brow + ni * 32 * STRIDE * kRowBytes);
-                };
-                auto mma = [&](const bf16x8 *af, const bf16x8(&bf)[NT]) {
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+            };
+            wave_lds_fence();
+            read_b(b0, 0, 0);
+            const int total_pairs = nmy * P;
+            for (int g = 0; g < total_pairs; ++g) {
+                const bool st = has_next && pr < nitems;  // this pair stages item `pr` of the next chunk
+                StageRegs<MODE> sr;
+                if (st) stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * pr, sr);
+                const int k = 2 * pr;
+                fetch_pair(afB);
+                read_b(b1, k, 1);
+                mma(&afA[0], b0);
+                read_b(b0, k + 1, 0);
+                mma(&afA[2], b1);
+                read_b(b1, k + 1, 1);
+                mma(&afA[4], b0);
+                read_b(b0, min(k + 2, p.Kp - 1), 0);
+                mma(&afA[6], b1);
 #pragma unroll
-                    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                        for (int ni = 0; ni < NT; ++ni)
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
-                };
-                read_b(b0, 0, 0);
-
-                // one pair of taps = 4 k-steps of 16 channels, 2*NT MFMAs each; B fragments are
-                // read one k-step ahead of their use
-                auto tap_pair = [&](int k) {
-                    fetch_pair(afB);
-                    read_b(b1, k, 1);
-                    mma(&afA[0], b0);
-                    read_b(b0, k + 1, 0);
-                    mma(&afA[2], b1);
-                    read_b(b1, k + 1, 1);
-                    mma(&afA[4], b0);
-                    read_b(b0, min(k + 2, K - 1), 0);
-                    mma(&afA[6], b1);
-#pragma unroll
-                    for (int f = 0; f < 8; ++f) afA[f] = afB[f];
-                };
-                // the last tap of an odd-length kernel
-                auto tap_single = [&](int k) {
-                    fetch_pair(afB);
-                    read_b(b1, k, 1);
-                    mma(&afA[0], b0);
-                    mma(&afA[2], b1);
-#pragma unroll
-                    for (int f = 0; f < 8; ++f) afA[f] = afB[f];
-                };
-
-                const int nst = has_next ? nitems : 0;
-                int k = 0, it = 0;
-                for (; k + 1 < K; k += 2, ++it) {
-                    const bool st = it < nst;  // this pair also stages one item of the next chunk
-                    StageRegs s;
-                    if (st) stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
-                    tap_pair(k);
-                    if (st) stage_write(nxt, lane + 64 * it, s);
-                }
-                for (; k < K; ++k, ++it) {
-                    const bool st = it < nst;
-                    StageRegs s;
-                    if (st) stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
-                    tap_single(k);
-                    if (st) stage_write(nxt, lane + 64 * it, s);
-                }
-                for (; it < nst; ++it) {  // more items than tap pairs (short kernels)
-                    StageRegs s;
-                    stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s);
-                    stage_write(nxt, lane + 64 * it, s);
+                for (int f = 0; f < 8; ++f) afA[f] = afB[f];
+                if (st) stage_write<MODE>(p, nxt, lane + 64 * pr, sr);
+                ++pr;
+                if (pr == P) {  // end of a chunk
+                    if (has_next) {
+                        for (int it = P; it < nitems; ++it) {  // more items than tap pairs (short kernels)
+                            StageRegs<MODE> s2;
+                            stage_load<MODE>(p, b, c_next, ws_al, lane + 64 * it, s2);
+                            stage_write<MODE>(p, nxt, lane + 64 * it, s2);
+                        }
+                    }
+                    ++ci_ord;
+                    pr = 0;
+                    if (ci_ord < nmy) {
+                        has_next = ci_ord + 1 < nmy;
+                        c_next = wave + kWaves * (ci_ord + 1);
+                        bbase = wbuf0 + (size_t)(ci_ord & 1) * p.buf_bytes + lane_off;
+                        nxt = reinterpret_cast<uint32_t *>(wbuf0 + (size_t)((ci_ord + 1) & 1) * p.buf_bytes);
+                        wave_lds_fence();
+                        read_b(b0, 0, 0);
+                    }
                 }
             }
         }
@@ -334,66 +344,114 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             for (int tl = 0; tl < kTiles; ++tl) own[tl] += red[((wave * 3 + slot) * kTiles + tl) * 64 + lane];
         __syncthreads();  // the staging buffers of the next tile alias `red`
 
-        // ---- epilogue on the rows this wave owns
+        // ---- epilogue on the rows this wave owns: all residual loads are issued first (with
+        // clamped addresses, no branches) so that their latencies overlap
         const int tcol = lane & 31;
+        const int m_base = mt * kTileM + 8 * wave + 4 * (lane >> 5);
+        uint32_t rv[2][4][NT];
+        if (MODE == MODE_FWD && p.res) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int m = m_base + mi * 32 + j;
+                    const size_t orow = ((size_t)b * p.M + m) * p.Tout;
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const int t = t0 + ni * 32 + tcol;
+                        const bool ok = m < p.M && t < p.Tout;
+                        rv[mi][j][ni] = p.res[ok ? orow + t : (size_t)0];
+                    }
+                }
+        } else {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) rv[mi][j][ni] = 0u;
+        }
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int m = mt * kTileM + mi * 32 + 8 * wave + 4 * (lane >> 5) + j;
-                if (m >= p.M) continue;
+                const int m = m_base + mi * 32 + j;
+                const int mc = m < p.M ? m : 0;
                 float sc = 1.f, sh = 0.f;
                 if (MODE == MODE_FWD) {
-                    if (p.scale) sc = p.scale[m];
-                    if (p.shift) sh = p.shift[m];
+                    if (p.scale) sc = p.scale[mc];
+                    if (p.shift) sh = p.shift[mc];
                 }
                 const size_t orow = ((size_t)b * p.M + m) * p.Tout;
 #pragma unroll
                 for (int ni = 0; ni < NT; ++ni) {
                     const int t = t0 + ni * 32 + tcol;
-                    if (t >= p.Tout) continue;
                     float v = own[mi * NT + ni][j];
                     if (MODE == MODE_FWD) {
-                        v = v * sc + sh;
-                        if (p.res) v += bf16_to_f32(p.res[orow + t]);
+                        v = v * sc + sh + __uint_as_float(rv[mi][j][ni] << 16);
                         if (p.relu) v = v > 0.f ? v : 0.f;
                     }
-                    p.out[orow + t] = f32_to_bf16(v);
+                    if (m < p.M && t < p.Tout) p.out[orow + t] = f32_to_bf16(v);
                 }
             }
         }
     }
 }
 
-// Packed weights: [mt][chunk][tap][ks][mi][lane][8]; element (lane, j) of fragment (ks, mi) is
-// W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside.
-// W'[m][r][k] = w[m*sm + r*sr + (flip ? K-1-k : k)].
-__global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp,
-                                                      int M, int R, int K, int nmt, int nch, long sm, long sr,
-                                                      int flip)
+// Packed weights: [mt][chunk][tap < Kp][ks][mi][lane][8] (Kp = K rounded up to even, the extra
+// tap is zero); element (lane, j) of fragment (ks, mi) is
+// W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside,
+// with W'[m][r][k] = w[m][r][k] (forward) or w[r][m][K-1-k] (input gradient: FLIP).
+// One block packs 16 of the 64 channels of one (mt, chunk): it copies that 16x32xK block of w
+// into LDS with coalesced reads (runs of 32*K, resp. 16*K, contiguous elements) and gathers the
+// fragments from there.
+constexpr int kPackRows = 16;
+template <bool FLIP>
+__global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
+                                                      int R, int K, int nch, int ld /* row length of w */)
 {
-    const size_t total = (size_t)nmt * nch * K * 256;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int lane = idx & 63;
-    const int f = (idx >> 6) & 3;
-    const size_t rest = idx >> 8;
-    const int k = (int)(rest % K);
-    const int c = (int)((rest / K) % nch);
-    const int mt = (int)(rest / ((size_t)K * nch));
-    const int m = mt * kTileM + (f & 1) * 32 + (lane & 31);
-    const int r0 = c * kChunk + (f >> 1) * 16 + 8 * (lane >> 5);
-    const int kk = flip ? K - 1 - k : k;
-    u32x4 out = {0u, 0u, 0u, 0u};
-    if (m < M) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = r0 + j;
-            uint32_t v = (r < R) ? (uint32_t)w[(size_t)m * sm + (size_t)r * sr + kk] : 0u;
-            out[j >> 1] |= v << ((j & 1) * 16);
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as (m*32 + r)*K + k
+    const int q = blockIdx.x & 3;                      // which 16 channels of the 64
+    const int c = (blockIdx.x >> 2) % nch, mt = (blockIdx.x >> 2) / nch;
+    const int m0 = mt * kTileM + q * kPackRows, r0 = c * kChunk;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (!FLIP) {
+        // w[m][r][k]: for each m a run of 32*K elements starting at (m0+m)*ld + r0*K
+        const int run = kChunk * K;
+        const int rvalid = min(kChunk, R - r0) * K;
+        for (int m = wv; m < kPackRows; m += 4) {
+            const bool m_ok = m0 + m < M;
+            const bf16_t *src = w + (size_t)(m_ok ? m0 + m : 0) * ld + (size_t)r0 * K;
+            for (int o = lane; o < run; o += 64) tile[m * run + o] = (m_ok && o < rvalid) ? src[o] : (bf16_t)0;
+        }
+    } else {
+        // w[r][m][k]: for each r a run of 16*K elements starting at (r0+r)*ld + m0*K
+        const int run = kPackRows * K;
+        const int mvalid = max(0, min(kPackRows, M - m0)) * K;
+        for (int r = wv; r < kChunk; r += 4) {
+            const bool r_ok = r0 + r < R;
+            const bf16_t *src = w + (size_t)(r_ok ? r0 + r : 0) * ld + (size_t)m0 * K;
+            for (int o = lane; o < run; o += 64) {
+                const int m = o / K, k = o - m * K;
+                tile[(m * kChunk + r) * K + (K - 1 - k)] = (r_ok && o < mvalid) ? src[o] : (bf16_t)0;
+            }
         }
     }
-    wp[idx] = out;
+    __syncthreads();
+    const int Kp = (K + 1) & ~1;  // an odd K gets one zero tap
+    u32x4 *dst = wp + (size_t)(blockIdx.x >> 2) * Kp * 256;
+    const int mi = q >> 1, lane_lo = (q & 1) * 16;
+    for (int idx = threadIdx.x; idx < Kp * 64; idx += 256) {
+        const int m16 = idx & 15, half = (idx >> 4) & 1, ks = (idx >> 5) & 1, k = idx >> 6;
+        u32x4 out = {0u, 0u, 0u, 0u};
+        if (k < K) {
+            const bf16_t *src = tile + (m16 * kChunk + ks * 16 + 8 * half) * K + k;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[j] = (uint32_t)src[(2 * j) * K] | ((uint32_t)src[(2 * j + 1) * K] << 16);
+        }
+        dst[(k * 4 + ks * 2 + mi) * 64 + half * 32 + lane_lo + m16] = out;
+    }
 }
 
 struct Plan {
@@ -411,11 +469,13 @@ Plan make_plan(int Tin, int Tout, int K, int stride, int dil)
     Plan pl = {false, 0, stride, 0, 0, 0};
     if (stride != 1 && stride != 2) return pl;
     if (Tin % 8 != 0) return pl;
+    if ((size_t)kPackRows * kChunk * K * sizeof(bf16_t) > (size_t)kMaxLds) return pl;  // weight packing tile
     const int cands[2] = {5, 2};
     for (int ci = 0; ci < 2; ++ci) {
         const int nt = cands[ci];
         if (ci == 0 && Tout <= 64) continue;  // short sequences: the narrow tile wastes less
-        const long rows = (long)(nt * 32 - 1) * stride + (long)(K - 1) * dil + 1 + 7;
+        const long Kp = (K + 1) & ~1;  // the zero tap of an odd K is still read
+        const long rows = (long)(nt * 32 - 1) * stride + (Kp - 1) * dil + 1 + 7;
         const long NR = (rows + 7) / 8 * 8;
         const long nitems = (NR / 8 * 16 + 63) / 64;
         const size_t stage = (size_t)kWaves * 2 * (nitems * 32) * kRowBytes;
@@ -436,7 +496,8 @@ Plan make_plan(int Tin, int Tout, int K, int stride, int dil)
 size_t packed_bytes(int M, int R, int K)
 {
     const size_t nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
-    return align_up(nmt * nch * K * 256 * sizeof(u32x4), 256);
+    const size_t Kp = (size_t)((K + 1) & ~1);
+    return align_up(nmt * nch * Kp * 256 * sizeof(u32x4), 256);
 }
 
 template <int NT, int STRIDE, int MODE>
@@ -468,19 +529,35 @@ hipError_t launch_mode(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
-hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, long sm, long sr, bool flip, hipStream_t s)
+size_t prepack_lds(int K) { return (size_t)kPackRows * kChunk * K * sizeof(bf16_t); }
+
+// flip == false: W'[m][r][k] = w[m][r][k] (w is [M][R][K]); flip == true: W'[m][r][k] = w[r][m][K-1-k]
+// (w is [R][M][K]).
+hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, bool flip, hipStream_t s)
 {
     const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
-    const size_t total = (size_t)nmt * nch * K * 256;
-    hipLaunchKernelGGL(prepack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t *)w,
-                       (u32x4 *)wp, M, R, K, nmt, nch, sm, sr, flip ? 1 : 0);
+    const size_t lds = prepack_lds(K);
+    hipError_t e;
+    if (flip) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(prepack_kernel<true>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
+                           M, R, K, nch, M * K);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(prepack_kernel<false>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
+                           M, R, K, nch, R * K);
+    }
     return hipGetLastError();
 }
 
 void fill_common(ConvGemmParams &p, const Plan &pl, int B, int M, int R, int Tin, int Tout, int K, int dil, int padL,
                  const void *)
 {
-    p.B = B; p.M = M; p.R = R; p.Tin = Tin; p.Tout = Tout; p.K = K; p.dil = dil; p.padL = padL;
+    p.B = B; p.M = M; p.R = R; p.Tin = Tin; p.Tout = Tout; p.K = K; p.Kp = (K + 1) & ~1; p.dil = dil; p.padL = padL;
     p.nmt = (M + kTileM - 1) / kTileM;
     p.nch = (R + kChunk - 1) / kChunk;
     p.ntt = (Tout + pl.nt * 32 - 1) / (pl.nt * 32);
@@ -502,7 +579,7 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 {
     const Plan pl = make_plan(g.T, g.To, g.K, g.stride, g.dil);
     if (!pl.ok) return hipErrorInvalidValue;
-    hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, (long)g.Cin * g.K, g.K, false, s);
+    hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, s);
     if (e != hipSuccess) return e;
     ConvGemmParams p = {};
     fill_common(p, pl, g.B, g.Cout, g.Cin, g.T, g.To, g.K, g.dil, g.pad, x);
@@ -528,10 +605,12 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
 {
     const Plan pl = make_plan(g.To, g.T, g.K, 1, g.dil);
     if (!pl.ok) return hipErrorInvalidValue;
-    hipError_t e = run_prepack(w, ws, g.Cin, g.Cout, g.K, g.K, (long)g.Cin * g.K, true, s);
+    hipError_t e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, s);
     if (e != hipSuccess) return e;
     if (dres) {
-        e = launch_epilogue_bwd(g, true, dy, y, nullptr, relu, nullptr, dres, s);
+        // To % 8 == 0 on this path; dres is written with 2-byte granularity only if misaligned
+        if (((uintptr_t)dres % 16) == 0) e = launch_epilogue_bwd_vec8(g, dy, y, nullptr, relu, nullptr, dres, s);
+        else e = launch_epilogue_bwd(g, true, dy, y, nullptr, relu, nullptr, dres, s);
         if (e != hipSuccess) return e;
     }
     ConvGemmParams p = {};

@@ -55,16 +55,6 @@ struct WgradParams {
     float *part;               // [S][K][Cout][Cin]
 };
 
-// Eight consecutive time steps of one 16-byte aligned channel row as 4 packed dwords; zero when
-// the row or the time range lies outside the tensor (the address is clamped: no branch).
-__device__ __forceinline__ u32x4 load_row8(const bf16_t *base, size_t row_off, int t, int Tlen, bool row_ok)
-{
-    const bool ok = row_ok && t >= 0 && t + 8 <= Tlen;
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(base + (ok ? row_off + (size_t)t : (size_t)0));
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    return ok ? v : z;
-}
-
 __device__ __forceinline__ void wave_lds_fence()
 {
     // LDS operations of one wavefront execute in order; this only keeps the compiler from
@@ -74,55 +64,22 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Staging of one unit: n_dz dz items then n_x x items per lane.
-//  dz item idx: row = lane/4 + 16*(idx&3), time group = lane%4 + 4*(idx>>2) (8 steps each);
-//               groups past the chunk land in the row's spare columns and are never read.
-//  x item idx:  channel pair pp = item & 15, time group q = item >> 4, item = lane + 64*idx.
-struct StageSlot {
-    u32x4 a, b;
-};
-
-__device__ __forceinline__ void stage_load(const WgradParams &p, int co0, int ci0, int b, int tbase, int xs_al,
-                                           int idx, int lane, StageSlot &s)
+// 16-byte buffer load: `voff` is the byte offset of the lane inside the tensor, `soff` a
+// wave-uniform addend.  A lane whose data lies outside its row passes kOutOfRange, which the
+// hardware bounds check turns into zeros: no branch and nothing to fix up after the load.
+constexpr uint32_t kOutOfRange = 0xffffffffu;
+__device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
-    if (idx < p.n_dz) {
-        const int row = (lane >> 2) + 16 * (idx & 3);
-        const int grp = (lane & 3) + 4 * (idx >> 2);
-        const int co = co0 + row;
-        s.a = load_row8(p.dz, ((size_t)b * p.Cout + co) * p.To, tbase + 8 * grp, p.To, co < p.Cout);
-        s.b = s.a;
-    } else {
-        const int item = lane + 64 * (idx - p.n_dz);
-        const int pp = item & 15, q = item >> 4;
-        const int ci = ci0 + 2 * pp;
-        const int t = xs_al + 8 * q;
-        const size_t row = ((size_t)b * p.Cin + ci) * p.T;
-        s.a = load_row8(p.x, row, t, p.T, ci < p.Cin);
-        s.b = load_row8(p.x, row + p.T, t, p.T, ci + 1 < p.Cin);
-    }
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
 }
 
-__device__ __forceinline__ void stage_write(const WgradParams &p, unsigned char *buf, int idx, int lane,
-                                            const StageSlot &s)
-{
-    if (idx < p.n_dz) {
-        const int row = (lane >> 2) + 16 * (idx & 3);
-        const int grp = (lane & 3) + 4 * (idx >> 2);
-        *reinterpret_cast<u32x4 *>(buf + row * p.dz_row_bytes + grp * 16) = s.a;
-    } else {
-        const int item = lane + 64 * (idx - p.n_dz);
-        const int pp = item & 15, q = item >> 4;
-        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + p.dz_bytes) + (q * 8) * kXRowDwords + pp;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            dst[(2 * j) * kXRowDwords] = (s.a[j] & 0xffffu) | (s.b[j] << 16);
-            dst[(2 * j + 1) * kXRowDwords] = (s.a[j] >> 16) | (s.b[j] & 0xffff0000u);
-        }
-    }
-}
+constexpr int kMaxDzItems = 12;  // staging items per lane and unit the kernel is built for:
+constexpr int kMaxXItems = 6;    // dz rows (one 16-byte load each) and x channel pairs (two loads)
 
-constexpr int kStagePerStep = 4;  // at most this many staging items ride on one MFMA step
-
+// Staging of one unit.
+//  dz item q: row = lane/4 + 16*(q&3), time group = lane%4 + 4*(q>>2) (8 steps each); groups
+//             past the chunk land in the row's spare columns and are never read.
+//  x item q:  channel pair pp = lane & 15, time group = lane/16 + 4*q.
 template <int KT>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 {
@@ -166,10 +123,71 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
             for (int r = 0; r < 16; ++r) acc[mi][kk][r] = 0.f;
 
     unsigned char *wbuf0 = smem + (size_t)wave * 2 * p.buf_bytes;
-    const int nitems = p.n_dz + p.n_x;
     const int nsteps = p.TCH >> 4;
     const int slot_id = sp * kWaves + wave;
     const int slots = p.S * kWaves;
+    const __amdgpu_buffer_rsrc_t rs_dz =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.dz, 0, (int)((size_t)p.B * p.Cout * p.To * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)((size_t)p.B * p.Cin * p.T * 2), 0x00020000);
+
+    // per-lane pieces of the staging addresses that do not change with the unit
+    const int dz_row = lane >> 2, dz_grp = lane & 3;  // + 16*(q&3), + 4*(q>>2)
+    const int x_pp = lane & 15, x_q = lane >> 4;        // time group x_q + 4*q
+    const uint32_t dz_lane_off = (uint32_t)(((co0 + dz_row) * p.To + 8 * dz_grp) * 2);
+    const uint32_t x_lane_off = (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q) * 2);
+    uint32_t dz_lds_off = (uint32_t)(dz_row * p.dz_row_bytes + dz_grp * 16);
+    uint32_t x_lds_off = (uint32_t)(p.dz_bytes + (x_q * 8) * kXRowBytes + x_pp * 4);
+
+    u32x4 dzr[kMaxDzItems];
+    u32x4 xra[kMaxXItems], xrb[kMaxXItems];
+
+    // issue every load of unit (b, tbase, xs_al)
+    auto stage_load = [&](int b, int tbase, int xs_al) {
+        const uint32_t dz_unit = (uint32_t)(((size_t)b * p.Cout * p.To + tbase) * 2);
+#pragma unroll
+        for (int q = 0; q < kMaxDzItems; ++q) {
+            if (q < p.n_dz) {
+                const int row = dz_row + 16 * (q & 3), t = tbase + 8 * (dz_grp + 4 * (q >> 2));
+                const bool ok = co0 + row < p.Cout && t + 8 <= p.To;
+                const uint32_t so = dz_unit + (uint32_t)((16 * (q & 3) * p.To + 32 * (q >> 2)) * 2);
+                dzr[q] = buf_load16(rs_dz, ok ? dz_lane_off : kOutOfRange, so);
+            }
+        }
+        // xs_al may be negative: fold it into the lane offset (wrap-around arithmetic is exact
+        // for the lanes that are in range)
+        const uint32_t x_unit = (uint32_t)((size_t)b * p.Cin * p.T * 2) + (uint32_t)(xs_al * 2);
+#pragma unroll
+        for (int q = 0; q < kMaxXItems; ++q) {
+            if (q < p.n_x) {
+                const int t = xs_al + 8 * (x_q + 4 * q);
+                const bool t_ok = t >= 0 && t + 8 <= p.T;
+                const bool oka = t_ok && ci0 + 2 * x_pp < p.Cin, okb = t_ok && ci0 + 2 * x_pp + 1 < p.Cin;
+                const uint32_t off = x_lane_off + x_unit + (uint32_t)(64 * q);
+                xra[q] = buf_load16(rs_x, oka ? off : kOutOfRange, 0);
+                xrb[q] = buf_load16(rs_x, okb ? off + (uint32_t)(p.T * 2) : kOutOfRange, 0);
+            }
+        }
+    };
+    // write them to the staging buffer `buf`
+    auto stage_write = [&](unsigned char *buf) {
+#pragma unroll
+        for (int q = 0; q < kMaxDzItems; ++q) {
+            if (q < p.n_dz)
+                *reinterpret_cast<u32x4 *>(buf + dz_lds_off + (16 * (q & 3)) * p.dz_row_bytes + (q >> 2) * 64) = dzr[q];
+        }
+#pragma unroll
+        for (int q = 0; q < kMaxXItems; ++q) {
+            if (q < p.n_x) {
+                uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kXRowBytes);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dst[(2 * e) * kXRowDwords] = (xra[q][e] & 0xffffu) | (xrb[q][e] << 16);
+                    dst[(2 * e + 1) * kXRowDwords] = (xra[q][e] >> 16) | (xrb[q][e] & 0xffff0000u);
+                }
+            }
+        }
+    };
 
     auto unit_coords = [&](int u, int &b, int &tbase, int &xs_al, int &off0) {
         b = u / p.nchunk;
@@ -192,23 +210,24 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
     if (u < p.units) {
         int b, tbase, xs_al, off0;
         unit_coords(u, b, tbase, xs_al, off0);
-        // first unit of this wavefront: nothing to overlap with; four items in flight
-        for (int it = 0; it < nitems; it += 4) {
-            StageSlot s[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) stage_load(p, co0, ci0, b, tbase, xs_al, min(it + q, nitems - 1), lane, s[q]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) stage_write(p, wbuf0, min(it + q, nitems - 1), lane, s[q]);
-        }
+        // first unit of this wavefront: nothing to overlap with
+        stage_load(b, tbase, xs_al);
+        stage_write(wbuf0);
+
         int parity = 0;
         for (; u < p.units; u += slots, parity ^= 1) {
             unit_coords(u, b, tbase, xs_al, off0);
             const int un = u + slots;
             const bool has_next = un < p.units;
-            int bn = 0, tbn = 0, xsn = 0, offn = 0;
-            if (has_next) unit_coords(un, bn, tbn, xsn, offn);
             const unsigned char *cur = wbuf0 + (size_t)parity * p.buf_bytes;
             unsigned char *nxt = wbuf0 + (size_t)(parity ^ 1) * p.buf_bytes;
+            // the whole next unit is requested now and written to LDS after this unit's MFMAs:
+            // one unit of MFMA work (about 2000 cycles) hides the memory latency
+            if (has_next) {
+                int bn, tbn, xsn, offn;
+                unit_coords(un, bn, tbn, xsn, offn);
+                stage_load(bn, tbn, xsn);
+            }
             wave_lds_fence();
             const unsigned char *abase = cur + a_lane_off;
             const unsigned char *xbase = cur + p.dz_bytes + (size_t)(trow * p.stride + off0) * kXRowBytes + tcol * 2;
@@ -236,14 +255,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 
             bf16x8 a0[2], a1[2], b0[KT], b1[KT];
             read_frags(0, a0, b0);
-            // the next unit's items ride on this unit's MFMA steps
-            const int ips = has_next ? p.ips : 0;
-            int it = 0;
             for (int st = 0; st < nsteps; ++st) {
-                StageSlot s[kStagePerStep];
-#pragma unroll
-                for (int q = 0; q < kStagePerStep; ++q)
-                    if (q < ips && it + q < nitems) stage_load(p, co0, ci0, bn, tbn, xsn, it + q, lane, s[q]);
                 read_frags(min(st + 1, nsteps - 1), a1, b1);
 #pragma unroll
                 for (int kk = 0; kk < KT; ++kk) {
@@ -254,14 +266,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < kStagePerStep; ++q)
-                    if (q < ips && it + q < nitems) stage_write(p, nxt, it + q, lane, s[q]);
-                it += ips;
-#pragma unroll
                 for (int mi = 0; mi < 2; ++mi) a0[mi] = a1[mi];
 #pragma unroll
                 for (int kk = 0; kk < KT; ++kk) b0[kk] = b1[kk];
             }
+            if (has_next) stage_write(nxt);
         }
     }
 
@@ -348,31 +357,6 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     }
 }
 
-// dz = dy*[y>0]*scale in bf16, 8 elements per thread (To % 8 == 0, 16-byte aligned rows).
-__global__ __launch_bounds__(256) void dz_vec8_kernel(size_t n8, int Cout, int To8, const u32x4 *__restrict__ dy,
-                                                      const u32x4 *__restrict__ y, const float *__restrict__ scale,
-                                                      int relu, u32x4 *__restrict__ dz)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n8) return;
-    const int co = (int)((i / (size_t)To8) % (size_t)Cout);
-    const float sc = scale ? scale[co] : 1.f;
-    const u32x4 g = dy[i];
-    u32x4 yv = {0u, 0u, 0u, 0u};
-    if (relu) yv = y[i];
-    u32x4 r;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        float g0 = __uint_as_float(g[jj] << 16), g1 = __uint_as_float(g[jj] & 0xffff0000u);
-        if (relu) {
-            if (!(__uint_as_float(yv[jj] << 16) > 0.f)) g0 = 0.f;
-            if (!(__uint_as_float(yv[jj] & 0xffff0000u) > 0.f)) g1 = 0.f;
-        }
-        r[jj] = (uint32_t)f32_to_bf16(g0 * sc) | ((uint32_t)f32_to_bf16(g1 * sc) << 16);
-    }
-    dz[i] = r;
-}
-
 struct WPlan {
     bool ok;
     int KTg, ntg, TCH, NRX, S;
@@ -406,7 +390,7 @@ WPlan make_wplan(const Geom &g)
         const long ips = (n_dz + n_x + nsteps - 1) / nsteps;
         const size_t stage = (size_t)kWaves * 2 * (dzb + xb);
         const size_t lds = stage > red ? stage : red;
-        if (lds <= (size_t)kMaxLds && ips <= kStagePerStep) {
+        if (lds <= (size_t)kMaxLds && n_dz <= kMaxDzItems && n_x <= kMaxXItems) {
             w.ok = true;
             w.TCH = tch; w.NRX = (int)nrx;
             w.n_dz = (int)n_dz; w.n_x = (int)n_x; w.ips = (int)ips;
@@ -462,10 +446,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
     if (relu || scale) {
         void *dzbuf = (unsigned char *)ws + part_bytes(g, w.S);
         // rows are 16-byte aligned here: To % 8 == 0 and the caller checked the pointers
-        const size_t n8 = (size_t)g.B * g.Cout * g.To / 8;
-        hipLaunchKernelGGL(dz_vec8_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, n8, g.Cout,
-                           g.To / 8, (const u32x4 *)dy, (const u32x4 *)y, scale, relu ? 1 : 0, (u32x4 *)dzbuf);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_epilogue_bwd_vec8(g, dy, y, scale, relu, dzbuf, nullptr, s);
         if (e != hipSuccess) return e;
         dz = dzbuf;
     }

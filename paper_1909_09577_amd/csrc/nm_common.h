@@ -43,6 +43,9 @@ hipError_t launch_direct_fwd(const Geom &g, bool is_bf16, const void *x, const v
 // dz = dy*[y>0]*scale (any of dz/dres may be NULL); y may be NULL when !relu.
 hipError_t launch_epilogue_bwd(const Geom &g, bool is_bf16, const void *dy, const void *y,
                                const float *scale, bool relu, void *dz, void *dres, hipStream_t s);
+// Same for bf16 tensors with To % 8 == 0 and 16-byte aligned pointers (8 elements per thread).
+hipError_t launch_epilogue_bwd_vec8(const Geom &g, const void *dy, const void *y, const float *scale, bool relu,
+                                    void *dz, void *dres, hipStream_t s);
 hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx,
                                hipStream_t s);
 hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, float *dw,

@@ -64,13 +64,30 @@ SMALL = [
 
 # Medium: several 64x160 tiles with ragged tails in every dimension (oracle: a few seconds each).
 MEDIUM = [
-    L("m_ragged", 3, 72, 100, 333, 11, pad=5, residual=True),
+    L("m_ragged", 3, 72, 100, 336, 11, pad=5, residual=True),
+    L("m_odd_len", 2, 40, 48, 333, 7, pad=3, residual=True),      # T % 8 != 0: plain kernels
     L("m_two_tiles", 2, 128, 192, 320, 17, pad=8, residual=True),
-    L("m_dil2", 2, 96, 80, 250, 9, dilation=2, pad=8),
+    L("m_dil2", 2, 96, 80, 248, 9, dilation=2, pad=8),
+    L("m_pad_not_same", 2, 64, 64, 176, 5, pad=6),               # T_out = T + 8
+    L("m_k29_d2", 1, 48, 72, 240, 29, dilation=2, pad=28),
     L("m_k1_wide", 2, 200, 29, 400, 1, affine=False, relu=False),
     L("m_stride2_prolog", 2, 64, 96, 400, 11, stride=2, pad=5),
     L("m_cin_small", 2, 16, 64, 480, 5, pad=2),
 ]
+
+
+FULL = [syn.JASPER_B1, syn.JASPER_B3, syn.EPILOG_A, syn.EPILOG_B, syn.EPILOG_C]
+
+
+def takes_matrix_core_path(cfg):
+    """The forward matrix-core kernel needs scratch for packed weights, the plain one none."""
+    return nm.nm_conv1d_workspace_bytes(nm.NM_OP_FWD, *cfg.dims(), nm.NM_BF16, 0) > 0
+
+
+def test_matrix_core_path_is_selected_for_the_jasper_shapes():
+    for cfg in FULL + [syn.TINY] + [c for c in MEDIUM if c.name != "m_odd_len"]:
+        assert takes_matrix_core_path(cfg), cfg.name
+        assert nm.nm_conv1d_workspace_bytes(nm.NM_OP_FWD, *cfg.dims(), nm.NM_BF16, nm.NM_FORCE_DIRECT) == 0
 
 
 def check_layer(cfg, dtype, force_direct):
@@ -120,9 +137,6 @@ def edge_indices(shape):
             for c in {0, 1, min(159, d2 - 1), min(160, d2 - 1), d2 - 2 if d2 > 1 else 0, d2 - 1}:
                 picks.append((a * d1 + b) * d2 + c)
     return picks
-
-
-FULL = [syn.JASPER_B1, syn.JASPER_B3, syn.EPILOG_A, syn.EPILOG_B, syn.EPILOG_C]
 
 
 @pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
