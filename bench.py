@@ -1,0 +1,146 @@
+#!/usr/bin/env python3
+"""Throughput of the conv1d sub-block hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch of the headline workload
+(Jasper B3-shaped block: B=32, Cin=Cout=512, T=800, K=17, stride 1, pad 8, bf16 storage,
+float32 accumulation, folded-BN affine + residual + ReLU):
+    nm_conv1d_block_fwd  ->  nm_conv1d_bwd_data (dx and dres)  ->  nm_conv1d_bwd_weight
+with every helper kernel of those calls (weight packing, dz pass, dw reduction) inside the timed
+region and all inputs resident in HBM before it starts.  The metric is
+3 * 2*B*Cout*T_out*Cin*K flop per step divided by the measured time, in TFLOP/s.
+
+The JSON line also carries
+  roofline     -- the dominant kernel (largest share of the step) against the bf16 dense MFMA
+                  peak; its average duration is measured in the timed region with HIP events
+                  recorded on the launch stream right around that kernel (the library's
+                  nm_conv1d_time_next_main_kernel hook);
+  cpu_baseline -- the fp64 CPU oracle, untuned, timed on the host cores on the first 8 of the
+                  32 batch items of the same workload (a baseline, not the target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+
+
+def cpu_baseline(cfg_full):
+    """Oracle forward + both gradients on a bounded sample (first 8 batch items)."""
+    import numpy as np
+    import _util as U
+    from oracle import conv1d_oracle as orc
+    from paper_1909_09577_amd import inputs as syn
+    nb = min(8, cfg_full.B)
+    cfg = syn.shrink(cfg_full, B=nb)
+    inp = syn.make_inputs(cfg, "bf16")
+    t0 = time.perf_counter()
+    y = U.oracle_fwd(cfg, inp)
+    dx, dw, dres = U.oracle_bwd(cfg, inp, y)
+    dt = time.perf_counter() - t0
+    flops = 3 * cfg.flops_per_pass
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"first {nb} of {cfg_full.B} batch items of the same workload, fp64, fwd+dgrad+wgrad, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import _util as U
+    from paper_1909_09577_amd import binding as nm
+    from paper_1909_09577_amd import inputs as syn
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    nm.lib()  # fails loudly if the HIP library has not been built
+
+    cfg = syn.HEADLINE
+    dt = "bf16"
+    inp = syn.make_inputs(cfg, dt)
+    kw = U.geom_kw(cfg)
+    x, w = U.to_dev(inp, "x", dt), U.to_dev(inp, "w", dt)
+    scale, shift = U.to_dev(inp, "scale", dt), U.to_dev(inp, "shift", dt)
+    res, dy = U.to_dev(inp, "residual", dt), U.to_dev(inp, "dy", dt)
+    To = cfg.T_out
+    y = torch.empty((cfg.B, cfg.Cout, To), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty_like(x)
+    dres = torch.empty_like(y)
+    dw = torch.empty((cfg.Cout, cfg.Cin, cfg.K), dtype=torch.float32, device="cuda")
+    ws_bytes = max(nm.nm_conv1d_workspace_bytes(op, *cfg.dims(), nm.NM_BF16, nm.NM_RELU) for op in (0, 1, 2))
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()  # torch creates the handle on first record
+        return e
+
+    names = ("fwd", "dgrad", "wgrad")
+    pairs = {n: [(ev(), ev()) for _ in range(args.steps)] for n in names}
+
+    def step(i=None):
+        if i is not None:
+            nm.nm_conv1d_time_next_main_kernel(*pairs["fwd"][i])
+        nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw)
+        if i is not None:
+            nm.nm_conv1d_time_next_main_kernel(*pairs["dgrad"][i])
+        nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=y, scale=scale, dx=dx, dres=dres, relu=True, workspace=ws, **kw)
+        if i is not None:
+            nm.nm_conv1d_time_next_main_kernel(*pairs["wgrad"][i])
+        nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / args.steps * 1e3
+    flops_step = 3 * cfg.flops_per_pass
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    kern_ms = {n: sum(a.elapsed_time(b) for a, b in pairs[n]) / args.steps for n in names}
+    dominant = max(kern_ms, key=kern_ms.get)
+    kernel_names = {"fwd": "conv_gemm_kernel<5,1,FWD>", "dgrad": "conv_gemm_kernel<5,1,DGRAD>",
+                    "wgrad": "wgrad_kernel<6>"}
+    achieved = cfg.flops_per_pass / (kern_ms[dominant] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "kernel": kernel_names[dominant],
+                "flops_per_launch": cfg.flops_per_pass,
+                "avg_launch_ms": round(kern_ms[dominant], 4),
+                "main_kernels_ms": {n: round(v, 4) for n, v in kern_ms.items()}}
+
+    out = {
+        "metric": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), C=512 K=17 T=800",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "Jasper B3-shaped block: B=32 Cin=Cout=512 T=800 K=17 stride 1 dilation 1 pad 8, "
+                               "affine+residual+ReLU, fwd+dgrad(+dres)+wgrad", "seed": cfg.seed},
+        "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -116,6 +116,15 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
                          float *dw, unsigned flags, int dtype,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid (no effect on results).  Arms a one-shot timer for the calling thread: the
+ * next nm_conv1d_block_fwd / nm_conv1d_bwd_data / nm_conv1d_bwd_weight call made by this thread
+ * records `start_event` immediately before and `stop_event` immediately after its main
+ * convolution kernel, on that call's stream (helper kernels of the call -- weight packing, the
+ * dz = dy*m*scale pass, the final dw reduction -- stay outside the pair).  Both arguments are
+ * hipEvent_t handles created by the caller with timing enabled; passing NULL for either
+ * disarms.  The pair is consumed by that call whether it succeeds or not.  Returns NM_OK. */
+int nm_conv1d_time_next_main_kernel(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

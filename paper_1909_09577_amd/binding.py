@@ -21,7 +21,7 @@ NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
 NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
-           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight")
+           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_data.restype = i
         L.nm_conv1d_bwd_weight.argtypes = [i] * 8 + [vp] * 5 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd_weight.restype = i
+        L.nm_conv1d_time_next_main_kernel.argtypes = [vp, vp]
+        L.nm_conv1d_time_next_main_kernel.restype = i
         _lib = L
     return _lib
 
@@ -68,6 +70,15 @@ def nm_conv1d_out_len(T: int, K: int, stride: int = 1, dilation: int = 1, pad: i
 def nm_conv1d_workspace_bytes(op: int, B, Cin, Cout, T, K, stride=1, dilation=1, pad=0, dtype=NM_BF16,
                               flags=0) -> int:
     return int(lib().nm_conv1d_workspace_bytes(op, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags))
+
+
+def nm_conv1d_time_next_main_kernel(start_event, stop_event) -> None:
+    """Arm the one-shot timer with two torch.cuda.Event(enable_timing=True) objects that have
+    been recorded at least once (torch creates the underlying handle lazily), or None to disarm."""
+    if start_event is None or stop_event is None:
+        lib().nm_conv1d_time_next_main_kernel(None, None)
+        return
+    lib().nm_conv1d_time_next_main_kernel(ctypes.c_void_p(start_event.cuda_event), ctypes.c_void_p(stop_event.cuda_event))
 
 
 # ---- tensor marshalling -----------------------------------------------------------------

@@ -513,6 +513,7 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
     }
     const int grid = p.num_tiles < cus ? p.num_tiles : cus;
+    MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
     return hipGetLastError();
 }

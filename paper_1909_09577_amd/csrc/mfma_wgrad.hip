@@ -421,6 +421,7 @@ hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
     return hipGetLastError();
 }

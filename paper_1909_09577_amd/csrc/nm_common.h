@@ -36,6 +36,15 @@ __device__ __forceinline__ float round_to_storage(float v, const bf16_t *) { ret
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// One-shot event pair armed by nm_conv1d_time_next_main_kernel (thread local, nm_conv1d_api.hip).
+// Construct right before the launch of a call's main kernel, destroy right after it.
+struct MainKernelTimer {
+    explicit MainKernelTimer(hipStream_t s);
+    ~MainKernelTimer();
+    hipStream_t stream;
+    hipEvent_t stop;
+};
+
 // ---- plain kernels (direct_kernels.hip); is_bf16 selects the storage type ---------------
 hipError_t launch_direct_fwd(const Geom &g, bool is_bf16, const void *x, const void *w,
                              const float *scale, const float *shift, const void *res, void *y,

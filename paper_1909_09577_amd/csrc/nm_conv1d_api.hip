@@ -8,6 +8,27 @@
 using namespace nm;
 
 namespace {
+thread_local hipEvent_t t_start_event = nullptr;
+thread_local hipEvent_t t_stop_event = nullptr;
+}  // namespace
+
+namespace nm {
+MainKernelTimer::MainKernelTimer(hipStream_t s) : stream(s), stop(nullptr)
+{
+    if (t_start_event && t_stop_event) {
+        (void)hipEventRecord(t_start_event, s);
+        stop = t_stop_event;
+    }
+    t_start_event = nullptr;
+    t_stop_event = nullptr;
+}
+MainKernelTimer::~MainKernelTimer()
+{
+    if (stop) (void)hipEventRecord(stop, stream);
+}
+}  // namespace nm
+
+namespace {
 
 constexpr unsigned kAllFlags = NM_RELU | NM_ACCUM_DW | NM_FORCE_DIRECT;
 constexpr size_t kWsAlign = 256;
@@ -88,6 +109,15 @@ int check_workspace(const void *ws, size_t have, size_t need)
 
 int dev(hipError_t e) { return e == hipSuccess ? NM_OK : NM_ERR_DEVICE; }
 
+// Consumes the armed event pair when an entry point returns without launching its main kernel.
+struct DisarmOnExit {
+    ~DisarmOnExit()
+    {
+        t_start_event = nullptr;
+        t_stop_event = nullptr;
+    }
+};
+
 }  // namespace
 
 extern "C" {
@@ -111,6 +141,13 @@ size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K,
     return plain > fast ? plain : fast;
 }
 
+int nm_conv1d_time_next_main_kernel(void *start_event, void *stop_event)
+{
+    t_start_event = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
+    t_stop_event = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
+    return NM_OK;
+}
+
 const char *nm_strerror(int status)
 {
     switch (status) {
@@ -128,6 +165,7 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
                         const void *residual, void *y, unsigned flags, int dtype, void *workspace,
                         size_t workspace_bytes, void *hip_stream)
 {
+    DisarmOnExit disarm;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
                             NM_RELU | NM_FORCE_DIRECT, &g);
@@ -146,6 +184,7 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
     hipStream_t s = (hipStream_t)hip_stream;
     const bool relu = (flags & NM_RELU) != 0;
     if (mfma) return dev(launch_mfma_fwd(g, x, w, scale, shift, residual, y, relu, workspace, s));
+    MainKernelTimer timer(s);
     return dev(launch_direct_fwd(g, dtype == NM_BF16, x, w, scale, shift, residual, y, relu, s));
 }
 
@@ -154,6 +193,7 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
                        void *dres, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
                        void *hip_stream)
 {
+    DisarmOnExit disarm;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
                             NM_RELU | NM_FORCE_DIRECT, &g);
@@ -181,6 +221,7 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
         if (err != hipSuccess) return NM_ERR_DEVICE;
         if (dzneeded) dz = workspace;
     }
+    MainKernelTimer timer(s);
     return dev(launch_direct_dgrad(g, bf, dz, w, dx, s));
 }
 
@@ -189,6 +230,7 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
                          unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
                          void *hip_stream)
 {
+    DisarmOnExit disarm;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
     if (st != NM_OK) return st;
@@ -216,6 +258,7 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
         if (err != hipSuccess) return NM_ERR_DEVICE;
         dz = workspace;
     }
+    MainKernelTimer timer(s);
     return dev(launch_direct_wgrad(g, bf, x, dz, dw, accum, s));
 }
 
