@@ -53,6 +53,9 @@ struct WgradParams {
     const bf16_t *x;           // [B][Cin][T]
     const bf16_t *dz;          // [B][Cout][To]
     float *part;               // [S][K][Cout][Cin]
+    // stride-1, dilation-1 kernel only: dz in MFMA A-fragment order [B][ncm][nst][64 lanes][8]
+    const u32x4 *dzf;
+    int ncm, nst;              // 32-channel blocks (2 per tile), 16-step blocks per batch row
 };
 
 __device__ __forceinline__ void wave_lds_fence()
@@ -73,6 +76,96 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
     return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
 }
 
+// Which (split, tile) a workgroup owns.  Work items are numbered so that the workgroups the
+// hardware places on one XCD (blockIdx mod 8) form a contiguous range of items that share the
+// T-slice and neighbouring channel tiles.
+struct TileCoords {
+    int sp, tg, cot, cit;
+    bool valid;
+};
+__device__ __forceinline__ TileCoords decode_tile(const WgradParams &p)
+{
+    TileCoords tc;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int v = xcd * p.per_xcd + j;
+    tc.valid = !(j >= p.per_xcd || v >= p.total);
+    int r = tc.valid ? v : 0;
+    if (p.CL > 0) {
+        // digits, slowest to fastest: sp, cot_hi, tg, cot_lo, cit
+        tc.cit = r % p.ncit; r /= p.ncit;
+        const int cot_lo = r % p.CL; r /= p.CL;
+        tc.tg = r % p.ntg; r /= p.ntg;
+        const int nhi = p.ncot / p.CL;
+        const int cot_hi = r % nhi; r /= nhi;
+        tc.sp = r;
+        tc.cot = cot_hi * p.CL + cot_lo;
+    } else {
+        tc.cit = r % p.ncit; r /= p.ncit;
+        tc.cot = r % p.ncot; r /= p.ncot;
+        tc.tg = r % p.ntg; r /= p.ntg;
+        tc.sp = r;
+    }
+    return tc;
+}
+
+// Sum the four wavefronts' partial tiles through LDS (wave g finishes rows [4g,4g+4) of every
+// 32x32 block), then write this workgroup's tile to the scratch [S][K][Cout][Cin].
+template <int KT>
+__device__ __forceinline__ void reduce_and_store(const WgradParams &p, unsigned char *smem, f32x16 (&acc)[2][KT],
+                                                 int lane, int wave, int sp, int k0, int kt, int co0, int ci0)
+{
+    constexpr int kTiles = 2 * KT;
+    __syncthreads();
+    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+#pragma unroll
+    for (int g = 0; g < kWaves; ++g) {
+        if (g != wave) {
+            const int slot = wave < g ? wave : wave - 1;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk) {
+                    f32x4 val = {acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
+                                 acc[mi][kk][4 * g + 3]};
+                    red[((g * 3 + slot) * kTiles + mi * KT + kk) * 64 + lane] = val;
+                }
+        }
+    }
+    __syncthreads();
+    f32x4 own[kTiles];
+#pragma unroll
+    for (int g = 0; g < kWaves; ++g) {
+        if (g == wave) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int kk = 0; kk < KT; ++kk)
+                    own[mi * KT + kk] = f32x4{acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
+                                              acc[mi][kk][4 * g + 3]};
+        }
+    }
+#pragma unroll
+    for (int slot = 0; slot < 3; ++slot)
+#pragma unroll
+        for (int tl = 0; tl < kTiles; ++tl) own[tl] += red[((wave * 3 + slot) * kTiles + tl) * 64 + lane];
+
+    const int ci = ci0 + (lane & 31);
+    if (ci < p.Cin) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int kk = 0; kk < KT; ++kk) {
+                if (kk >= kt) continue;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int co = co0 + mi * 32 + 8 * wave + 4 * (lane >> 5) + jj;
+                    if (co < p.Cout)
+                        p.part[(((size_t)sp * p.K + k0 + kk) * p.Cout + co) * p.Cin + ci] = own[mi * KT + kk][jj];
+                }
+            }
+    }
+}
+
 constexpr int kMaxDzItems = 12;  // staging items per lane and unit the kernel is built for:
 constexpr int kMaxXItems = 6;    // dz rows (one 16-byte load each) and x channel pairs (two loads)
 
@@ -87,29 +180,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    // ---- which (split, tile) this workgroup owns: work items are numbered so that the
-    // workgroups the hardware places on one XCD (blockIdx mod 8) form a contiguous range
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int v = xcd * p.per_xcd + j;
-    if (j >= p.per_xcd || v >= p.total) return;
-    int sp, tg, cot, cit;
-    if (p.CL > 0) {
-        // digits, slowest to fastest: sp, cot_hi, tg, cot_lo, cit
-        int r = v;
-        cit = r % p.ncit; r /= p.ncit;
-        const int cot_lo = r % p.CL; r /= p.CL;
-        tg = r % p.ntg; r /= p.ntg;
-        const int nhi = p.ncot / p.CL;
-        const int cot_hi = r % nhi; r /= nhi;
-        sp = r;
-        cot = cot_hi * p.CL + cot_lo;
-    } else {
-        int r = v;
-        cit = r % p.ncit; r /= p.ncit;
-        cot = r % p.ncot; r /= p.ncot;
-        tg = r % p.ntg; r /= p.ntg;
-        sp = r;
-    }
+    const TileCoords tcd = decode_tile(p);
+    if (!tcd.valid) return;
+    const int sp = tcd.sp, tg = tcd.tg, cot = tcd.cot, cit = tcd.cit;
     const int k0 = tg * p.KTg;
     const int kt = min(p.KTg, p.K - k0);
     const int co0 = cot * kTileCo, ci0 = cit * kTileCi;
@@ -274,58 +347,195 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
         }
     }
 
-    // ---- sum the four wavefronts' partial tiles through LDS (wave g finishes rows [4g,4g+4)
-    // of every 32x32 block), then write this workgroup's tile to the scratch.
-    constexpr int kTiles = 2 * KT;
-    __syncthreads();
-    f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+    reduce_and_store<KT>(p, smem, acc, lane, wave, sp, k0, kt, co0, ci0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stride-1, dilation-1 weight gradient (every block of the Jasper encoder proper).
+//
+// Same tiling and split over time as wgrad_kernel, with two changes that cut LDS traffic and
+// instruction count per MFMA:
+//   * dz is produced directly in MFMA A-fragment order by dz_pack_kernel
+//     ([b][co/32][t/16][lane][8]: lane l holds co = l%32, t = 8*(l/32)+j), so the A fragments of a
+//     whole unit are ten contiguous 1 KiB loads from L2 straight into registers, requested one
+//     unit ahead; only x goes through LDS;
+//   * a unit is 80 time steps = 5 MFMA steps, fully unrolled: the x window is staged transposed in
+//     64-byte rows (any 4 consecutive rows cover all 64 banks, so the transposing reads are
+//     conflict-free) and every fragment read is `base + immediate`.
+// All KT taps of the group are always multiplied (a short last group computes one unused tap).
+constexpr int kFastTCH = 80;
+constexpr int kFastSteps = kFastTCH / 16;
+constexpr int kFastXRowBytes = 64;
+constexpr int kFastXItems = 3;  // (80 + 5 + 7 -> 96 rows) * 16 channel pairs / 64 lanes
+
+__global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm, int nst, const bf16_t *__restrict__ dy,
+                                                      const bf16_t *__restrict__ y, const float *__restrict__ scale,
+                                                      int relu, u32x4 *__restrict__ dzf)
+{
+    const int lane = threadIdx.x & 63;
+    const int st = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int cm = blockIdx.y, b = blockIdx.z;
+    if (st >= nst) return;
+    const int co = cm * 32 + (lane & 31);
+    const int t = 16 * st + 8 * (lane >> 5);
+    u32x4 g = {0u, 0u, 0u, 0u};
+    if (co < Cout && t + 8 <= To) {
+        const size_t off = ((size_t)b * Cout + co) * To + t;
+        g = *reinterpret_cast<const u32x4 *>(dy + off);
+        if (relu) {
+            const u32x4 yv = *reinterpret_cast<const u32x4 *>(y + off);
 #pragma unroll
-    for (int g = 0; g < kWaves; ++g) {
-        if (g != wave) {
-            const int slot = wave < g ? wave : wave - 1;
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
+                g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
+            }
+        }
+        if (scale) {
+            const float sc = scale[co];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
+                g[j] = (uint32_t)f32_to_bf16(g0) | ((uint32_t)f32_to_bf16(g1) << 16);
+            }
+        }
+    }
+    dzf[(((size_t)b * ncm + cm) * nst + st) * 64 + lane] = g;
+}
+
+template <int KT>
+__global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const TileCoords tcd = decode_tile(p);
+    if (!tcd.valid) return;
+    const int sp = tcd.sp;
+    const int k0 = tcd.tg * p.KTg;
+    const int kt = min(p.KTg, p.K - k0);
+    const int co0 = tcd.cot * kTileCo, ci0 = tcd.cit * kTileCi;
+
+    f32x16 acc[2][KT];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int kk = 0; kk < KT; ++kk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][kk][r] = 0.f;
+
+    constexpr int kRows = kFastXItems * 32;                 // rows of one x buffer
+    constexpr int kBufBytes = kRows * kFastXRowBytes;
+    unsigned char *wbuf0 = smem + (size_t)wave * 2 * kBufBytes;
+    const int slot_id = sp * kWaves + wave;
+    const int slots = p.S * kWaves;
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)((size_t)p.B * p.Cin * p.T * 2), 0x00020000);
+
+    // x staging: lane = channel pair (lane & 15) x time group (lane >> 4) + 4*q, q < 3
+    const int x_pp = lane & 15, x_q = lane >> 4;
+    const uint32_t x_lane_off = (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q) * 2);
+    const bool ch_a = ci0 + 2 * x_pp < p.Cin, ch_b = ci0 + 2 * x_pp + 1 < p.Cin;
+    const uint32_t x_lds_off = (uint32_t)((x_q * 8) * kFastXRowBytes + x_pp * 4);
+    // window start of a unit relative to its first output step: -pad + k0, aligned down to 8
+    const int xs_rel = k0 - p.pad;
+    const int xs_rel_al = (xs_rel >> 3) * 8;
+    const int off0 = xs_rel - xs_rel_al;
+
+    u32x4 xra[kFastXItems], xrb[kFastXItems];
+    auto x_load = [&](int b, int tbase) {
+        const int xs_al = tbase + xs_rel_al;
+        const uint32_t unit = (uint32_t)((size_t)b * p.Cin * p.T * 2) + (uint32_t)(xs_al * 2);
+#pragma unroll
+        for (int q = 0; q < kFastXItems; ++q) {
+            const int t = xs_al + 8 * (x_q + 4 * q);
+            const bool t_ok = t >= 0 && t + 8 <= p.T;
+            const uint32_t off = x_lane_off + unit + (uint32_t)(64 * q);
+            xra[q] = buf_load16(rs_x, (t_ok && ch_a) ? off : kOutOfRange, 0);
+            xrb[q] = buf_load16(rs_x, (t_ok && ch_b) ? off + (uint32_t)(p.T * 2) : kOutOfRange, 0);
+        }
+    };
+    auto x_write = [&](unsigned char *buf) {
+#pragma unroll
+        for (int q = 0; q < kFastXItems; ++q) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kFastXRowBytes);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dst[(2 * e) * (kFastXRowBytes / 4)] = (xra[q][e] & 0xffffu) | (xrb[q][e] << 16);
+                dst[(2 * e + 1) * (kFastXRowBytes / 4)] = (xra[q][e] >> 16) | (xrb[q][e] & 0xffff0000u);
+            }
+        }
+    };
+    // A fragments of one unit: [mi][step], 1 KiB contiguous per wavefront and fragment.  The
+    // fragment of step st is reloaded for the next unit right after its last use, so one set
+    // of registers gives a prefetch distance of a whole unit.
+    const u32x4 *dzf_tile = p.dzf + ((size_t)(co0 >> 5) * p.nst) * 64 + lane;
+    const size_t dzf_b = (size_t)p.ncm * p.nst * 64, dzf_m = (size_t)p.nst * 64;
+    u32x4 afr[2][kFastSteps];
+
+    // transposing reads: this lane addresses 4 channels 16*((lane/16)&1) + 4*(lane&3) at time row
+    // 8*(lane/32) + (lane&15)/4 (+4 for the second read of a fragment)
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const int trow = 8 * (g4 >> 1) + (i16 >> 2) + off0;
+    const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);
+    const unsigned char *xb0 = wbuf0 + trow * kFastXRowBytes + tcol * 2;
+
+    int u = slot_id;
+    if (u < p.units) {
+        int b = u / p.nchunk, chunk = u - b * p.nchunk;
+        {
+            const u32x4 *src = dzf_tile + (size_t)b * dzf_b + (size_t)chunk * (kFastSteps * 64);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int st = 0; st < kFastSteps; ++st) afr[mi][st] = src[mi * dzf_m + st * 64];
+        }
+        x_load(b, chunk * kFastTCH);
+        x_write(wbuf0);
+        int parity = 0;
+        for (; u < p.units; u += slots, parity ^= 1) {
+            // the next unit (or, at the end, this one again: harmless) is requested during this one
+            const int un = (u + slots < p.units) ? u + slots : u;
+            const int bn = un / p.nchunk, cn = un - bn * p.nchunk;
+            const u32x4 *asrc = dzf_tile + (size_t)bn * dzf_b + (size_t)cn * (kFastSteps * 64);
+            x_load(bn, cn * kFastTCH);
+            wave_lds_fence();
+            const unsigned char *xb = xb0 + parity * kBufBytes;
+            auto read_b = [&](int st, bf16x8(&bfr)[KT]) {
 #pragma unroll
                 for (int kk = 0; kk < KT; ++kk) {
-                    f32x4 val = {acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
-                                 acc[mi][kk][4 * g + 3]};
-                    red[((g * 3 + slot) * kTiles + mi * KT + kk) * 64 + lane] = val;
+                    const unsigned char *xa = xb + (st * 16 + kk) * kFastXRowBytes;
+                    union {
+                        s16x4 h[2];
+                        bf16x8 v;
+                    } cvt;
+                    cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa));
+                    cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa + 4 * kFastXRowBytes));
+                    bfr[kk] = cvt.v;
                 }
-        }
-    }
-    __syncthreads();
-    f32x4 own[kTiles];
+            };
+            bf16x8 bq[2][KT];
+            read_b(0, bq[0]);
 #pragma unroll
-    for (int g = 0; g < kWaves; ++g) {
-        if (g == wave) {
+            for (int st = 0; st < kFastSteps; ++st) {
+                if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+                for (int mi = 0; mi < 2; ++mi) {
+                    union {
+                        u32x4 u;
+                        bf16x8 v;
+                    } af;
+                    af.u = afr[mi][st];
 #pragma unroll
-                for (int kk = 0; kk < KT; ++kk)
-                    own[mi * KT + kk] = f32x4{acc[mi][kk][4 * g], acc[mi][kk][4 * g + 1], acc[mi][kk][4 * g + 2],
-                                              acc[mi][kk][4 * g + 3]};
-        }
-    }
-#pragma unroll
-    for (int slot = 0; slot < 3; ++slot)
-#pragma unroll
-        for (int tl = 0; tl < kTiles; ++tl) own[tl] += red[((wave * 3 + slot) * kTiles + tl) * 64 + lane];
-
-    const int ci = ci0 + (lane & 31);
-    if (ci < p.Cin) {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int kk = 0; kk < KT; ++kk) {
-                if (kk >= kt) continue;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const int co = co0 + mi * 32 + 8 * wave + 4 * (lane >> 5) + jj;
-                    if (co < p.Cout)
-                        p.part[(((size_t)sp * p.K + k0 + kk) * p.Cout + co) * p.Cin + ci] = own[mi * KT + kk][jj];
+                    for (int kk = 0; kk < KT; ++kk)
+                        acc[mi][kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bq[st & 1][kk], acc[mi][kk], 0, 0, 0);
                 }
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) afr[mi][st] = asrc[mi * dzf_m + st * 64];
             }
+            x_write(wbuf0 + (parity ^ 1) * kBufBytes);
+        }
     }
+    reduce_and_store<KT>(p, smem, acc, lane, wave, sp, k0, kt, co0, ci0);
 }
 
 // dw[co][ci][k] = (accumulate ? dw : 0) + sum_s part[s][k][co][ci]; one block per (co, 64 ci).
@@ -411,8 +621,63 @@ WPlan make_wplan(const Geom &g)
     return w;
 }
 
+// The stride-1, dilation-1 kernel applies when rows are 16-byte aligned; its split count.
+bool fast_ok(const Geom &g) { return g.stride == 1 && g.dil == 1 && g.T % 8 == 0 && g.To % 8 == 0; }
+struct FastPlan {
+    int KTg, ntg, S, nchunk, ncm, nst;
+    size_t lds;
+};
+FastPlan make_fast_plan(const Geom &g)
+{
+    FastPlan f = {};
+    const int ntg = (g.K + kMaxKT - 1) / kMaxKT;
+    f.KTg = (g.K + ntg - 1) / ntg;
+    f.ntg = (g.K + f.KTg - 1) / f.KTg;
+    f.nchunk = (g.To + kFastTCH - 1) / kFastTCH;
+    const int ncot = (g.Cout + kTileCo - 1) / kTileCo, ncit = (g.Cin + kTileCi - 1) / kTileCi;
+    f.ncm = ncot * 2;
+    f.nst = f.nchunk * kFastSteps;
+    const long ntiles = (long)ncot * ncit * f.ntg, units = (long)g.B * f.nchunk;
+    long S = (512 + ntiles - 1) / ntiles;
+    if (S > 8) S = 8;
+    if (S > units / kWaves) S = units / kWaves;
+    if (S < 1) S = 1;
+    f.S = (int)S;
+    const size_t stage = (size_t)kWaves * 2 * kFastXItems * 32 * kFastXRowBytes;
+    const size_t red = (size_t)kWaves * 3 * (2 * f.KTg) * 64 * sizeof(f32x4);
+    f.lds = stage > red ? stage : red;
+    return f;
+}
+size_t dzf_bytes(const Geom &g, const FastPlan &f) { return align_up((size_t)g.B * f.ncm * f.nst * 1024, 256); }
+
 size_t part_bytes(const Geom &g, int S) { return align_up((size_t)S * g.K * g.Cout * g.Cin * sizeof(float), 256); }
 size_t dz_buf_bytes(const Geom &g) { return align_up((size_t)g.B * g.Cout * g.To * sizeof(bf16_t), 256); }
+
+template <int KT>
+hipError_t launch_fast_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
+{
+    auto kern = wgrad_fast_kernel<KT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+void number_work_items(WgradParams &p)
+{
+    p.total = p.ncot * p.ncit * p.ntg * p.S;
+    p.per_xcd = (p.total + 7) / 8;
+    p.CL = 0;
+    if (p.total % 8 == 0) {
+        const int denom = p.ntg * p.ncit;
+        if (p.per_xcd % denom == 0) {
+            const int cl = p.per_xcd / denom;
+            if (cl >= 1 && p.ncot % cl == 0) p.CL = cl;
+        }
+    }
+}
 
 template <int KT>
 hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
@@ -428,10 +693,14 @@ hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 
 }  // namespace
 
-bool mfma_wgrad_supported(const Geom &g) { return make_wplan(g).ok; }
+bool mfma_wgrad_supported(const Geom &g) { return fast_ok(g) || make_wplan(g).ok; }
 
 size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
 {
+    if (fast_ok(g)) {
+        const FastPlan f = make_fast_plan(g);
+        return part_bytes(g, f.S) + dzf_bytes(g, f);
+    }
     const WPlan w = make_wplan(g);
     if (!w.ok) return 0;
     return part_bytes(g, w.S) + (need_dz ? dz_buf_bytes(g) : 0);
@@ -440,6 +709,39 @@ size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
 hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y, const float *scale,
                              float *dw, bool relu, bool accumulate, void *ws, hipStream_t s)
 {
+    if (fast_ok(g)) {
+        const FastPlan f = make_fast_plan(g);
+        float *part = (float *)ws;
+        u32x4 *dzf = (u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
+        hipLaunchKernelGGL(dz_pack_kernel, dim3((f.nst + 3) / 4, f.ncm, g.B), dim3(256), 0, s, g.Cout, g.To, f.ncm,
+                           f.nst, (const bf16_t *)dy, (const bf16_t *)y, scale, relu ? 1 : 0, dzf);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        WgradParams p = {};
+        p.B = g.B; p.Cin = g.Cin; p.Cout = g.Cout; p.T = g.T; p.To = g.To; p.K = g.K;
+        p.stride = 1; p.dil = 1; p.pad = g.pad;
+        p.ncot = (g.Cout + kTileCo - 1) / kTileCo;
+        p.ncit = (g.Cin + kTileCi - 1) / kTileCi;
+        p.ntg = f.ntg; p.KTg = f.KTg; p.S = f.S;
+        p.TCH = kFastTCH; p.nchunk = f.nchunk; p.units = g.B * f.nchunk;
+        p.ncm = f.ncm; p.nst = f.nst;
+        number_work_items(p);
+        p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
+        const int grid = p.per_xcd * 8;
+        switch (f.KTg) {
+        case 1: e = launch_fast_kt<1>(p, f.lds, grid, s); break;
+        case 2: e = launch_fast_kt<2>(p, f.lds, grid, s); break;
+        case 3: e = launch_fast_kt<3>(p, f.lds, grid, s); break;
+        case 4: e = launch_fast_kt<4>(p, f.lds, grid, s); break;
+        case 5: e = launch_fast_kt<5>(p, f.lds, grid, s); break;
+        default: e = launch_fast_kt<6>(p, f.lds, grid, s); break;
+        }
+        if (e != hipSuccess) return e;
+        dim3 rgrid((g.Cin + 63) / 64, g.Cout);
+        hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, f.S, g.K,
+                           g.Cout, g.Cin, accumulate ? 1 : 0);
+        return hipGetLastError();
+    }
     const WPlan w = make_wplan(g);
     if (!w.ok) return hipErrorInvalidValue;
     float *part = (float *)ws;
@@ -461,16 +763,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
     p.NRX = w.NRX;
     p.n_dz = w.n_dz; p.n_x = w.n_x; p.ips = w.ips;
     p.dz_row_bytes = w.dz_row_bytes; p.dz_bytes = w.dz_bytes; p.x_bytes = w.x_bytes; p.buf_bytes = w.buf_bytes;
-    p.total = p.ncot * p.ncit * p.ntg * p.S;
-    p.per_xcd = (p.total + 7) / 8;
-    p.CL = 0;
-    if (p.total % 8 == 0) {
-        const int denom = p.ntg * p.ncit;
-        if (p.per_xcd % denom == 0) {
-            const int cl = p.per_xcd / denom;
-            if (cl >= 1 && p.ncot % cl == 0) p.CL = cl;
-        }
-    }
+    number_work_items(p);
     p.x = (const bf16_t *)x; p.dz = (const bf16_t *)dz; p.part = part;
     const int grid = p.per_xcd * 8;
     hipError_t e;
