@@ -45,7 +45,6 @@ constexpr int kRowBytes = 80;    // LDS row: 32 channels * 2 B + 16 B pad (bank-
 constexpr int kRowDwords = kRowBytes / 4;
 constexpr int kDumpRows = 8;     // rows at the end of a staging buffer that absorb idle staging writes
 constexpr int kMaxLds = 160 * 1024;
-constexpr int kPrologueBatch = 6;
 
 struct ConvGemmParams {
     int B, M, R, Tin, Tout, K, Kp, dil, padL;  // Kp: K rounded up to even (packed weights)
@@ -56,6 +55,7 @@ struct ConvGemmParams {
     int relu;
     const bf16_t *in;       // [B][R][Tin]
     const bf16x8 *wp;       // packed weights
+    size_t wp_zero;         // offset (in fragments of 16 bytes) of one tap pair of zero weights
     const float *scale;     // epilogue (may be NULL)
     const float *shift;     // epilogue (may be NULL)
     const bf16_t *res;      // epilogue (may be NULL)
@@ -131,42 +131,77 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             dst[(2 * j + 1) * kRowDwords] = (xa[j] >> 16) | (xb[j] & 0xffff0000u);
         }
     };
+    constexpr int kSlots = 6;      // staging items of the next chunk held in registers
+    u32x4 sxa[kSlots], sxb[kSlots];
     // a whole chunk, nothing to overlap with (first tile, or every tile without cross-tile staging)
     auto stage_chunk_now = [&](int b, int c, int ws_al, unsigned char *buf) {
-        for (int it0 = 0; it0 < nitems; it0 += kPrologueBatch) {
-            u32x4 xa[kPrologueBatch], xb[kPrologueBatch];
+        for (int it0 = 0; it0 < nitems; it0 += kSlots) {
 #pragma unroll
-            for (int q = 0; q < kPrologueBatch; ++q) stage_load(b, c, ws_al, it0 + q, it0 + q < nitems, xa[q], xb[q]);
+            for (int q = 0; q < kSlots; ++q) stage_load(b, c, ws_al, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
 #pragma unroll
-            for (int q = 0; q < kPrologueBatch; ++q) stage_write(buf, it0 + q, it0 + q < nitems, xa[q], xb[q]);
+            for (int q = 0; q < kSlots; ++q) stage_write(buf, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
         }
     };
 
-    bf16x8 af[8];  // weight fragments of the current tap pair: [tap 2][ks 2][mi 2]
-    auto fetch_all = [&](const bf16x8 *src) {
-#pragma unroll
-        for (int f = 0; f < 8; ++f) af[f] = src[f * 64];
+    // ---- weight fragment stream.  Tap pairs are multiplied alternately from two register sets
+    // (afA, afB: [tap 2][ks 2][mi 2] fragments each); a set is reloaded right after its last use
+    // with the pair that comes two pairs later in this wavefront's stream, which runs across
+    // chunks and tiles, so the loads have two pairs of MFMA work (about 2.5 us) to arrive.  A tile
+    // with an odd number of pairs gets one pair of zero weights, so that tiles start on afA.
+    bf16x8 afA[8], afB[8];
+    const int total_pairs = nmy * P;
+    const int odd_total = total_pairs & 1;
+    const bf16x8 *wzero = p.wp + p.wp_zero + lane;
+    auto w_base = [&](int tile) { return p.wp + ((size_t)(tile % p.nmt) * p.nch + wave) * chunk_stride + lane; };
+    int w_tile = blockIdx.x, w_ci = 0, w_pr = 0;
+    bool w_live = w_tile < p.num_tiles && nmy > 0, w_dummy = false;
+    const bf16x8 *w_chunk = w_base(w_live ? w_tile : 0);
+    auto w_next = [&]() -> const bf16x8 * {  // fragments of the cursor pair; moves the cursor on
+        const bf16x8 *ptr = (!w_live || w_dummy) ? wzero : w_chunk + (size_t)w_pr * 512;
+        if (w_live) {
+            bool tile_done = false;
+            if (w_dummy) {
+                w_dummy = false;
+                tile_done = true;
+            } else if (++w_pr == P) {
+                w_pr = 0;
+                w_chunk += kWaves * chunk_stride;
+                if (++w_ci == nmy) {
+                    if (odd_total) w_dummy = true;
+                    else tile_done = true;
+                }
+            }
+            if (tile_done) {
+                w_tile += gridDim.x;
+                w_ci = 0;
+                w_live = w_tile < p.num_tiles;
+                w_chunk = w_base(w_live ? w_tile : 0);
+            }
+        }
+        return ptr;
     };
+    {
+        const bf16x8 *s0 = w_next();
+#pragma unroll
+        for (int f = 0; f < 8; ++f) afA[f] = s0[f * 64];
+        const bf16x8 *s1 = w_next();
+#pragma unroll
+        for (int f = 0; f < 8; ++f) afB[f] = s1[f * 64];
+    }
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     const int first_tile = blockIdx.x;
     if (first_tile < p.num_tiles && nmy > 0 && p.overlap) {
         const TileCoords tc = tile_coords(first_tile);
         stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(0));
-        fetch_all(p.wp + ((size_t)tc.mt * p.nch + wave) * chunk_stride + lane);
     }
 
     for (int tile = first_tile; tile < p.num_tiles; tile += gridDim.x) {
         const TileCoords tc = tile_coords(tile);
         const bool next_ok = p.overlap && tile + (int)gridDim.x < p.num_tiles;
         const TileCoords tn = tile_coords(next_ok ? tile + (int)gridDim.x : tile);
-        const bf16x8 *wtile = p.wp + ((size_t)tc.mt * p.nch + wave) * chunk_stride + lane;
-        const bf16x8 *wtile_next = p.wp + ((size_t)tn.mt * p.nch + wave) * chunk_stride + lane;
 
-        if (!p.overlap && nmy > 0) {
-            stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(cc));
-            fetch_all(wtile);
-        }
+        if (!p.overlap && nmy > 0) stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(cc));
 
         f32x16 acc[2][NT];
 #pragma unroll
@@ -181,13 +216,12 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             // (the packed weights pad an odd K with one zero tap).  All MFMAs sit in this loop.
             const int lane_off = ((lane & 31) * STRIDE + tc.off0) * kRowBytes + (lane >> 5) * 16;
             int ci_ord = 0, pr = 0;
-            // where the staging items of this chunk's pairs go: the next chunk of this tile, or the
-            // first chunk of the next tile, or nowhere
+            // where the staging items of this chunk go: the next chunk of this tile, or the first
+            // chunk of the next tile, or nowhere
             bool has_t = nmy > 1 || next_ok;
             int t_b = nmy > 1 ? tc.b : tn.b, t_ws = nmy > 1 ? tc.ws_al : tn.ws_al, t_c = nmy > 1 ? wave + kWaves : wave;
             const unsigned char *bbase = buf_ptr(cc) + lane_off;
             unsigned char *nxt = buf_ptr(cc + 1);
-            const bf16x8 *wcur = wtile;  // weights of the current chunk
             bf16x8 b0[NT], b1[NT];
             auto read_b = [&](bf16x8(&dst)[NT], int k, int ks) {
                 const unsigned char *brow = bbase + (size_t)k * tap_bytes + ks * 32;
@@ -195,49 +229,53 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 for (int ni = 0; ni < NT; ++ni)
                     dst[ni] = *reinterpret_cast<const bf16x8 *>(brow + ni * 32 * STRIDE * kRowBytes);
             };
-            auto mma = [&](int f0, const bf16x8(&bf)[NT]) {
+            auto mma = [&](const bf16x8 &a0, const bf16x8 &a1, const bf16x8(&bf)[NT]) {
 #pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
+                for (int ni = 0; ni < NT; ++ni) acc[0][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf[ni], acc[0][ni], 0, 0, 0);
 #pragma unroll
-                    for (int ni = 0; ni < NT; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[f0 + mi], bf[ni], acc[mi][ni], 0, 0, 0);
+                for (int ni = 0; ni < NT; ++ni) acc[1][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bf[ni], acc[1][ni], 0, 0, 0);
             };
-            wave_lds_fence();
-            read_b(b0, 0, 0);
-            const int total_pairs = nmy * P;
-            for (int g = 0; g < total_pairs; ++g) {
-                // weights of the next pair: next pair of this chunk, first pair of the next chunk, first
-                // pair of the next tile, or (at the very end) this pair again
-                const bf16x8 *wn;
-                if (pr + 1 < P) wn = wcur + (size_t)(pr + 1) * 512;
-                else if (ci_ord + 1 < nmy) wn = wcur + kWaves * chunk_stride;
-                else if (next_ok) wn = wtile_next;
-                else wn = wcur + (size_t)pr * 512;
-                const bool active = has_t && pr < nitems;
-                u32x4 xa, xb;
-                stage_load(t_b, t_c, t_ws, pr, active, xa, xb);
+            // one tap pair from the register set `af`; `real` is false only for the zero pad pair
+            auto do_pair = [&](bf16x8(&af)[8], bool real) {
+                // the whole next chunk is requested at the first pair of this one (static register
+                // slots) and written to LDS in groups of two items behind the last pairs, so the
+                // loads have most of a chunk (several microseconds) to arrive
+                if (pr == 0 && has_t) {
+#pragma unroll
+                    for (int it = 0; it < kSlots; ++it)
+                        if (it < nitems) stage_load(t_b, t_c, t_ws, it, true, sxa[it], sxb[it]);
+                }
                 const int k = 2 * pr;
                 read_b(b1, k, 1);
-                mma(0, b0);
+                mma(af[0], af[1], b0);
+                const bf16x8 *wn = w_next();
                 af[0] = wn[0];
                 af[1] = wn[64];
                 read_b(b0, k + 1, 0);
-                mma(2, b1);
+                mma(af[2], af[3], b1);
                 af[2] = wn[128];
                 af[3] = wn[192];
                 read_b(b1, k + 1, 1);
-                mma(4, b0);
+                mma(af[4], af[5], b0);
                 af[4] = wn[256];
                 af[5] = wn[320];
                 read_b(b0, min(k + 2, p.Kp - 1), 0);
-                mma(6, b1);
+                mma(af[6], af[7], b1);
                 af[6] = wn[384];
                 af[7] = wn[448];
-                stage_write(nxt, pr, active, xa, xb);
-                ++pr;
-                if (pr == P) {  // end of a chunk
+                if (has_t) {
+#pragma unroll
+                    for (int gq = 0; gq < kSlots / 2; ++gq) {
+                        if (pr == max(0, P - kSlots / 2 + gq)) {
+#pragma unroll
+                            for (int e = 0; e < 2; ++e)
+                                if (2 * gq + e < nitems) stage_write(nxt, 2 * gq + e, true, sxa[2 * gq + e], sxb[2 * gq + e]);
+                        }
+                    }
+                }
+                if (real && ++pr == P) {  // end of a chunk
                     if (has_t) {
-                        for (int it = P; it < nitems; ++it) {  // more items than tap pairs (short kernels)
+                        for (int it = kSlots; it < nitems; ++it) {  // windows longer than the register slots
                             u32x4 ya, yb;
                             stage_load(t_b, t_c, t_ws, it, true, ya, yb);
                             stage_write(nxt, it, true, ya, yb);
@@ -246,8 +284,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                     ++ci_ord;
                     ++cc;
                     pr = 0;
+                    has_t = false;
                     if (ci_ord < nmy) {
-                        wcur += kWaves * chunk_stride;
                         const bool more = ci_ord + 1 < nmy;
                         has_t = more || next_ok;
                         t_b = more ? tc.b : tn.b;
@@ -259,6 +297,12 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                         read_b(b0, 0, 0);
                     }
                 }
+            };
+            wave_lds_fence();
+            read_b(b0, 0, 0);
+            for (int g = 0; g < total_pairs; g += 2) {
+                do_pair(afA, true);
+                do_pair(afB, g + 1 < total_pairs);
             }
         }
 
@@ -269,28 +313,21 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         // first chunk has been staged (buffer parity cc & 1), the other parity.
         const int tcol = lane & 31;
         const int m_base = tc.mt * kTileM + 8 * wave + 4 * (lane >> 5);
-        uint32_t rv[2][4][NT];
-        if (p.res) {
+        // The affine results go through a wave-private LDS tile [16 rows][TN] (float32) so that each
+        // lane finishes 8 consecutive time steps with one 16-byte residual load and one 16-byte
+        // store (rows of out and res are 16-byte aligned: checked by the host).
+        constexpr int kOutItems = NT;  // 16 rows * (TN/8) groups / 64 lanes
+        u32x4 rvec[kOutItems];
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int m = m_base + mi * 32 + j;
-                    const size_t orow = ((size_t)tc.b * p.M + m) * p.Tout;
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) {
-                        const int t = tc.t0 + ni * 32 + tcol;
-                        const bool ok = m < p.M && t < p.Tout;
-                        rv[mi][j][ni] = p.res[ok ? orow + t : (size_t)0];
-                    }
-                }
-        } else {
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) rv[mi][j][ni] = 0u;
+        for (int q = 0; q < kOutItems; ++q) {
+            const int idx = lane + 64 * q;
+            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+            const int m = tc.mt * kTileM + (r >> 3) * 32 + 8 * wave + (r & 7);
+            const int t = tc.t0 + c8 * 8;
+            const bool ok = m < p.M && t < p.Tout;
+            const size_t o = ((size_t)tc.b * p.M + m) * p.Tout + t;
+            rvec[q] = u32x4{0u, 0u, 0u, 0u};
+            if (p.res) rvec[q] = *reinterpret_cast<const u32x4 *>(p.res + (ok ? o : (size_t)0));
         }
         const bool live0 = next_ok && (cc & 1) == 0;  // parity-0 buffers hold the next tile's first chunk
         f32x4 *red = reinterpret_cast<f32x4 *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0));
@@ -326,24 +363,46 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((wave * 3 + slot) * NT + ni) * 64 + lane];
             __syncthreads();  // scratch is reused by the next round / overwritten by the next tile's staging
         }
+        // this wave's slice of the dead staging buffers: [16 rows][TN] float32
+        float *tp = reinterpret_cast<float *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0) +
+                                              (size_t)wave * p.buf_bytes);
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int m = m_base + mi * 32 + j;
                 const int mc = m < p.M ? m : 0;
                 const float sc = p.scale ? p.scale[mc] : 1.f;
                 const float sh = p.shift ? p.shift[mc] : 0.f;
-                const size_t orow = ((size_t)tc.b * p.M + m) * p.Tout;
+                const int r = mi * 8 + 4 * (lane >> 5) + j;
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni) {
-                    const int t = tc.t0 + ni * 32 + tcol;
-                    float v = own[mi][ni][j] * sc + sh + __uint_as_float(rv[mi][j][ni] << 16);
-                    if (p.relu) v = v > 0.f ? v : 0.f;
-                    if (m < p.M && t < p.Tout) p.out[orow + t] = f32_to_bf16(v);
-                }
+                for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = own[mi][ni][j] * sc + sh;
             }
+        wave_lds_fence();
+#pragma unroll
+        for (int q = 0; q < kOutItems; ++q) {
+            const int idx = lane + 64 * q;
+            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+            const int m = tc.mt * kTileM + (r >> 3) * 32 + 8 * wave + (r & 7);
+            const int t = tc.t0 + c8 * 8;
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
+            u32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
+                float v0 = a0 + __uint_as_float(rvec[q][e] << 16);
+                float v1 = a1 + __uint_as_float(rvec[q][e] & 0xffff0000u);
+                if (p.relu) {
+                    v0 = v0 > 0.f ? v0 : 0.f;
+                    v1 = v1 > 0.f ? v1 : 0.f;
+                }
+                o[e] = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+            }
+            if (m < p.M && t < p.Tout)
+                *reinterpret_cast<u32x4 *>(p.out + ((size_t)tc.b * p.M + m) * p.Tout + t) = o;
         }
+        wave_lds_fence();
     }
 }
 
@@ -357,10 +416,13 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 constexpr int kPackRows = 16;
 template <bool FLIP>
 __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
-                                                      int R, int K, int nch, int ld /* row length of w */)
+                                                      int R, int K, int nch, int ld /* row length of w */,
+                                                      size_t zero_off)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as (m*32 + r)*K + k
+    if (blockIdx.x == 0)  // one tap pair of zero weights after the packed tensor
+        for (int i = threadIdx.x; i < 512; i += 256) wp[zero_off + i] = u32x4{0u, 0u, 0u, 0u};
     const int q = blockIdx.x & 3;                      // which 16 channels of the 64
     const int c = (blockIdx.x >> 2) % nch, mt = (blockIdx.x >> 2) / nch;
     const int m0 = mt * kTileM + q * kPackRows, r0 = c * kChunk;
@@ -413,14 +475,14 @@ struct Plan {
     size_t lds;
 };
 
-// Tin: length of the rows that are staged; they must be 16-byte aligned (Tin % 8 == 0).
+// Tin, Tout: lengths of the rows that are staged / written; both must be 16-byte aligned (% 8 == 0).
 // R: reduction channels (cross-tile staging needs every wavefront to own the same number of chunks).
 Plan make_plan(int Tin, int Tout, int R, int K, int stride, int dil)
 {
     Plan pl = {};
     pl.stride = stride;
     if (stride != 1 && stride != 2) return pl;
-    if (Tin % 8 != 0) return pl;
+    if (Tin % 8 != 0 || Tout % 8 != 0) return pl;
     if ((size_t)kPackRows * kChunk * K * sizeof(bf16_t) > (size_t)kMaxLds) return pl;  // weight packing tile
     const int nch = (R + kChunk - 1) / kChunk;
     const int cands[2] = {5, 2};
@@ -436,7 +498,7 @@ Plan make_plan(int Tin, int Tout, int R, int K, int stride, int dil)
         // with cross-tile staging the scratch must fit in the buffers of one parity
         const bool overlap = (nch % kWaves == 0) && (kWaves * buf >= round_bytes);
         const size_t lds = stage > round_bytes ? stage : round_bytes;
-        if (lds <= (size_t)kMaxLds) {
+        if (lds <= (size_t)kMaxLds && buf >= (size_t)16 * nt * 32 * sizeof(float)) {  // buf also holds the output transpose tile
             pl.ok = true;
             pl.nt = nt;
             pl.nitems = (int)nitems;
@@ -453,7 +515,7 @@ size_t packed_bytes(int M, int R, int K)
 {
     const size_t nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
     const size_t Kp = (size_t)((K + 1) & ~1);
-    return align_up(nmt * nch * Kp * 256 * sizeof(u32x4), 256);
+    return align_up((nmt * nch * Kp * 256 + 512) * sizeof(u32x4), 256);  // + one tap pair of zeros
 }
 
 template <int NT, int STRIDE>
@@ -491,19 +553,20 @@ hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, bool flip, 
 {
     const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
     const size_t lds = prepack_lds(K);
+    const size_t zero_off = (size_t)nmt * nch * ((K + 1) & ~1) * 256;
     hipError_t e;
     if (flip) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prepack_kernel<true>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, M * K);
+                           M, R, K, nch, M * K, zero_off);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prepack_kernel<false>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, R * K);
+                           M, R, K, nch, R * K, zero_off);
     }
     return hipGetLastError();
 }
@@ -515,6 +578,7 @@ void fill_common(ConvGemmParams &p, const Plan &pl, int B, int M, int R, int Tin
     p.nch = (R + kChunk - 1) / kChunk;
     p.ntt = (Tout + pl.nt * 32 - 1) / (pl.nt * 32);
     p.num_tiles = p.nmt * p.ntt * B;
+    p.wp_zero = (size_t)p.nmt * p.nch * p.Kp * 256;
     p.nitems = pl.nitems;
     p.buf_bytes = pl.buf_bytes;
     p.overlap = pl.overlap;

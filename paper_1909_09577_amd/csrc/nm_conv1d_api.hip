@@ -176,7 +176,7 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
     if (overlap(y, ny, x, (size_t)g.B * g.Cin * g.T * e) || overlap(y, ny, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(y, ny, residual, ny))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags) && aligned16(x);
+    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags) && aligned16(x) && aligned16(y) && aligned16(residual);
     const size_t need = workspace_for(NM_OP_FWD, g, dtype, mfma, true);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
@@ -206,7 +206,8 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
     if (overlap(dx, ndx, dy, ndy) || overlap(dx, ndx, y, ndy) || overlap(dx, ndx, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(dx, ndx, dres, ndy) || overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && aligned16(dy) && (!relu || aligned16(y));
+    const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && aligned16(dy) && aligned16(dx) &&
+                      (!relu || aligned16(y));
     const bool dzneeded = needs_dz(flags, scale);
     const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
