@@ -29,6 +29,8 @@
 //     one XCD (blockIdx mod 8) keep reusing the same slice of the packed weights in that L2.
 #include "nm_common.h"
 
+#include <type_traits>
+
 namespace nm {
 namespace {
 
@@ -55,6 +57,7 @@ struct ConvGemmParams {
     int relu;
     const bf16_t *in;       // [B][R][Tin]
     const bf16x8 *wp;       // packed weights
+    size_t wp_bytes;        // size of the packed weights including the zero pair (< 2 GiB)
     size_t wp_zero;         // offset (in fragments of 16 bytes) of one tap pair of zero weights
     const float *scale;     // epilogue (may be NULL)
     const float *shift;     // epilogue (may be NULL)
@@ -71,7 +74,19 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-constexpr uint32_t kOutOfRange = 0xffffffffu;  // buffer offset beyond any tensor: the load returns zeros
+// Buffer offset beyond any tensor this engine accepts (the host limits them to 1 GiB): the load
+// returns zeros.  Small additions to it neither wrap nor come back into range.
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+// The lane number, recomputed where it is needed.  The staging code runs once per chunk inside a
+// loop whose registers are all taken; values derived from a long-lived lane id would be spilled
+// and their reload would wait for every load in flight.  Two ALU operations avoid that.
+__device__ __forceinline__ int fresh_lane()
+{
+    int l = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(l));
+    return l;
+}
 
 struct TileCoords {
     int mt, b, t0, ws_al, off0;
@@ -94,10 +109,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)((size_t)p.B * p.R * p.Tin * 2), 0x00020000);
 
     // staging item `it` of a lane: channel pair pp = lane & 15, time group q0 + 4*it (8 steps)
-    const int pp = lane & 15, q0 = lane >> 4;
-    const uint32_t x_lane_off = (uint32_t)(((2 * pp) * p.Tin + 8 * q0) * 2);
-    const uint32_t x_lds_off = (uint32_t)((q0 * 8) * kRowBytes + pp * 4);
-    const uint32_t dump_off = (uint32_t)(nitems * 32 * kRowBytes + pp * 4);
     auto buf_ptr = [&](int par) { return smem + ((size_t)(par & 1) * kWaves + wave) * p.buf_bytes; };
 
     auto tile_coords = [&](int tile) {
@@ -111,20 +122,38 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         tc.off0 = ws - tc.ws_al;
         return tc;
     };
-    // issue the two loads of item `it` of chunk c of batch item b (window start ws_al)
-    auto stage_load = [&](int b, int c, int ws_al, int it, bool active, u32x4 &xa, u32x4 &xb) {
-        const int t = ws_al + 8 * (q0 + 4 * it);
-        const bool t_ok = active && t >= 0 && t + 8 <= p.Tin;
-        const int ch = c * kChunk + 2 * pp;
-        const uint32_t off = x_lane_off + (uint32_t)(64 * it) + (uint32_t)(((size_t)b * p.R + c * kChunk) * p.Tin * 2) +
-                             (uint32_t)(ws_al * 2);
-        xa = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (t_ok && ch < p.R) ? off : kOutOfRange, 0, 0);
-        xb = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (t_ok && ch + 1 < p.R) ? off + (uint32_t)(p.Tin * 2) : kOutOfRange,
-                                                   0, 0);
+    // Staging loads of chunk c of batch item b, window start ws_al.  The scalar part of the address
+    // (batch item, chunk) travels as the scalar offset of the buffer load; lanes whose 8 time steps
+    // or whose channel lie outside the tensor get an offset beyond the buffer and read zeros.
+    struct StageAddr {
+        uint32_t soff, va, vb;  // scalar offset; lane offsets of the even / odd channel (or out of range)
+        int tq;                 // first time step of item 0 of this lane
+    };
+    auto stage_addr = [&](int b, int c, int ws_al) {
+        StageAddr a;
+        a.soff = (uint32_t)(((size_t)b * p.R + (size_t)c * kChunk) * p.Tin * 2);
+        const int rem = p.R - c * kChunk;  // channels left from this chunk on
+        const int l = fresh_lane();
+        const int pp = l & 15, q0 = l >> 4;
+        const uint32_t base = (uint32_t)(((2 * pp) * p.Tin + 8 * q0 + ws_al) * 2);
+        const int tq = ws_al + 8 * q0;
+        a.va = 2 * pp < rem ? base : kOutOfRange;
+        a.vb = 2 * pp + 1 < rem ? base + (uint32_t)(p.Tin * 2) : kOutOfRange;
+        a.tq = tq;
+        return a;
+    };
+    auto stage_load = [&](const StageAddr &a, int it, bool active, u32x4 &xa, u32x4 &xb) {
+        const bool t_ok = active && (unsigned)(a.tq + 32 * it) <= (unsigned)(p.Tin - 8);  // 0 <= t and t + 8 <= Tin
+        // a lane of a missing channel holds kOutOfRange: adding 64*it keeps it beyond the buffer
+        xa = __builtin_amdgcn_raw_buffer_load_b128(rs_in, t_ok ? a.va + (uint32_t)(64 * it) : kOutOfRange, a.soff, 0);
+        xb = __builtin_amdgcn_raw_buffer_load_b128(rs_in, t_ok ? a.vb + (uint32_t)(64 * it) : kOutOfRange, a.soff, 0);
     };
     // transposing write of an item: one dword (channel pair) per time step
     auto stage_write = [&](unsigned char *buf, int it, bool active, const u32x4 &xa, const u32x4 &xb) {
-        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (active ? x_lds_off + (uint32_t)(it * 32 * kRowBytes) : dump_off));
+        const int l = fresh_lane();
+        const int pp = l & 15, q0 = l >> 4;
+        const uint32_t row = active ? (uint32_t)(q0 * 8 + it * 32) : (uint32_t)(nitems * 32);  // idle writes go to the dump rows
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + row * kRowBytes + pp * 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             dst[(2 * j) * kRowDwords] = (xa[j] & 0xffffu) | (xb[j] << 16);
@@ -135,9 +164,10 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     u32x4 sxa[kSlots], sxb[kSlots];
     // a whole chunk, nothing to overlap with (first tile, or every tile without cross-tile staging)
     auto stage_chunk_now = [&](int b, int c, int ws_al, unsigned char *buf) {
+        const StageAddr sa = stage_addr(b, c, ws_al);
         for (int it0 = 0; it0 < nitems; it0 += kSlots) {
 #pragma unroll
-            for (int q = 0; q < kSlots; ++q) stage_load(b, c, ws_al, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
+            for (int q = 0; q < kSlots; ++q) stage_load(sa, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
 #pragma unroll
             for (int q = 0; q < kSlots; ++q) stage_write(buf, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
         }
@@ -146,48 +176,63 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     // ---- weight fragment stream.  Tap pairs are multiplied alternately from two register sets
     // (afA, afB: [tap 2][ks 2][mi 2] fragments each); a set is reloaded right after its last use
     // with the pair that comes two pairs later in this wavefront's stream, which runs across
-    // chunks and tiles, so the loads have two pairs of MFMA work (about 2.5 us) to arrive.  A tile
-    // with an odd number of pairs gets one pair of zero weights, so that tiles start on afA.
+    // chunks and tiles, so the loads have about two pairs of MFMA work to arrive.  A tile with an
+    // odd number of pairs gets one pair of zero weights, so that tiles start on afA.  The cursor
+    // is kept in scalar registers and moves without branches except at a tile end; the loads are
+    // buffer loads whose scalar offset is the cursor.
     bf16x8 afA[8], afB[8];
     const int total_pairs = nmy * P;
-    const int odd_total = total_pairs & 1;
-    const bf16x8 *wzero = p.wp + p.wp_zero + lane;
-    auto w_base = [&](int tile) { return p.wp + ((size_t)(tile % p.nmt) * p.nch + wave) * chunk_stride + lane; };
-    int w_tile = blockIdx.x, w_ci = 0, w_pr = 0;
-    bool w_live = w_tile < p.num_tiles && nmy > 0, w_dummy = false;
-    const bf16x8 *w_chunk = w_base(w_live ? w_tile : 0);
-    auto w_next = [&]() -> const bf16x8 * {  // fragments of the cursor pair; moves the cursor on
-        const bf16x8 *ptr = (!w_live || w_dummy) ? wzero : w_chunk + (size_t)w_pr * 512;
-        if (w_live) {
-            bool tile_done = false;
-            if (w_dummy) {
-                w_dummy = false;
-                tile_done = true;
-            } else if (++w_pr == P) {
-                w_pr = 0;
-                w_chunk += kWaves * chunk_stride;
-                if (++w_ci == nmy) {
-                    if (odd_total) w_dummy = true;
-                    else tile_done = true;
-                }
-            }
-            if (tile_done) {
-                w_tile += gridDim.x;
-                w_ci = 0;
-                w_live = w_tile < p.num_tiles;
-                w_chunk = w_base(w_live ? w_tile : 0);
-            }
+    const int slots = total_pairs + (total_pairs & 1);  // pairs per tile including the zero pair
+    constexpr uint32_t kPairBytes = 512 * 16;           // one tap pair of one chunk
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
+    const uint32_t zero_soff = (uint32_t)(p.wp_zero * 16);
+    const uint32_t chunk_jump = kPairBytes * (uint32_t)(1 + (kWaves - 1) * P);  // last pair of a chunk -> first of the next
+    const uint32_t w_lane = (uint32_t)lane * 16;
+    const int gstep = (int)(gridDim.x % (unsigned)p.nmt);
+    auto w_base = [&](int mt) { return (uint32_t)(mt * p.nch + wave) * (uint32_t)P * kPairBytes; };
+    int w_tile = blockIdx.x, w_mt = (int)(blockIdx.x % (unsigned)p.nmt), w_pr = 0, w_s = 0;
+    bool w_live = w_tile < p.num_tiles && nmy > 0;
+    uint32_t w_soff = w_base(w_mt);
+    auto w_next = [&]() -> uint32_t {  // offset of the cursor pair; moves the cursor on
+        const uint32_t off = (w_live && w_s < total_pairs) ? w_soff : zero_soff;
+        ++w_s;
+        ++w_pr;
+        const bool chunk_end = w_pr == P;
+        w_soff += chunk_end ? chunk_jump : kPairBytes;
+        w_pr = chunk_end ? 0 : w_pr;
+        if (__builtin_expect(w_s == slots, 0)) {  // tile end
+            w_s = 0;
+            w_pr = 0;
+            w_tile += gridDim.x;
+            w_mt += gstep;
+            w_mt -= w_mt >= p.nmt ? p.nmt : 0;
+            w_live = w_live && w_tile < p.num_tiles;
+            w_soff = w_base(w_mt);
         }
-        return ptr;
+        return off;
+    };
+    auto w_load = [&](uint32_t soff, int f) {
+        return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_lane + (uint32_t)f * 1024u, soff, 0));
     };
     {
-        const bf16x8 *s0 = w_next();
+        const uint32_t s0 = w_next();
 #pragma unroll
-        for (int f = 0; f < 8; ++f) afA[f] = s0[f * 64];
-        const bf16x8 *s1 = w_next();
+        for (int f = 0; f < 8; ++f) afA[f] = w_load(s0, f);
+        const uint32_t s1 = w_next();
 #pragma unroll
-        for (int f = 0; f < 8; ++f) afB[f] = s1[f * 64];
+        for (int f = 0; f < 8; ++f) afB[f] = w_load(s1, f);
     }
+
+    // epilogue operands as buffer descriptors; an absent one is empty and reads zeros
+    const int out_bytes = (int)((size_t)p.B * p.M * p.Tout * 2);
+    const bool has_scale = p.scale != nullptr;
+    const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, out_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_res =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.res, 0, p.res ? out_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_scale =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.scale, 0, p.scale ? p.M * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_shift =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.shift, 0, p.shift ? p.M * 4 : 0, 0x00020000);
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     const int first_tile = blockIdx.x;
@@ -214,7 +259,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         if (nmy > 0) {
             // ---- main loop over (chunk, tap pair): 4 k-steps of 16 channels = 8*NT MFMAs per pair
             // (the packed weights pad an odd K with one zero tap).  All MFMAs sit in this loop.
-            const int lane_off = ((lane & 31) * STRIDE + tc.off0) * kRowBytes + (lane >> 5) * 16;
+            const int ll = fresh_lane();
+            const int lane_off = ((ll & 31) * STRIDE + tc.off0) * kRowBytes + (ll >> 5) * 16;
             int ci_ord = 0, pr = 0;
             // where the staging items of this chunk go: the next chunk of this tile, or the first
             // chunk of the next tile, or nowhere
@@ -240,30 +286,31 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 // the whole next chunk is requested at the first pair of this one (static register
                 // slots) and written to LDS in groups of two items behind the last pairs, so the
                 // loads have most of a chunk (several microseconds) to arrive
-                if (pr == 0 && has_t) {
+                if (__builtin_expect(pr == 0 && has_t, 0)) {
+                    const StageAddr sa = stage_addr(t_b, t_c, t_ws);
 #pragma unroll
                     for (int it = 0; it < kSlots; ++it)
-                        if (it < nitems) stage_load(t_b, t_c, t_ws, it, true, sxa[it], sxb[it]);
+                        if (it < nitems) stage_load(sa, it, true, sxa[it], sxb[it]);
                 }
                 const int k = 2 * pr;
                 read_b(b1, k, 1);
                 mma(af[0], af[1], b0);
-                const bf16x8 *wn = w_next();
-                af[0] = wn[0];
-                af[1] = wn[64];
+                const uint32_t wn = w_next();
+                af[0] = w_load(wn, 0);
+                af[1] = w_load(wn, 1);
                 read_b(b0, k + 1, 0);
                 mma(af[2], af[3], b1);
-                af[2] = wn[128];
-                af[3] = wn[192];
+                af[2] = w_load(wn, 2);
+                af[3] = w_load(wn, 3);
                 read_b(b1, k + 1, 1);
                 mma(af[4], af[5], b0);
-                af[4] = wn[256];
-                af[5] = wn[320];
+                af[4] = w_load(wn, 4);
+                af[5] = w_load(wn, 5);
                 read_b(b0, min(k + 2, p.Kp - 1), 0);
                 mma(af[6], af[7], b1);
-                af[6] = wn[384];
-                af[7] = wn[448];
-                if (has_t) {
+                af[6] = w_load(wn, 6);
+                af[7] = w_load(wn, 7);
+                if (__builtin_expect(has_t && pr >= P - kSlots / 2, 0)) {
 #pragma unroll
                     for (int gq = 0; gq < kSlots / 2; ++gq) {
                         if (pr == max(0, P - kSlots / 2 + gq)) {
@@ -273,11 +320,11 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                         }
                     }
                 }
-                if (real && ++pr == P) {  // end of a chunk
+                if (__builtin_expect(real && ++pr == P, 0)) {  // end of a chunk
                     if (has_t) {
                         for (int it = kSlots; it < nitems; ++it) {  // windows longer than the register slots
                             u32x4 ya, yb;
-                            stage_load(t_b, t_c, t_ws, it, true, ya, yb);
+                            stage_load(stage_addr(t_b, t_c, t_ws), it, true, ya, yb);
                             stage_write(nxt, it, true, ya, yb);
                         }
                     }
@@ -306,101 +353,108 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             }
         }
 
-        // ---- epilogue.  Residual values are requested first so that their latency overlaps the
-        // cross-wave sum.  Wave g finishes accumulator rows [4g, 4g+4) of every 32x32 block: each
-        // wave hands the other three quarters over through LDS, one row of blocks (mi) per round.
-        // The scratch lies in the staging buffers that hold no live data: when the next tile's
-        // first chunk has been staged (buffer parity cc & 1), the other parity.
-        const int tcol = lane & 31;
-        const int m_base = tc.mt * kTileM + 8 * wave + 4 * (lane >> 5);
-        // The affine results go through a wave-private LDS tile [16 rows][TN] (float32) so that each
-        // lane finishes 8 consecutive time steps with one 16-byte residual load and one 16-byte
-        // store (rows of out and res are 16-byte aligned: checked by the host).
+        // ---- epilogue.  Wave g finishes accumulator rows [4g, 4g+4) of every 32x32 block: each wave
+        // hands the other three quarters over through LDS, one row of blocks (mi) per round; the
+        // scratch lies in the staging buffers that hold no live data (when the next tile's first
+        // chunk has been staged into parity cc & 1, the other parity).  The sums then go through a
+        // wave-private LDS tile [16 rows][TN] (float32) so that each lane finishes 8 consecutive
+        // time steps of one channel: one 16-byte residual load, one scale, one shift, one 16-byte
+        // store per item (rows of out and res are 16-byte aligned: checked by the host).  Those
+        // loads are requested before the sum; all of them are buffer accesses without branches
+        // (absent operands have empty descriptors and read zeros, masked lanes go out of range).
         constexpr int kOutItems = NT;  // 16 rows * (TN/8) groups / 64 lanes
+        const int el = fresh_lane();  // nothing lane-dependent is kept alive across the main loop for this
         u32x4 rvec[kOutItems];
+        float scv[kOutItems], shv[kOutItems];
+        uint32_t ooff[kOutItems];
 #pragma unroll
         for (int q = 0; q < kOutItems; ++q) {
-            const int idx = lane + 64 * q;
+            const int idx = el + 64 * q;
             const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
             const int m = tc.mt * kTileM + (r >> 3) * 32 + 8 * wave + (r & 7);
             const int t = tc.t0 + c8 * 8;
             const bool ok = m < p.M && t < p.Tout;
-            const size_t o = ((size_t)tc.b * p.M + m) * p.Tout + t;
-            rvec[q] = u32x4{0u, 0u, 0u, 0u};
-            if (p.res) rvec[q] = *reinterpret_cast<const u32x4 *>(p.res + (ok ? o : (size_t)0));
+            ooff[q] = ok ? (uint32_t)((((size_t)tc.b * p.M + m) * p.Tout + t) * 2) : kOutOfRange;
+            const uint32_t moff = ok ? (uint32_t)m * 4u : kOutOfRange;
+            rvec[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_res, ooff[q], 0, 0);
+            scv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_scale, moff, 0, 0));
+            shv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_shift, moff, 0, 0));
         }
         const bool live0 = next_ok && (cc & 1) == 0;  // parity-0 buffers hold the next tile's first chunk
         f32x4 *red = reinterpret_cast<f32x4 *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0));
-        f32x4 own[2][NT];
-        __syncthreads();  // every wavefront has left the main loop
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-            for (int g = 0; g < kWaves; ++g) {
-                if (g != wave) {
-                    const int slot = wave < g ? wave : wave - 1;
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) {
-                        f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
-                                   acc[mi][ni][4 * g + 3]};
-                        red[((g * 3 + slot) * NT + ni) * 64 + lane] = v;
-                    }
-                }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int g = 0; g < kWaves; ++g) {
-                if (g == wave) {
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni)
-                        own[mi][ni] = f32x4{acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
-                                            acc[mi][ni][4 * g + 3]};
-                }
-            }
-#pragma unroll
-            for (int slot = 0; slot < 3; ++slot)
-#pragma unroll
-                for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((wave * 3 + slot) * NT + ni) * 64 + lane];
-            __syncthreads();  // scratch is reused by the next round / overwritten by the next tile's staging
-        }
         // this wave's slice of the dead staging buffers: [16 rows][TN] float32
         float *tp = reinterpret_cast<float *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0) +
                                               (size_t)wave * p.buf_bytes);
+        __syncthreads();  // every wavefront has left the main loop
+        // One copy of the exchange per wave number, so that the accumulator quarters are named
+        // statically and nothing has to be merged between the copies.
+        auto exchange = [&](auto wave_const) {
+            constexpr int G = decltype(wave_const)::value;
+            f32x4 own[2][NT];
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int m = m_base + mi * 32 + j;
-                const int mc = m < p.M ? m : 0;
-                const float sc = p.scale ? p.scale[mc] : 1.f;
-                const float sh = p.shift ? p.shift[mc] : 0.f;
-                const int r = mi * 8 + 4 * (lane >> 5) + j;
+                for (int g = 0; g < kWaves; ++g) {
+                    if (g != G) {
+                        constexpr int slot_lo = G;  // position of this wave among the three senders of quarter g
+                        const int slot = G < g ? slot_lo : slot_lo - 1;
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = own[mi][ni][j] * sc + sh;
+                        for (int ni = 0; ni < NT; ++ni) {
+                            f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
+                                       acc[mi][ni][4 * g + 3]};
+                            red[((g * 3 + slot) * NT + ni) * 64 + el] = v;
+                        }
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni)
+                    own[mi][ni] = f32x4{acc[mi][ni][4 * G], acc[mi][ni][4 * G + 1], acc[mi][ni][4 * G + 2],
+                                        acc[mi][ni][4 * G + 3]};
+#pragma unroll
+                for (int slot = 0; slot < 3; ++slot) {
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((G * 3 + slot) * NT + ni) * 64 + el];
+                }
+                __syncthreads();  // scratch is reused by the next round / the transpose tile / the next tile's staging
             }
+            const int tcol = el & 31;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = mi * 8 + 4 * (el >> 5) + j;
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = own[mi][ni][j];
+                }
+        };
+        switch (wave) {
+        case 0: exchange(std::integral_constant<int, 0>{}); break;
+        case 1: exchange(std::integral_constant<int, 1>{}); break;
+        case 2: exchange(std::integral_constant<int, 2>{}); break;
+        default: exchange(std::integral_constant<int, 3>{}); break;
+        }
         wave_lds_fence();
 #pragma unroll
         for (int q = 0; q < kOutItems; ++q) {
-            const int idx = lane + 64 * q;
+            const int idx = el + 64 * q;
             const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
-            const int m = tc.mt * kTileM + (r >> 3) * 32 + 8 * wave + (r & 7);
-            const int t = tc.t0 + c8 * 8;
             const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
             const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
+            const float sc = has_scale ? scv[q] : 1.f;
             u32x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
-                float v0 = a0 + __uint_as_float(rvec[q][e] << 16);
-                float v1 = a1 + __uint_as_float(rvec[q][e] & 0xffff0000u);
+                float v0 = a0 * sc + shv[q] + __uint_as_float(rvec[q][e] << 16);
+                float v1 = a1 * sc + shv[q] + __uint_as_float(rvec[q][e] & 0xffff0000u);
                 if (p.relu) {
                     v0 = v0 > 0.f ? v0 : 0.f;
                     v1 = v1 > 0.f ? v1 : 0.f;
                 }
                 o[e] = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
             }
-            if (m < p.M && t < p.Tout)
-                *reinterpret_cast<u32x4 *>(p.out + ((size_t)tc.b * p.M + m) * p.Tout + t) = o;
+            __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ooff[q], 0, 0);
         }
         wave_lds_fence();
     }
@@ -518,6 +572,9 @@ size_t packed_bytes(int M, int R, int K)
     return align_up((nmt * nch * Kp * 256 + 512) * sizeof(u32x4), 256);  // + one tap pair of zeros
 }
 
+constexpr size_t kMaxPacked = (size_t)1 << 31;  // the kernel addresses packed weights with 32-bit offsets
+constexpr size_t kMaxInput = (size_t)1 << 30;   // and the activation tensors through buffer descriptors
+
 template <int NT, int STRIDE>
 hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 {
@@ -579,6 +636,7 @@ void fill_common(ConvGemmParams &p, const Plan &pl, int B, int M, int R, int Tin
     p.ntt = (Tout + pl.nt * 32 - 1) / (pl.nt * 32);
     p.num_tiles = p.nmt * p.ntt * B;
     p.wp_zero = (size_t)p.nmt * p.nch * p.Kp * 256;
+    p.wp_bytes = (p.wp_zero + 512) * sizeof(u32x4);
     p.nitems = pl.nitems;
     p.buf_bytes = pl.buf_bytes;
     p.overlap = pl.overlap;
@@ -587,7 +645,12 @@ void fill_common(ConvGemmParams &p, const Plan &pl, int B, int M, int R, int Tin
 }  // namespace
 
 // ---- forward ---------------------------------------------------------------------------
-bool mfma_fwd_supported(const Geom &g) { return make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil).ok; }
+bool mfma_fwd_supported(const Geom &g)
+{
+    if ((size_t)g.B * g.Cin * g.T * sizeof(bf16_t) > kMaxInput) return false;
+    if ((size_t)g.B * g.Cout * g.To * sizeof(bf16_t) > kMaxInput) return false;
+    return packed_bytes(g.Cout, g.Cin, g.K) < kMaxPacked && make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil).ok;
+}
 
 size_t mfma_fwd_workspace(const Geom &g) { return packed_bytes(g.Cout, g.Cin, g.K); }
 
@@ -595,7 +658,7 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
                            const void *res, void *y, bool relu, void *ws, hipStream_t s)
 {
     const Plan pl = make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil);
-    if (!pl.ok) return hipErrorInvalidValue;
+    if (!pl.ok || !mfma_fwd_supported(g)) return hipErrorInvalidValue;
     hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, s);
     if (e != hipSuccess) return e;
     ConvGemmParams p = {};
@@ -612,7 +675,9 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 // Workspace: packed (flipped, transposed) weights, then dz when it differs from dy.
 bool mfma_dgrad_supported(const Geom &g)
 {
-    if (g.stride != 1) return false;
+    if (g.stride != 1 || packed_bytes(g.Cin, g.Cout, g.K) >= kMaxPacked) return false;
+    if ((size_t)g.B * g.Cout * g.To * sizeof(bf16_t) > kMaxInput) return false;
+    if ((size_t)g.B * g.Cin * g.T * sizeof(bf16_t) > kMaxInput) return false;
     return make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil).ok;
 }
 
@@ -625,7 +690,7 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
                              void *dx, void *dres, bool relu, void *ws, hipStream_t s)
 {
     const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
-    if (!pl.ok) return hipErrorInvalidValue;
+    if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
     hipError_t e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, s);
     if (e != hipSuccess) return e;
     // one elementwise pass forms dz = dy*[y>0]*scale (bf16) and dres = dy*[y>0]
