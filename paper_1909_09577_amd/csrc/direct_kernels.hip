@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void epilogue_bwd_vec8_kernel(size_t n8, 
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
-                r[j] = (uint32_t)f32_to_bf16(g0) | ((uint32_t)f32_to_bf16(g1) << 16);
+                r[j] = pack_bf16x2(g0, g1);
             }
         }
         dz[i] = r;

@@ -30,6 +30,7 @@
 #include "nm_common.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace nm {
 namespace {
@@ -88,11 +89,20 @@ __device__ __forceinline__ int fresh_lane()
     return l;
 }
 
+// f(integral_constant<0>), f(integral_constant<1>), ... in order
+template <class F, int... Is>
+__device__ __forceinline__ void for_each_index(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+
 struct TileCoords {
     int mt, b, t0, ws_al, off0;
 };
 
-template <int NT, int STRIDE>
+// KT > 0: the number of taps is a compile-time constant and a chunk is one straight-line block
+// (see the unrolled main loop below); KT == 0: any K, tap pairs in a loop.
+template <int NT, int STRIDE, int KT>
 __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -160,6 +170,17 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             dst[(2 * j + 1) * kRowDwords] = (xa[j] >> 16) | (xb[j] & 0xffff0000u);
         }
     };
+    // the same with the lane's LDS offsets computed by the caller: lane_lds = ((lane/16)*8 rows,
+    // channel pair lane%16) for real items, lane_dump = (first dump row, channel pair) for idle ones
+    auto stage_write_at = [&](unsigned char *buf, uint32_t lane_lds, uint32_t lane_dump, int it, bool active,
+                              const u32x4 &xa, const u32x4 &xb) {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (active ? lane_lds + (uint32_t)(it * 32 * kRowBytes) : lane_dump));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dst[(2 * j) * kRowDwords] = (xa[j] & 0xffffu) | (xb[j] << 16);
+            dst[(2 * j + 1) * kRowDwords] = (xa[j] >> 16) | (xb[j] & 0xffff0000u);
+        }
+    };
     constexpr int kSlots = 6;      // staging items of the next chunk held in registers
     u32x4 sxa[kSlots], sxb[kSlots];
     // a whole chunk, nothing to overlap with (first tile, or every tile without cross-tile staging)
@@ -173,7 +194,15 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         }
     };
 
-    // ---- weight fragment stream.  Tap pairs are multiplied alternately from two register sets
+    // ---- weight fragment stream: buffer loads whose scalar offset is a cursor into the packed weights
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
+    const uint32_t w_lane = (uint32_t)lane * 16;
+    const int gstep = (int)(gridDim.x % (unsigned)p.nmt);  // tile += gridDim.x moves the channel tile by this much
+    auto w_load = [&](uint32_t soff, int f) {
+        return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_lane + (uint32_t)f * 1024u, soff, 0));
+    };
+
+    // (KT == 0)  Tap pairs are multiplied alternately from two register sets
     // (afA, afB: [tap 2][ks 2][mi 2] fragments each); a set is reloaded right after its last use
     // with the pair that comes two pairs later in this wavefront's stream, which runs across
     // chunks and tiles, so the loads have about two pairs of MFMA work to arrive.  A tile with an
@@ -184,11 +213,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     const int total_pairs = nmy * P;
     const int slots = total_pairs + (total_pairs & 1);  // pairs per tile including the zero pair
     constexpr uint32_t kPairBytes = 512 * 16;           // one tap pair of one chunk
-    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
     const uint32_t zero_soff = (uint32_t)(p.wp_zero * 16);
     const uint32_t chunk_jump = kPairBytes * (uint32_t)(1 + (kWaves - 1) * P);  // last pair of a chunk -> first of the next
-    const uint32_t w_lane = (uint32_t)lane * 16;
-    const int gstep = (int)(gridDim.x % (unsigned)p.nmt);
     auto w_base = [&](int mt) { return (uint32_t)(mt * p.nch + wave) * (uint32_t)P * kPairBytes; };
     int w_tile = blockIdx.x, w_mt = (int)(blockIdx.x % (unsigned)p.nmt), w_pr = 0, w_s = 0;
     bool w_live = w_tile < p.num_tiles && nmy > 0;
@@ -211,16 +237,40 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         }
         return off;
     };
-    auto w_load = [&](uint32_t soff, int f) {
-        return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_lane + (uint32_t)f * 1024u, soff, 0));
-    };
-    {
+    if constexpr (KT == 0) {
         const uint32_t s0 = w_next();
 #pragma unroll
         for (int f = 0; f < 8; ++f) afA[f] = w_load(s0, f);
         const uint32_t s1 = w_next();
 #pragma unroll
         for (int f = 0; f < 8; ++f) afB[f] = w_load(s1, f);
+    }
+
+
+    // (KT > 0)  One register set of four fragments ([ks 2][mi 2]) per tap, rotating over NS sets
+    // plus one extra set for each of the KT % NS last taps, so that the assignment of taps to sets
+    // is the same in every chunk.  A set is reloaded right after its last multiplication with the
+    // tap that uses it next: NS taps later in this chunk, or in the next chunk of this wavefront's
+    // stream (w_cur / w_nxt: byte offsets of the current and the next chunk), which runs across
+    // tiles.  The zero tap that pads an odd K in the packed tensor is never touched.
+    constexpr int NS = 4, NQ = KT / NS, NR = KT % NS, NSETS = KT > 0 ? NS + NR : 1;
+    bf16x8 wf[NSETS][4];
+    constexpr uint32_t kTapBytes = 4 * 64 * 16;
+    const uint32_t chunk_bytes = (uint32_t)p.Kp * kTapBytes;
+    auto chunk_off = [&](int mt, int c) { return (uint32_t)(mt * p.nch + c) * chunk_bytes; };
+    int mt_cur = (int)(blockIdx.x % (unsigned)p.nmt);
+    uint32_t w_cur = chunk_off(mt_cur, wave);
+    if constexpr (KT > 0) {
+        if (blockIdx.x < (unsigned)p.num_tiles && nmy > 0) {
+#pragma unroll
+            for (int k = 0; k < NS; ++k)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) wf[k][f] = w_load(w_cur + (uint32_t)k * kTapBytes, f);
+#pragma unroll
+            for (int e = 0; e < NR; ++e)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) wf[NS + e][f] = w_load(w_cur + (uint32_t)(NS * NQ + e) * kTapBytes, f);
+        }
     }
 
     // epilogue operands as buffer descriptors; an absent one is empty and reads zeros
@@ -256,7 +306,80 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-        if (nmy > 0) {
+        if constexpr (KT > 0) {
+            if (nmy > 0) {
+                // ---- unrolled main loop: one chunk (KT taps, 4*NT*KT MFMAs) is a single straight-line
+                // block, so staging loads, staging writes, weight reloads and LDS reads are placed
+                // between the MFMAs by the compiler and every wait counts exactly what is in flight.
+                // The six staging items of the next chunk are requested one per tap during the
+                // first six taps and written one per tap during the last six.
+                static_assert(KT == 0 || KT >= 11, "the staging schedule needs eleven taps");
+                const int ll = fresh_lane();
+                const int lane_off = ((ll & 31) * STRIDE + tc.off0) * kRowBytes + (ll >> 5) * 16;
+                const uint32_t lane_lds = (uint32_t)(((ll >> 4) * 8) * kRowBytes + (ll & 15) * 4);
+                const uint32_t lane_dump = (uint32_t)(nitems * 32 * kRowBytes + (ll & 15) * 4);
+                const bool w_next_tile = tile + (int)gridDim.x < p.num_tiles;
+                int mt_n = mt_cur + gstep;
+                mt_n -= mt_n >= p.nmt ? p.nmt : 0;
+                for (int ci = 0; ci < nmy; ++ci) {
+                    const bool more = ci + 1 < nmy;
+                    const bool has_t = more || next_ok;  // is there a chunk to stage for
+                    const uint32_t w_nxt = more ? w_cur + kWaves * chunk_bytes : (w_next_tile ? chunk_off(mt_n, wave) : w_cur);
+                    StageAddr sa = stage_addr(more ? tc.b : tn.b, more ? wave + kWaves * (ci + 1) : wave,
+                                              more ? tc.ws_al : tn.ws_al);
+                    sa.va = has_t ? sa.va : kOutOfRange;
+                    sa.vb = has_t ? sa.vb : kOutOfRange;
+                    const unsigned char *bbase = buf_ptr(cc) + lane_off;
+                    unsigned char *nxt = buf_ptr(cc + 1);
+                    bf16x8 b0[NT], b1[NT];
+                    auto read_b = [&](bf16x8(&dst)[NT], int k, int ks) {
+                        const unsigned char *brow = bbase + (size_t)k * tap_bytes + ks * 32;
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni)
+                            dst[ni] = *reinterpret_cast<const bf16x8 *>(brow + ni * 32 * STRIDE * kRowBytes);
+                    };
+                    auto mma = [&](const bf16x8 &a0, const bf16x8 &a1, const bf16x8(&bf)[NT]) {
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni)
+                            acc[0][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf[ni], acc[0][ni], 0, 0, 0);
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni)
+                            acc[1][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bf[ni], acc[1][ni], 0, 0, 0);
+                    };
+                    wave_lds_fence();  // the staged chunk is visible to every lane
+                    read_b(b0, 0, 0);
+                    auto tap = [&](auto kc) {
+                        constexpr int k = decltype(kc)::value;
+                        constexpr int set = k < NS * NQ ? k % NS : NS + (k - NS * NQ);
+                        // the tap that uses this set next
+                        constexpr bool same_chunk = k < NS * NQ && k + NS < NS * NQ;
+                        constexpr int next_tap = same_chunk ? k + NS : (k < NS * NQ ? k % NS : k);
+                        const uint32_t src = (same_chunk ? w_cur : w_nxt) + (uint32_t)next_tap * kTapBytes;
+                        // (a scheduling barrier per k-step keeps every load where it is written: the
+                        // compiler would otherwise move the reloads down to their use)
+                        read_b(b1, k, 1);
+                        mma(wf[set][0], wf[set][1], b0);
+                        wf[set][0] = w_load(src, 0);
+                        wf[set][1] = w_load(src, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (k + 1 < KT) read_b(b0, k + 1, 0);
+                        mma(wf[set][2], wf[set][3], b1);
+                        wf[set][2] = w_load(src, 2);
+                        wf[set][3] = w_load(src, 3);
+                        if constexpr (k < kSlots) stage_load(sa, k, k < nitems, sxa[k], sxb[k]);
+                        if constexpr (k >= KT - kSlots) {
+                            constexpr int it = k - (KT - kSlots);
+                            stage_write_at(nxt, lane_lds, lane_dump, it, has_t && it < nitems, sxa[it], sxb[it]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    };
+                    for_each_index(tap, std::make_integer_sequence<int, (KT > 0 ? KT : 1)>{});
+                    w_cur = w_nxt;
+                    ++cc;
+                }
+                mt_cur = mt_n;
+            }
+        } else if (nmy > 0) {
             // ---- main loop over (chunk, tap pair): 4 k-steps of 16 channels = 8*NT MFMAs per pair
             // (the packed weights pad an odd K with one zero tap).  All MFMAs sit in this loop.
             const int ll = fresh_lane();
@@ -265,6 +388,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             // where the staging items of this chunk go: the next chunk of this tile, or the first
             // chunk of the next tile, or nowhere
             bool has_t = nmy > 1 || next_ok;
+            const bool async_stage = P > kSlots / 2;  // shorter chunks stage the next one at their end
             int t_b = nmy > 1 ? tc.b : tn.b, t_ws = nmy > 1 ? tc.ws_al : tn.ws_al, t_c = nmy > 1 ? wave + kWaves : wave;
             const unsigned char *bbase = buf_ptr(cc) + lane_off;
             unsigned char *nxt = buf_ptr(cc + 1);
@@ -283,10 +407,22 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             };
             // one tap pair from the register set `af`; `real` is false only for the zero pad pair
             auto do_pair = [&](bf16x8(&af)[8], bool real) {
-                // the whole next chunk is requested at the first pair of this one (static register
-                // slots) and written to LDS in groups of two items behind the last pairs, so the
-                // loads have most of a chunk (several microseconds) to arrive
-                if (__builtin_expect(pr == 0 && has_t, 0)) {
+                // Staging of the next chunk: its items are requested at the first pair of this chunk
+                // (static register slots) and written to LDS two at a time at the top of the last
+                // three pairs, so the loads have most of a chunk (several microseconds) to arrive.
+                // The writes come first in program order and only in pairs after the first, which
+                // lets the wait they need leave the latest weight loads in flight.
+                if (__builtin_expect(has_t && async_stage && pr >= P - kSlots / 2, 0)) {
+#pragma unroll
+                    for (int gq = 0; gq < kSlots / 2; ++gq) {
+                        if (pr == P - kSlots / 2 + gq) {
+#pragma unroll
+                            for (int e = 0; e < 2; ++e)
+                                if (2 * gq + e < nitems) stage_write(nxt, 2 * gq + e, true, sxa[2 * gq + e], sxb[2 * gq + e]);
+                        }
+                    }
+                }
+                if (__builtin_expect(pr == 0 && has_t && async_stage, 0)) {
                     const StageAddr sa = stage_addr(t_b, t_c, t_ws);
 #pragma unroll
                     for (int it = 0; it < kSlots; ++it)
@@ -310,19 +446,10 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 mma(af[6], af[7], b1);
                 af[6] = w_load(wn, 6);
                 af[7] = w_load(wn, 7);
-                if (__builtin_expect(has_t && pr >= P - kSlots / 2, 0)) {
-#pragma unroll
-                    for (int gq = 0; gq < kSlots / 2; ++gq) {
-                        if (pr == max(0, P - kSlots / 2 + gq)) {
-#pragma unroll
-                            for (int e = 0; e < 2; ++e)
-                                if (2 * gq + e < nitems) stage_write(nxt, 2 * gq + e, true, sxa[2 * gq + e], sxb[2 * gq + e]);
-                        }
-                    }
-                }
                 if (__builtin_expect(real && ++pr == P, 0)) {  // end of a chunk
                     if (has_t) {
-                        for (int it = kSlots; it < nitems; ++it) {  // windows longer than the register slots
+                        // windows longer than the register slots, or everything when chunks are short
+                        for (int it = async_stage ? kSlots : 0; it < nitems; ++it) {
                             u32x4 ya, yb;
                             stage_load(stage_addr(t_b, t_c, t_ws), it, true, ya, yb);
                             stage_write(nxt, it, true, ya, yb);
@@ -452,7 +579,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                     v0 = v0 > 0.f ? v0 : 0.f;
                     v1 = v1 > 0.f ? v1 : 0.f;
                 }
-                o[e] = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+                o[e] = pack_bf16x2(v0, v1);
             }
             __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ooff[q], 0, 0);
         }
@@ -575,10 +702,10 @@ size_t packed_bytes(int M, int R, int K)
 constexpr size_t kMaxPacked = (size_t)1 << 31;  // the kernel addresses packed weights with 32-bit offsets
 constexpr size_t kMaxInput = (size_t)1 << 30;   // and the activation tensors through buffer descriptors
 
-template <int NT, int STRIDE>
+template <int NT, int STRIDE, int KT>
 hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 {
-    auto kern = conv_gemm_kernel<NT, STRIDE>;
+    auto kern = conv_gemm_kernel<NT, STRIDE, KT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -595,10 +722,24 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 {
-    if (pl.nt == 5 && pl.stride == 1) return launch_t<5, 1>(p, pl.lds, s);
-    if (pl.nt == 2 && pl.stride == 1) return launch_t<2, 1>(p, pl.lds, s);
-    if (pl.nt == 5 && pl.stride == 2) return launch_t<5, 2>(p, pl.lds, s);
-    if (pl.nt == 2 && pl.stride == 2) return launch_t<2, 2>(p, pl.lds, s);
+    // kernel sizes with an unrolled chunk: wide tiles, stride 1, windows that fit the register slots
+    if (pl.nt == 5 && pl.stride == 1 && pl.nitems <= 6) {
+        switch (p.K) {
+#ifndef NM_ONLY_K17
+        case 11: return launch_t<5, 1, 11>(p, pl.lds, s);
+        case 13: return launch_t<5, 1, 13>(p, pl.lds, s);
+        case 21: return launch_t<5, 1, 21>(p, pl.lds, s);
+        case 25: return launch_t<5, 1, 25>(p, pl.lds, s);
+        case 29: return launch_t<5, 1, 29>(p, pl.lds, s);
+#endif
+        case 17: return launch_t<5, 1, 17>(p, pl.lds, s);
+        default: break;
+        }
+    }
+    if (pl.nt == 5 && pl.stride == 1) return launch_t<5, 1, 0>(p, pl.lds, s);
+    if (pl.nt == 2 && pl.stride == 1) return launch_t<2, 1, 0>(p, pl.lds, s);
+    if (pl.nt == 5 && pl.stride == 2) return launch_t<5, 2, 0>(p, pl.lds, s);
+    if (pl.nt == 2 && pl.stride == 2) return launch_t<2, 2, 0>(p, pl.lds, s);
     return hipErrorInvalidValue;
 }
 

@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm,
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
-                g[j] = (uint32_t)f32_to_bf16(g0) | ((uint32_t)f32_to_bf16(g1) << 16);
+                g[j] = pack_bf16x2(g0, g1);
             }
         }
     }

@@ -29,6 +29,15 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 __device__ __forceinline__ float load_as_f32(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void store_from_f32(float *p, size_t i, float v) { p[i] = v; }
+// Two floats to a packed bf16 pair (lo in the low half) with the hardware conversion: round to
+// nearest even like f32_to_bf16, a NaN stays a NaN.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ void store_from_f32(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
 // Value a stored element will read back as (identity for float, bf16 rounding otherwise).
 __device__ __forceinline__ float round_to_storage(float v, const float *) { return v; }
