@@ -13,7 +13,7 @@ The JSON line also carries
   roofline     -- the dominant kernel (largest share of the step) against the bf16 dense MFMA
                   peak; its average duration is measured in the timed region with HIP events
                   recorded on the launch stream right around that kernel (the library's
-                  nm_conv1d_time_next_main_kernel hook);
+                  nm_conv1d_time_next_main_kernel hook) in every fourth step;
   cpu_baseline -- the fp64 CPU oracle, untuned, timed on the host cores on the first 8 of the
                   32 batch items of the same workload (a baseline, not the target).
 """
@@ -89,25 +89,35 @@ def main():
         return e
 
     names = ("fwd", "dgrad", "wgrad")
-    pairs = {n: [(ev(), ev()) for _ in range(args.steps)] for n in names}
+    # Events around a kernel split the stream's back-to-back dispatch (a few microseconds per pair), so
+    # the timed region carries them only around the dominant kernel and only in every fourth step; which
+    # kernel dominates is found with events around all three during the warmup steps.
+    every = 4
+    warm_pairs = {n: [(ev(), ev()) for _ in range(max(args.warmup, 1))] for n in names}
+    timed_steps = list(range(0, args.steps, every))
+    pairs = [(ev(), ev()) for _ in timed_steps]
 
-    def step(i=None):
-        if i is not None:
-            nm.nm_conv1d_time_next_main_kernel(*pairs["fwd"][i])
+    def step(hook=None):
+        if hook and "fwd" in hook:
+            nm.nm_conv1d_time_next_main_kernel(*hook["fwd"])
         nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw)
-        if i is not None:
-            nm.nm_conv1d_time_next_main_kernel(*pairs["dgrad"][i])
+        if hook and "dgrad" in hook:
+            nm.nm_conv1d_time_next_main_kernel(*hook["dgrad"])
         nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=y, scale=scale, dx=dx, dres=dres, relu=True, workspace=ws, **kw)
-        if i is not None:
-            nm.nm_conv1d_time_next_main_kernel(*pairs["wgrad"][i])
+        if hook and "wgrad" in hook:
+            nm.nm_conv1d_time_next_main_kernel(*hook["wgrad"])
         nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(max(args.warmup, 1)):
+        step({n: warm_pairs[n][i] for n in names})
+    torch.cuda.synchronize()
+    warm_ms = {n: sorted(a.elapsed_time(b) for a, b in warm_pairs[n])[len(warm_pairs[n]) // 2] for n in names}
+    dominant = max(warm_ms, key=warm_ms.get)
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        step({dominant: pairs[i // every]} if i % every == 0 else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -115,17 +125,16 @@ def main():
     flops_step = 3 * cfg.flops_per_pass
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    kern_ms = {n: sum(a.elapsed_time(b) for a, b in pairs[n]) / args.steps for n in names}
-    dominant = max(kern_ms, key=kern_ms.get)
-    kernel_names = {"fwd": "conv_gemm_kernel<5,1,FWD>", "dgrad": "conv_gemm_kernel<5,1,DGRAD>",
-                    "wgrad": "wgrad_kernel<6>"}
-    achieved = cfg.flops_per_pass / (kern_ms[dominant] * 1e-3) / 1e12
+    dom_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+    kernel_names = {"fwd": "conv_gemm_kernel<5,1,17> (forward)", "dgrad": "conv_gemm_kernel<5,1,17> (input gradient)",
+                    "wgrad": "wgrad_fast_kernel<6>"}
+    achieved = cfg.flops_per_pass / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
                 "kernel": kernel_names[dominant],
                 "flops_per_launch": cfg.flops_per_pass,
-                "avg_launch_ms": round(kern_ms[dominant], 4),
-                "main_kernels_ms": {n: round(v, 4) for n, v in kern_ms.items()}}
+                "avg_launch_ms": round(dom_ms, 4), "timed_launches": len(pairs),
+                "warmup_main_kernels_ms": {n: round(v, 4) for n, v in warm_ms.items()}}
 
     out = {
         "metric": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), C=512 K=17 T=800",

@@ -115,22 +115,44 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     const int P = p.Kp >> 1;                               // tap pairs per chunk
     const size_t chunk_stride = (size_t)p.Kp * 256;        // bf16x8 per (tile, chunk)
     const int tap_bytes = p.dil * kRowBytes;
+    const int gstep = (int)(gridDim.x % (unsigned)p.nmt);  // tile += gridDim.x moves the channel tile by this much
     const __amdgpu_buffer_rsrc_t rs_in =
         __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)((size_t)p.B * p.R * p.Tin * 2), 0x00020000);
 
     // staging item `it` of a lane: channel pair pp = lane & 15, time group q0 + 4*it (8 steps)
     auto buf_ptr = [&](int par) { return smem + ((size_t)(par & 1) * kWaves + wave) * p.buf_bytes; };
 
-    auto tile_coords = [&](int tile) {
+    auto finish_coords = [&](TileCoords &tc, int tt) {
+        tc.t0 = tt * TN;
+        const int ws = tc.t0 * STRIDE - p.padL;
+        tc.ws_al = (ws >> 3) * 8;  // arithmetic shift: floor
+        tc.off0 = ws - tc.ws_al;
+    };
+    auto tile_coords = [&](int tile, int &tt) {
         TileCoords tc;
         tc.mt = tile % p.nmt;
         const int ntile = tile / p.nmt;
         tc.b = ntile / p.ntt;
-        tc.t0 = (ntile - tc.b * p.ntt) * TN;
-        const int ws = tc.t0 * STRIDE - p.padL;
-        tc.ws_al = (ws >> 3) * 8;  // arithmetic shift: floor
-        tc.off0 = ws - tc.ws_al;
+        tt = ntile - tc.b * p.ntt;
+        finish_coords(tc, tt);
         return tc;
+    };
+    // Coordinates of tile + gridDim.x from those of tile, without divisions: the step is split once
+    // into (channel tiles, time tiles, batch items), for a carry of 0 and of 1 out of the channel tiles.
+    const int step_n = (int)(gridDim.x / (unsigned)p.nmt);
+    const int step_b0 = step_n / p.ntt, step_t0 = step_n % p.ntt;
+    const int step_b1 = (step_n + 1) / p.ntt, step_t1 = (step_n + 1) % p.ntt;
+    auto next_coords = [&](const TileCoords &tc, int &tt) {
+        TileCoords tn;
+        tn.mt = tc.mt + gstep;
+        const bool carry = tn.mt >= p.nmt;
+        tn.mt -= carry ? p.nmt : 0;
+        tt += carry ? step_t1 : step_t0;
+        const bool carry2 = tt >= p.ntt;
+        tt -= carry2 ? p.ntt : 0;
+        tn.b = tc.b + (carry ? step_b1 : step_b0) + (carry2 ? 1 : 0);
+        finish_coords(tn, tt);
+        return tn;
     };
     // Staging loads of chunk c of batch item b, window start ws_al.  The scalar part of the address
     // (batch item, chunk) travels as the scalar offset of the buffer load; lanes whose 8 time steps
@@ -197,7 +219,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     // ---- weight fragment stream: buffer loads whose scalar offset is a cursor into the packed weights
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
     const uint32_t w_lane = (uint32_t)lane * 16;
-    const int gstep = (int)(gridDim.x % (unsigned)p.nmt);  // tile += gridDim.x moves the channel tile by this much
     auto w_load = [&](uint32_t soff, int f) {
         return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_lane + (uint32_t)f * 1024u, soff, 0));
     };
@@ -286,25 +307,27 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     const int first_tile = blockIdx.x;
-    if (first_tile < p.num_tiles && nmy > 0 && p.overlap) {
-        const TileCoords tc = tile_coords(first_tile);
-        stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(0));
-    }
+    // accumulators: zero here, and again in the epilogue as soon as a tile's values have been handed over
+    f32x16 acc[2][NT];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    int tt_next = 0;  // time-tile index that belongs to tc_next
+    TileCoords tc_next = tile_coords(first_tile < p.num_tiles ? first_tile : 0, tt_next);
+    if (first_tile < p.num_tiles && nmy > 0 && p.overlap) stage_chunk_now(tc_next.b, wave, tc_next.ws_al, buf_ptr(0));
 
     for (int tile = first_tile; tile < p.num_tiles; tile += gridDim.x) {
-        const TileCoords tc = tile_coords(tile);
+        const TileCoords tc = tc_next;
         const bool next_ok = p.overlap && tile + (int)gridDim.x < p.num_tiles;
-        const TileCoords tn = tile_coords(next_ok ? tile + (int)gridDim.x : tile);
+        tc_next = next_coords(tc, tt_next);  // meaningful only while tiles remain; used for staging when next_ok
+        const TileCoords tn = tc_next;
 
         if (!p.overlap && nmy > 0) stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(cc));
 
-        f32x16 acc[2][NT];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
         if constexpr (KT > 0) {
             if (nmy > 0) {
@@ -539,6 +562,10 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                     own[mi][ni] = f32x4{acc[mi][ni][4 * G], acc[mi][ni][4 * G + 1], acc[mi][ni][4 * G + 2],
                                         acc[mi][ni][4 * G + 3]};
 #pragma unroll
+                for (int ni = 0; ni < NT; ++ni)  // this row of blocks is done: ready for the next tile
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+#pragma unroll
                 for (int slot = 0; slot < 3; ++slot) {
 #pragma unroll
                     for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((G * 3 + slot) * NT + ni) * 64 + el];
@@ -730,7 +757,6 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
         case 13: return launch_t<5, 1, 13>(p, pl.lds, s);
         case 21: return launch_t<5, 1, 21>(p, pl.lds, s);
         case 25: return launch_t<5, 1, 25>(p, pl.lds, s);
-        case 29: return launch_t<5, 1, 29>(p, pl.lds, s);
 #endif
         case 17: return launch_t<5, 1, 17>(p, pl.lds, s);
         default: break;

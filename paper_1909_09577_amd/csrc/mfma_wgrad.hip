@@ -71,6 +71,9 @@ __device__ __forceinline__ void wave_lds_fence()
 // wave-uniform addend.  A lane whose data lies outside its row passes kOutOfRange, which the
 // hardware bounds check turns into zeros: no branch and nothing to fix up after the load.
 constexpr uint32_t kOutOfRange = 0xffffffffu;
+// An offset beyond every tensor this file addresses through a descriptor (the host keeps them below
+// 1 GiB) that stays beyond them when a small immediate or scalar offset is added.
+constexpr uint32_t kFar = 0x80000000u;
 __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
     return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
@@ -402,6 +405,163 @@ __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm,
     dzf[(((size_t)b * ncm + cm) * nst + st) * 64 + lane] = g;
 }
 
+// The unit loop of the stride-1 kernel for KA active taps (KA == KT, or KT - 1 for a short last
+// group).  Units come in pairs so that two register sets for each operand and the two LDS buffers
+// are named statically: the x window of unit i+2 is requested at the start of unit i and written
+// to LDS at the end of unit i+1, and the dz fragments of unit i+2 are requested, fragment by
+// fragment, right after their last use in unit i: two units of MFMA work for every load.  A wave
+// with an odd number of units runs one more on offsets beyond the tensors: both operands read
+// zeros and nothing is added.
+template <int KT, int KA>
+__device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *smem, f32x16 (&acc)[2][KT], int sp,
+                                           int k0, int co0, int ci0)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int kRows = kFastXItems * 32;  // rows of one x buffer
+    constexpr int kBufBytes = kRows * kFastXRowBytes;
+    unsigned char *wbuf0 = smem + (size_t)wave * 2 * kBufBytes;
+    const int slot_id = sp * kWaves + wave;
+    const int slots = p.S * kWaves;
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)((size_t)p.B * p.Cin * p.T * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_dz = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)p.dzf, 0, (int)((size_t)p.B * p.ncm * p.nst * 1024), 0x00020000);
+
+    // x staging: lane = channel pair (lane & 15) x time group (lane >> 4) + 4*q, q < 3
+    const int x_pp = lane & 15, x_q = lane >> 4;
+    const bool ch_a = ci0 + 2 * x_pp < p.Cin, ch_b = ci0 + 2 * x_pp + 1 < p.Cin;
+    const uint32_t x_lds_off = (uint32_t)((x_q * 8) * kFastXRowBytes + x_pp * 4);
+    // window start of a unit relative to its first output step: -pad + k0, aligned down to 8
+    const int xs_rel = k0 - p.pad;
+    const int xs_rel_al = (xs_rel >> 3) * 8;
+    const int off0 = xs_rel - xs_rel_al;
+    const uint32_t x_lane_a = ch_a ? (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q + xs_rel_al) * 2) : kFar;
+    const uint32_t x_lane_b = ch_b ? x_lane_a + (uint32_t)(p.T * 2) : kFar;
+    const int x_t0 = xs_rel_al + 8 * x_q;
+
+    // unit number -> (batch item, chunk); units past the end get offsets beyond both tensors
+    struct UnitAddr {
+        uint32_t xs;  // scalar byte offset of the unit's batch item in x
+        int tbase;    // first output step
+        uint32_t as;  // scalar byte offset of the unit's dz fragments (channel block 0, step 0)
+        bool live;
+    };
+    auto unit_addr = [&](int u) {
+        UnitAddr a;
+        a.live = u < p.units;
+        const int uu = a.live ? u : 0;
+        const int b = uu / p.nchunk, chunk = uu - b * p.nchunk;
+        a.tbase = chunk * kFastTCH;
+        a.xs = (uint32_t)((size_t)b * p.Cin * p.T * 2);
+        a.as = (uint32_t)((((size_t)b * p.ncm + (co0 >> 5)) * p.nst + (size_t)chunk * kFastSteps) * 1024);
+        return a;
+    };
+    auto x_load = [&](const UnitAddr &a, u32x4(&xa)[kFastXItems], u32x4(&xb)[kFastXItems]) {
+#pragma unroll
+        for (int q = 0; q < kFastXItems; ++q) {
+            const int t = a.tbase + x_t0 + 32 * q;
+            const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);  // 0 <= t and t + 8 <= T
+            // the lane offset carries the time (it is negative only where t is, and those lanes are masked)
+            xa[q] = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
+            xb[q] = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
+        }
+    };
+    auto x_write = [&](unsigned char *buf, const u32x4(&xa)[kFastXItems], const u32x4(&xb)[kFastXItems]) {
+#pragma unroll
+        for (int q = 0; q < kFastXItems; ++q) {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kFastXRowBytes);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dst[(2 * e) * (kFastXRowBytes / 4)] = (xa[q][e] & 0xffffu) | (xb[q][e] << 16);
+                dst[(2 * e + 1) * (kFastXRowBytes / 4)] = (xa[q][e] >> 16) | (xb[q][e] & 0xffff0000u);
+            }
+        }
+    };
+    // A fragments of one unit: [mi][step], 1 KiB contiguous per wavefront and fragment
+    const uint32_t a_lane = (uint32_t)lane * 16;
+    const uint32_t a_mi = (uint32_t)p.nst * 1024;  // from channel block mi to mi + 1
+    u32x4 afr0[2][kFastSteps], afr1[2][kFastSteps];  // even / odd unit of a pair
+    auto a_load = [&](const UnitAddr &a, int mi, int st) {
+        return buf_load16(rs_dz, a.live ? a_lane + (uint32_t)(st * 1024) : kFar, a.as + (uint32_t)mi * a_mi);
+    };
+
+    // transposing reads: this lane addresses 4 channels 16*((lane/16)&1) + 4*(lane&3) at time row
+    // 8*(lane/32) + (lane&15)/4 (+4 for the second read of a fragment)
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const int trow = 8 * (g4 >> 1) + (i16 >> 2) + off0;
+    const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);
+    const unsigned char *xb0 = wbuf0 + trow * kFastXRowBytes + tcol * 2;
+
+    const int my_units = slot_id < p.units ? (p.units - slot_id + slots - 1) / slots : 0;
+    if (my_units == 0) return;
+    u32x4 xa0[kFastXItems], xb0r[kFastXItems], xa1[kFastXItems], xb1r[kFastXItems];
+    {
+        const UnitAddr a0 = unit_addr(slot_id), a1 = unit_addr(slot_id + slots);
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int st = 0; st < kFastSteps; ++st) {
+                afr0[mi][st] = a_load(a0, mi, st);
+                afr1[mi][st] = a_load(a1, mi, st);
+            }
+        x_load(a0, xa0, xb0r);
+        x_load(a1, xa1, xb1r);   // written at the end of the first unit
+        x_write(wbuf0, xa0, xb0r);
+    }
+    // one unit: multiply from LDS buffer `par` and the fragment set afr; request the dz fragments and
+    // the x window of unit u + 2*slots into afr and (xa, xb) -- the x set that was written before
+    // this unit started -- and write the other x set (xo_a, xo_b: unit u + slots) into the other
+    // buffer at the end.  Loads complete in order, so both streams run two units ahead: a wait for
+    // a fragment also waits for every x load requested before it.
+    auto unit = [&](int u, int par, u32x4(&afr)[2][kFastSteps], u32x4(&xa)[kFastXItems], u32x4(&xb)[kFastXItems],
+                    const u32x4(&xo_a)[kFastXItems], const u32x4(&xo_b)[kFastXItems]) {
+        const UnitAddr an = unit_addr(u + 2 * slots);
+        x_load(an, xa, xb);
+        wave_lds_fence();
+        const unsigned char *xb_ = xb0 + par * kBufBytes;
+        auto read_b = [&](int st, bf16x8(&bfr)[KA]) {
+#pragma unroll
+            for (int kk = 0; kk < KA; ++kk) {
+                const unsigned char *xp = xb_ + (st * 16 + kk) * kFastXRowBytes;
+                union {
+                    s16x4 h[2];
+                    bf16x8 v;
+                } cvt;
+                cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp));
+                cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp + 4 * kFastXRowBytes));
+                bfr[kk] = cvt.v;
+            }
+        };
+        bf16x8 bq[2][KA];
+        read_b(0, bq[0]);
+#pragma unroll
+        for (int st = 0; st < kFastSteps; ++st) {
+            if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                union {
+                    u32x4 u;
+                    bf16x8 v;
+                } af;
+                af.u = afr[mi][st];
+#pragma unroll
+                for (int kk = 0; kk < KA; ++kk)
+                    acc[mi][kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bq[st & 1][kk], acc[mi][kk], 0, 0, 0);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
+        }
+        x_write(wbuf0 + (par ^ 1) * kBufBytes, xo_a, xo_b);
+    };
+    const int npairs = (my_units + 1) >> 1;
+    int u = slot_id;
+    for (int i = 0; i < npairs; ++i, u += 2 * slots) {
+        unit(u, 0, afr0, xa0, xb0r, xa1, xb1r);
+        unit(u + slots, 1, afr1, xa1, xb1r, xa0, xb0r);
+    }
+}
+
 template <int KT>
 __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams p)
 {
@@ -423,118 +583,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][kk][r] = 0.f;
 
-    constexpr int kRows = kFastXItems * 32;                 // rows of one x buffer
-    constexpr int kBufBytes = kRows * kFastXRowBytes;
-    unsigned char *wbuf0 = smem + (size_t)wave * 2 * kBufBytes;
-    const int slot_id = sp * kWaves + wave;
-    const int slots = p.S * kWaves;
-    const __amdgpu_buffer_rsrc_t rs_x =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)((size_t)p.B * p.Cin * p.T * 2), 0x00020000);
-
-    // x staging: lane = channel pair (lane & 15) x time group (lane >> 4) + 4*q, q < 3
-    const int x_pp = lane & 15, x_q = lane >> 4;
-    const uint32_t x_lane_off = (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q) * 2);
-    const bool ch_a = ci0 + 2 * x_pp < p.Cin, ch_b = ci0 + 2 * x_pp + 1 < p.Cin;
-    const uint32_t x_lds_off = (uint32_t)((x_q * 8) * kFastXRowBytes + x_pp * 4);
-    // window start of a unit relative to its first output step: -pad + k0, aligned down to 8
-    const int xs_rel = k0 - p.pad;
-    const int xs_rel_al = (xs_rel >> 3) * 8;
-    const int off0 = xs_rel - xs_rel_al;
-
-    u32x4 xra[kFastXItems], xrb[kFastXItems];
-    auto x_load = [&](int b, int tbase) {
-        const int xs_al = tbase + xs_rel_al;
-        const uint32_t unit = (uint32_t)((size_t)b * p.Cin * p.T * 2) + (uint32_t)(xs_al * 2);
-#pragma unroll
-        for (int q = 0; q < kFastXItems; ++q) {
-            const int t = xs_al + 8 * (x_q + 4 * q);
-            const bool t_ok = t >= 0 && t + 8 <= p.T;
-            const uint32_t off = x_lane_off + unit + (uint32_t)(64 * q);
-            xra[q] = buf_load16(rs_x, (t_ok && ch_a) ? off : kOutOfRange, 0);
-            xrb[q] = buf_load16(rs_x, (t_ok && ch_b) ? off + (uint32_t)(p.T * 2) : kOutOfRange, 0);
-        }
-    };
-    auto x_write = [&](unsigned char *buf) {
-#pragma unroll
-        for (int q = 0; q < kFastXItems; ++q) {
-            uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kFastXRowBytes);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                dst[(2 * e) * (kFastXRowBytes / 4)] = (xra[q][e] & 0xffffu) | (xrb[q][e] << 16);
-                dst[(2 * e + 1) * (kFastXRowBytes / 4)] = (xra[q][e] >> 16) | (xrb[q][e] & 0xffff0000u);
-            }
-        }
-    };
-    // A fragments of one unit: [mi][step], 1 KiB contiguous per wavefront and fragment.  The
-    // fragment of step st is reloaded for the next unit right after its last use, so one set
-    // of registers gives a prefetch distance of a whole unit.
-    const u32x4 *dzf_tile = p.dzf + ((size_t)(co0 >> 5) * p.nst) * 64 + lane;
-    const size_t dzf_b = (size_t)p.ncm * p.nst * 64, dzf_m = (size_t)p.nst * 64;
-    u32x4 afr[2][kFastSteps];
-
-    // transposing reads: this lane addresses 4 channels 16*((lane/16)&1) + 4*(lane&3) at time row
-    // 8*(lane/32) + (lane&15)/4 (+4 for the second read of a fragment)
-    const int g4 = lane >> 4, i16 = lane & 15;
-    const int trow = 8 * (g4 >> 1) + (i16 >> 2) + off0;
-    const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);
-    const unsigned char *xb0 = wbuf0 + trow * kFastXRowBytes + tcol * 2;
-
-    int u = slot_id;
-    if (u < p.units) {
-        int b = u / p.nchunk, chunk = u - b * p.nchunk;
-        {
-            const u32x4 *src = dzf_tile + (size_t)b * dzf_b + (size_t)chunk * (kFastSteps * 64);
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int st = 0; st < kFastSteps; ++st) afr[mi][st] = src[mi * dzf_m + st * 64];
-        }
-        x_load(b, chunk * kFastTCH);
-        x_write(wbuf0);
-        int parity = 0;
-        for (; u < p.units; u += slots, parity ^= 1) {
-            // the next unit (or, at the end, this one again: harmless) is requested during this one
-            const int un = (u + slots < p.units) ? u + slots : u;
-            const int bn = un / p.nchunk, cn = un - bn * p.nchunk;
-            const u32x4 *asrc = dzf_tile + (size_t)bn * dzf_b + (size_t)cn * (kFastSteps * 64);
-            x_load(bn, cn * kFastTCH);
-            wave_lds_fence();
-            const unsigned char *xb = xb0 + parity * kBufBytes;
-            auto read_b = [&](int st, bf16x8(&bfr)[KT]) {
-#pragma unroll
-                for (int kk = 0; kk < KT; ++kk) {
-                    const unsigned char *xa = xb + (st * 16 + kk) * kFastXRowBytes;
-                    union {
-                        s16x4 h[2];
-                        bf16x8 v;
-                    } cvt;
-                    cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa));
-                    cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xa + 4 * kFastXRowBytes));
-                    bfr[kk] = cvt.v;
-                }
-            };
-            bf16x8 bq[2][KT];
-            read_b(0, bq[0]);
-#pragma unroll
-            for (int st = 0; st < kFastSteps; ++st) {
-                if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    union {
-                        u32x4 u;
-                        bf16x8 v;
-                    } af;
-                    af.u = afr[mi][st];
-#pragma unroll
-                    for (int kk = 0; kk < KT; ++kk)
-                        acc[mi][kk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bq[st & 1][kk], acc[mi][kk], 0, 0, 0);
-                }
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) afr[mi][st] = asrc[mi * dzf_m + st * 64];
-            }
-            x_write(wbuf0 + (parity ^ 1) * kBufBytes);
-        }
-    }
+    // a last group that is one tap short skips that tap's MFMAs (shorter ones multiply unused taps)
+    if (KT > 1 && kt == KT - 1)
+        fast_units<KT, (KT > 1 ? KT - 1 : 1)>(p, smem, acc, sp, k0, co0, ci0);
+    else
+        fast_units<KT, KT>(p, smem, acc, sp, k0, co0, ci0);
     reduce_and_store<KT>(p, smem, acc, lane, wave, sp, k0, kt, co0, ci0);
 }
 
@@ -622,7 +675,15 @@ WPlan make_wplan(const Geom &g)
 }
 
 // The stride-1, dilation-1 kernel applies when rows are 16-byte aligned; its split count.
-bool fast_ok(const Geom &g) { return g.stride == 1 && g.dil == 1 && g.T % 8 == 0 && g.To % 8 == 0; }
+bool fast_ok(const Geom &g)
+{
+    if (!(g.stride == 1 && g.dil == 1 && g.T % 8 == 0 && g.To % 8 == 0)) return false;
+    // both operands are addressed through buffer descriptors with 32-bit offsets
+    const size_t lim = (size_t)1 << 30;
+    const size_t nst = (size_t)((g.To + kFastTCH - 1) / kFastTCH) * kFastSteps;
+    const size_t ncm = (size_t)((g.Cout + kTileCo - 1) / kTileCo) * 2;
+    return (size_t)g.B * g.Cin * g.T * sizeof(bf16_t) <= lim && (size_t)g.B * ncm * nst * 1024 <= lim;
+}
 struct FastPlan {
     int KTg, ntg, S, nchunk, ncm, nst;
     size_t lds;

@@ -73,6 +73,10 @@ MEDIUM = [
     L("m_k1_wide", 2, 200, 29, 400, 1, affine=False, relu=False),
     L("m_stride2_prolog", 2, 64, 96, 400, 11, stride=2, pad=5),
     L("m_cin_small", 2, 16, 64, 480, 5, pad=2),
+    # the remaining Jasper filter widths, with 3, 5 and 2 reduction chunks (uneven over the four wavefronts)
+    L("m_k13", 2, 96, 64, 320, 13, pad=6, residual=True),
+    L("m_k21", 1, 160, 72, 328, 21, pad=10),
+    L("m_k25", 1, 64, 128, 336, 25, pad=12, residual=True),
 ]
 
 
