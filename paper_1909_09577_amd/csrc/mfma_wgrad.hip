@@ -535,6 +535,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         };
         bf16x8 bq[2][KA];
         read_b(0, bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int st = 0; st < kFastSteps; ++st) {
             if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
@@ -551,8 +552,19 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
             }
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
+            // Issue order inside the step: one LDS read of the next step behind every MFMA of this
+            // one, then the two fragment reloads (left alone, the compiler puts the reads after the
+            // MFMAs, into the registers these have just freed, and waits for them at the next step).
+#pragma unroll
+            for (int i = 0; i < 2 * KA; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // VMEM read
+            __builtin_amdgcn_sched_barrier(0);
         }
         x_write(wbuf0 + (par ^ 1) * kBufBytes, xo_a, xo_b);
+        __builtin_amdgcn_sched_barrier(0);
     };
     const int npairs = (my_units + 1) >> 1;
     int u = slot_id;
