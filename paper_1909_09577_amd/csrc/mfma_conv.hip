@@ -622,39 +622,72 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 // into LDS with coalesced reads (runs of 32*K, resp. 16*K, contiguous elements) and gathers the
 // fragments from there.
 constexpr int kPackRows = 16;
+// elements between consecutive channels m of the LDS tile: 32*K plus one dword of padding, which
+// makes the stride an odd number of dwords so that lanes with different m hit different banks
+__host__ __device__ constexpr int pack_m_stride(int K) { return kChunk * K + 2; }
 template <bool FLIP>
 __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
                                                       int R, int K, int nch, int ld /* row length of w */,
-                                                      size_t zero_off)
+                                                      size_t zero_off, int vec /* 16-byte aligned runs */)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as (m*32 + r)*K + k
+    bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as m*ms + r*K + k
+    const int ms = pack_m_stride(K);
     if (blockIdx.x == 0)  // one tap pair of zero weights after the packed tensor
         for (int i = threadIdx.x; i < 512; i += 256) wp[zero_off + i] = u32x4{0u, 0u, 0u, 0u};
     const int q = blockIdx.x & 3;                      // which 16 channels of the 64
     const int c = (blockIdx.x >> 2) % nch, mt = (blockIdx.x >> 2) / nch;
     const int m0 = mt * kTileM + q * kPackRows, r0 = c * kChunk;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (!FLIP) {
-        // w[m][r][k]: for each m a run of 32*K elements starting at (m0+m)*ld + r0*K
-        const int run = kChunk * K;
-        const int rvalid = min(kChunk, R - r0) * K;
-        for (int m = wv; m < kPackRows; m += 4) {
-            const bool m_ok = m0 + m < M;
-            const bf16_t *src = w + (size_t)(m_ok ? m0 + m : 0) * ld + (size_t)r0 * K;
-            for (int o = lane; o < run; o += 64) tile[m * run + o] = (m_ok && o < rvalid) ? src[o] : (bf16_t)0;
+    // Copy the block of w into LDS.  Rows of w that start on a 16-byte boundary (vec != 0) are read
+    // with 16-byte buffer loads, four per thread in flight (the copy is latency bound otherwise);
+    // elements beyond the tensor read zeros, elements of a neighbouring block are masked.
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)w, 0, (int)((size_t)M * R * K * 2), 0x00020000);
+    const int nrows = FLIP ? kChunk : kPackRows;            // runs of contiguous elements: one per r, resp. per m
+    const int run = (FLIP ? kPackRows : kChunk) * K;        // elements per run (a multiple of 8)
+    const int valid = FLIP ? max(0, min(kPackRows, M - m0)) * K : max(0, min(kChunk, R - r0)) * K;
+    auto row_ok = [&](int row) { return FLIP ? r0 + row < R : m0 + row < M; };
+    auto row_off = [&](int row) {  // element offset of the run in w
+        return FLIP ? (size_t)(r0 + row) * ld + (size_t)m0 * K : (size_t)(m0 + row) * ld + (size_t)r0 * K;
+    };
+    auto put = [&](int row, int o, bf16_t v) {  // element o of run `row`
+        if (FLIP) {
+            const int m = o / K, k = o - m * K;
+            tile[m * ms + row * K + (K - 1 - k)] = v;
+        } else {
+            tile[row * ms + o] = v;
+        }
+    };
+    if (vec) {
+        const int vpr = run / 8, nvec = nrows * vpr;
+        for (int v0 = threadIdx.x; v0 < nvec; v0 += 256 * 4) {
+            u32x4 d[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int v = v0 + u * 256;
+                const int row = v / vpr, o = (v - row * vpr) * 8;
+                const bool ok = v < nvec && row_ok(row) && o < valid;
+                d[u] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? (uint32_t)((row_off(row) + o) * 2) : 0x80000000u, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int v = v0 + u * 256;
+                if (v < nvec) {
+                    const int row = v / vpr, o = (v - row * vpr) * 8;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t word = d[u][e >> 1];
+                        const bf16_t val = (bf16_t)((e & 1) ? word >> 16 : word & 0xffffu);
+                        put(row, o + e, (o + e < valid) ? val : (bf16_t)0);
+                    }
+                }
+            }
         }
     } else {
-        // w[r][m][k]: for each r a run of 16*K elements starting at (r0+r)*ld + m0*K
-        const int run = kPackRows * K;
-        const int mvalid = max(0, min(kPackRows, M - m0)) * K;
-        for (int r = wv; r < kChunk; r += 4) {
-            const bool r_ok = r0 + r < R;
-            const bf16_t *src = w + (size_t)(r_ok ? r0 + r : 0) * ld + (size_t)m0 * K;
-            for (int o = lane; o < run; o += 64) {
-                const int m = o / K, k = o - m * K;
-                tile[(m * kChunk + r) * K + (K - 1 - k)] = (r_ok && o < mvalid) ? src[o] : (bf16_t)0;
-            }
+        for (int row = wv; row < nrows; row += 4) {
+            const bool ok = row_ok(row);
+            const bf16_t *src = w + (ok ? row_off(row) : (size_t)0);
+            for (int o = lane; o < run; o += 64) put(row, o, (ok && o < valid) ? src[o] : (bf16_t)0);
         }
     }
     __syncthreads();
@@ -665,7 +698,7 @@ __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__
         const int m16 = idx & 15, half = (idx >> 4) & 1, ks = (idx >> 5) & 1, k = idx >> 6;
         u32x4 out = {0u, 0u, 0u, 0u};
         if (k < K) {
-            const bf16_t *src = tile + (m16 * kChunk + ks * 16 + 8 * half) * K + k;
+            const bf16_t *src = tile + m16 * ms + (ks * 16 + 8 * half) * K + k;
 #pragma unroll
             for (int j = 0; j < 4; ++j) out[j] = (uint32_t)src[(2 * j) * K] | ((uint32_t)src[(2 * j + 1) * K] << 16);
         }
@@ -691,7 +724,7 @@ Plan make_plan(int Tin, int Tout, int R, int K, int stride, int dil)
     pl.stride = stride;
     if (stride != 1 && stride != 2) return pl;
     if (Tin % 8 != 0 || Tout % 8 != 0) return pl;
-    if ((size_t)kPackRows * kChunk * K * sizeof(bf16_t) > (size_t)kMaxLds) return pl;  // weight packing tile
+    if ((size_t)kPackRows * pack_m_stride(K) * sizeof(bf16_t) > (size_t)kMaxLds) return pl;  // weight packing tile
     const int nch = (R + kChunk - 1) / kChunk;
     const int cands[2] = {5, 2};
     for (int ci = 0; ci < 2; ++ci) {
@@ -769,7 +802,7 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
-size_t prepack_lds(int K) { return (size_t)kPackRows * kChunk * K * sizeof(bf16_t); }
+size_t prepack_lds(int K) { return (size_t)kPackRows * pack_m_stride(K) * sizeof(bf16_t); }
 
 // flip == false: W'[m][r][k] = w[m][r][k] (w is [M][R][K]); flip == true: W'[m][r][k] = w[r][m][K-1-k]
 // (w is [R][M][K]).
@@ -778,19 +811,23 @@ hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, bool flip, 
     const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
     const size_t lds = prepack_lds(K);
     const size_t zero_off = (size_t)nmt * nch * ((K + 1) & ~1) * 256;
+    // runs start at multiples of 2*K*(row length) bytes from w: 16-byte aligned when w is and the other
+    // channel count is a multiple of 8 (the tensor must also fit a 32-bit byte offset)
+    const int other = flip ? M : R;
+    const int vec = ((uintptr_t)w % 16 == 0 && other % 8 == 0 && (size_t)M * R * K * 2 < ((size_t)1 << 31)) ? 1 : 0;
     hipError_t e;
     if (flip) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prepack_kernel<true>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, M * K, zero_off);
+                           M, R, K, nch, M * K, zero_off, vec);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(prepack_kernel<false>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, R * K, zero_off);
+                           M, R, K, nch, R * K, zero_off, vec);
     }
     return hipGetLastError();
 }
