@@ -163,7 +163,6 @@ __global__ __launch_bounds__(kThreads) void direct_wgrad_kernel(Geom g, const TS
 
 // Vectorised form of epilogue_bwd_kernel for bf16 tensors whose rows are 16-byte aligned
 // (To % 8 == 0): 8 elements per thread.
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(kThreads) void epilogue_bwd_vec8_kernel(size_t n8, int Cout, int To8,
                                                                      const u32x4_t *__restrict__ dy,
                                                                      const u32x4_t *__restrict__ y,
@@ -172,32 +171,7 @@ __global__ __launch_bounds__(kThreads) void epilogue_bwd_vec8_kernel(size_t n8, 
                                                                      u32x4_t *__restrict__ dres)
 {
     const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n8) return;
-    u32x4_t g = dy[i];
-    if (relu) {
-        const u32x4_t yv = y[i];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            // y > 0 on the bf16 bits: 0x0001..0x7f80 (positive, not zero, not NaN)
-            const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;
-            const uint32_t keep_lo = (lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u;
-            const uint32_t keep_hi = (hi - 1u < 0x7f80u) ? 0xffff0000u : 0u;
-            g[j] &= keep_lo | keep_hi;
-        }
-    }
-    if (dres) dres[i] = g;
-    if (dz) {
-        u32x4_t r = g;
-        if (scale) {
-            const float sc = scale[(int)((i / (size_t)To8) % (size_t)Cout)];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
-                r[j] = pack_bf16x2(g0, g1);
-            }
-        }
-        dz[i] = r;
-    }
+    if (i < n8) epilogue_bwd_vec8_item(i, Cout, To8, dy, y, scale, relu, dz, dres);
 }
 
 template <typename TS>

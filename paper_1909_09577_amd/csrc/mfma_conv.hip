@@ -626,17 +626,16 @@ constexpr int kPackRows = 16;
 // makes the stride an odd number of dwords so that lanes with different m hit different banks
 __host__ __device__ constexpr int pack_m_stride(int K) { return kChunk * K + 2; }
 template <bool FLIP>
-__global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
-                                                      int R, int K, int nch, int ld /* row length of w */,
-                                                      size_t zero_off, int vec /* 16-byte aligned runs */)
+__device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem, const bf16_t *__restrict__ w,
+                                              u32x4 *__restrict__ wp, int M, int R, int K, int nch,
+                                              int ld /* row length of w */, size_t zero_off, int vec /* 16-byte aligned runs */)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as m*ms + r*K + k
     const int ms = pack_m_stride(K);
-    if (blockIdx.x == 0)  // one tap pair of zero weights after the packed tensor
+    if (blk == 0)  // one tap pair of zero weights after the packed tensor
         for (int i = threadIdx.x; i < 512; i += 256) wp[zero_off + i] = u32x4{0u, 0u, 0u, 0u};
-    const int q = blockIdx.x & 3;                      // which 16 channels of the 64
-    const int c = (blockIdx.x >> 2) % nch, mt = (blockIdx.x >> 2) / nch;
+    const int q = blk & 3;                      // which 16 channels of the 64
+    const int c = (blk >> 2) % nch, mt = (blk >> 2) / nch;
     const int m0 = mt * kTileM + q * kPackRows, r0 = c * kChunk;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     // Copy the block of w into LDS.  Rows of w that start on a 16-byte boundary (vec != 0) are read
@@ -692,7 +691,7 @@ __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__
     }
     __syncthreads();
     const int Kp = (K + 1) & ~1;  // an odd K gets one zero tap
-    u32x4 *dst = wp + (size_t)(blockIdx.x >> 2) * Kp * 256;
+    u32x4 *dst = wp + (size_t)(blk >> 2) * Kp * 256;
     const int mi = q >> 1, lane_lo = (q & 1) * 16;
     for (int idx = threadIdx.x; idx < Kp * 64; idx += 256) {
         const int m16 = idx & 15, half = (idx >> 4) & 1, ks = (idx >> 5) & 1, k = idx >> 6;
@@ -703,6 +702,33 @@ __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__
             for (int j = 0; j < 4; ++j) out[j] = (uint32_t)src[(2 * j) * K] | ((uint32_t)src[(2 * j + 1) * K] << 16);
         }
         dst[(k * 4 + ks * 2 + mi) * 64 + half * 32 + lane_lo + m16] = out;
+    }
+}
+
+template <bool FLIP>
+__global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
+                                                      int R, int K, int nch, int ld, size_t zero_off, int vec)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    prepack_block<FLIP>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+}
+
+// Everything the input-gradient engine needs, in one launch: the first npack blocks pack the
+// flipped weights (a latency-bound job), the others run the elementwise epilogue backward
+// (dz and dres; bandwidth bound), so the two overlap instead of following each other.
+__global__ __launch_bounds__(256) void dgrad_prepare_kernel(unsigned npack, const bf16_t *__restrict__ w,
+                                                            u32x4 *__restrict__ wp, int M, int R, int K, int nch,
+                                                            int ld, size_t zero_off, int vec, size_t n8, int Cout,
+                                                            int To8, const u32x4_t *__restrict__ dy,
+                                                            const u32x4_t *__restrict__ y, const float *__restrict__ scale,
+                                                            int relu, u32x4_t *__restrict__ dz, u32x4_t *__restrict__ dres)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (blockIdx.x < npack) {
+        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+    } else {
+        const size_t i = (size_t)(blockIdx.x - npack) * 256 + threadIdx.x;
+        if (i < n8) epilogue_bwd_vec8_item(i, Cout, To8, dy, y, scale, relu, dz, dres);
     }
 }
 
@@ -895,20 +921,38 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
 {
     const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
     if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
-    hipError_t e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, s);
-    if (e != hipSuccess) return e;
-    // one elementwise pass forms dz = dy*[y>0]*scale (bf16) and dres = dy*[y>0]
+    // dz = dy*[y>0]*scale (bf16) and dres = dy*[y>0] come from one elementwise pass; when it can use
+    // 16-byte accesses (To % 8 == 0 on this path, dres aligned) it shares a launch with the weight packing
+    hipError_t e;
     const void *dz = dy;
     const bool need_dz = relu || scale != nullptr;
     void *dzbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
-    if (need_dz || dres) {
-        // To % 8 == 0 on this path; a misaligned dres falls back to the 2-byte kernel
-        if (!dres || ((uintptr_t)dres % 16) == 0)
-            e = launch_epilogue_bwd_vec8(g, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
-        else
-            e = launch_epilogue_bwd(g, true, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
+    if ((need_dz || dres) && (!dres || ((uintptr_t)dres % 16) == 0)) {
+        const int M = g.Cin, R = g.Cout;  // the engine's roles for this pass
+        const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
+        const size_t lds = prepack_lds(g.K);
+        const size_t zero_off = (size_t)nmt * nch * ((g.K + 1) & ~1) * 256;
+        const int vec = ((uintptr_t)w % 16 == 0 && M % 8 == 0 && (size_t)M * R * g.K * 2 < ((size_t)1 << 31)) ? 1 : 0;
+        const unsigned npack = (unsigned)(nmt * nch * 4);
+        const size_t n8 = (size_t)g.B * g.Cout * g.To / 8;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(dgrad_prepare_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(npack + (unsigned)((n8 + 255) / 256)), dim3(256), lds, s, npack,
+                           (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, nch, M * g.K, zero_off, vec, n8, g.Cout, g.To / 8,
+                           (const u32x4_t *)dy, (const u32x4_t *)y, scale, relu ? 1 : 0,
+                           (u32x4_t *)(need_dz ? dzbuf : nullptr), (u32x4_t *)dres);
+        e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (need_dz) dz = dzbuf;
+    } else {
+        e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, s);
+        if (e != hipSuccess) return e;
+        if (need_dz || dres) {  // a misaligned dres: the 2-byte kernel
+            e = launch_epilogue_bwd(g, true, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
+            if (e != hipSuccess) return e;
+            if (need_dz) dz = dzbuf;
+        }
     }
     ConvGemmParams p = {};
     fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad);

@@ -43,6 +43,40 @@ __device__ __forceinline__ void store_from_f32(bf16_t *p, size_t i, float v) { p
 __device__ __forceinline__ float round_to_storage(float v, const float *) { return v; }
 __device__ __forceinline__ float round_to_storage(float v, const bf16_t *) { return bf16_to_f32(f32_to_bf16(v)); }
 
+// Eight consecutive elements (one 16-byte group, index i) of the epilogue backward for bf16 tensors
+// whose rows are 16-byte aligned: g = dy * [y > 0]; dres = g; dz = bf16(g * scale[co]).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void epilogue_bwd_vec8_item(size_t i, int Cout, int To8, const u32x4_t *__restrict__ dy,
+                                                       const u32x4_t *__restrict__ y, const float *__restrict__ scale,
+                                                       int relu, u32x4_t *__restrict__ dz, u32x4_t *__restrict__ dres)
+{
+    u32x4_t g = dy[i];
+    if (relu) {
+        const u32x4_t yv = y[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // y > 0 on the bf16 bits: 0x0001..0x7f80 (positive, not zero, not NaN)
+            const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;
+            const uint32_t keep_lo = (lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u;
+            const uint32_t keep_hi = (hi - 1u < 0x7f80u) ? 0xffff0000u : 0u;
+            g[j] &= keep_lo | keep_hi;
+        }
+    }
+    if (dres) dres[i] = g;
+    if (dz) {
+        u32x4_t r = g;
+        if (scale) {
+            const float sc = scale[(int)((i / (size_t)To8) % (size_t)Cout)];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
+                r[j] = pack_bf16x2(g0, g1);
+            }
+        }
+        dz[i] = r;
+    }
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // One-shot event pair armed by nm_conv1d_time_next_main_kernel (thread local, nm_conv1d_api.hip).
