@@ -31,5 +31,24 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+PROBE_SRC = os.path.join(_PKG, "probes", "mfma_rate.hip")
+PROBE_BIN = os.path.join(_PKG, "probes", "mfma_rate")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Compile the stand-alone MFMA rate probe (an executable, not part of the library)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-o", PROBE_BIN, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    if len(sys.argv) > 1 and sys.argv[1] == "probe":
+        print(build_probe(verbose=True))
+    else:
+        print(build_library(verbose=True))
