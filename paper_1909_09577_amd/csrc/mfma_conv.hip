@@ -188,8 +188,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         uint32_t *dst = reinterpret_cast<uint32_t *>(buf + row * kRowBytes + pp * 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            dst[(2 * j) * kRowDwords] = (xa[j] & 0xffffu) | (xb[j] << 16);
-            dst[(2 * j + 1) * kRowDwords] = (xa[j] >> 16) | (xb[j] & 0xffff0000u);
+            dst[(2 * j) * kRowDwords] = zip_lo16(xa[j], xb[j]);
+            dst[(2 * j + 1) * kRowDwords] = zip_hi16(xa[j], xb[j]);
         }
     };
     // the same with the lane's LDS offsets computed by the caller: lane_lds = ((lane/16)*8 rows,
@@ -199,8 +199,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (active ? lane_lds + (uint32_t)(it * 32 * kRowBytes) : lane_dump));
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            dst[(2 * j) * kRowDwords] = (xa[j] & 0xffffu) | (xb[j] << 16);
-            dst[(2 * j + 1) * kRowDwords] = (xa[j] >> 16) | (xb[j] & 0xffff0000u);
+            dst[(2 * j) * kRowDwords] = zip_lo16(xa[j], xb[j]);
+            dst[(2 * j + 1) * kRowDwords] = zip_hi16(xa[j], xb[j]);
         }
     };
     constexpr int kSlots = 6;      // staging items of the next chunk held in registers

@@ -258,8 +258,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
                 uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kXRowBytes);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    dst[(2 * e) * kXRowDwords] = (xra[q][e] & 0xffffu) | (xrb[q][e] << 16);
-                    dst[(2 * e + 1) * kXRowDwords] = (xra[q][e] >> 16) | (xrb[q][e] & 0xffff0000u);
+                    dst[(2 * e) * kXRowDwords] = zip_lo16(xra[q][e], xrb[q][e]);
+                    dst[(2 * e + 1) * kXRowDwords] = zip_hi16(xra[q][e], xrb[q][e]);
                 }
             }
         }
@@ -457,26 +457,28 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         a.as = (uint32_t)((((size_t)b * p.ncm + (co0 >> 5)) * p.nst + (size_t)chunk * kFastSteps) * 1024);
         return a;
     };
+    auto x_load_item = [&](const UnitAddr &a, int q, u32x4 &xa, u32x4 &xb) {
+        const int t = a.tbase + x_t0 + 32 * q;
+        const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);  // 0 <= t and t + 8 <= T
+        // the lane offset carries the time (it is negative only where t is, and those lanes are masked)
+        xa = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
+        xb = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
+    };
     auto x_load = [&](const UnitAddr &a, u32x4(&xa)[kFastXItems], u32x4(&xb)[kFastXItems]) {
 #pragma unroll
-        for (int q = 0; q < kFastXItems; ++q) {
-            const int t = a.tbase + x_t0 + 32 * q;
-            const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);  // 0 <= t and t + 8 <= T
-            // the lane offset carries the time (it is negative only where t is, and those lanes are masked)
-            xa[q] = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
-            xb[q] = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
+        for (int q = 0; q < kFastXItems; ++q) x_load_item(a, q, xa[q], xb[q]);
+    };
+    auto x_write_item = [&](unsigned char *buf, int q, const u32x4 &xa, const u32x4 &xb) {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kFastXRowBytes);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dst[(2 * e) * (kFastXRowBytes / 4)] = zip_lo16(xa[e], xb[e]);
+            dst[(2 * e + 1) * (kFastXRowBytes / 4)] = zip_hi16(xa[e], xb[e]);
         }
     };
     auto x_write = [&](unsigned char *buf, const u32x4(&xa)[kFastXItems], const u32x4(&xb)[kFastXItems]) {
 #pragma unroll
-        for (int q = 0; q < kFastXItems; ++q) {
-            uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off + q * 32 * kFastXRowBytes);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                dst[(2 * e) * (kFastXRowBytes / 4)] = (xa[q][e] & 0xffffu) | (xb[q][e] << 16);
-                dst[(2 * e + 1) * (kFastXRowBytes / 4)] = (xa[q][e] >> 16) | (xb[q][e] & 0xffff0000u);
-            }
-        }
+        for (int q = 0; q < kFastXItems; ++q) x_write_item(buf, q, xa[q], xb[q]);
     };
     // A fragments of one unit: [mi][step], 1 KiB contiguous per wavefront and fragment
     const uint32_t a_lane = (uint32_t)lane * 16;
@@ -517,9 +519,9 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
     auto unit = [&](int u, int par, u32x4(&afr)[2][kFastSteps], u32x4(&xa)[kFastXItems], u32x4(&xb)[kFastXItems],
                     const u32x4(&xo_a)[kFastXItems], const u32x4(&xo_b)[kFastXItems]) {
         const UnitAddr an = unit_addr(u + 2 * slots);
-        x_load(an, xa, xb);
         wave_lds_fence();
         const unsigned char *xb_ = xb0 + par * kBufBytes;
+        unsigned char *wr = wbuf0 + (par ^ 1) * kBufBytes;
         auto read_b = [&](int st, bf16x8(&bfr)[KA]) {
 #pragma unroll
             for (int kk = 0; kk < KA; ++kk) {
@@ -536,6 +538,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         bf16x8 bq[2][KA];
         read_b(0, bq[0]);
         __builtin_amdgcn_sched_barrier(0);
+        static_assert(kFastXItems == 3 && kFastSteps == 5, "x items ride on steps 0..2 (loads) and 2..4 (writes)");
 #pragma unroll
         for (int st = 0; st < kFastSteps; ++st) {
             if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
@@ -552,19 +555,29 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
             }
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
-            // Issue order inside the step: one LDS read of the next step behind every MFMA of this
-            // one, then the two fragment reloads (left alone, the compiler puts the reads after the
-            // MFMAs, into the registers these have just freed, and waits for them at the next step).
+            // the x traffic of the unit rides on the steps: one item requested in each of the first
+            // three (the window of unit u + 2*slots), one item of the other set written in each of
+            // the last three (the window of unit u + slots, for the next unit)
+            if (st < kFastXItems) x_load_item(an, st, xa[st], xb[st]);
+            if (st >= kFastSteps - kFastXItems) {
+                const int q = st - (kFastSteps - kFastXItems);
+                x_write_item(wr, q, xo_a[q], xo_b[q]);
+            }
+            // Issue order inside the step: behind every MFMA one LDS read of the next step and a
+            // little of the staging work (left alone, the compiler puts the reads after the MFMAs,
+            // into the registers these have just freed, and waits for them at the next step).
 #pragma unroll
             for (int i = 0; i < 2 * KA; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU (addresses, packing)
+                if (i % 3 == 2) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                }
             }
-            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // VMEM read
             __builtin_amdgcn_sched_barrier(0);
         }
-        x_write(wbuf0 + (par ^ 1) * kBufBytes, xo_a, xo_b);
-        __builtin_amdgcn_sched_barrier(0);
     };
     const int npairs = (my_units + 1) >> 1;
     int u = slot_id;

@@ -29,6 +29,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 __device__ __forceinline__ float load_as_f32(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_as_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
 __device__ __forceinline__ void store_from_f32(float *p, size_t i, float v) { p[i] = v; }
+// Interleave two registers of packed 16-bit values: (lo halves of a, b) and (hi halves of a, b), each
+// with a's half in the low 16 bits -- one byte-permute instruction apiece.
+__device__ __forceinline__ uint32_t zip_lo16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t zip_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
 // Two floats to a packed bf16 pair (lo in the low half) with the hardware conversion: round to
 // nearest even like f32_to_bf16, a NaN stays a NaN.
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
