@@ -55,6 +55,7 @@ struct ConvGemmParams {
     int nitems;      // staging items per lane and chunk = ceil(rows/8 * 16 / 64)
     int buf_bytes;   // bytes of one staging buffer: (nitems*32 + kDumpRows) rows of kRowBytes
     int overlap;     // the next tile's first chunk is staged during the current tile
+    int full;        // tiles every wavefront computes on its own, over the whole reduction, before the shared ones
     int relu;
     const bf16_t *in;       // [B][R][Tin]
     const bf16x8 *wp;       // packed weights
@@ -136,23 +137,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         tt = ntile - tc.b * p.ntt;
         finish_coords(tc, tt);
         return tc;
-    };
-    // Coordinates of tile + gridDim.x from those of tile, without divisions: the step is split once
-    // into (channel tiles, time tiles, batch items), for a carry of 0 and of 1 out of the channel tiles.
-    const int step_n = (int)(gridDim.x / (unsigned)p.nmt);
-    const int step_b0 = step_n / p.ntt, step_t0 = step_n % p.ntt;
-    const int step_b1 = (step_n + 1) / p.ntt, step_t1 = (step_n + 1) % p.ntt;
-    auto next_coords = [&](const TileCoords &tc, int &tt) {
-        TileCoords tn;
-        tn.mt = tc.mt + gstep;
-        const bool carry = tn.mt >= p.nmt;
-        tn.mt -= carry ? p.nmt : 0;
-        tt += carry ? step_t1 : step_t0;
-        const bool carry2 = tt >= p.ntt;
-        tt -= carry2 ? p.ntt : 0;
-        tn.b = tc.b + (carry ? step_b1 : step_b0) + (carry2 ? 1 : 0);
-        finish_coords(tn, tt);
-        return tn;
     };
     // Staging loads of chunk c of batch item b, window start ws_al.  The scalar part of the address
     // (batch item, chunk) travels as the scalar offset of the buffer load; lanes whose 8 time steps
@@ -279,20 +263,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     constexpr uint32_t kTapBytes = 4 * 64 * 16;
     const uint32_t chunk_bytes = (uint32_t)p.Kp * kTapBytes;
     auto chunk_off = [&](int mt, int c) { return (uint32_t)(mt * p.nch + c) * chunk_bytes; };
-    int mt_cur = (int)(blockIdx.x % (unsigned)p.nmt);
-    uint32_t w_cur = chunk_off(mt_cur, wave);
-    if constexpr (KT > 0) {
-        if (blockIdx.x < (unsigned)p.num_tiles && nmy > 0) {
-#pragma unroll
-            for (int k = 0; k < NS; ++k)
-#pragma unroll
-                for (int f = 0; f < 4; ++f) wf[k][f] = w_load(w_cur + (uint32_t)k * kTapBytes, f);
-#pragma unroll
-            for (int e = 0; e < NR; ++e)
-#pragma unroll
-                for (int f = 0; f < 4; ++f) wf[NS + e][f] = w_load(w_cur + (uint32_t)(NS * NQ + e) * kTapBytes, f);
-        }
-    }
+    uint32_t w_cur = 0;
 
     // epilogue operands as buffer descriptors; an absent one is empty and reads zeros
     const int out_bytes = (int)((size_t)p.B * p.M * p.Tout * 2);
@@ -306,7 +277,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         __builtin_amdgcn_make_buffer_rsrc((void *)p.shift, 0, p.shift ? p.M * 4 : 0, 0x00020000);
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
-    const int first_tile = blockIdx.x;
     // accumulators: zero here, and again in the epilogue as soon as a tile's values have been handed over
     f32x16 acc[2][NT];
 #pragma unroll
@@ -316,21 +286,56 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    int tt_next = 0;  // time-tile index that belongs to tc_next
-    TileCoords tc_next = tile_coords(first_tile < p.num_tiles ? first_tile : 0, tt_next);
-    if (first_tile < p.num_tiles && nmy > 0 && p.overlap) stage_chunk_now(tc_next.b, wave, tc_next.ws_al, buf_ptr(0));
+    // ---- work items of this wavefront.  First `full` private tiles: tile k*4G + wave*G + blockIdx
+    // (G workgroups), computed by this wavefront alone over every reduction chunk, so they need no
+    // exchange between wavefronts; then the shared tiles 4G*full + blockIdx + j*G, whose reduction
+    // chunks the four wavefronts split (chunk wave, wave+4, ...) and whose partial sums they add
+    // through LDS.  With 1280 tiles on 256 CUs that is one private tile per wavefront and one
+    // shared tile per workgroup: four fifths of the work skip the exchange.  Both numberings keep
+    // tile mod (channel tiles) = blockIdx mod (channel tiles) when G is a multiple of it, i.e.
+    // one slice of the packed weights per XCD.
+    const int G = (int)gridDim.x;
+    const int nA = KT > 0 ? p.full : 0;
+    const int tilesA = nA * kWaves * G;
+    auto item_tile = [&](int k) {
+        return k < nA ? (k * kWaves + wave) * G + (int)blockIdx.x : tilesA + (int)blockIdx.x + (k - nA) * G;
+    };
+    auto first_chunk = [&](bool priv) { return priv ? 0 : wave; };
+    int item = 0, tile = item_tile(0);
+    int tt_unused = 0;
+    TileCoords tc_next = tile_coords(tile < p.num_tiles ? tile : 0, tt_unused);
+    if (tile < p.num_tiles && p.overlap && (nA > 0 || nmy > 0))
+        stage_chunk_now(tc_next.b, first_chunk(nA > 0), tc_next.ws_al, buf_ptr(0));
+    if constexpr (KT > 0) {
+        if (tile < p.num_tiles && (nA > 0 || nmy > 0)) {
+            w_cur = chunk_off(tc_next.mt, first_chunk(nA > 0));
+#pragma unroll
+            for (int k = 0; k < NS; ++k)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) wf[k][f] = w_load(w_cur + (uint32_t)k * kTapBytes, f);
+#pragma unroll
+            for (int e = 0; e < NR; ++e)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) wf[NS + e][f] = w_load(w_cur + (uint32_t)(NS * NQ + e) * kTapBytes, f);
+        }
+    }
 
-    for (int tile = first_tile; tile < p.num_tiles; tile += gridDim.x) {
+    for (; tile < p.num_tiles; ++item) {
+        const bool priv = item < nA;
+        const bool next_priv = item + 1 < nA;
+        const int next_tile = item_tile(item + 1);
         const TileCoords tc = tc_next;
-        const bool next_ok = p.overlap && tile + (int)gridDim.x < p.num_tiles;
-        tc_next = next_coords(tc, tt_next);  // meaningful only while tiles remain; used for staging when next_ok
+        const bool next_ok = p.overlap && next_tile < p.num_tiles;
+        tc_next = tile_coords(next_tile < p.num_tiles ? next_tile : tile, tt_unused);
         const TileCoords tn = tc_next;
+        tile = next_tile;
 
         if (!p.overlap && nmy > 0) stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(cc));
 
-
         if constexpr (KT > 0) {
-            if (nmy > 0) {
+            const int n_ch = priv ? p.nch : nmy;  // chunks of this item for this wavefront
+            auto chunk_of = [&](int i) { return priv ? i : wave + kWaves * i; };
+            if (n_ch > 0) {
                 // ---- unrolled main loop: one chunk (KT taps, 4*NT*KT MFMAs) is a single straight-line
                 // block, so staging loads, staging writes, weight reloads and LDS reads are placed
                 // between the MFMAs by the compiler and every wait counts exactly what is in flight.
@@ -341,15 +346,12 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                 const int lane_off = ((ll & 31) * STRIDE + tc.off0) * kRowBytes + (ll >> 5) * 16;
                 const uint32_t lane_lds = (uint32_t)(((ll >> 4) * 8) * kRowBytes + (ll & 15) * 4);
                 const uint32_t lane_dump = (uint32_t)(nitems * 32 * kRowBytes + (ll & 15) * 4);
-                const bool w_next_tile = tile + (int)gridDim.x < p.num_tiles;
-                int mt_n = mt_cur + gstep;
-                mt_n -= mt_n >= p.nmt ? p.nmt : 0;
-                for (int ci = 0; ci < nmy; ++ci) {
-                    const bool more = ci + 1 < nmy;
+                for (int ci = 0; ci < n_ch; ++ci) {
+                    const bool more = ci + 1 < n_ch;
                     const bool has_t = more || next_ok;  // is there a chunk to stage for
-                    const uint32_t w_nxt = more ? w_cur + kWaves * chunk_bytes : (w_next_tile ? chunk_off(mt_n, wave) : w_cur);
-                    StageAddr sa = stage_addr(more ? tc.b : tn.b, more ? wave + kWaves * (ci + 1) : wave,
-                                              more ? tc.ws_al : tn.ws_al);
+                    const int c_nxt = more ? chunk_of(ci + 1) : first_chunk(next_priv);
+                    const uint32_t w_nxt = has_t ? chunk_off(more ? tc.mt : tn.mt, c_nxt) : w_cur;
+                    StageAddr sa = stage_addr(more ? tc.b : tn.b, c_nxt, more ? tc.ws_al : tn.ws_al);
                     sa.va = has_t ? sa.va : kOutOfRange;
                     sa.vb = has_t ? sa.vb : kOutOfRange;
                     const unsigned char *bbase = buf_ptr(cc) + lane_off;
@@ -400,7 +402,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                     w_cur = w_nxt;
                     ++cc;
                 }
-                mt_cur = mt_n;
             }
         } else if (nmy > 0) {
             // ---- main loop over (chunk, tap pair): 4 k-steps of 16 channels = 8*NT MFMAs per pair
@@ -503,114 +504,158 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             }
         }
 
-        // ---- epilogue.  Wave g finishes accumulator rows [4g, 4g+4) of every 32x32 block: each wave
-        // hands the other three quarters over through LDS, one row of blocks (mi) per round; the
-        // scratch lies in the staging buffers that hold no live data (when the next tile's first
-        // chunk has been staged into parity cc & 1, the other parity).  The sums then go through a
-        // wave-private LDS tile [16 rows][TN] (float32) so that each lane finishes 8 consecutive
-        // time steps of one channel: one 16-byte residual load, one scale, one shift, one 16-byte
-        // store per item (rows of out and res are 16-byte aligned: checked by the host).  Those
-        // loads are requested before the sum; all of them are buffer accesses without branches
-        // (absent operands have empty descriptors and read zeros, masked lanes go out of range).
+        // ---- epilogue.  The sums leave the accumulators through a wave-private LDS tile
+        // [16 rows][TN] (float32) so that each lane finishes 8 consecutive time steps of one
+        // channel: one 16-byte residual load, one scale, one shift, one 16-byte store per item
+        // (rows of out and res are 16-byte aligned: checked by the host).  All of these are buffer
+        // accesses without branches (absent operands have empty descriptors and read zeros,
+        // masked lanes go out of range).  The tile lies in a staging buffer that holds no live
+        // data: when the next item's first chunk has been staged into parity cc & 1, the other one.
         constexpr int kOutItems = NT;  // 16 rows * (TN/8) groups / 64 lanes
         const int el = fresh_lane();  // nothing lane-dependent is kept alive across the main loop for this
-        u32x4 rvec[kOutItems];
-        float scv[kOutItems], shv[kOutItems];
-        uint32_t ooff[kOutItems];
+        const int dead_par = next_ok ? ((cc & 1) ^ 1) : 0;
+        float *tp = reinterpret_cast<float *>(smem + ((size_t)dead_par * kWaves + wave) * p.buf_bytes);
+        struct RowLoads {
+            u32x4 rvec[kOutItems];
+            float scv[kOutItems], shv[kOutItems];
+            uint32_t ooff[kOutItems];
+        };
+        // operands of the 16 tile rows whose first channel is m0 (tile row r is channel m0 + r, or
+        // m0 + 32*(r/8) + r%8 when `split`: eight rows from each row of blocks)
+        auto request_rows = [&](int m0, bool split) {
+            RowLoads ld;
 #pragma unroll
-        for (int q = 0; q < kOutItems; ++q) {
-            const int idx = el + 64 * q;
-            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
-            const int m = tc.mt * kTileM + (r >> 3) * 32 + 8 * wave + (r & 7);
-            const int t = tc.t0 + c8 * 8;
-            const bool ok = m < p.M && t < p.Tout;
-            ooff[q] = ok ? (uint32_t)((((size_t)tc.b * p.M + m) * p.Tout + t) * 2) : kOutOfRange;
-            const uint32_t moff = ok ? (uint32_t)m * 4u : kOutOfRange;
-            rvec[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_res, ooff[q], 0, 0);
-            scv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_scale, moff, 0, 0));
-            shv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_shift, moff, 0, 0));
-        }
-        const bool live0 = next_ok && (cc & 1) == 0;  // parity-0 buffers hold the next tile's first chunk
-        f32x4 *red = reinterpret_cast<f32x4 *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0));
-        // this wave's slice of the dead staging buffers: [16 rows][TN] float32
-        float *tp = reinterpret_cast<float *>(smem + (live0 ? (size_t)kWaves * p.buf_bytes : (size_t)0) +
-                                              (size_t)wave * p.buf_bytes);
-        __syncthreads();  // every wavefront has left the main loop
-        // One copy of the exchange per wave number, so that the accumulator quarters are named
-        // statically and nothing has to be merged between the copies.
-        auto exchange = [&](auto wave_const) {
-            constexpr int G = decltype(wave_const)::value;
-            f32x4 own[2][NT];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-                for (int g = 0; g < kWaves; ++g) {
-                    if (g != G) {
-                        constexpr int slot_lo = G;  // position of this wave among the three senders of quarter g
-                        const int slot = G < g ? slot_lo : slot_lo - 1;
-#pragma unroll
-                        for (int ni = 0; ni < NT; ++ni) {
-                            f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
-                                       acc[mi][ni][4 * g + 3]};
-                            red[((g * 3 + slot) * NT + ni) * 64 + el] = v;
-                        }
-                    }
-                }
-                __syncthreads();
-#pragma unroll
-                for (int ni = 0; ni < NT; ++ni)
-                    own[mi][ni] = f32x4{acc[mi][ni][4 * G], acc[mi][ni][4 * G + 1], acc[mi][ni][4 * G + 2],
-                                        acc[mi][ni][4 * G + 3]};
-#pragma unroll
-                for (int ni = 0; ni < NT; ++ni)  // this row of blocks is done: ready for the next tile
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-#pragma unroll
-                for (int slot = 0; slot < 3; ++slot) {
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((G * 3 + slot) * NT + ni) * 64 + el];
-                }
-                __syncthreads();  // scratch is reused by the next round / the transpose tile / the next tile's staging
+            for (int q = 0; q < kOutItems; ++q) {
+                const int idx = el + 64 * q;
+                const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+                const int m = m0 + (split ? (r >> 3) * 32 + (r & 7) : r);
+                const int t = tc.t0 + c8 * 8;
+                const bool ok = m < p.M && t < p.Tout;
+                ld.ooff[q] = ok ? (uint32_t)((((size_t)tc.b * p.M + m) * p.Tout + t) * 2) : kOutOfRange;
+                const uint32_t moff = ok ? (uint32_t)m * 4u : kOutOfRange;
+                ld.rvec[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_res, ld.ooff[q], 0, 0);
+                ld.scv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_scale, moff, 0, 0));
+                ld.shv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_shift, moff, 0, 0));
             }
-            const int tcol = el & 31;
+            return ld;
+        };
+        // affine, residual, ReLU, rounding and the stores of the 16 rows that sit in the LDS tile
+        auto finish_rows = [&](const RowLoads &ld) {
+#pragma unroll
+            for (int q = 0; q < kOutItems; ++q) {
+                const int idx = el + 64 * q;
+                const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
+                const float sc = has_scale ? ld.scv[q] : 1.f;
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
+                    float v0 = a0 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] << 16);
+                    float v1 = a1 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] & 0xffff0000u);
+                    if (p.relu) {
+                        v0 = v0 > 0.f ? v0 : 0.f;
+                        v1 = v1 > 0.f ? v1 : 0.f;
+                    }
+                    o[e] = pack_bf16x2(v0, v1);
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ld.ooff[q], 0, 0);
+            }
+        };
+        const int tcol = el & 31, thalf = el >> 5;
+
+        if (priv) {
+            // A private tile: this wavefront holds all 64 rows.  Four rounds of 16 rows (row of
+            // blocks mi, accumulator registers 8*gp .. 8*gp+7); the operands of the next round are
+            // requested before the current one is finished.
+            RowLoads ld = request_rows(tc.mt * kTileM, false);
+#pragma unroll
+            for (int rd = 0; rd < 4; ++rd) {
+                const int mi = rd >> 1, gp = rd & 1;
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int r = g * 8 + 4 * thalf + j;
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = acc[mi][ni][4 * (2 * gp + g) + j];
+                    }
+                wave_lds_fence();
+                RowLoads ldn = ld;
+                if (rd < 3) ldn = request_rows(tc.mt * kTileM + (rd + 1) * 16, false);
+                finish_rows(ld);
+                ld = ldn;
+                wave_lds_fence();
+            }
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int r = mi * 8 + 4 * (el >> 5) + j;
+                for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = own[mi][ni][j];
+                    for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+        } else {
+            // A shared tile.  Wave g finishes accumulator rows [4g, 4g+4) of every 32x32 block: each
+            // wave hands the other three quarters over through LDS, one row of blocks (mi) per
+            // round; the scratch is the dead-parity staging buffers of all four wavefronts.  The
+            // operands of this wave's 16 rows are requested before the sum.
+            const RowLoads ld = request_rows(tc.mt * kTileM + 8 * wave, true);
+            f32x4 *red = reinterpret_cast<f32x4 *>(smem + (size_t)dead_par * kWaves * p.buf_bytes);
+            __syncthreads();  // every wavefront has left the main loop
+            // One copy of the exchange per wave number, so that the accumulator quarters are named
+            // statically and nothing has to be merged between the copies.
+            auto exchange = [&](auto wave_const) {
+                constexpr int Gw = decltype(wave_const)::value;
+                f32x4 own[2][NT];
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+                    for (int g = 0; g < kWaves; ++g) {
+                        if (g != Gw) {
+                            const int slot = Gw < g ? Gw : Gw - 1;  // position of this wave among the three senders of quarter g
+#pragma unroll
+                            for (int ni = 0; ni < NT; ++ni) {
+                                f32x4 v = {acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1], acc[mi][ni][4 * g + 2],
+                                           acc[mi][ni][4 * g + 3]};
+                                red[((g * 3 + slot) * NT + ni) * 64 + el] = v;
+                            }
+                        }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni)
+                        own[mi][ni] = f32x4{acc[mi][ni][4 * Gw], acc[mi][ni][4 * Gw + 1], acc[mi][ni][4 * Gw + 2],
+                                            acc[mi][ni][4 * Gw + 3]};
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni)  // this row of blocks is done: ready for the next tile
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+#pragma unroll
+                    for (int slot = 0; slot < 3; ++slot) {
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni) own[mi][ni] += red[((Gw * 3 + slot) * NT + ni) * 64 + el];
+                    }
+                    __syncthreads();  // scratch is reused by the next round / the transpose tile / the next tile's staging
                 }
-        };
-        switch (wave) {
-        case 0: exchange(std::integral_constant<int, 0>{}); break;
-        case 1: exchange(std::integral_constant<int, 1>{}); break;
-        case 2: exchange(std::integral_constant<int, 2>{}); break;
-        default: exchange(std::integral_constant<int, 3>{}); break;
-        }
-        wave_lds_fence();
 #pragma unroll
-        for (int q = 0; q < kOutItems; ++q) {
-            const int idx = el + 64 * q;
-            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
-            const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
-            const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
-            const float sc = has_scale ? scv[q] : 1.f;
-            u32x4 o;
+                for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
-                float v0 = a0 * sc + shv[q] + __uint_as_float(rvec[q][e] << 16);
-                float v1 = a1 * sc + shv[q] + __uint_as_float(rvec[q][e] & 0xffff0000u);
-                if (p.relu) {
-                    v0 = v0 > 0.f ? v0 : 0.f;
-                    v1 = v1 > 0.f ? v1 : 0.f;
-                }
-                o[e] = pack_bf16x2(v0, v1);
+                    for (int j = 0; j < 4; ++j) {
+                        const int r = mi * 8 + 4 * thalf + j;
+#pragma unroll
+                        for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = own[mi][ni][j];
+                    }
+            };
+            switch (wave) {
+            case 0: exchange(std::integral_constant<int, 0>{}); break;
+            case 1: exchange(std::integral_constant<int, 1>{}); break;
+            case 2: exchange(std::integral_constant<int, 2>{}); break;
+            default: exchange(std::integral_constant<int, 3>{}); break;
             }
-            __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ooff[q], 0, 0);
+            wave_lds_fence();
+            finish_rows(ld);
+            wave_lds_fence();
         }
-        wave_lds_fence();
     }
 }
 
@@ -801,15 +846,18 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
     }
     const int grid = p.num_tiles < cus ? p.num_tiles : cus;
+    ConvGemmParams q = p;
+    q.full = KT > 0 ? p.num_tiles / (kWaves * grid) : 0;  // private tiles per wavefront (unrolled kernels only)
     MainKernelTimer timer(s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, q);
     return hipGetLastError();
 }
 
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 {
     // kernel sizes with an unrolled chunk: wide tiles, stride 1, windows that fit the register slots
-    if (pl.nt == 5 && pl.stride == 1 && pl.nitems <= 6) {
+    // and equal chunk counts for the four wavefronts (cross-tile staging)
+    if (pl.nt == 5 && pl.stride == 1 && pl.nitems <= 6 && pl.overlap) {
         switch (p.K) {
 #ifndef NM_ONLY_K17
         case 11: return launch_t<5, 1, 11>(p, pl.lds, s);

@@ -127,6 +127,20 @@ def test_medium_shapes_full_tensor(cfg, dtype, force_direct):
     check_layer(cfg, dtype, force_direct)
 
 
+# 1280 output tiles of 64 channels x 160 steps on 256 CUs: every wavefront computes one tile on its
+# own and every workgroup one more with its reduction split four ways -- both epilogues of the
+# unrolled kernel, compared on the whole tensor (forward for 128->512, input gradient for 512->128).
+PRIVATE_TILES = [
+    L("p_fwd_1280_tiles", 20, 128, 512, 1280, 11, pad=5, residual=True),
+    L("p_dgrad_1280_tiles", 20, 512, 128, 1280, 11, pad=5, residual=True),
+]
+
+
+@pytest.mark.parametrize("cfg", PRIVATE_TILES, ids=lambda c: c.name)
+def test_private_and_shared_tiles_full_tensor(cfg):
+    check_layer(cfg, "bf16", False)
+
+
 def sample_indices(n_total, n, rng, extra=()):
     idx = rng.choice(n_total, size=min(n, n_total), replace=False)
     return np.unique(np.concatenate([idx, np.asarray(list(extra), dtype=np.int64)])).astype(np.int64)
