@@ -567,9 +567,9 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 
         if (priv) {
             // A private tile: this wavefront holds all 64 rows.  Four rounds of 16 rows (row of
-            // blocks mi, accumulator registers 8*gp .. 8*gp+7); the operands of the next round are
-            // requested before the current one is finished.
-            RowLoads ld = request_rows(tc.mt * kTileM, false);
+            // blocks mi, accumulator registers 8*gp .. 8*gp+7); the operands of a round are requested
+            // two rounds ahead.
+            RowLoads ld[2] = {request_rows(tc.mt * kTileM, false), request_rows(tc.mt * kTileM + 16, false)};
 #pragma unroll
             for (int rd = 0; rd < 4; ++rd) {
                 const int mi = rd >> 1, gp = rd & 1;
@@ -582,10 +582,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                         for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = acc[mi][ni][4 * (2 * gp + g) + j];
                     }
                 wave_lds_fence();
-                RowLoads ldn = ld;
-                if (rd < 3) ldn = request_rows(tc.mt * kTileM + (rd + 1) * 16, false);
-                finish_rows(ld);
-                ld = ldn;
+                finish_rows(ld[rd & 1]);
+                if (rd + 2 < 4) ld[rd & 1] = request_rows(tc.mt * kTileM + (rd + 2) * 16, false);  // two rounds ahead
                 wave_lds_fence();
             }
 #pragma unroll
