@@ -48,12 +48,38 @@ def cpu_baseline(cfg_full):
             "sample": f"first {nb} of {cfg_full.B} batch items of the same workload, fp64, fwd+dgrad+wgrad, {dt:.1f} s"}
 
 
+def recorded_traffic(kernel_key):
+    """HBM bytes per launch of a kernel from profiles/hbm_traffic_b3_512_k17.md, or None when that
+    file is missing or the kernel sources have changed since the counters were taken."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_b3_512_k17.md")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"sources_sha256:\s*([0-9a-f]{64})", text)
+    if not m:
+        return None
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1909_09577_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".h")):
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    if h.hexdigest() != m.group(1):
+        return None
+    m = re.search(r"^\|\s*%s\s*\|.*\|\s*([0-9.]+)\s*MB\s*\|\s*$" % re.escape(kernel_key), text, re.M)
+    return float(m.group(1)) * 1e6 if m else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calibration-copies", type=int, default=0,
+                    help="run this many plain 256 MiB copy kernels (dst = src + 1) before the steps (counter runs only: "
+                         "the copy kernel's FETCH_SIZE / WRITE_SIZE per byte moved scale the other kernels' counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -108,6 +134,16 @@ def main():
             nm.nm_conv1d_time_next_main_kernel(*hook["wgrad"])
         nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
 
+    if args.calibration_copies:
+        # an elementwise kernel that reads 256 MiB and writes 256 MiB (a device-to-device memcpy may go
+        # through a DMA engine and never show up as a kernel)
+        src = torch.arange(64 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.calibration_copies):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(max(args.warmup, 1)):
         step({n: warm_pairs[n][i] for n in names})
     torch.cuda.synchronize()
@@ -130,7 +166,7 @@ def main():
                     "wgrad": "wgrad_fast_kernel<6>"}
     achieved = cfg.flops_per_pass / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": recorded_traffic(dominant),
                 "kernel": kernel_names[dominant],
                 "flops_per_launch": cfg.flops_per_pass,
                 "avg_launch_ms": round(dom_ms, 4), "timed_launches": len(pairs),
