@@ -157,12 +157,11 @@ def edge_indices(shape):
     return picks
 
 
-@pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
-def test_full_size_workloads_sampled(cfg):
-    """Full-size bf16 workloads in the launch configuration the benchmark times; the oracle
-    evaluates 4096 sampled elements (plus corners and tile edges) of each output tensor."""
+def check_sampled(cfg, n_act=4096, n_w=2048, seed=99):
+    """One bf16 layer in the launch configuration of its full size; the oracle evaluates sampled
+    elements (plus corners and tile edges) of each output tensor, dres is compared everywhere."""
     dtype = "bf16"
-    rng = np.random.default_rng(99)
+    rng = np.random.default_rng(seed)
     inp = syn.make_inputs(cfg, dtype)
     x64, w64 = inp["x"].astype(np.float64), inp["w"].astype(np.float64)
     scale = inp["scale"] if cfg.affine else None
@@ -172,7 +171,7 @@ def test_full_size_workloads_sampled(cfg):
     To = cfg.T_out
 
     y = U.to_host_f64(run_fwd(cfg, inp, dtype, False)).reshape(-1)
-    idx = sample_indices(y.size, 4096, rng, edge_indices((cfg.B, cfg.Cout, To)))
+    idx = sample_indices(y.size, n_act, rng, edge_indices((cfg.B, cfg.Cout, To)))
     y_ref = orc.block_fwd_at(x64, w64, idx, scale, shift, res, cfg.relu, **kw)
     # rms of the whole output is estimated from the sample (the sample is uniform)
     U.assert_close(y[idx], y_ref, dtype, f"{cfg.name} y (sampled)")
@@ -184,12 +183,39 @@ def test_full_size_workloads_sampled(cfg):
     dz, dres_ref = orc.epilogue_bwd(inp["dy"], inp["y_saved"] if cfg.relu else None, scale, cfg.relu)
     np.testing.assert_array_equal(U.to_host_f64(dres), dres_ref)
     dx = U.to_host_f64(dx).reshape(-1)
-    idx = sample_indices(dx.size, 4096, rng, edge_indices((cfg.B, cfg.Cin, cfg.T)))
+    idx = sample_indices(dx.size, n_act, rng, edge_indices((cfg.B, cfg.Cin, cfg.T)))
     U.assert_close(dx[idx], orc.bwd_data_at(dz, w64, cfg.T, idx, **kw), dtype, f"{cfg.name} dx (sampled)")
     dw = U.to_host_f64(dw).reshape(-1)
-    idx = sample_indices(dw.size, 2048, rng, [0, dw.size - 1, cfg.K - 1, cfg.Cin * cfg.K - 1])
+    idx = sample_indices(dw.size, n_w, rng, [0, dw.size - 1, cfg.K - 1, cfg.Cin * cfg.K - 1])
     U.assert_close(dw[idx], orc.bwd_weight_at(x64, dz, cfg.K, idx, **kw), dtype, f"{cfg.name} dw (sampled)",
                    rms_bound=U.RMS_DW_BF16)
+
+
+@pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
+def test_full_size_workloads_sampled(cfg):
+    """Full-size bf16 workloads in the launch configuration the benchmark times."""
+    check_sampled(cfg)
+
+
+def distinct_stack_layers():
+    """One layer per distinct shape of the 64-layer 10x5 encoder stack (B=32, T=1600 -> 800), each
+    with its own seed from the layer list; shapes already in FULL are left out."""
+    seen = {(c.Cin, c.Cout, c.K, c.stride, c.dilation, c.residual, c.affine, c.relu) for c in FULL}
+    out = []
+    for entry in syn.jasper_10x5_layers():
+        c = entry["cfg"]
+        key = (c.Cin, c.Cout, c.K, c.stride, c.dilation, c.residual, c.affine, c.relu)
+        if key not in seen:
+            seen.add(key)
+            out.append(c)
+    return out
+
+
+@pytest.mark.parametrize("cfg", distinct_stack_layers(), ids=lambda c: f"{c.name}_{c.Cin}to{c.Cout}_k{c.K}")
+def test_stack_layer_shapes_sampled(cfg):
+    """Every distinct layer shape of the full encoder stack at its full size, layer-local: seeded
+    synthetic inputs per layer (no tensor travels from one layer's GPU result into the oracle)."""
+    check_sampled(cfg, n_act=1024, n_w=512, seed=cfg.seed)
 
 
 def test_full_size_f32_mode_sampled():
