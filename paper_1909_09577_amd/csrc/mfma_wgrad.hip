@@ -354,7 +354,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stride-1, dilation-1 weight gradient (every block of the Jasper encoder proper).
+// Stride-1 weight gradient for dilation 1 (every block of the Jasper encoder proper) and 2 (its first
+// epilog layer).
 //
 // Same tiling and split over time as wgrad_kernel, with two changes that cut LDS traffic and
 // instruction count per MFMA:
@@ -365,11 +366,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 //   * a unit is 80 time steps = 5 MFMA steps, fully unrolled: the x window is staged transposed in
 //     64-byte rows (any 4 consecutive rows cover all 64 banks, so the transposing reads are
 //     conflict-free) and every fragment read is `base + immediate`.
-// All KT taps of the group are always multiplied (a short last group computes one unused tap).
+// A last tap group that is one tap short skips that tap; shorter ones multiply unused taps.
 constexpr int kFastTCH = 80;
 constexpr int kFastSteps = kFastTCH / 16;
 constexpr int kFastXRowBytes = 64;
-constexpr int kFastXItems = 3;  // (80 + 5 + 7 -> 96 rows) * 16 channel pairs / 64 lanes
+// x items (32 rows each) of a unit's window: 80 steps + (KT-1)*dilation taps + up to 7 rows of alignment
+constexpr int fast_x_items(int dil) { return dil == 1 ? 3 : 4; }  // 92 rows -> 3, 97 rows (dilation 2, 6 taps) -> 4
 
 __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm, int nst, const bf16_t *__restrict__ dy,
                                                       const bf16_t *__restrict__ y, const float *__restrict__ scale,
@@ -412,12 +414,13 @@ __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm,
 // fragment, right after their last use in unit i: two units of MFMA work for every load.  A wave
 // with an odd number of units runs one more on offsets beyond the tensors: both operands read
 // zeros and nothing is added.
-template <int KT, int KA>
+template <int KT, int KA, int DIL>
 __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *smem, f32x16 (&acc)[2][KT], int sp,
                                            int k0, int co0, int ci0)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int kFastXItems = fast_x_items(DIL);
     constexpr int kRows = kFastXItems * 32;  // rows of one x buffer
     constexpr int kBufBytes = kRows * kFastXRowBytes;
     unsigned char *wbuf0 = smem + (size_t)wave * 2 * kBufBytes;
@@ -433,7 +436,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
     const bool ch_a = ci0 + 2 * x_pp < p.Cin, ch_b = ci0 + 2 * x_pp + 1 < p.Cin;
     const uint32_t x_lds_off = (uint32_t)((x_q * 8) * kFastXRowBytes + x_pp * 4);
     // window start of a unit relative to its first output step: -pad + k0, aligned down to 8
-    const int xs_rel = k0 - p.pad;
+    const int xs_rel = k0 * DIL - p.pad;
     const int xs_rel_al = (xs_rel >> 3) * 8;
     const int off0 = xs_rel - xs_rel_al;
     const uint32_t x_lane_a = ch_a ? (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q + xs_rel_al) * 2) : kFar;
@@ -525,7 +528,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         auto read_b = [&](int st, bf16x8(&bfr)[KA]) {
 #pragma unroll
             for (int kk = 0; kk < KA; ++kk) {
-                const unsigned char *xp = xb_ + (st * 16 + kk) * kFastXRowBytes;
+                const unsigned char *xp = xb_ + (st * 16 + kk * DIL) * kFastXRowBytes;
                 union {
                     s16x4 h[2];
                     bf16x8 v;
@@ -538,7 +541,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         bf16x8 bq[2][KA];
         read_b(0, bq[0]);
         __builtin_amdgcn_sched_barrier(0);
-        static_assert(kFastXItems == 3 && kFastSteps == 5, "x items ride on steps 0..2 (loads) and 2..4 (writes)");
+        static_assert(kFastXItems <= kFastSteps, "one x item rides on a step: loads on the first steps, writes on the last");
 #pragma unroll
         for (int st = 0; st < kFastSteps; ++st) {
             if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
@@ -556,8 +559,8 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
             // the x traffic of the unit rides on the steps: one item requested in each of the first
-            // three (the window of unit u + 2*slots), one item of the other set written in each of
-            // the last three (the window of unit u + slots, for the next unit)
+            // steps (the window of unit u + 2*slots), one item of the other set written in each of
+            // the last steps (the window of unit u + slots, for the next unit)
             if (st < kFastXItems) x_load_item(an, st, xa[st], xb[st]);
             if (st >= kFastSteps - kFastXItems) {
                 const int q = st - (kFastSteps - kFastXItems);
@@ -587,7 +590,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
     }
 }
 
-template <int KT>
+template <int KT, int DIL>
 __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -610,9 +613,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams 
 
     // a last group that is one tap short skips that tap's MFMAs (shorter ones multiply unused taps)
     if (KT > 1 && kt == KT - 1)
-        fast_units<KT, (KT > 1 ? KT - 1 : 1)>(p, smem, acc, sp, k0, co0, ci0);
+        fast_units<KT, (KT > 1 ? KT - 1 : 1), DIL>(p, smem, acc, sp, k0, co0, ci0);
     else
-        fast_units<KT, KT>(p, smem, acc, sp, k0, co0, ci0);
+        fast_units<KT, KT, DIL>(p, smem, acc, sp, k0, co0, ci0);
     reduce_and_store<KT>(p, smem, acc, lane, wave, sp, k0, kt, co0, ci0);
 }
 
@@ -702,7 +705,7 @@ WPlan make_wplan(const Geom &g)
 // The stride-1, dilation-1 kernel applies when rows are 16-byte aligned; its split count.
 bool fast_ok(const Geom &g)
 {
-    if (!(g.stride == 1 && g.dil == 1 && g.T % 8 == 0 && g.To % 8 == 0)) return false;
+    if (!(g.stride == 1 && (g.dil == 1 || g.dil == 2) && g.T % 8 == 0 && g.To % 8 == 0)) return false;
     // both operands are addressed through buffer descriptors with 32-bit offsets
     const size_t lim = (size_t)1 << 30;
     const size_t nst = (size_t)((g.To + kFastTCH - 1) / kFastTCH) * kFastSteps;
@@ -729,7 +732,7 @@ FastPlan make_fast_plan(const Geom &g)
     if (S > units / kWaves) S = units / kWaves;
     if (S < 1) S = 1;
     f.S = (int)S;
-    const size_t stage = (size_t)kWaves * 2 * kFastXItems * 32 * kFastXRowBytes;
+    const size_t stage = (size_t)kWaves * 2 * fast_x_items(g.dil) * 32 * kFastXRowBytes;
     const size_t red = (size_t)kWaves * 3 * (2 * f.KTg) * 64 * sizeof(f32x4);
     f.lds = stage > red ? stage : red;
     return f;
@@ -739,10 +742,10 @@ size_t dzf_bytes(const Geom &g, const FastPlan &f) { return align_up((size_t)g.B
 size_t part_bytes(const Geom &g, int S) { return align_up((size_t)S * g.K * g.Cout * g.Cin * sizeof(float), 256); }
 size_t dz_buf_bytes(const Geom &g) { return align_up((size_t)g.B * g.Cout * g.To * sizeof(bf16_t), 256); }
 
-template <int KT>
+template <int KT, int DIL>
 hipError_t launch_fast_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 {
-    auto kern = wgrad_fast_kernel<KT>;
+    auto kern = wgrad_fast_kernel<KT, DIL>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -805,7 +808,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
         if (e != hipSuccess) return e;
         WgradParams p = {};
         p.B = g.B; p.Cin = g.Cin; p.Cout = g.Cout; p.T = g.T; p.To = g.To; p.K = g.K;
-        p.stride = 1; p.dil = 1; p.pad = g.pad;
+        p.stride = 1; p.dil = g.dil; p.pad = g.pad;
         p.ncot = (g.Cout + kTileCo - 1) / kTileCo;
         p.ncit = (g.Cin + kTileCi - 1) / kTileCi;
         p.ntg = f.ntg; p.KTg = f.KTg; p.S = f.S;
@@ -814,13 +817,24 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
         number_work_items(p);
         p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
         const int grid = p.per_xcd * 8;
-        switch (f.KTg) {
-        case 1: e = launch_fast_kt<1>(p, f.lds, grid, s); break;
-        case 2: e = launch_fast_kt<2>(p, f.lds, grid, s); break;
-        case 3: e = launch_fast_kt<3>(p, f.lds, grid, s); break;
-        case 4: e = launch_fast_kt<4>(p, f.lds, grid, s); break;
-        case 5: e = launch_fast_kt<5>(p, f.lds, grid, s); break;
-        default: e = launch_fast_kt<6>(p, f.lds, grid, s); break;
+        if (g.dil == 1) {
+            switch (f.KTg) {
+            case 1: e = launch_fast_kt<1, 1>(p, f.lds, grid, s); break;
+            case 2: e = launch_fast_kt<2, 1>(p, f.lds, grid, s); break;
+            case 3: e = launch_fast_kt<3, 1>(p, f.lds, grid, s); break;
+            case 4: e = launch_fast_kt<4, 1>(p, f.lds, grid, s); break;
+            case 5: e = launch_fast_kt<5, 1>(p, f.lds, grid, s); break;
+            default: e = launch_fast_kt<6, 1>(p, f.lds, grid, s); break;
+            }
+        } else {
+            switch (f.KTg) {
+            case 1: e = launch_fast_kt<1, 2>(p, f.lds, grid, s); break;
+            case 2: e = launch_fast_kt<2, 2>(p, f.lds, grid, s); break;
+            case 3: e = launch_fast_kt<3, 2>(p, f.lds, grid, s); break;
+            case 4: e = launch_fast_kt<4, 2>(p, f.lds, grid, s); break;
+            case 5: e = launch_fast_kt<5, 2>(p, f.lds, grid, s); break;
+            default: e = launch_fast_kt<6, 2>(p, f.lds, grid, s); break;
+            }
         }
         if (e != hipSuccess) return e;
         dim3 rgrid((g.Cin + 63) / 64, g.Cout);
