@@ -97,6 +97,9 @@ __device__ __forceinline__ void for_each_index(F &&f, std::integer_sequence<int,
     (f(std::integral_constant<int, Is>{}), ...);
 }
 
+// Staging items the unrolled kernel built for K taps keeps in registers; 0: no such kernel.
+__host__ __device__ constexpr int unrolled_slots(int K) { return K == 29 ? 7 : (K == 11 || K == 13 || K == 17 || K == 21 || K == 25) ? 6 : 0; }
+
 struct TileCoords {
     int mt, b, t0, ws_al, off0;
 };
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             dst[(2 * j + 1) * kRowDwords] = zip_hi16(xa[j], xb[j]);
         }
     };
-    constexpr int kSlots = 6;      // staging items of the next chunk held in registers
+    constexpr int kSlots = KT > 0 ? unrolled_slots(KT) : 6;  // staging items of the next chunk held in registers
     u32x4 sxa[kSlots], sxb[kSlots];
     // a whole chunk, nothing to overlap with (first tile, or every tile without cross-tile staging)
     auto stage_chunk_now = [&](int b, int c, int ws_al, unsigned char *buf) {
@@ -782,6 +785,7 @@ struct Plan {
     int nitems;   // staging items per lane; a buffer holds nitems*32 + kDumpRows rows
     int buf_bytes;
     int overlap;  // cross-tile staging possible
+    bool unrolled;  // the kernel instance with an unrolled chunk for this K applies
     size_t lds;
 };
 
@@ -795,25 +799,32 @@ Plan make_plan(int Tin, int Tout, int R, int K, int stride, int dil)
     if (Tin % 8 != 0 || Tout % 8 != 0) return pl;
     if ((size_t)kPackRows * pack_m_stride(K) * sizeof(bf16_t) > (size_t)kMaxLds) return pl;  // weight packing tile
     const int nch = (R + kChunk - 1) / kChunk;
-    const int cands[2] = {5, 2};
-    for (int ci = 0; ci < 2; ++ci) {
-        const int nt = cands[ci];
-        if (ci == 0 && Tout <= 64) continue;  // short sequences: the narrow tile wastes less
-        const long Kp = (K + 1) & ~1;  // the zero tap of an odd K is still read
-        const long rows = (long)(nt * 32 - 1) * stride + (Kp - 1) * dil + 1 + 7;
+    // candidate 0: the kernel with an unrolled chunk (tap counts it is built for, stride 1, wide tile,
+    // equal chunk counts for the four wavefronts); it skips the zero tap of an odd K, so its window
+    // counts K taps.  Candidates 1, 2: the tap-pair loop with the wide, then the narrow tile.
+    for (int ci = 0; ci < 3; ++ci) {
+        const bool unrolled = ci == 0;
+        const int nt = ci == 2 ? 2 : 5;
+        if (nt == 5 && Tout <= 64) continue;  // short sequences: the narrow tile wastes less
+        if (unrolled && !(stride == 1 && unrolled_slots(K) > 0 && nch % kWaves == 0)) continue;
+        const long taps = unrolled ? K : (K + 1) & ~1;  // the tap-pair loop also reads the zero tap of an odd K
+        const long rows = (long)(nt * 32 - 1) * stride + (taps - 1) * dil + 1 + 7;
         const long nitems = ((rows + 7) / 8 * 16 + 63) / 64;
+        if (unrolled && nitems > unrolled_slots(K)) continue;
         const size_t buf = (size_t)(nitems * 32 + kDumpRows) * kRowBytes;
         const size_t stage = (size_t)kWaves * 2 * buf;
         const size_t round_bytes = (size_t)kWaves * 3 * nt * 64 * sizeof(f32x4);  // one row of blocks per round
         // with cross-tile staging the scratch must fit in the buffers of one parity
         const bool overlap = (nch % kWaves == 0) && (kWaves * buf >= round_bytes);
         const size_t lds = stage > round_bytes ? stage : round_bytes;
+        if (unrolled && !overlap) continue;
         if (lds <= (size_t)kMaxLds && buf >= (size_t)16 * nt * 32 * sizeof(float)) {  // buf also holds the output transpose tile
             pl.ok = true;
             pl.nt = nt;
             pl.nitems = (int)nitems;
             pl.buf_bytes = (int)buf;
             pl.overlap = overlap ? 1 : 0;
+            pl.unrolled = unrolled;
             pl.lds = lds;
             return pl;
         }
@@ -853,18 +864,17 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 {
-    // kernel sizes with an unrolled chunk: wide tiles, stride 1, windows that fit the register slots
-    // and equal chunk counts for the four wavefronts (cross-tile staging)
-    if (pl.nt == 5 && pl.stride == 1 && pl.nitems <= 6 && pl.overlap) {
+    if (pl.unrolled) {
         switch (p.K) {
 #ifndef NM_ONLY_K17
         case 11: return launch_t<5, 1, 11>(p, pl.lds, s);
         case 13: return launch_t<5, 1, 13>(p, pl.lds, s);
         case 21: return launch_t<5, 1, 21>(p, pl.lds, s);
         case 25: return launch_t<5, 1, 25>(p, pl.lds, s);
+        case 29: return launch_t<5, 1, 29>(p, pl.lds, s);
 #endif
         case 17: return launch_t<5, 1, 17>(p, pl.lds, s);
-        default: break;
+        default: return hipErrorInvalidValue;
         }
     }
     if (pl.nt == 5 && pl.stride == 1) return launch_t<5, 1, 0>(p, pl.lds, s);
