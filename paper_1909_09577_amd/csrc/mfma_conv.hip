@@ -6,27 +6,30 @@
 // of a stride-1 convolution, (m, r) = (ci, co), W'[ci,co,k] = w[co,ci,K-1-k],
 // padL = dil*(K-1) - pad, in = dz (materialised by the caller of this engine).
 //
-// Work decomposition (one workgroup = 4 wavefronts of 64 lanes, one workgroup per CU,
-// persistent over output tiles):
-//   * an output tile is 64 channels x NT*32 time steps of one batch item;
-//   * the four wavefronts split the reduction channels in chunks of 32 (wave w takes chunks
-//     w, w+4, ...), each accumulating the whole tile in 2*NT 32x32 MFMA accumulators, so the
-//     main loop needs no workgroup barrier; the four partial tiles are summed through LDS
-//     at the end of the tile and each wavefront finishes a quarter of the rows;
-//   * the activation window of a chunk (32 channels x all time steps the K taps touch) is
-//     read once with 16-byte buffer loads along T (lanes outside the row are sent out of range and
-//     read zeros) and written to the wavefront's private LDS region transposed to
-//     [time][channel], so that every tap is a row offset and each MFMA B fragment (8 consecutive
-//     channels of one time step) is one aligned 16-byte LDS read; one staging item of the next
-//     chunk rides on every pair of taps of the current one;
-//   * weights are prepacked once per call into MFMA A-fragment order and stream from L2
-//     straight into registers (each lane reads 16 contiguous bytes, a wavefront 1 KiB); a
-//     fragment register is reloaded for the next tap pair right after its last use;
-//   * the first chunk and first weights of the next tile are requested during the last chunk of
-//     the current one, and the LDS scratch of the cross-wave sum is placed in the staging
-//     buffers that are dead at that moment, so a tile boundary costs little more than the sum;
-//   * tiles are numbered channel-tile fastest, so the workgroups that the hardware places on
-//     one XCD (blockIdx mod 8) keep reusing the same slice of the packed weights in that L2.
+// Work decomposition (one workgroup = 4 wavefronts of 64 lanes, one workgroup per CU, one
+// wavefront per SIMD with up to 512 registers, persistent over work items):
+//   * an output tile is 64 channels x NT*32 time steps of one batch item, accumulated by one
+//     wavefront in 2*NT 32x32 MFMA accumulators;
+//   * work items: every wavefront first computes some tiles on its own over all reduction chunks
+//     (no exchange with the others: the unrolled kernels only), then the four wavefronts of a
+//     workgroup share tiles by splitting the reduction channels in chunks of 32 (wave w takes chunks
+//     w, w+4, ...), sum the four partial tiles through LDS at the end of the tile and finish a
+//     quarter of the rows each; neither form has a workgroup barrier in its main loop;
+//   * the activation window of a chunk (32 channels x all time steps the K taps touch) is read
+//     once with 16-byte buffer loads along T (lanes outside the row are sent out of range and read
+//     zeros) and written to the wavefront's private LDS region transposed to [time][channel], so
+//     that every tap is a row offset and each MFMA B fragment (8 consecutive channels of one time
+//     step) is one aligned 16-byte LDS read; the next chunk (of this work item or the next one) is
+//     staged while the current one is multiplied;
+//   * weights are prepacked once per call into MFMA A-fragment order and stream from L2 straight
+//     into registers (each lane reads 16 contiguous bytes, a wavefront 1 KiB); a fragment register
+//     set is reloaded right after its last use with the data of its next use, across chunks and
+//     work items;
+//   * tiles are numbered channel-tile fastest, so the workgroups that the hardware places on one
+//     XCD (blockIdx mod 8) keep reusing the same slice of the packed weights in that L2.
+// Two forms of the main loop: for the tap counts of the Jasper blocks (KT > 0) a chunk is one
+// straight-line block of 4*NT*KT MFMAs with every load, LDS write and wait placed between them;
+// for any other K (KT == 0) tap pairs run in a loop with staging in out-of-line blocks.
 #include "nm_common.h"
 
 #include <type_traits>
@@ -117,7 +120,6 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     const int nitems = p.nitems;                           // staging items per lane and chunk
     const int nmy = (p.nch - wave + kWaves - 1) / kWaves;  // chunks of this wavefront (may be 0)
     const int P = p.Kp >> 1;                               // tap pairs per chunk
-    const size_t chunk_stride = (size_t)p.Kp * 256;        // bf16x8 per (tile, chunk)
     const int tap_bytes = p.dil * kRowBytes;
     const int gstep = (int)(gridDim.x % (unsigned)p.nmt);  // tile += gridDim.x moves the channel tile by this much
     const __amdgpu_buffer_rsrc_t rs_in =

@@ -361,8 +361,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 // instruction count per MFMA:
 //   * dz is produced directly in MFMA A-fragment order by dz_pack_kernel
 //     ([b][co/32][t/16][lane][8]: lane l holds co = l%32, t = 8*(l/32)+j), so the A fragments of a
-//     whole unit are ten contiguous 1 KiB loads from L2 straight into registers, requested one
-//     unit ahead; only x goes through LDS;
+//     whole unit are ten contiguous 1 KiB loads from L2 straight into registers, requested two
+//     units ahead; only x goes through LDS;
 //   * a unit is 80 time steps = 5 MFMA steps, fully unrolled: the x window is staged transposed in
 //     64-byte rows (any 4 consecutive rows cover all 64 banks, so the transposing reads are
 //     conflict-free) and every fragment read is `base + immediate`.
