@@ -64,7 +64,7 @@ enum {
                             matrix-core kernels (always used for NM_F32) */
 };
 
-enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2 };
+enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2, NM_OP_BWD = 3 };
 
 /* T_out of the convolution (formula above), or NM_ERR_BAD_ARG (<0) if any argument is
  * out of range or no output position exists.  Host only. */
@@ -115,6 +115,17 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
                          const void *x, const void *dy, const void *y, const float *scale,
                          float *dw, unsigned flags, int dtype,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Both gradients of the block in one call (paper Section 3.3: the backward pass of a module).
+ * Same results as nm_conv1d_bwd_data followed by nm_conv1d_bwd_weight on the same arguments,
+ * bit for bit; where the matrix-core kernels apply, the mask-and-scale pass over dy and y that
+ * forms dz runs once and feeds both gradients.  Arguments as for those two calls; dres may be
+ * NULL; workspace of nm_conv1d_workspace_bytes(NM_OP_BWD, ...) bytes.  The one-shot timer of
+ * nm_conv1d_time_next_main_kernel brackets the input-gradient kernel of this call. */
+int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                  const void *x, const void *dy, const void *y, const float *scale, const void *w,
+                  void *dx, void *dres, float *dw, unsigned flags, int dtype,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Measurement aid (no effect on results).  Arms a one-shot timer for the calling thread: the
  * next nm_conv1d_block_fwd / nm_conv1d_bwd_data / nm_conv1d_bwd_weight call made by this thread

@@ -18,10 +18,10 @@ LIB_PATH = os.path.join(_PKG, "libnmconv1d.so")
 NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE = 0, -1, -2, -3, -4
 NM_BF16, NM_F32 = 0, 1
 NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
-NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT = 0, 1, 2
+NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
-           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_data.restype = i
         L.nm_conv1d_bwd_weight.argtypes = [i] * 8 + [vp] * 5 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd_weight.restype = i
+        L.nm_conv1d_bwd.argtypes = [i] * 8 + [vp] * 8 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd.restype = i
         L.nm_conv1d_time_next_main_kernel.argtypes = [vp, vp]
         L.nm_conv1d_time_next_main_kernel.restype = i
         _lib = L
@@ -192,3 +194,32 @@ def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dil
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_bwd_weight")
     return dw
+
+
+def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, stride=1, dilation=1, pad=0,
+                  relu=False, want_dres=False, accumulate=False, force_direct=False, workspace=None, stream=None):
+    """Both gradients in one call; returns (dx, dres, dw)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = dy.shape[2]
+    code = _dtype_code(x)
+    if dx is None:
+        dx = torch.empty((B, Cin, T), dtype=x.dtype, device=x.device)
+    if dres is None and want_dres:
+        dres = torch.empty_like(dy)
+    if dw is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dw")
+        dw = torch.empty((Cout, Cin, K), dtype=torch.float32, device=x.device)
+    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD, dims, code, flags, workspace, x.device)
+    st = lib().nm_conv1d_bwd(
+        *dims, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
+        _ptr(dx, x.dtype, (B, Cin, T), "dx"), _ptr(dres, x.dtype, (B, Cout, To), "dres"),
+        _ptr(dw, torch.float32, (Cout, Cin, K), "dw"), flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bwd")
+    return dx, dres, dw

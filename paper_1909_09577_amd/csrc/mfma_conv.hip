@@ -780,6 +780,55 @@ __global__ __launch_bounds__(256) void dgrad_prepare_kernel(unsigned npack, cons
     }
 }
 
+// The same for a fused backward call: the elementwise part also writes dz in the fragment order
+// of the stride-1 weight-gradient kernel, so dy and y are read once for both gradients.  Its
+// threads are laid out like the fragments (one wavefront per 32 channels x 16 time steps: lane l
+// handles channel l%32, time steps 8*(l/32) .. +7), which makes the fragment stores contiguous.
+__global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const bf16_t *__restrict__ w,
+                                                          u32x4 *__restrict__ wp, int M, int R, int K, int nch, int ld,
+                                                          size_t zero_off, int vec, int B, int Cout, int To, int ncm,
+                                                          int nst, const bf16_t *__restrict__ dy,
+                                                          const bf16_t *__restrict__ y, const float *__restrict__ scale,
+                                                          int relu, u32x4 *__restrict__ dz, u32x4 *__restrict__ dzf,
+                                                          u32x4 *__restrict__ dres)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (blockIdx.x < npack) {
+        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const unsigned frag = (blockIdx.x - npack) * 4 + (threadIdx.x >> 6);  // (b, cm, st), st fastest
+    const unsigned nfrag = (unsigned)B * ncm * nst;
+    if (frag >= nfrag) return;
+    const int st = frag % nst, cm = (frag / nst) % ncm, b = frag / ((unsigned)nst * ncm);
+    const int co = cm * 32 + (lane & 31);
+    const int t = 16 * st + 8 * (lane >> 5);
+    u32x4 g = {0u, 0u, 0u, 0u}, r = {0u, 0u, 0u, 0u};
+    if (co < Cout && t + 8 <= To) {
+        const size_t i = (((size_t)b * Cout + co) * To + t) / 8;  // 16-byte group index
+        g = reinterpret_cast<const u32x4 *>(dy)[i];
+        if (relu) {
+            const u32x4 yv = reinterpret_cast<const u32x4 *>(y)[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
+                g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
+            }
+        }
+        r = g;
+        if (scale) {
+            const float sc = scale[co];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                r[j] = pack_bf16x2(__uint_as_float(g[j] << 16) * sc, __uint_as_float(g[j] & 0xffff0000u) * sc);
+        }
+        if (dres) dres[i] = g;
+        dz[i] = r;
+    }
+    dzf[(size_t)frag * 64 + lane] = r;
+}
+
 struct Plan {
     bool ok;
     int nt;       // NT template value (5 or 2)
@@ -1016,6 +1065,41 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
     fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad);
     p.relu = 0;
     p.in = (const bf16_t *)dz;
+    p.wp = (const bf16x8 *)ws;
+    p.out = (bf16_t *)dx;
+    return launch_plan(pl, p, s);
+}
+
+// ---- fused backward -------------------------------------------------------------------------
+hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
+                              bool relu, void *ws, void *dzf, const DzfLayout &layout, void *dres, hipStream_t s)
+{
+    const int M = g.Cin, R = g.Cout;  // the engine's roles for the input gradient
+    const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
+    const size_t lds = prepack_lds(g.K);
+    const size_t zero_off = (size_t)nmt * nch * ((g.K + 1) & ~1) * 256;
+    const int vec = ((uintptr_t)w % 16 == 0 && M % 8 == 0 && (size_t)M * R * g.K * 2 < ((size_t)1 << 31)) ? 1 : 0;
+    const unsigned npack = (unsigned)(nmt * nch * 4);
+    const size_t nfrag = (size_t)g.B * layout.ncm * layout.nst;
+    void *dzbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_prepare_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bwd_prepare_kernel, dim3(npack + (unsigned)((nfrag + 3) / 4)), dim3(256), lds, s, npack,
+                       (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, nch, M * g.K, zero_off, vec, g.B, g.Cout, g.To,
+                       layout.ncm, layout.nst, (const bf16_t *)dy, (const bf16_t *)y, scale, relu ? 1 : 0,
+                       (u32x4 *)dzbuf, (u32x4 *)dzf, (u32x4 *)dres);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_dgrad_prepared(const Geom &g, void *dx, void *ws, hipStream_t s)
+{
+    const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
+    if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
+    ConvGemmParams p = {};
+    fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad);
+    p.relu = 0;
+    p.in = (const bf16_t *)((unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K));
     p.wp = (const bf16x8 *)ws;
     p.out = (bf16_t *)dx;
     return launch_plan(pl, p, s);

@@ -795,52 +795,74 @@ size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
     return part_bytes(g, w.S) + (need_dz ? dz_buf_bytes(g) : 0);
 }
 
+// ---- stride-1 kernel with dz already in fragment order (dz_pack_kernel's layout) ----------------
+bool mfma_wgrad_fast_supported(const Geom &g) { return fast_ok(g); }
+
+DzfLayout mfma_wgrad_dzf_layout(const Geom &g)
+{
+    const FastPlan f = make_fast_plan(g);
+    DzfLayout l;
+    l.ncm = f.ncm;
+    l.nst = f.nst;
+    l.offset = part_bytes(g, f.S);
+    l.bytes = dzf_bytes(g, f);
+    return l;
+}
+
+hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, bool accumulate, void *ws, hipStream_t s)
+{
+    const FastPlan f = make_fast_plan(g);
+    float *part = (float *)ws;
+    const u32x4 *dzf = (const u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
+    WgradParams p = {};
+    p.B = g.B; p.Cin = g.Cin; p.Cout = g.Cout; p.T = g.T; p.To = g.To; p.K = g.K;
+    p.stride = 1; p.dil = g.dil; p.pad = g.pad;
+    p.ncot = (g.Cout + kTileCo - 1) / kTileCo;
+    p.ncit = (g.Cin + kTileCi - 1) / kTileCi;
+    p.ntg = f.ntg; p.KTg = f.KTg; p.S = f.S;
+    p.TCH = kFastTCH; p.nchunk = f.nchunk; p.units = g.B * f.nchunk;
+    p.ncm = f.ncm; p.nst = f.nst;
+    number_work_items(p);
+    p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
+    const int grid = p.per_xcd * 8;
+    hipError_t e;
+    if (g.dil == 1) {
+        switch (f.KTg) {
+        case 1: e = launch_fast_kt<1, 1>(p, f.lds, grid, s); break;
+        case 2: e = launch_fast_kt<2, 1>(p, f.lds, grid, s); break;
+        case 3: e = launch_fast_kt<3, 1>(p, f.lds, grid, s); break;
+        case 4: e = launch_fast_kt<4, 1>(p, f.lds, grid, s); break;
+        case 5: e = launch_fast_kt<5, 1>(p, f.lds, grid, s); break;
+        default: e = launch_fast_kt<6, 1>(p, f.lds, grid, s); break;
+        }
+    } else {
+        switch (f.KTg) {
+        case 1: e = launch_fast_kt<1, 2>(p, f.lds, grid, s); break;
+        case 2: e = launch_fast_kt<2, 2>(p, f.lds, grid, s); break;
+        case 3: e = launch_fast_kt<3, 2>(p, f.lds, grid, s); break;
+        case 4: e = launch_fast_kt<4, 2>(p, f.lds, grid, s); break;
+        case 5: e = launch_fast_kt<5, 2>(p, f.lds, grid, s); break;
+        default: e = launch_fast_kt<6, 2>(p, f.lds, grid, s); break;
+        }
+    }
+    if (e != hipSuccess) return e;
+    dim3 rgrid((g.Cin + 63) / 64, g.Cout);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, f.S, g.K,
+                       g.Cout, g.Cin, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y, const float *scale,
                              float *dw, bool relu, bool accumulate, void *ws, hipStream_t s)
 {
     if (fast_ok(g)) {
         const FastPlan f = make_fast_plan(g);
-        float *part = (float *)ws;
         u32x4 *dzf = (u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
         hipLaunchKernelGGL(dz_pack_kernel, dim3((f.nst + 3) / 4, f.ncm, g.B), dim3(256), 0, s, g.Cout, g.To, f.ncm,
                            f.nst, (const bf16_t *)dy, (const bf16_t *)y, scale, relu ? 1 : 0, dzf);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        WgradParams p = {};
-        p.B = g.B; p.Cin = g.Cin; p.Cout = g.Cout; p.T = g.T; p.To = g.To; p.K = g.K;
-        p.stride = 1; p.dil = g.dil; p.pad = g.pad;
-        p.ncot = (g.Cout + kTileCo - 1) / kTileCo;
-        p.ncit = (g.Cin + kTileCi - 1) / kTileCi;
-        p.ntg = f.ntg; p.KTg = f.KTg; p.S = f.S;
-        p.TCH = kFastTCH; p.nchunk = f.nchunk; p.units = g.B * f.nchunk;
-        p.ncm = f.ncm; p.nst = f.nst;
-        number_work_items(p);
-        p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
-        const int grid = p.per_xcd * 8;
-        if (g.dil == 1) {
-            switch (f.KTg) {
-            case 1: e = launch_fast_kt<1, 1>(p, f.lds, grid, s); break;
-            case 2: e = launch_fast_kt<2, 1>(p, f.lds, grid, s); break;
-            case 3: e = launch_fast_kt<3, 1>(p, f.lds, grid, s); break;
-            case 4: e = launch_fast_kt<4, 1>(p, f.lds, grid, s); break;
-            case 5: e = launch_fast_kt<5, 1>(p, f.lds, grid, s); break;
-            default: e = launch_fast_kt<6, 1>(p, f.lds, grid, s); break;
-            }
-        } else {
-            switch (f.KTg) {
-            case 1: e = launch_fast_kt<1, 2>(p, f.lds, grid, s); break;
-            case 2: e = launch_fast_kt<2, 2>(p, f.lds, grid, s); break;
-            case 3: e = launch_fast_kt<3, 2>(p, f.lds, grid, s); break;
-            case 4: e = launch_fast_kt<4, 2>(p, f.lds, grid, s); break;
-            case 5: e = launch_fast_kt<5, 2>(p, f.lds, grid, s); break;
-            default: e = launch_fast_kt<6, 2>(p, f.lds, grid, s); break;
-            }
-        }
-        if (e != hipSuccess) return e;
-        dim3 rgrid((g.Cin + 63) / 64, g.Cout);
-        hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, f.S, g.K,
-                           g.Cout, g.Cin, accumulate ? 1 : 0);
-        return hipGetLastError();
+        return launch_mfma_wgrad_prepared(g, x, dw, accumulate, ws, s);
     }
     const WPlan w = make_wplan(g);
     if (!w.ok) return hipErrorInvalidValue;

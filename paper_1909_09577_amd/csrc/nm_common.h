@@ -128,4 +128,25 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
                              const float *scale, float *dw, bool relu, bool accumulate, void *ws,
                              hipStream_t s);
 
+// ---- fused backward: one pass over dy / y feeds both gradients --------------------------------
+// The stride-1 weight-gradient kernel reads dz in MFMA fragment order
+// [B][ncm = 2*ceil(Cout/64)][nst][64 lanes][8]: lane l of block (b, cm, st) holds channel cm*32 + l%32,
+// time steps 16*st + 8*(l/32) .. +7 (zeros outside the tensor).  It lives `offset` bytes into that
+// kernel's workspace (mfma_wgrad_workspace(g, true) bytes in all).
+struct DzfLayout {
+    int ncm, nst;
+    size_t offset, bytes;
+};
+bool mfma_wgrad_fast_supported(const Geom &g);
+DzfLayout mfma_wgrad_dzf_layout(const Geom &g);
+// weight gradient from a workspace whose dz has been written already
+hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, bool accumulate, void *ws,
+                                      hipStream_t s);
+// packs the flipped weights into ws (as launch_mfma_dgrad does) and, in the same launch, forms
+// dz (plain, behind the packed weights in ws), dz in fragment order (dzf) and dres (may be NULL)
+hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
+                              bool relu, void *ws, void *dzf, const DzfLayout &layout, void *dres, hipStream_t s);
+// input gradient from a workspace prepared by launch_bwd_prepare
+hipError_t launch_mfma_dgrad_prepared(const Geom &g, void *dx, void *ws, hipStream_t s);
+
 }  // namespace nm

@@ -131,14 +131,19 @@ size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K,
                                  int pad, int dtype, unsigned flags)
 {
     Geom g;
-    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT) return 0;
+    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT && op != NM_OP_BWD) return 0;
     if (check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g) != NM_OK)
         return 0;
     // The query sees neither the scale pointer nor the alignment of the tensors (misaligned
     // tensors take the plain kernels); it sizes for the larger of the cases.
-    const size_t plain = workspace_for(op, g, dtype, false, true);
-    const size_t fast = use_mfma(op, g, dtype, flags) ? workspace_for(op, g, dtype, true, true) : 0;
-    return plain > fast ? plain : fast;
+    auto one = [&](int o) {
+        const size_t plain = workspace_for(o, g, dtype, false, true);
+        const size_t fast = use_mfma(o, g, dtype, flags) ? workspace_for(o, g, dtype, true, true) : 0;
+        return plain > fast ? plain : fast;
+    };
+    // the fused backward keeps the two gradients' workspaces side by side
+    if (op == NM_OP_BWD) return one(NM_OP_BWD_DATA) + one(NM_OP_BWD_WEIGHT);
+    return one(op);
 }
 
 int nm_conv1d_time_next_main_kernel(void *start_event, void *stop_event)
@@ -261,6 +266,58 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
     }
     MainKernelTimer timer(s);
     return dev(launch_direct_wgrad(g, bf, x, dz, dw, accum, s));
+}
+
+int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                  const void *dy, const void *y, const float *scale, const void *w, void *dx, void *dres, float *dw,
+                  unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
+    if (st == NM_OK && (!x || !dy || !w || !dx || !dw)) st = NM_ERR_BAD_ARG;
+    if (st == NM_OK && (flags & NM_RELU) && !y) st = NM_ERR_BAD_ARG;
+    const size_t need =
+        st == NM_OK ? nm_conv1d_workspace_bytes(NM_OP_BWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags) : 0;
+    if (st == NM_OK) st = check_workspace(workspace, workspace_bytes, need);
+    if (st != NM_OK) {
+        DisarmOnExit disarm;  // an armed timer is consumed by this call whatever happens
+        return st;
+    }
+    const bool relu = (flags & NM_RELU) != 0;
+    const bool fused = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) &&
+                       mfma_wgrad_fast_supported(g) && needs_dz(flags, scale) && aligned16(x) && aligned16(dy) &&
+                       aligned16(dx) && (!relu || aligned16(y)) && (!dres || aligned16(dres));
+    const size_t ws_data = mfma_dgrad_workspace(g);  // only meaningful when fused
+    if (!fused) {
+        // two calls sharing the workspace one after the other (their own argument checks apply)
+        const size_t w1 = nm_conv1d_workspace_bytes(NM_OP_BWD_DATA, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
+        st = nm_conv1d_bwd_data(B, Cin, Cout, T, K, stride, dilation, pad, dy, y, scale, w, dx, dres, flags & ~NM_ACCUM_DW,
+                                dtype, workspace, w1, hip_stream);
+        if (st != NM_OK) return st;
+        return nm_conv1d_bwd_weight(B, Cin, Cout, T, K, stride, dilation, pad, x, dy, y, scale, dw, flags, dtype,
+                                    workspace, workspace_bytes, hip_stream);
+    }
+    DisarmOnExit disarm;
+    const size_t e = elt(dtype);
+    const size_t ndy = (size_t)g.B * g.Cout * g.To * e, nx = (size_t)g.B * g.Cin * g.T * e;
+    const size_t nw = (size_t)g.Cout * g.Cin * g.K * e, ndw = (size_t)g.Cout * g.Cin * g.K * sizeof(float);
+    if (overlap(dx, nx, dy, ndy) || overlap(dx, nx, y, ndy) || overlap(dx, nx, w, nw) || overlap(dx, nx, x, nx) ||
+        overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy) || overlap(dres, ndy, dx, nx) ||
+        overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, nx) || overlap(dw, ndw, dx, nx) ||
+        overlap(dw, ndw, dres, ndy) || overlap(dx, nx, workspace, need) || overlap(dres, ndy, workspace, need) ||
+        overlap(dw, ndw, workspace, need))
+        return NM_ERR_BAD_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    void *ws_w = (unsigned char *)workspace + ws_data;  // the weight gradient's workspace: partials, then dz fragments
+    const DzfLayout layout = mfma_wgrad_dzf_layout(g);
+    hipError_t err = launch_bwd_prepare(g, dy, y, scale, w, relu, workspace, (unsigned char *)ws_w + layout.offset, layout,
+                                        dres, s);
+    if (err != hipSuccess) return NM_ERR_DEVICE;
+    err = launch_mfma_dgrad_prepared(g, dx, workspace, s);  // carries the one-shot timer
+    if (err != hipSuccess) return NM_ERR_DEVICE;
+    t_start_event = nullptr;
+    t_stop_event = nullptr;
+    return dev(launch_mfma_wgrad_prepared(g, x, dw, (flags & NM_ACCUM_DW) != 0, ws_w, s));
 }
 
 }  // extern "C"

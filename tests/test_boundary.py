@@ -15,6 +15,7 @@ FAKE = ctypes.c_void_p(0x1000)        # never dereferenced: every call below fai
 FAKE2 = ctypes.c_void_p(0x7F0000000000)
 FAKE3 = ctypes.c_void_p(0x7E0000000000)
 FAKE4 = ctypes.c_void_p(0x7D0000000000)
+FAKE5 = ctypes.c_void_p(0x7C0000000000)
 
 
 def declared_functions():
@@ -73,7 +74,13 @@ def bwd_weight(dims=None, x=FAKE2, dy=FAKE3, yv=None, dw=FAKE4, flags=0, dtype=0
                                          d["pad"], x, dy, yv, None, dw, flags, dtype, None, 0, None)
 
 
-@pytest.mark.parametrize("call", [fwd, bwd_data, bwd_weight])
+def bwd(dims=None, x=FAKE, dy=FAKE2, yv=None, w=FAKE3, dx=FAKE4, dw=FAKE5, flags=0, dtype=0):
+    d = dict(GOOD, **(dims or {}))
+    return nm.lib().nm_conv1d_bwd(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"],
+                                  x, dy, yv, None, w, dx, None, dw, flags, dtype, None, 0, None)
+
+
+@pytest.mark.parametrize("call", [fwd, bwd_data, bwd_weight, bwd])
 def test_bad_geometry_is_rejected(call):
     for bad in (dict(B=0), dict(Cin=0), dict(Cout=-1), dict(T=0), dict(K=0), dict(stride=0), dict(dilation=0),
                 dict(pad=-1), dict(T=2, K=5, pad=0)):
@@ -96,6 +103,9 @@ def test_null_pointers_are_rejected():
     assert bwd_weight(dy=None) == nm.NM_ERR_BAD_ARG
     assert bwd_weight(dw=None) == nm.NM_ERR_BAD_ARG
     assert bwd_weight(flags=nm.NM_RELU, yv=None) == nm.NM_ERR_BAD_ARG
+    for missing in ("x", "dy", "w", "dx", "dw"):
+        assert bwd(**{missing: None}) == nm.NM_ERR_BAD_ARG, missing
+    assert bwd(flags=nm.NM_RELU, yv=None) == nm.NM_ERR_BAD_ARG
     assert fwd(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG                # flag of another entry point
     assert bwd_data(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG
 

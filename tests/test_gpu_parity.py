@@ -313,3 +313,53 @@ def test_determinism_and_guard_bands():
     for a, b in zip(*outs):
         assert torch.equal(a, b), "results differ between two identical calls"
     assert torch.equal(x, x0) and torch.equal(w, w0)
+
+
+# ---- both gradients in one call ------------------------------------------------------------------
+FUSED = [
+    L("f_ragged", 3, 72, 100, 336, 11, pad=5, residual=True),        # fused path, ragged channel tiles
+    L("f_two_tiles", 2, 128, 192, 320, 17, pad=8, residual=True),
+    L("f_dil2", 2, 96, 80, 248, 9, dilation=2, pad=8),
+    L("f_no_epilogue", 2, 64, 64, 176, 5, pad=6, affine=False, relu=False),  # dz = dy: two calls inside
+    L("f_odd_len", 2, 40, 48, 333, 7, pad=3, residual=True),         # plain kernels: two calls inside
+    L("f_stride2", 2, 64, 96, 400, 11, stride=2, pad=5),
+]
+
+
+@pytest.mark.parametrize("cfg", FUSED, ids=lambda c: c.name)
+def test_fused_backward_equals_the_two_calls_and_the_oracle(cfg):
+    dtype = "bf16"
+    inp = syn.make_inputs(cfg, dtype)
+    scale = U.to_dev(inp, "scale", dtype) if cfg.affine else None
+    x, dy, w = U.to_dev(inp, "x", dtype), U.to_dev(inp, "dy", dtype), U.to_dev(inp, "w", dtype)
+    ysv = U.to_dev(inp, "y_saved", dtype) if cfg.relu else None
+    kw = U.geom_kw(cfg)
+    dx2, dres2 = nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, relu=cfg.relu, want_dres=True, **kw)
+    dw2 = nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=ysv, scale=scale, relu=cfg.relu, **kw)
+    dx1, dres1, dw1 = nm.nm_conv1d_bwd(x, dy, w, y=ysv, scale=scale, relu=cfg.relu, want_dres=True, **kw)
+    for a, b, what in ((dx1, dx2, "dx"), (dres1, dres2, "dres"), (dw1, dw2, "dw")):
+        assert np.array_equal(U.to_host_f64(a), U.to_host_f64(b)), f"{cfg.name}: fused {what} differs from the separate call"
+    # and against the oracle (saved output from the input recipe)
+    dx_ref, dw_ref, dres_ref = U.oracle_bwd(cfg, inp, inp["y_saved"].astype(np.float64))
+    U.assert_close(U.to_host_f64(dx1), dx_ref, dtype, f"{cfg.name} fused dx")
+    U.assert_close(U.to_host_f64(dw1), dw_ref, dtype, f"{cfg.name} fused dw", rms_bound=U.RMS_DW_BF16)
+    np.testing.assert_array_equal(U.to_host_f64(dres1), dres_ref)
+    # accumulation and a call without dres
+    dw_acc = dw2.clone()
+    dx3, none, dw3 = nm.nm_conv1d_bwd(x, dy, w, y=ysv, scale=scale, dw=dw_acc, relu=cfg.relu, accumulate=True, **kw)
+    assert none is None and np.array_equal(U.to_host_f64(dx3), U.to_host_f64(dx2))
+    np.testing.assert_allclose(U.to_host_f64(dw3), 2.0 * U.to_host_f64(dw2), rtol=1e-6, atol=0)
+
+
+def test_fused_backward_full_size_headline_matches_the_two_calls():
+    cfg = syn.HEADLINE
+    dtype = "bf16"
+    inp = syn.make_inputs(cfg, dtype)
+    scale = U.to_dev(inp, "scale", dtype)
+    x, dy, w, ysv = (U.to_dev(inp, n, dtype) for n in ("x", "dy", "w", "y_saved"))
+    kw = U.geom_kw(cfg)
+    dx2, dres2 = nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, relu=True, want_dres=True, **kw)
+    dw2 = nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=ysv, scale=scale, relu=True, **kw)
+    dx1, dres1, dw1 = nm.nm_conv1d_bwd(x, dy, w, y=ysv, scale=scale, relu=True, want_dres=True, **kw)
+    import torch
+    assert torch.equal(dx1, dx2) and torch.equal(dres1, dres2) and torch.equal(dw1, dw2)
