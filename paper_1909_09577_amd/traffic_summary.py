@@ -42,13 +42,15 @@ def per_kernel(path: str, counter: str):
         name = r["Kernel_Name"]
         key = None
         if "conv_gemm_kernel" in name:
-            key = "dgrad" if "dgrad_prepare" in prev else "fwd"
+            key = "dgrad" if "_prepare_kernel" in prev else "fwd"  # the input gradient follows a preparation kernel
         elif "wgrad_fast_kernel" in name or "wgrad_kernel" in name:
             key = "wgrad"
         elif "prepack_kernel" in name:
             key = "weight packing (fwd)"
         elif "dgrad_prepare" in name:
             key = "weight packing + dz/dres pass (dgrad)"
+        elif "bwd_prepare" in name:
+            key = "weight packing + dz pass for both gradients (nm_conv1d_bwd)"
         elif "dz_pack" in name:
             key = "dz pass (wgrad)"
         elif "wgrad_reduce" in name:
@@ -79,7 +81,8 @@ def main():
         "| kernel | launches | fetched MB | written MB | total MB |", "|---|---|---|---|---|",
     ]
     for key in ("fwd", "dgrad", "wgrad", "weight packing (fwd)", "weight packing + dz/dres pass (dgrad)",
-                "dz pass (wgrad)", "dw reduction", "calibration copy"):
+                "weight packing + dz pass for both gradients (nm_conv1d_bwd)", "dz pass (wgrad)", "dw reduction",
+                "calibration copy"):
         if key in fetch and key in write:
             fb = avg(fetch[key]) * 1024.0 * f_scale / 1e6
             wb = avg(write[key]) * 1024.0 * w_scale / 1e6
