@@ -103,6 +103,111 @@ __device__ __forceinline__ void for_each_index(F &&f, std::integer_sequence<int,
 // Staging items the unrolled kernel built for K taps keeps in registers; 0: no such kernel.
 __host__ __device__ constexpr int unrolled_slots(int K) { return K == 29 ? 7 : (K == 11 || K == 13 || K == 17 || K == 21 || K == 25) ? 6 : 0; }
 
+// ---- epilogue shared by the engines of this file ------------------------------------------------
+// The sums leave the accumulators through a wave-private LDS tile [16 rows][NT*32] (float32) so that
+// each lane finishes 8 consecutive time steps of one channel: one 16-byte residual load, one scale,
+// one shift, one 16-byte store per item (rows of out and res are 16-byte aligned: checked by the
+// host).  All of these are buffer accesses without branches: absent operands have empty descriptors
+// and read zeros, masked lanes go out of range.
+template <int NT>
+struct Epilogue {
+    static constexpr int TN = NT * 32;
+    static constexpr int kItems = NT;  // 16 rows * (TN/8) groups / 64 lanes
+    __amdgpu_buffer_rsrc_t rs_out, rs_res, rs_scale, rs_shift;
+    int M, Tout;
+    bool has_scale, relu;
+
+    struct RowLoads {
+        u32x4 rvec[kItems];
+        float scv[kItems], shv[kItems];
+        uint32_t ooff[kItems];
+    };
+
+    __device__ __forceinline__ void init(const bf16_t *out, const bf16_t *res, const float *scale, const float *shift, int B,
+                                         int M_, int Tout_, int relu_)
+    {
+        const int out_bytes = (int)((size_t)B * M_ * Tout_ * 2);
+        M = M_;
+        Tout = Tout_;
+        has_scale = scale != nullptr;
+        relu = relu_ != 0;
+        rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, out_bytes, 0x00020000);
+        rs_res = __builtin_amdgcn_make_buffer_rsrc((void *)res, 0, res ? out_bytes : 0, 0x00020000);
+        rs_scale = __builtin_amdgcn_make_buffer_rsrc((void *)scale, 0, scale ? M_ * 4 : 0, 0x00020000);
+        rs_shift = __builtin_amdgcn_make_buffer_rsrc((void *)shift, 0, shift ? M_ * 4 : 0, 0x00020000);
+    }
+    // operands of the 16 tile rows whose first channel is m0 (tile row r is channel m0 + r, or
+    // m0 + 32*(r/8) + r%8 when `split`: eight rows from each row of blocks); el: the lane number
+    __device__ __forceinline__ RowLoads request_rows(int el, int b, int t0, int m0, bool split) const
+    {
+        RowLoads ld;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) {
+            const int idx = el + 64 * q;
+            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+            const int m = m0 + (split ? (r >> 3) * 32 + (r & 7) : r);
+            const int t = t0 + c8 * 8;
+            const bool ok = m < M && t < Tout;
+            ld.ooff[q] = ok ? (uint32_t)((((size_t)b * M + m) * Tout + t) * 2) : kOutOfRange;
+            const uint32_t moff = ok ? (uint32_t)m * 4u : kOutOfRange;
+            ld.rvec[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_res, ld.ooff[q], 0, 0);
+            ld.scv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_scale, moff, 0, 0));
+            ld.shv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_shift, moff, 0, 0));
+        }
+        return ld;
+    }
+    // affine, residual, ReLU, rounding and the stores of the 16 rows that sit in the LDS tile tp
+    __device__ __forceinline__ void finish_rows(int el, const float *tp, const RowLoads &ld) const
+    {
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) {
+            const int idx = el + 64 * q;
+            const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
+            const float sc = has_scale ? ld.scv[q] : 1.f;
+            u32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
+                float v0 = a0 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] << 16);
+                float v1 = a1 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] & 0xffff0000u);
+                if (relu) {
+                    v0 = v0 > 0.f ? v0 : 0.f;
+                    v1 = v1 > 0.f ? v1 : 0.f;
+                }
+                o[e] = pack_bf16x2(v0, v1);
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ld.ooff[q], 0, 0);
+        }
+    }
+    // A whole 64-row tile held by one wavefront (rows m_first .. m_first+63): four rounds of 16 rows
+    // (row of blocks mi, accumulator registers 8*gp .. 8*gp+7) through tp; the operands of a round
+    // are requested two rounds ahead.
+    __device__ __forceinline__ void store_private_tile(const f32x16 (&acc)[2][NT], float *tp, int el, int b, int t0,
+                                                       int m_first) const
+    {
+        const int tcol = el & 31, thalf = el >> 5;
+        RowLoads ld[2] = {request_rows(el, b, t0, m_first, false), request_rows(el, b, t0, m_first + 16, false)};
+#pragma unroll
+        for (int rd = 0; rd < 4; ++rd) {
+            const int mi = rd >> 1, gp = rd & 1;
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = g * 8 + 4 * thalf + j;
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = acc[mi][ni][4 * (2 * gp + g) + j];
+                }
+            wave_lds_fence();
+            finish_rows(el, tp, ld[rd & 1]);
+            if (rd + 2 < 4) ld[rd & 1] = request_rows(el, b, t0, m_first + (rd + 2) * 16, false);
+            wave_lds_fence();
+        }
+    }
+};
+
 struct TileCoords {
     int mt, b, t0, ws_al, off0;
 };
@@ -270,16 +375,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     auto chunk_off = [&](int mt, int c) { return (uint32_t)(mt * p.nch + c) * chunk_bytes; };
     uint32_t w_cur = 0;
 
-    // epilogue operands as buffer descriptors; an absent one is empty and reads zeros
-    const int out_bytes = (int)((size_t)p.B * p.M * p.Tout * 2);
-    const bool has_scale = p.scale != nullptr;
-    const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, out_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_res =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.res, 0, p.res ? out_bytes : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_scale =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.scale, 0, p.scale ? p.M * 4 : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_shift =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.shift, 0, p.shift ? p.M * 4 : 0, 0x00020000);
+    Epilogue<NT> epi;
+    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu);
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     // accumulators: zero here, and again in the epilogue as soon as a tile's values have been handed over
@@ -509,88 +606,16 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             }
         }
 
-        // ---- epilogue.  The sums leave the accumulators through a wave-private LDS tile
-        // [16 rows][TN] (float32) so that each lane finishes 8 consecutive time steps of one
-        // channel: one 16-byte residual load, one scale, one shift, one 16-byte store per item
-        // (rows of out and res are 16-byte aligned: checked by the host).  All of these are buffer
-        // accesses without branches (absent operands have empty descriptors and read zeros,
-        // masked lanes go out of range).  The tile lies in a staging buffer that holds no live
-        // data: when the next item's first chunk has been staged into parity cc & 1, the other one.
-        constexpr int kOutItems = NT;  // 16 rows * (TN/8) groups / 64 lanes
+        // ---- epilogue (see Epilogue above).  The LDS tile lies in a staging buffer that holds no
+        // live data: when the next item's first chunk has been staged into parity cc & 1, the other one.
         const int el = fresh_lane();  // nothing lane-dependent is kept alive across the main loop for this
         const int dead_par = next_ok ? ((cc & 1) ^ 1) : 0;
         float *tp = reinterpret_cast<float *>(smem + ((size_t)dead_par * kWaves + wave) * p.buf_bytes);
-        struct RowLoads {
-            u32x4 rvec[kOutItems];
-            float scv[kOutItems], shv[kOutItems];
-            uint32_t ooff[kOutItems];
-        };
-        // operands of the 16 tile rows whose first channel is m0 (tile row r is channel m0 + r, or
-        // m0 + 32*(r/8) + r%8 when `split`: eight rows from each row of blocks)
-        auto request_rows = [&](int m0, bool split) {
-            RowLoads ld;
-#pragma unroll
-            for (int q = 0; q < kOutItems; ++q) {
-                const int idx = el + 64 * q;
-                const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
-                const int m = m0 + (split ? (r >> 3) * 32 + (r & 7) : r);
-                const int t = tc.t0 + c8 * 8;
-                const bool ok = m < p.M && t < p.Tout;
-                ld.ooff[q] = ok ? (uint32_t)((((size_t)tc.b * p.M + m) * p.Tout + t) * 2) : kOutOfRange;
-                const uint32_t moff = ok ? (uint32_t)m * 4u : kOutOfRange;
-                ld.rvec[q] = __builtin_amdgcn_raw_buffer_load_b128(rs_res, ld.ooff[q], 0, 0);
-                ld.scv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_scale, moff, 0, 0));
-                ld.shv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_shift, moff, 0, 0));
-            }
-            return ld;
-        };
-        // affine, residual, ReLU, rounding and the stores of the 16 rows that sit in the LDS tile
-        auto finish_rows = [&](const RowLoads &ld) {
-#pragma unroll
-            for (int q = 0; q < kOutItems; ++q) {
-                const int idx = el + 64 * q;
-                const int r = idx / (TN / 8), c8 = idx - r * (TN / 8);
-                const f32x4 lo = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8);
-                const f32x4 hi = *reinterpret_cast<const f32x4 *>(tp + r * TN + c8 * 8 + 4);
-                const float sc = has_scale ? ld.scv[q] : 1.f;
-                u32x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float a0 = (e < 2 ? lo[2 * e] : hi[2 * e - 4]), a1 = (e < 2 ? lo[2 * e + 1] : hi[2 * e - 3]);
-                    float v0 = a0 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] << 16);
-                    float v1 = a1 * sc + ld.shv[q] + __uint_as_float(ld.rvec[q][e] & 0xffff0000u);
-                    if (p.relu) {
-                        v0 = v0 > 0.f ? v0 : 0.f;
-                        v1 = v1 > 0.f ? v1 : 0.f;
-                    }
-                    o[e] = pack_bf16x2(v0, v1);
-                }
-                __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ld.ooff[q], 0, 0);
-            }
-        };
         const int tcol = el & 31, thalf = el >> 5;
 
         if (priv) {
-            // A private tile: this wavefront holds all 64 rows.  Four rounds of 16 rows (row of
-            // blocks mi, accumulator registers 8*gp .. 8*gp+7); the operands of a round are requested
-            // two rounds ahead.
-            RowLoads ld[2] = {request_rows(tc.mt * kTileM, false), request_rows(tc.mt * kTileM + 16, false)};
-#pragma unroll
-            for (int rd = 0; rd < 4; ++rd) {
-                const int mi = rd >> 1, gp = rd & 1;
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int r = g * 8 + 4 * thalf + j;
-#pragma unroll
-                        for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = acc[mi][ni][4 * (2 * gp + g) + j];
-                    }
-                wave_lds_fence();
-                finish_rows(ld[rd & 1]);
-                if (rd + 2 < 4) ld[rd & 1] = request_rows(tc.mt * kTileM + (rd + 2) * 16, false);  // two rounds ahead
-                wave_lds_fence();
-            }
+            // A private tile: this wavefront holds all 64 rows.
+            epi.store_private_tile(acc, tp, el, tc.b, tc.t0, tc.mt * kTileM);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -602,7 +627,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             // wave hands the other three quarters over through LDS, one row of blocks (mi) per
             // round; the scratch is the dead-parity staging buffers of all four wavefronts.  The
             // operands of this wave's 16 rows are requested before the sum.
-            const RowLoads ld = request_rows(tc.mt * kTileM + 8 * wave, true);
+            const auto ld = epi.request_rows(el, tc.b, tc.t0, tc.mt * kTileM + 8 * wave, true);
             f32x4 *red = reinterpret_cast<f32x4 *>(smem + (size_t)dead_par * kWaves * p.buf_bytes);
             __syncthreads();  // every wavefront has left the main loop
             // One copy of the exchange per wave number, so that the accumulator quarters are named
@@ -656,7 +681,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             default: exchange(std::integral_constant<int, 3>{}); break;
             }
             wave_lds_fence();
-            finish_rows(ld);
+            epi.finish_rows(el, tp, ld);
             wave_lds_fence();
         }
     }
