@@ -687,6 +687,226 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     }
 }
 
+// ---- K = 1 (pointwise convolution: a plain GEMM  out[b] = W' . in[b]) ----------------------------
+// With one tap an activation element is used for one output row tile only, so the private staging
+// of conv_gemm_kernel (each wavefront its own chunk) is staging-bound and reads the activations
+// once per 64 output channels.  Here the four wavefronts of a workgroup take four 64-channel row
+// tiles of the same 160 time steps and share the staged activations: a workgroup tile is
+// 256 channels x 160 steps, the reduction runs in stages of 128 channels ([time][channel] in LDS,
+// 272-byte rows, written cooperatively by all 256 lanes with the same transposing scheme), one
+// workgroup barrier per stage.  Stages form one stream across the tiles of a workgroup: stage n is
+// requested during stage n-2 (two register sets), written to LDS buffer n&1 during stage n-1, and
+// each wavefront reloads a weight fragment right after its use with the next stage's.  Every
+// wavefront finishes its own 64 rows (no exchange); the LDS tile of that epilogue lies in the buffer
+// the tile's last stage has just used.  Packed weights: the layout of prepack_kernel (Kp = 2, tap 0).
+constexpr int kPwStageCh = 128;
+constexpr int kPwChunks = kPwStageCh / kChunk;      // 4 chunks of 32 channels per stage
+constexpr int kPwRowBytes = kPwStageCh * 2 + 16;    // 272: any 16 consecutive rows cover all banks with 16-byte reads
+constexpr int kPwRows = 160;                        // time steps per tile (NT = 5)
+constexpr int kPwBufBytes = kPwRows * kPwRowBytes;  // 43520
+constexpr int kPwItems = kPwRows / 8 * (kPwStageCh / 2) / kThreads;  // 5 staging items per lane and stage
+static_assert(kPwItems * kWaves == 20, "20 blocks of 16 channel pairs x 4 time groups");
+constexpr size_t kPwLds = 2 * (size_t)kPwBufBytes;
+
+__global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemmParams p)
+{
+    constexpr int NT = 5, TN = NT * 32;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int T = p.Tout;                                  // == p.Tin
+    const int nmt4 = (p.nmt + kWaves - 1) / kWaves;        // workgroup row tiles
+    const int nst = (p.R + kPwStageCh - 1) / kPwStageCh;   // stages per tile
+    const int ncols = p.ntt * p.B;                         // time tiles of all batch items
+    const int ntiles = nmt4 * ncols;
+    const int G = (int)gridDim.x;
+    // Which tiles a workgroup takes.  Grouped (G a multiple of 8*nmt4): the nmt4 workgroups that need
+    // the same activations run on the same XCD at the same time (XCD = blockIdx % 8), so those are
+    // fetched into that L2 once: workgroup x = 8*j + c takes row tile j % nmt4 of time tile
+    // it*(G/nmt4) + 8*(j/nmt4) + c in its it-th turn.  Otherwise tile x + it*G, row tile fastest.
+    const bool grouped = G % (8 * nmt4) == 0;
+    const int per_turn = grouped ? G / nmt4 : 0;
+    const int col0 = grouped ? 8 * (((int)blockIdx.x >> 3) / nmt4) + ((int)blockIdx.x & 7) : 0;
+    const int my_tiles = grouped ? (col0 < ncols ? (ncols - col0 + per_turn - 1) / per_turn : 0)
+                                 : ((int)blockIdx.x < ntiles ? (ntiles - (int)blockIdx.x + G - 1) / G : 0);
+    const int total = my_tiles * nst;                      // stages in this workgroup's stream
+    if (total == 0) return;
+
+    const __amdgpu_buffer_rsrc_t rs_in =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)((size_t)p.B * p.R * T * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
+    Epilogue<NT> epi;
+    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu);
+
+    // position in the stream: tile coordinates and stage; advanced without divisions except at a tile change
+    struct Pos {
+        bool valid;
+        int tile, mt4, b, t0, s;  // tile: which turn of this workgroup
+    };
+    auto decode = [&](Pos &q) {  // (mt4, b, t0) of turn q.tile; wave-uniform, pinned to scalar registers
+        int ntile, mt4;
+        if (grouped) {
+            ntile = q.tile * per_turn + col0;
+            mt4 = ((int)blockIdx.x >> 3) % nmt4;
+            q.valid = ntile < ncols;
+        } else {
+            const int tile = (int)blockIdx.x + q.tile * G;
+            q.valid = tile < ntiles;
+            ntile = tile / nmt4;
+            mt4 = tile - ntile * nmt4;
+        }
+        ntile = q.valid ? ntile : 0;
+        const int b = ntile / p.ntt;
+        q.mt4 = __builtin_amdgcn_readfirstlane(mt4);
+        q.b = __builtin_amdgcn_readfirstlane(b);
+        q.t0 = __builtin_amdgcn_readfirstlane((ntile - b * p.ntt) * TN);
+    };
+    auto advance = [&](Pos &q) {
+        if (++q.s == nst) {
+            q.s = 0;
+            q.tile += 1;
+            decode(q);
+        }
+    };
+    // ---- activations: the stage is 64 channel pairs x 20 time groups (8 steps each), cut into 20 blocks
+    // of 16 pairs x 4 groups; block 5*wave + it is item `it` of this wavefront: lane = (group, pair), so
+    // a load instruction reads 16 rows x 64 contiguous bytes and a write instruction 16 consecutive
+    // dwords in each of 4 rows
+    u32x4 xa0[kPwItems], xb0[kPwItems], xa1[kPwItems], xb1[kPwItems];
+    auto x_load_item = [&](const Pos &q, int it, u32x4 &xa, u32x4 &xb) {
+        const uint32_t soff = (uint32_t)(q.b * p.R + q.s * kPwStageCh) * (uint32_t)(T * 2);  // < 2^30: checked by the host
+        const int rem = p.R - q.s * kPwStageCh;  // channels left from this stage on
+        const int blk = wave * kPwItems + it;
+        const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
+        const int t = q.t0 + 8 * tg;
+        const bool ok = q.valid && t + 8 <= T;
+        const uint32_t off = (uint32_t)(((2 * pair) * T + t) * 2);
+        xa = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (ok && 2 * pair < rem) ? off : kOutOfRange, soff, 0);
+        xb = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (ok && 2 * pair + 1 < rem) ? off + (uint32_t)(T * 2) : kOutOfRange, soff, 0);
+    };
+    auto x_load = [&](const Pos &q, u32x4(&xa)[kPwItems], u32x4(&xb)[kPwItems]) {
+#pragma unroll
+        for (int it = 0; it < kPwItems; ++it) x_load_item(q, it, xa[it], xb[it]);
+    };
+    auto x_write_item = [&](unsigned char *buf, int it, const u32x4 &xa, const u32x4 &xb) {
+        const int blk = wave * kPwItems + it;
+        const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (8 * tg) * kPwRowBytes + pair * 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dst[(2 * j) * (kPwRowBytes / 4)] = zip_lo16(xa[j], xb[j]);
+            dst[(2 * j + 1) * (kPwRowBytes / 4)] = zip_hi16(xa[j], xb[j]);
+        }
+    };
+    // ---- weights of this wavefront's 64 rows: [chunk of the stage][ks][mi], reloaded in place
+    bf16x8 wf[kPwChunks][2][2];
+    const uint32_t w_lane = (uint32_t)lane * 16;
+    const uint32_t chunk_bytes = (uint32_t)p.Kp * 4 * 64 * 16;
+    auto w_off = [&](const Pos &q, int j) {  // byte offset of chunk j of the stage for this wavefront, or out of range
+        const int mt = q.mt4 * kWaves + wave, c = q.s * kPwChunks + j;
+        return (q.valid && mt < p.nmt && c < p.nch) ? (uint32_t)(mt * p.nch + c) * chunk_bytes : kOutOfRange;
+    };
+    auto w_load = [&](uint32_t off, int f) {
+        // an absent chunk: offset beyond the packed tensor (the hardware returns zeros)
+        return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, w_lane + (uint32_t)f * 1024u + (off == kOutOfRange ? kOutOfRange : 0u),
+                                                                                off == kOutOfRange ? 0u : off, 0));
+    };
+
+    f32x16 acc[2][NT];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    // ---- prologue: stage 0 into buffer 0, stage 1 into the second register set, weights of stage 0
+    Pos q0, q1, q2;  // this stage, the next, the one after
+    q0.tile = 0;  // turn number
+    q0.s = 0;
+    decode(q0);
+    q1 = q0;
+    advance(q1);
+    q2 = q1;
+    advance(q2);
+    {
+#pragma unroll
+        for (int j = 0; j < kPwChunks; ++j) {
+            const uint32_t o = w_off(q0, j);
+#pragma unroll
+            for (int f = 0; f < 4; ++f) wf[j][f >> 1][f & 1] = w_load(o, f);
+        }
+        x_load(q0, xa0, xb0);
+        x_load(q1, xa1, xb1);
+#pragma unroll
+        for (int it = 0; it < kPwItems; ++it) x_write_item(smem, it, xa0[it], xb0[it]);
+        __syncthreads();
+    }
+    const int lane_off = (lane & 31) * kPwRowBytes + (lane >> 5) * 16;
+    // one stage: k even uses buffer 0 / requests into set 0 (whose data, stage k, is in LDS already) and
+    // writes set 1 (stage k+1) into buffer 1; k odd the other way round
+    auto stage = [&](unsigned char *cur, unsigned char *nxt, u32x4(&xa)[kPwItems], u32x4(&xb)[kPwItems],
+                     const u32x4(&xo_a)[kPwItems], const u32x4(&xo_b)[kPwItems]) {
+        const Pos q = q0;
+        const unsigned char *bbase = cur + lane_off;
+        bf16x8 b0[NT], b1[NT];
+        auto read_b = [&](bf16x8(&dst)[NT], int j, int ks) {
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+                dst[ni] = *reinterpret_cast<const bf16x8 *>(bbase + ni * 32 * kPwRowBytes + j * 64 + ks * 32);
+        };
+        read_b(b0, 0, 0);
+        // one k-step: 2*NT MFMAs from fragments (j, ks), which are then reloaded with the next stage's
+        auto kstep = [&](int j, int ks, const bf16x8(&bc)[NT], uint32_t o) {
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+                acc[0][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][ks][0], bc[ni], acc[0][ni], 0, 0, 0);
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+                acc[1][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][ks][1], bc[ni], acc[1][ni], 0, 0, 0);
+            wf[j][ks][0] = w_load(o, ks * 2);
+            wf[j][ks][1] = w_load(o, ks * 2 + 1);
+            // the writes of the next stage ride on the last k-steps (its loads are two stages old)
+            constexpr int first = 2 * kPwChunks - kPwItems;
+            const int step = 2 * j + ks;
+            if (step < kPwItems) x_load_item(q2, step, xa[step], xb[step]);  // the stage after the next, one item per k-step
+            if (step >= first) x_write_item(nxt, step - first, xo_a[step - first], xo_b[step - first]);
+            __builtin_amdgcn_sched_barrier(0);  // keeps every load where it is written
+        };
+#pragma unroll
+        for (int j = 0; j < kPwChunks; ++j) {
+            const uint32_t o = w_off(q1, j);
+            read_b(b1, j, 1);
+            kstep(j, 0, b0, o);
+            if (j + 1 < kPwChunks) read_b(b0, j + 1, 0);
+            kstep(j, 1, b1, o);
+        }
+        __syncthreads();  // stage k+1 is complete in LDS; buffer `cur` may be overwritten
+        if (q.valid && q.s == nst - 1) {
+            // the tile is finished: this wavefront's 64 rows leave through its slice of `cur`
+            const int el = fresh_lane();
+            float *tp = reinterpret_cast<float *>(cur + (size_t)wave * 16 * TN * sizeof(float));
+            epi.store_private_tile(acc, tp, el, q.b, q.t0, (q.mt4 * kWaves + wave) * kTileM);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+            __syncthreads();  // before the next stage writes into `cur`
+        }
+        q0 = q1;
+        q1 = q2;
+        advance(q2);
+    };
+    static_assert(kPwItems <= 2 * kPwChunks, "one staging item per k-step");
+    static_assert((size_t)kWaves * 16 * TN * sizeof(float) <= (size_t)kPwBufBytes, "the epilogue tiles fit one buffer");
+    for (int k = 0; k < total; k += 2) {
+        stage(smem, smem + kPwBufBytes, xa0, xb0, xa1, xb1);
+        stage(smem + kPwBufBytes, smem, xa1, xb1, xa0, xb0);
+    }
+}
+
 // Packed weights: [mt][chunk][tap < Kp][ks][mi][lane][8] (Kp = K rounded up to even, the extra
 // tap is zero); element (lane, j) of fragment (ks, mi) is
 // W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside,
@@ -938,8 +1158,27 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
     return hipGetLastError();
 }
 
+hipError_t launch_pointwise(const ConvGemmParams &p, hipStream_t s)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pointwise_gemm_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwLds);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+    }
+    const int ntiles = (p.nmt + kWaves - 1) / kWaves * p.ntt * p.B;
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL(pointwise_gemm_kernel, dim3(ntiles < cus ? ntiles : cus), dim3(kThreads), kPwLds, s, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 {
+    // one tap, no padding, wide tiles: the GEMM kernel whose wavefronts share the staged activations
+    // (worth it from two 64-channel row tiles on: a single one would leave three wavefronts idle)
+    if (p.K == 1 && p.nmt >= 2 && pl.nt == 5 && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout) return launch_pointwise(p, s);
     if (pl.unrolled) {
         switch (p.K) {
 #ifndef NM_ONLY_K17
