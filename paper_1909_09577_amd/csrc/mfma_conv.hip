@@ -1074,6 +1074,42 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const 
     dzf[(size_t)frag * 64 + lane] = r;
 }
 
+// ---- input gradient of a stride-2 convolution (the encoder's first layer) -------------------------
+// dx[ci, s] only receives taps k with s + pad - k even, so the samples of each parity r form a
+// stride-1 correlation of dz with every second tap:  dx[ci, 2u+r] = sum_co sum_k' w[co,ci,kp_r+2k'] *
+// dz[co, u + c_r - k'],  kp_r = (r+pad) mod 2,  c_r = (r+pad-kp_r)/2.  Each phase runs through the
+// stride-1 engine on its own sub-filter; two small kernels cut the sub-filters out of w and
+// interleave the two phase outputs into dx.
+__global__ __launch_bounds__(256) void tap_subsample_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ w0,
+                                                            bf16_t *__restrict__ w1, size_t rows, int K, int kp0, int K0,
+                                                            int kp1, int K1)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= rows) return;
+    const bf16_t *src = w + i * K;
+    for (int j = 0; j < K0; ++j) w0[i * K0 + j] = src[kp0 + 2 * j];
+    for (int j = 0; j < K1; ++j) w1[i * K1 + j] = src[kp1 + 2 * j];
+}
+
+// dx[row][2u] = a0[row][u], dx[row][2u+1] = a1[row][u]; 8 values of u per thread (U % 8 == 0)
+__global__ __launch_bounds__(256) void interleave2_kernel(const u32x4 *__restrict__ a0, const u32x4 *__restrict__ a1,
+                                                          u32x4 *__restrict__ dx, size_t n8)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const u32x4 e = a0[i], o = a1[i];
+    u32x4 lo, hi;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        lo[2 * j] = zip_lo16(e[j], o[j]);
+        lo[2 * j + 1] = zip_hi16(e[j], o[j]);
+        hi[2 * j] = zip_lo16(e[2 + j], o[2 + j]);
+        hi[2 * j + 1] = zip_hi16(e[2 + j], o[2 + j]);
+    }
+    dx[2 * i] = lo;
+    dx[2 * i + 1] = hi;
+}
+
 struct Plan {
     bool ok;
     int nt;       // NT template value (5 or 2)
@@ -1274,22 +1310,111 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 
 // ---- input gradient (stride 1 only; other strides use the plain kernels) ----------------
 // Workspace: packed (flipped, transposed) weights, then dz when it differs from dy.
+namespace {
+// stride 2 as two stride-1 phases (see tap_subsample_kernel)
+struct Phase2 {
+    int kp[2], K[2], c[2], U;  // first tap, taps, dz offset of each phase; outputs per phase
+    bool ok;
+};
+Phase2 phases_of_stride2(const Geom &g)
+{
+    Phase2 ph = {};
+    if (g.stride != 2 || g.dil != 1 || g.T % 16 != 0 || g.To % 8 != 0) return ph;
+    ph.U = g.T / 2;
+    for (int r = 0; r < 2; ++r) {
+        ph.kp[r] = (r + g.pad) & 1;
+        ph.K[r] = g.K > ph.kp[r] ? (g.K - ph.kp[r] + 1) / 2 : 0;
+        ph.c[r] = (r + g.pad - ph.kp[r]) / 2;
+        if (ph.K[r] < 1) return ph;
+        if (!make_plan(g.To, ph.U, g.Cout, ph.K[r], 1, 1).ok || packed_bytes(g.Cin, g.Cout, ph.K[r]) >= kMaxPacked) return ph;
+    }
+    ph.ok = true;
+    return ph;
+}
+size_t dz_bytes_of(const Geom &g) { return align_up((size_t)g.B * g.Cout * g.To * sizeof(bf16_t), 256); }
+}  // namespace
+
 bool mfma_dgrad_supported(const Geom &g)
 {
-    if (g.stride != 1 || packed_bytes(g.Cin, g.Cout, g.K) >= kMaxPacked) return false;
     if ((size_t)g.B * g.Cout * g.To * sizeof(bf16_t) > kMaxInput) return false;
     if ((size_t)g.B * g.Cin * g.T * sizeof(bf16_t) > kMaxInput) return false;
+    if (g.stride == 2) return phases_of_stride2(g).ok;
+    if (g.stride != 1 || packed_bytes(g.Cin, g.Cout, g.K) >= kMaxPacked) return false;
     return make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil).ok;
 }
 
 size_t mfma_dgrad_workspace(const Geom &g)
 {
-    return packed_bytes(g.Cin, g.Cout, g.K) + align_up((size_t)g.B * g.Cout * g.To * sizeof(bf16_t), 256);
+    if (g.stride == 2) {
+        const Phase2 ph = phases_of_stride2(g);
+        size_t n = dz_bytes_of(g);
+        for (int r = 0; r < 2; ++r)
+            n += align_up((size_t)g.Cout * g.Cin * ph.K[r] * sizeof(bf16_t), 256) + packed_bytes(g.Cin, g.Cout, ph.K[r]) +
+                 align_up((size_t)g.B * g.Cin * ph.U * sizeof(bf16_t), 256);
+        return n;
+    }
+    return packed_bytes(g.Cin, g.Cout, g.K) + dz_bytes_of(g);
 }
+
+namespace {
+hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
+                                     void *dx, void *dres, bool relu, void *ws, hipStream_t s)
+{
+    const Phase2 ph = phases_of_stride2(g);
+    if (!ph.ok) return hipErrorInvalidValue;
+    unsigned char *cur = (unsigned char *)ws;
+    void *dzbuf = cur;
+    cur += dz_bytes_of(g);
+    void *wsub[2], *packed[2], *phase_out[2];
+    for (int r = 0; r < 2; ++r) {
+        wsub[r] = cur;
+        cur += align_up((size_t)g.Cout * g.Cin * ph.K[r] * sizeof(bf16_t), 256);
+        packed[r] = cur;
+        cur += packed_bytes(g.Cin, g.Cout, ph.K[r]);
+        phase_out[r] = cur;
+        cur += align_up((size_t)g.B * g.Cin * ph.U * sizeof(bf16_t), 256);
+    }
+    hipError_t e;
+    const void *dz = dy;
+    const bool need_dz = relu || scale != nullptr;
+    if (need_dz || dres) {
+        if (!dres || ((uintptr_t)dres % 16) == 0)
+            e = launch_epilogue_bwd_vec8(g, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
+        else
+            e = launch_epilogue_bwd(g, true, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
+        if (e != hipSuccess) return e;
+        if (need_dz) dz = dzbuf;
+    }
+    const size_t rows = (size_t)g.Cout * g.Cin;
+    hipLaunchKernelGGL(tap_subsample_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, (const bf16_t *)w,
+                       (bf16_t *)wsub[0], (bf16_t *)wsub[1], rows, g.K, ph.kp[0], ph.K[0], ph.kp[1], ph.K[1]);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    for (int r = 0; r < 2; ++r) {
+        const Plan pl = make_plan(g.To, ph.U, g.Cout, ph.K[r], 1, 1);
+        e = run_prepack(wsub[r], packed[r], g.Cin, g.Cout, ph.K[r], true, s);
+        if (e != hipSuccess) return e;
+        ConvGemmParams p = {};
+        // out[u] = sum_j W'[j] * dz[u - padL + j] with j = K_r-1-k'  ->  padL = K_r - 1 - c_r
+        fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, ph.U, ph.K[r], 1, ph.K[r] - 1 - ph.c[r]);
+        p.relu = 0;
+        p.in = (const bf16_t *)dz;
+        p.wp = (const bf16x8 *)packed[r];
+        p.out = (bf16_t *)phase_out[r];
+        e = launch_plan(pl, p, s);  // the first of the two carries the one-shot timer
+        if (e != hipSuccess) return e;
+    }
+    const size_t n8 = (size_t)g.B * g.Cin * ph.U / 8;
+    hipLaunchKernelGGL(interleave2_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, (const u32x4 *)phase_out[0],
+                       (const u32x4 *)phase_out[1], (u32x4 *)dx, n8);
+    return hipGetLastError();
+}
+}  // namespace
 
 hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
                              void *dx, void *dres, bool relu, void *ws, hipStream_t s)
 {
+    if (g.stride == 2) return launch_mfma_dgrad_stride2(g, dy, y, scale, w, dx, dres, relu, ws, s);
     const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
     if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
     // dz = dy*[y>0]*scale (bf16) and dres = dy*[y>0] come from one elementwise pass; when it can use
