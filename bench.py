@@ -72,6 +72,60 @@ def recorded_traffic(kernel_key):
     return float(m.group(1)) * 1e6 if m else None
 
 
+def stack_report():
+    """Time of one forward+backward step of the whole 64-layer 10x5-shaped stack (B=32, T=1600->800):
+    every distinct layer shape is timed on its own (block forward + nm_conv1d_bwd) and weighted with
+    the number of times it occurs; prints one JSON line.  Not the headline: `--stack` only."""
+    import torch
+    from paper_1909_09577_amd import binding as nm
+    from paper_1909_09577_amd import inputs as syn
+    groups = {}
+    for e in syn.jasper_10x5_layers():
+        c = e["cfg"]
+        key = (c.Cin, c.Cout, c.K, c.stride, c.dilation, c.residual, c.affine, c.relu, c.T)
+        groups.setdefault(key, [0, c])[0] += 1
+    total_ms = total_flop = 0.0
+    rows = []
+    for cnt, c in groups.values():
+        To = c.T_out
+        x = torch.randn(c.B, c.Cin, c.T, device="cuda").bfloat16()
+        w = (torch.randn(c.Cout, c.Cin, c.K, device="cuda") / (c.Cin * c.K) ** 0.5).bfloat16()
+        dy = torch.randn(c.B, c.Cout, To, device="cuda").bfloat16()
+        res = torch.randn(c.B, c.Cout, To, device="cuda").bfloat16() if c.residual else None
+        scale = (torch.rand(c.Cout, device="cuda") + 0.5) if c.affine else None
+        shift = torch.randn(c.Cout, device="cuda") * 0.1 if c.affine else None
+        y = torch.empty(c.B, c.Cout, To, device="cuda", dtype=torch.bfloat16)
+        dx = torch.empty_like(x)
+        dres = torch.empty_like(y) if c.residual else None
+        dw = torch.empty(c.Cout, c.Cin, c.K, device="cuda")
+        kw = dict(stride=c.stride, dilation=c.dilation, pad=c.pad)
+        ws = torch.empty(max(nm.nm_conv1d_workspace_bytes(op, *c.dims(), nm.NM_BF16, nm.NM_RELU) for op in (0, 3)) + 256,
+                         dtype=torch.uint8, device="cuda")
+
+        def step():
+            nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=c.relu, workspace=ws, **kw)
+            nm.nm_conv1d_bwd(x, dy, w, y=y if c.relu else None, scale=scale, dx=dx, dres=dres, dw=dw, relu=c.relu,
+                             workspace=ws, **kw)
+
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = 10
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / n * 1e3
+        total_ms += ms * cnt
+        total_flop += 3 * c.flops_per_pass * cnt
+        rows.append({"layer": f"{c.Cin}->{c.Cout} K={c.K} s={c.stride} d={c.dilation}" + (" +res" if c.residual else ""),
+                     "count": cnt, "ms": round(ms, 4), "TFLOP/s": round(3 * c.flops_per_pass / ms / 1e9, 1)})
+    print(json.dumps({"metric": "10x5 stack fwd+bwd, layer by layer (bf16)", "ms_per_step": round(total_ms, 3),
+                      "value": round(total_flop / total_ms / 1e9, 1), "unit": "TFLOP/s",
+                      "frac_of_bf16_mfma_peak": round(total_flop / total_ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                      "layers": sorted(rows, key=lambda r: -r["ms"] * r["count"])}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +135,8 @@ def main():
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="run this many plain 256 MiB copy kernels (dst = src + 1) before the steps (counter runs only: "
                          "the copy kernel's FETCH_SIZE / WRITE_SIZE per byte moved scale the other kernels' counters)")
+    ap.add_argument("--stack", action="store_true",
+                    help="instead of the headline: time every layer shape of the 64-layer stack (one extra JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -94,6 +150,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     nm.lib()  # fails loudly if the HIP library has not been built
+    if args.stack:
+        stack_report()
+        return
 
     cfg = syn.HEADLINE
     dt = "bf16"
