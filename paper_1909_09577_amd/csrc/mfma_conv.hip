@@ -1188,7 +1188,9 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
     }
     const int grid = p.num_tiles < cus ? p.num_tiles : cus;
     ConvGemmParams q = p;
-    q.full = KT > 0 ? p.num_tiles / (kWaves * grid) : 0;  // private tiles per wavefront (unrolled kernels only)
+    // private tiles per wavefront (unrolled kernels only); a remainder of more than three shared rounds
+    // is cheaper as one more private round in which some wavefronts stay idle (no exchange epilogues)
+    q.full = KT > 0 ? p.num_tiles / (kWaves * grid) + (p.num_tiles % (kWaves * grid) > 3 * grid ? 1 : 0) : 0;
     MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, q);
     return hipGetLastError();
