@@ -126,6 +126,48 @@ def stack_report():
                       "layers": sorted(rows, key=lambda r: -r["ms"] * r["count"])}), flush=True)
 
 
+def decoder_report(steps, warmup, with_cpu):
+    """Decoder tail (1x1 convolution to 29 classes + log-softmax) at the encoder's output size; an
+    HBM-bound step: one JSON line with the achieved bandwidth on its algorithmic bytes.  `--decoder` only."""
+    import numpy as np
+    import torch
+    from paper_1909_09577_amd import binding as nm
+    B, Cin, Ncls, T = 32, 1024, 29, 800
+    x = torch.randn(B, Cin, T, device="cuda").bfloat16()
+    w = (torch.randn(Ncls, Cin, device="cuda") / Cin ** 0.5).bfloat16()
+    bias = torch.randn(Ncls, device="cuda") * 0.5
+    logp = torch.empty(B, Ncls, T, device="cuda")
+    for _ in range(max(warmup, 1)):
+        nm.nm_decoder_logsoftmax_fwd(x, w, bias, logp)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()  # the kernel runs on torch's current stream, the one these events are recorded on
+    for _ in range(steps):
+        nm.nm_decoder_logsoftmax_fwd(x, w, bias, logp)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = x.numel() * 2 + w.numel() * 2 + bias.numel() * 4 + logp.numel() * 4
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    out = {"metric": "decoder tail: 1x1 conv 1024->29 + log-softmax, frames/s", "value": round(B * T / (ms * 1e-3), 1),
+           "unit": "frames/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 5),
+           "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "B=32 Cin=1024 Ncls=29 T=800"},
+           "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                        "frac": round(gbs / 8000.0, 4), "traffic": None, "kernel": "decoder_mfma_kernel",
+                        "bytes_per_launch": nbytes}}
+    if with_cpu:
+        from oracle import decoder_oracle as dorc
+        nb = 8
+        xs, ws, bs = x[:nb].float().cpu().numpy(), w.float().cpu().numpy(), bias.cpu().numpy()
+        t0 = time.perf_counter()
+        dorc.decoder_logsoftmax(xs, ws, bs)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(nb * T / dt, 1), "unit": "frames/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"first {nb} of {B} batch items, float64 numpy, {dt:.2f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +179,8 @@ def main():
                          "the copy kernel's FETCH_SIZE / WRITE_SIZE per byte moved scale the other kernels' counters)")
     ap.add_argument("--stack", action="store_true",
                     help="instead of the headline: time every layer shape of the 64-layer stack (one extra JSON line)")
+    ap.add_argument("--decoder", action="store_true",
+                    help="instead of the headline: the decoder tail (1x1 conv + log-softmax), an HBM-bound step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -152,6 +196,9 @@ def main():
     nm.lib()  # fails loudly if the HIP library has not been built
     if args.stack:
         stack_report()
+        return
+    if args.decoder:
+        decoder_report(args.steps, args.warmup, not args.no_cpu_baseline)
         return
 
     cfg = syn.HEADLINE

@@ -127,6 +127,20 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
                   void *dx, void *dres, float *dw, unsigned flags, int dtype,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Decoder tail (paper Section 4.1.1: the CTC decoder module turns the encoder output into per-frame
+ * log-probabilities over the vocabulary): a 1x1 convolution to Ncls classes followed by a log-softmax
+ * over the classes of every frame,
+ *   z[b,c,t] = sum_ci w[c,ci]*x[b,ci,t] + bias[c],   logp[b,c,t] = z[b,c,t] - log(sum_c' exp(z[b,c',t])).
+ *   x    [B][Cin][T]    in,  dtype
+ *   w    [Ncls][Cin]    in,  dtype
+ *   bias [Ncls] float   in,  NULL means 0
+ *   logp [B][Ncls][T]   out, float
+ * flags: 0 or NM_FORCE_DIRECT.  Needs no workspace.  Device pointers owned by the caller; the call
+ * only enqueues on hip_stream.  Errors as for the other entry points. */
+int nm_decoder_logsoftmax_fwd(int B, int Cin, int Ncls, int T, const void *x, const void *w,
+                              const float *bias, float *logp, unsigned flags, int dtype,
+                              void *hip_stream);
+
 /* Measurement aid (no effect on results).  Arms a one-shot timer for the calling thread: the
  * next nm_conv1d_block_fwd / nm_conv1d_bwd_data / nm_conv1d_bwd_weight call made by this thread
  * records `start_event` immediately before and `stop_event` immediately after its main

@@ -21,7 +21,7 @@ NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
 NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
-           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_weight.restype = i
         L.nm_conv1d_bwd.argtypes = [i] * 8 + [vp] * 8 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd.restype = i
+        L.nm_decoder_logsoftmax_fwd.argtypes = [i] * 4 + [vp] * 4 + [u, i, vp]
+        L.nm_decoder_logsoftmax_fwd.restype = i
         L.nm_conv1d_time_next_main_kernel.argtypes = [vp, vp]
         L.nm_conv1d_time_next_main_kernel.restype = i
         _lib = L
@@ -223,3 +225,19 @@ def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, 
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_bwd")
     return dx, dres, dw
+
+
+def nm_decoder_logsoftmax_fwd(x, w, bias=None, logp=None, *, force_direct=False, stream=None):
+    """logp [B,Ncls,T] float32 = log_softmax over classes of (w @ x + bias); w is [Ncls,Cin]."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Ncls = w.shape[0]
+    code = _dtype_code(x)
+    if logp is None:
+        logp = torch.empty((B, Ncls, T), dtype=torch.float32, device=x.device)
+    st = lib().nm_decoder_logsoftmax_fwd(
+        B, Cin, Ncls, T, _ptr(x, name="x"), _ptr(w, x.dtype, (Ncls, Cin), "w"), _ptr(bias, torch.float32, (Ncls,), "bias"),
+        _ptr(logp, torch.float32, (B, Ncls, T), "logp"), NM_FORCE_DIRECT if force_direct else 0, code, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_decoder_logsoftmax_fwd")
+    return logp

@@ -136,3 +136,15 @@ def test_workspace_is_checked_before_any_launch():
                 if op == nm.NM_OP_FWD:
                     assert fwd(d, ws=ctypes.c_void_p(0x10000100), ws_bytes=n - 1) == nm.NM_ERR_WORKSPACE
                     assert fwd(d, ws=ctypes.c_void_p(0x10000104), ws_bytes=n) == nm.NM_ERR_WORKSPACE
+
+
+def test_decoder_tail_arguments_are_checked():
+    f = nm.lib().nm_decoder_logsoftmax_fwd
+    assert f(2, 64, 29, 16, FAKE, FAKE2, None, None, 0, 0, None) == nm.NM_ERR_BAD_ARG       # no output
+    assert f(2, 64, 29, 16, None, FAKE2, None, FAKE3, 0, 0, None) == nm.NM_ERR_BAD_ARG
+    assert f(2, 64, 29, 16, FAKE, None, None, FAKE3, 0, 0, None) == nm.NM_ERR_BAD_ARG
+    for bad in ((0, 64, 29, 16), (2, 0, 29, 16), (2, 64, 0, 16), (2, 64, 29, 0)):
+        assert f(*bad, FAKE, FAKE2, None, FAKE3, 0, 0, None) == nm.NM_ERR_BAD_ARG
+    assert f(2, 64, 29, 16, FAKE, FAKE2, None, FAKE3, 0, 9, None) == nm.NM_ERR_BAD_ARG      # dtype
+    assert f(2, 64, 29, 16, FAKE, FAKE2, None, FAKE3, nm.NM_RELU, 0, None) == nm.NM_ERR_BAD_ARG  # foreign flag
+    assert f(60000, 60000, 29, 60000, FAKE, FAKE2, None, FAKE3, 0, 0, None) == nm.NM_ERR_UNSUPPORTED
