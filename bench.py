@@ -281,6 +281,42 @@ def main():
     torch.cuda.synchronize()
     ms_fused = (time.perf_counter() - t1) / args.steps * 1e3
 
+    # per-pass times (event pairs around each call, helper kernels included) and a cold variant of the
+    # step: six buffer sets (about 1 GB, four times the 256 MB Infinity Cache) used in rotation, so that
+    # no tensor is found in a cache from the previous step.  Reported beside the headline, which is the
+    # warm step above (the tensors of one layer stay resident between its forward and backward pass).
+    def timed(fn, n):
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    n_pass = max(args.steps // 4, 10)
+    per_pass = {
+        "fwd": timed(lambda: nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw), n_pass),
+        "dgrad": timed(lambda: nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=y, scale=scale, dx=dx, dres=dres, relu=True,
+                                                     workspace=ws, **kw), n_pass),
+        "wgrad": timed(lambda: nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws,
+                                                       **kw), n_pass),
+    }
+    sets = [tuple(torch.empty_like(t).copy_(t) for t in (x, res, dy, y, dx, dres)) for _ in range(6)]
+    state = {"i": 0}
+
+    def cold_step():
+        xs, rs, dys, ys, dxs, drs = sets[state["i"] % len(sets)]
+        state["i"] += 1
+        nm.nm_conv1d_block_fwd(xs, w, scale, shift, rs, y=ys, relu=True, workspace=ws, **kw)
+        nm.nm_conv1d_bwd_data(dys, w, cfg.T, y=ys, scale=scale, dx=dxs, dres=drs, relu=True, workspace=ws, **kw)
+        nm.nm_conv1d_bwd_weight(xs, dys, cfg.K, y=ys, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
+
+    for _ in range(len(sets)):
+        cold_step()
+    ms_cold = timed(cold_step, max(args.steps // 4, 12))
+    del sets
+
     ms_per_step = elapsed / args.steps * 1e3
     flops_step = 3 * cfg.flops_per_pass
     value = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -304,6 +340,10 @@ def main():
         "config": {"workload": "Jasper B3-shaped block: B=32 Cin=Cout=512 T=800 K=17 stride 1 dilation 1 pad 8, "
                                "affine+residual+ReLU, fwd+dgrad(+dres)+wgrad", "seed": cfg.seed},
         "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "per_pass_ms": {n: round(v, 4) for n, v in per_pass.items()},
+        "per_pass_tflops": {n: round(cfg.flops_per_pass / (v * 1e-3) / 1e12, 1) for n, v in per_pass.items()},
+        "cold": {"ms_per_step": round(ms_cold, 4), "value": round(flops_step / (ms_cold * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+                 "note": "six rotating sets of activation tensors (about 1 GB), nothing cached from the previous step"},
         "fused_backward": {"ms_per_step": round(ms_fused, 4), "value": round(flops_step / (ms_fused * 1e-3) / 1e12, 2),
                            "unit": "TFLOP/s", "note": "same step with nm_conv1d_bwd (one dz pass for both gradients)"},
         "roofline": roofline,
