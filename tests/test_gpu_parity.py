@@ -363,3 +363,33 @@ def test_fused_backward_full_size_headline_matches_the_two_calls():
     dx1, dres1, dw1 = nm.nm_conv1d_bwd(x, dy, w, y=ysv, scale=scale, relu=True, want_dres=True, **kw)
     import torch
     assert torch.equal(dx1, dx2) and torch.equal(dres1, dres2) and torch.equal(dw1, dw2)
+
+
+# ---- seeded random geometries ---------------------------------------------------------------------
+def random_layers(n, seed):
+    """Random small layers whose time lengths keep them on the matrix-core kernels (multiples of 16),
+    drawn so that every kernel family is hit: unrolled and tap-pair engines, private and shared tiles,
+    the K=1 GEMM, stride-2 forward and input gradient, dilations 1-3, ragged channel counts."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        K = int(rng.choice([1, 2, 3, 5, 7, 11, 13, 17, 21, 25, 29]))
+        stride = int(rng.choice([1, 1, 1, 2]))
+        dil = int(rng.choice([1, 1, 2, 3])) if K > 1 else 1
+        T = 16 * int(rng.integers(2, 30))
+        pad_same = dil * (K - 1) // 2
+        pad = int(rng.choice([pad_same, pad_same, 0, pad_same + 3]))
+        if T + 2 * pad - dil * (K - 1) - 1 < 0:
+            pad = pad_same
+        Cin = int(rng.choice([8, 24, 32, 64, 96, 128, 136, 256]))
+        Cout = int(rng.choice([5, 29, 64, 72, 128, 160, 256]))
+        B = int(rng.integers(1, 4))
+        out.append(L(f"r{i}_b{B}_{Cin}to{Cout}_t{T}_k{K}_s{stride}_d{dil}_p{pad}", B, Cin, Cout, T, K, stride=stride,
+                     dilation=dil, pad=pad, affine=bool(rng.integers(0, 2)), relu=bool(rng.integers(0, 2)),
+                     residual=bool(rng.integers(0, 2)), seed=1000 + i))
+    return out
+
+
+@pytest.mark.parametrize("cfg", random_layers(36, 2024), ids=lambda c: c.name)
+def test_random_geometries_full_tensor(cfg):
+    check_layer(cfg, "bf16", False)
