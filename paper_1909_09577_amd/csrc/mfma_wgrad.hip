@@ -93,7 +93,14 @@ __device__ __forceinline__ TileCoords decode_tile(const WgradParams &p)
     const int v = xcd * p.per_xcd + j;
     tc.valid = !(j >= p.per_xcd || v >= p.total);
     int r = tc.valid ? v : 0;
-    if (p.CL > 0) {
+    if (p.CL < 0) {
+        // digits, slowest to fastest: sp, tg, cit, cot (the kernel with shared staging: one XCD then holds
+        // all output-channel tiles of a few input-channel tiles, so x is fetched into one L2 only)
+        tc.cot = r % p.ncot; r /= p.ncot;
+        tc.cit = r % p.ncit; r /= p.ncit;
+        tc.tg = r % p.ntg; r /= p.ntg;
+        tc.sp = r;
+    } else if (p.CL > 0) {
         // digits, slowest to fastest: sp, cot_hi, tg, cot_lo, cit
         tc.cit = r % p.ncit; r /= p.ncit;
         const int cot_lo = r % p.CL; r /= p.CL;
@@ -619,6 +626,206 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams 
     reduce_and_store<KT>(p, smem, acc, lane, wave, sp, k0, kt, co0, ci0);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stride-1 weight gradient with the taps split over the wavefronts.
+//
+// In wgrad_fast_kernel every wavefront stages its own x window, and a staged element serves only
+// 2 x 6 accumulator blocks; the transposing staging (scattered 16-byte loads, 4-byte LDS writes) then
+// costs a quarter of the main loop.  Here the four wavefronts of a workgroup walk through the SAME
+// units and share one staged window that covers all KG taps of the group (128 rows: each wavefront
+// loads and writes one 32-row item, a quarter of the work), and split the 2*KG accumulator blocks
+// (tap, 32-channel half of the 64 output channels) evenly: ceil(2*KG/4) consecutive blocks each, in
+// tap-major order, so a wavefront reads only the 4-6 taps it owns.  A block is owned by one wavefront
+// for the whole reduction, so there is no exchange at the end: every wavefront stores its blocks to
+// the [S][K][Cout][Cin] scratch.  One workgroup barrier per unit (double-buffered window).  The dz
+// fragments stream as in wgrad_fast_kernel (all four wavefronts read the same ones: L1 hits).
+template <int KG, int DIL, int W>
+__device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char *smem, int sp, int k0, int kt, int co0,
+                                             int ci0)
+{
+    constexpr int NB = (2 * KG + kWaves - 1) / kWaves;         // accumulator blocks per wavefront
+    constexpr int J0 = W * NB < 2 * KG ? W * NB : 2 * KG;      // this wavefront's blocks [J0, J1), block j = (tap j/2, half j%2)
+    constexpr int J1 = J0 + NB < 2 * KG ? J0 + NB : 2 * KG;
+    constexpr int NBW = J1 - J0;
+    constexpr int T0 = J0 / 2, T1 = (J1 + 1) / 2;              // taps [T0, T1)
+    constexpr int NTAP = T1 - T0 > 0 ? T1 - T0 : 1;
+    constexpr int kRows = 128, kBufBytes = kRows * kFastXRowBytes;
+    const int lane = threadIdx.x & 63;
+    const int S = p.S;
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)((size_t)p.B * p.Cin * p.T * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_dz = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)p.dzf, 0, (int)((size_t)p.B * p.ncm * p.nst * 1024), 0x00020000);
+
+    // x staging: this wavefront's item is rows 32*W .. 32*W+31 of the window; lane = channel pair
+    // (lane & 15) x time group (lane >> 4)
+    const int x_pp = lane & 15, x_q = lane >> 4;
+    const bool ch_a = ci0 + 2 * x_pp < p.Cin, ch_b = ci0 + 2 * x_pp + 1 < p.Cin;
+    const uint32_t x_lds_off = (uint32_t)((32 * W + x_q * 8) * kFastXRowBytes + x_pp * 4);
+    const int xs_rel = k0 * DIL - p.pad;
+    const int xs_rel_al = (xs_rel >> 3) * 8;
+    const int off0 = xs_rel - xs_rel_al;
+    const uint32_t x_lane_a = ch_a ? (uint32_t)(((ci0 + 2 * x_pp) * p.T + 8 * x_q + xs_rel_al + 32 * W) * 2) : kFar;
+    const uint32_t x_lane_b = ch_b ? x_lane_a + (uint32_t)(p.T * 2) : kFar;
+    const int x_t0 = xs_rel_al + 8 * x_q + 32 * W;
+
+    struct UnitAddr {
+        uint32_t xs, as;
+        int tbase;
+        bool live;
+    };
+    auto unit_addr = [&](int u) {
+        UnitAddr a;
+        a.live = u < p.units;
+        const int uu = a.live ? u : 0;
+        const int b = uu / p.nchunk, chunk = uu - b * p.nchunk;
+        a.tbase = chunk * kFastTCH;
+        a.xs = (uint32_t)((size_t)b * p.Cin * p.T * 2);
+        a.as = (uint32_t)((((size_t)b * p.ncm + (co0 >> 5)) * p.nst + (size_t)chunk * kFastSteps) * 1024);
+        return a;
+    };
+    auto x_load_item = [&](const UnitAddr &a, u32x4 &xa, u32x4 &xb) {
+        const int t = a.tbase + x_t0;
+        const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);
+        xa = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2) : kFar, a.xs);
+        xb = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2) : kFar, a.xs);
+    };
+    auto x_write_item = [&](unsigned char *buf, const u32x4 &xa, const u32x4 &xb) {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(buf + x_lds_off);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dst[(2 * e) * (kFastXRowBytes / 4)] = zip_lo16(xa[e], xb[e]);
+            dst[(2 * e + 1) * (kFastXRowBytes / 4)] = zip_hi16(xa[e], xb[e]);
+        }
+    };
+    const uint32_t a_lane = (uint32_t)lane * 16;
+    const uint32_t a_mi = (uint32_t)p.nst * 1024;
+    u32x4 afr0[2][kFastSteps], afr1[2][kFastSteps];
+    auto a_load = [&](const UnitAddr &a, int mi, int st) {
+        return buf_load16(rs_dz, a.live ? a_lane + (uint32_t)(st * 1024) : kFar, a.as + (uint32_t)mi * a_mi);
+    };
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const int trow = 8 * (g4 >> 1) + (i16 >> 2) + off0;
+    const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);
+    const unsigned char *xb0 = smem + trow * kFastXRowBytes + tcol * 2;
+
+    f32x16 acc[NBW > 0 ? NBW : 1];
+#pragma unroll
+    for (int j = 0; j < (NBW > 0 ? NBW : 1); ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    const int my_units = sp < p.units ? (p.units - sp + S - 1) / S : 0;  // the same for all four wavefronts
+    u32x4 xa0, xb0r, xa1, xb1r;
+    {
+        const UnitAddr a0 = unit_addr(sp), a1 = unit_addr(sp + S);
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int st = 0; st < kFastSteps; ++st) {
+                afr0[mi][st] = a_load(a0, mi, st);
+                afr1[mi][st] = a_load(a1, mi, st);
+            }
+        x_load_item(a0, xa0, xb0r);
+        x_load_item(a1, xa1, xb1r);  // written during the first unit
+        x_write_item(smem, xa0, xb0r);
+        __syncthreads();
+    }
+    // one unit: multiply from window `par`; request the dz fragments and this wavefront's x item of
+    // unit u + 2S; write the x item of unit u + S (other register set) into the other window
+    auto unit = [&](int u, int par, u32x4(&afr)[2][kFastSteps], u32x4 &xa, u32x4 &xb, const u32x4 &xo_a, const u32x4 &xo_b) {
+        const UnitAddr an = unit_addr(u + 2 * S);
+        const unsigned char *xb_ = xb0 + par * kBufBytes;
+        unsigned char *wr = smem + (par ^ 1) * kBufBytes;
+        auto read_b = [&](int st, bf16x8(&bfr)[NTAP]) {
+#pragma unroll
+            for (int i = 0; i < NTAP; ++i) {
+                const unsigned char *xp = xb_ + (st * 16 + (T0 + i) * DIL) * kFastXRowBytes;
+                union {
+                    s16x4 h[2];
+                    bf16x8 v;
+                } cvt;
+                cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp));
+                cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp + 4 * kFastXRowBytes));
+                bfr[i] = cvt.v;
+            }
+        };
+        bf16x8 bq[2][NTAP];
+        read_b(0, bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < kFastSteps; ++st) {
+            if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                const int blk = J0 + j;
+                union {
+                    u32x4 u;
+                    bf16x8 v;
+                } af;
+                af.u = afr[blk & 1][st];
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bq[st & 1][(blk >> 1) - T0], acc[j], 0, 0, 0);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
+            if (st == 0) x_load_item(an, xa, xb);
+            if (st == kFastSteps - 1) x_write_item(wr, xo_a, xo_b);
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
+                if (i % 3 == 2) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();  // the other window is complete; this one may be overwritten
+    };
+    const int npairs = (my_units + 1) >> 1;
+    int u = sp;
+    for (int i = 0; i < npairs; ++i, u += 2 * S) {
+        unit(u, 0, afr0, xa0, xb0r, xa1, xb1r);
+        unit(u + S, 1, afr1, xa1, xb1r, xa0, xb0r);
+    }
+
+    // ---- every block goes straight to the scratch: register r of a block is output channel
+    // co0 + 32*half + 8*(r/4) + 4*(lane/32) + r%4, input channel ci0 + lane%32
+    const int ci = ci0 + (lane & 31);
+    if (ci < p.Cin) {
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+            const int blk = J0 + j, tap = blk >> 1, half = blk & 1;
+            if (tap >= kt) continue;  // a group shorter than KG
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = co0 + 32 * half + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (co < p.Cout) p.part[(((size_t)sp * p.K + k0 + tap) * p.Cout + co) * p.Cin + ci] = acc[j][r];
+            }
+        }
+    }
+}
+
+template <int KG, int DIL>
+__global__ __launch_bounds__(kThreads) void wgrad_shared_kernel(const WgradParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const TileCoords tcd = decode_tile(p);
+    if (!tcd.valid) return;
+    const int k0 = tcd.tg * p.KTg;
+    const int kt = min(p.KTg, p.K - k0);
+    const int co0 = tcd.cot * kTileCo, ci0 = tcd.cit * kTileCi;
+    switch (wave) {  // one copy per wavefront number: the block lists are static
+    case 0: shared_units<KG, DIL, 0>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    case 1: shared_units<KG, DIL, 1>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    case 2: shared_units<KG, DIL, 2>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    default: shared_units<KG, DIL, 3>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    }
+}
+
 // dw[co][ci][k] = (accumulate ? dw : 0) + sum_s part[s][k][co][ci]; one block per (co, 64 ci).
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw,
                                                            int S, int K, int Cout, int Cin, int accumulate)
@@ -715,7 +922,11 @@ bool fast_ok(const Geom &g)
 struct FastPlan {
     int KTg, ntg, S, nchunk, ncm, nst;
     size_t lds;
+    bool shared;  // wgrad_shared_kernel (taps split over the wavefronts) instead of wgrad_fast_kernel
 };
+// tap-group sizes wgrad_shared_kernel is built for
+constexpr bool shared_kernel_built(int KG, int dil) { return dil == 1 ? (KG == 11 || KG == 13 || KG == 17 || KG == 21) : (dil == 2 && KG == 15); }
+constexpr int kPlanCUs = 256;  // the planning below aims at this many CUs (a heuristic only: any count works)
 FastPlan make_fast_plan(const Geom &g)
 {
     FastPlan f = {};
@@ -735,6 +946,27 @@ FastPlan make_fast_plan(const Geom &g)
     const size_t stage = (size_t)kWaves * 2 * fast_x_items(g.dil) * 32 * kFastXRowBytes;
     const size_t red = (size_t)kWaves * 3 * (2 * f.KTg) * 64 * sizeof(f32x4);
     f.lds = stage > red ? stage : red;
+    // The kernel with shared staging: up to 24 taps per workgroup (12 accumulator blocks per wavefront);
+    // it has no dynamic balancing to speak of (few, long workgroups), so it is taken only when a split
+    // count S <= 8 makes the workgroups fill the CUs in whole rounds (>= 95 %).
+    {
+        const int ntg_s = (g.K + 23) / 24;
+        const int KG = (g.K + ntg_s - 1) / ntg_s;
+        const long tiles_s = (long)ncot * ncit * ((g.K + KG - 1) / KG);
+        if (shared_kernel_built(KG, g.dil) && 18 + 64 + (KG - 1) * g.dil + 4 < 128) {
+            for (long Ss = 1; Ss <= 8 && Ss * 2 <= units; ++Ss) {
+                const long wgs = tiles_s * Ss, rounds = (wgs + kPlanCUs - 1) / kPlanCUs;
+                if (wgs * 100 >= rounds * kPlanCUs * 95) {
+                    f.shared = true;
+                    f.KTg = KG;
+                    f.ntg = (g.K + KG - 1) / KG;
+                    f.S = (int)Ss;
+                    f.lds = 2 * 128 * kFastXRowBytes;
+                    break;
+                }
+            }
+        }
+    }
     return f;
 }
 size_t dzf_bytes(const Geom &g, const FastPlan &f) { return align_up((size_t)g.B * f.ncm * f.nst * 1024, 256); }
@@ -749,6 +981,15 @@ hipError_t launch_fast_kt(const WgradParams &p, size_t lds, int grid, hipStream_
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+template <int KG, int DIL>
+hipError_t launch_shared(const WgradParams &p, size_t lds, int grid, hipStream_t s)
+{
+    auto kern = wgrad_shared_kernel<KG, DIL>;
     MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
     return hipGetLastError();
@@ -823,10 +1064,20 @@ hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, b
     p.TCH = kFastTCH; p.nchunk = f.nchunk; p.units = g.B * f.nchunk;
     p.ncm = f.ncm; p.nst = f.nst;
     number_work_items(p);
+    if (f.shared) p.CL = -1;
     p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
     const int grid = p.per_xcd * 8;
     hipError_t e;
-    if (g.dil == 1) {
+    if (f.shared) {
+        switch (f.KTg * 10 + g.dil) {
+        case 111: e = launch_shared<11, 1>(p, f.lds, grid, s); break;
+        case 131: e = launch_shared<13, 1>(p, f.lds, grid, s); break;
+        case 171: e = launch_shared<17, 1>(p, f.lds, grid, s); break;
+        case 211: e = launch_shared<21, 1>(p, f.lds, grid, s); break;
+        case 152: e = launch_shared<15, 2>(p, f.lds, grid, s); break;
+        default: e = hipErrorInvalidValue; break;
+        }
+    } else if (g.dil == 1) {
         switch (f.KTg) {
         case 1: e = launch_fast_kt<1, 1>(p, f.lds, grid, s); break;
         case 2: e = launch_fast_kt<2, 1>(p, f.lds, grid, s); break;

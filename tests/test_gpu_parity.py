@@ -141,6 +141,27 @@ def test_private_and_shared_tiles_full_tensor(cfg):
     check_layer(cfg, "bf16", False)
 
 
+# Shapes on which the weight gradient takes the kernel that splits the taps over the wavefronts
+# (its planner wants the workgroups to fill 256 CUs in whole rounds: 8 x 32 = 256 output tiles here),
+# one per tap-group size it is built for; K=25 runs as two groups (13 + 12), K=29 with dilation 2 as 15 + 14.
+SHARED_WGRAD = [
+    L("w_k11", 2, 1024, 512, 160, 11, pad=5, affine=False, relu=False),
+    L("w_k13", 1, 1024, 512, 240, 13, pad=6, affine=False, relu=False),
+    L("w_k17", 2, 1024, 512, 160, 17, pad=8, affine=False, relu=False),
+    L("w_k21", 1, 1000, 500, 320, 21, pad=10, affine=False, relu=False),          # ragged channel tiles
+    L("w_k25", 1, 1024, 512, 160, 25, pad=12, affine=False, relu=False),
+    L("w_k29_d2", 1, 1024, 512, 160, 29, dilation=2, pad=28, affine=False, relu=False),
+]
+# (no affine, no ReLU: dz is dy itself, so the 5.6 million weight gradients of each case carry no bf16
+# rounding of dz, whose 6-sigma tail would sit right at the 1e-2 gate; that rounding is covered by
+# every other case)
+
+
+@pytest.mark.parametrize("cfg", SHARED_WGRAD, ids=lambda c: c.name)
+def test_weight_gradient_with_taps_split_over_wavefronts(cfg):
+    check_layer(cfg, "bf16", False)
+
+
 def sample_indices(n_total, n, rng, extra=()):
     idx = rng.choice(n_total, size=min(n, n_total), replace=False)
     return np.unique(np.concatenate([idx, np.asarray(list(extra), dtype=np.int64)])).astype(np.int64)
