@@ -323,7 +323,7 @@ def main():
 
     dom_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
     kernel_names = {"fwd": "conv_gemm_kernel<5,1,17> (forward)", "dgrad": "conv_gemm_kernel<5,1,17> (input gradient)",
-                    "wgrad": "wgrad_fast_kernel<6, 1>"}
+                    "wgrad": "wgrad_shared_kernel<17, 1>"}
     achieved = cfg.flops_per_pass / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": recorded_traffic(dominant),

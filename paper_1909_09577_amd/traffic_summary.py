@@ -43,7 +43,7 @@ def per_kernel(path: str, counter: str):
         key = None
         if "conv_gemm_kernel" in name:
             key = "dgrad" if "_prepare_kernel" in prev else "fwd"  # the input gradient follows a preparation kernel
-        elif "wgrad_fast_kernel" in name or "wgrad_kernel" in name:
+        elif "wgrad_shared_kernel" in name or "wgrad_fast_kernel" in name or "wgrad_kernel" in name:
             key = "wgrad"
         elif "prepack_kernel" in name:
             key = "weight packing (fwd)"
