@@ -674,14 +674,26 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         int tbase;
         bool live;
     };
-    auto unit_addr = [&](int u) {
+    // units of this workgroup: sp, sp + S, sp + 2S, ...; (batch item, chunk) advance without divisions
+    const int step_b = S / p.nchunk, step_c = S - step_b * p.nchunk;
+    struct UnitPos {
+        int b, c;
+    };
+    auto unit_pos = [&](int u) { return UnitPos{u / p.nchunk, u % p.nchunk}; };
+    auto advance = [&](UnitPos &q) {
+        q.b += step_b;
+        q.c += step_c;
+        const bool carry = q.c >= p.nchunk;
+        q.c -= carry ? p.nchunk : 0;
+        q.b += carry ? 1 : 0;
+    };
+    auto unit_addr = [&](const UnitPos &q) {
         UnitAddr a;
-        a.live = u < p.units;
-        const int uu = a.live ? u : 0;
-        const int b = uu / p.nchunk, chunk = uu - b * p.nchunk;
-        a.tbase = chunk * kFastTCH;
-        a.xs = (uint32_t)((size_t)b * p.Cin * p.T * 2);
-        a.as = (uint32_t)((((size_t)b * p.ncm + (co0 >> 5)) * p.nst + (size_t)chunk * kFastSteps) * 1024);
+        a.live = q.b < p.B;
+        const int b = a.live ? q.b : 0;
+        a.tbase = q.c * kFastTCH;
+        a.xs = (uint32_t)b * (uint32_t)(p.Cin * p.T * 2);
+        a.as = (uint32_t)((b * p.ncm + (co0 >> 5)) * p.nst + q.c * kFastSteps) * 1024u;
         return a;
     };
     auto x_load_item = [&](const UnitAddr &a, u32x4 &xa, u32x4 &xb) {
@@ -718,7 +730,9 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     const int my_units = sp < p.units ? (p.units - sp + S - 1) / S : 0;  // the same for all four wavefronts
     u32x4 xa0, xb0r, xa1, xb1r;
     {
-        const UnitAddr a0 = unit_addr(sp), a1 = unit_addr(sp + S);
+        UnitPos q0 = unit_pos(sp), q1 = q0;
+        advance(q1);
+        const UnitAddr a0 = unit_addr(q0), a1 = unit_addr(q1);
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -733,8 +747,12 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     }
     // one unit: multiply from window `par`; request the dz fragments and this wavefront's x item of
     // unit u + 2S; write the x item of unit u + S (other register set) into the other window
-    auto unit = [&](int u, int par, u32x4(&afr)[2][kFastSteps], u32x4 &xa, u32x4 &xb, const u32x4 &xo_a, const u32x4 &xo_b) {
-        const UnitAddr an = unit_addr(u + 2 * S);
+    UnitPos ahead = unit_pos(sp);  // the unit two ahead of the one being multiplied
+    advance(ahead);
+    advance(ahead);
+    auto unit = [&](int par, u32x4(&afr)[2][kFastSteps], u32x4 &xa, u32x4 &xb, const u32x4 &xo_a, const u32x4 &xo_b) {
+        const UnitAddr an = unit_addr(ahead);
+        advance(ahead);
         const unsigned char *xb_ = xb0 + par * kBufBytes;
         unsigned char *wr = smem + (par ^ 1) * kBufBytes;
         auto read_b = [&](int st, bf16x8(&bfr)[NTAP]) {
@@ -785,10 +803,9 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         __syncthreads();  // the other window is complete; this one may be overwritten
     };
     const int npairs = (my_units + 1) >> 1;
-    int u = sp;
-    for (int i = 0; i < npairs; ++i, u += 2 * S) {
-        unit(u, 0, afr0, xa0, xb0r, xa1, xb1r);
-        unit(u + S, 1, afr1, xa1, xb1r, xa0, xb0r);
+    for (int i = 0; i < npairs; ++i) {
+        unit(0, afr0, xa0, xb0r, xa1, xb1r);
+        unit(1, afr1, xa1, xb1r, xa0, xb0r);
     }
 
     // ---- every block goes straight to the scratch: register r of a block is output channel
