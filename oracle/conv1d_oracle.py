@@ -213,6 +213,42 @@ def bwd_weight_at(x, dz, K, index, *, stride=1, dilation=1, pad=0):
     return dw
 
 
+# ---- per-sample lengths ----------------------------------------------------------------------
+# The encoder of the paper's ASR example takes the length of every utterance besides the padded
+# batch and returns encoded lengths (Section 4.1.1: encoded, encoded_len = jasper_encoder(audio_signal,
+# length)); the paper gives no formula.  Reading used here: samples at t >= length[b] are padding and
+# count as zero for every block that reads them; a block's own output is not masked (the next block
+# masks what it reads); the gradient with respect to padding is zero; the valid length behind a block
+# is the convolution's output length applied to length[b].
+def mask_time(x, lengths):
+    """Copy of x [B][C][T] with x[b, :, t >= lengths[b]] set to zero (lengths are clipped to [0, T])."""
+    x = np.array(x, dtype=np.float64, copy=True)
+    for b, n in enumerate(np.asarray(lengths).reshape(-1)):
+        x[b, :, max(0, min(int(n), x.shape[2])):] = 0.0
+    return x
+
+
+def out_lengths(lengths, K: int, stride: int, dilation: int, pad: int):
+    """Valid length behind the block for every sample (0 where no output position exists)."""
+    return np.array([max(0, out_len(int(n), K, stride, dilation, pad)) if n > 0 else 0 for n in np.asarray(lengths).reshape(-1)],
+                    dtype=np.int64)
+
+
+def block_fwd_masked(x, w, lengths, scale=None, shift=None, residual=None, relu=False, *, stride=1, dilation=1, pad=0):
+    """Block forward on the batch with its padding zeroed."""
+    return block_fwd(mask_time(x, lengths), w, scale, shift, residual, relu, stride=stride, dilation=dilation, pad=pad)
+
+
+def bwd_data_masked(dz, w, T, lengths, *, stride=1, dilation=1, pad=0):
+    """Input gradient; zero on the padding."""
+    return mask_time(bwd_data(dz, w, T, stride=stride, dilation=dilation, pad=pad), lengths)
+
+
+def bwd_weight_masked(x, dz, K, lengths, *, stride=1, dilation=1, pad=0):
+    """Weight gradient from the batch with its padding zeroed."""
+    return bwd_weight(mask_time(x, lengths), dz, K, stride=stride, dilation=dilation, pad=pad)
+
+
 def num_threads() -> int:
     """Threads the OpenMP runtime uses for the loops of the C file."""
     return int(_load().oracle_num_threads())

@@ -285,3 +285,58 @@ def test_degenerate_geometries():
     assert orc.out_len(0, 1, 1, 1, 0) == -1
     z = orc.block_fwd(np.ones((1, 1, 1)), np.full((1, 1, 1), 3.0))
     assert z.shape == (1, 1, 1) and z[0, 0, 0] == 3.0
+
+
+# ---- per-sample lengths ------------------------------------------------------------------------
+def test_masking_ignores_whatever_lies_in_the_padding():
+    rng = np.random.default_rng(41)
+    B, Cin, Cout, T, K = 3, 5, 4, 23, 5
+    x, w = rng.standard_normal((B, Cin, T)), rng.standard_normal((Cout, Cin, K))
+    lengths = np.array([23, 9, 1])
+    ref = orc.block_fwd_masked(x, w, lengths, pad=2)
+    junk = x.copy()
+    for b, n in enumerate(lengths):
+        junk[b, :, n:] = 1e30 * rng.standard_normal((Cin, T - n))
+    np.testing.assert_array_equal(orc.block_fwd_masked(junk, w, lengths, pad=2), ref)
+    dz = rng.standard_normal((B, Cout, T))
+    np.testing.assert_array_equal(orc.bwd_weight_masked(junk, dz, K, lengths, pad=2), orc.bwd_weight_masked(x, dz, K, lengths, pad=2))
+    # full lengths: nothing changes
+    full = np.full(B, T)
+    np.testing.assert_array_equal(orc.block_fwd_masked(x, w, full, pad=2), orc.block_fwd(x, w, pad=2))
+
+
+def test_masked_forward_equals_the_convolution_of_the_cut_sample():
+    # Behind a cut-off sample the block sees zeros, exactly like the zero padding of the convolution itself:
+    # outputs whose taps all lie inside [0, len) equal those of the sample convolved on its own.
+    rng = np.random.default_rng(42)
+    Cin, Cout, T, K, pad, n = 3, 2, 30, 7, 3, 17
+    x, w = rng.standard_normal((1, Cin, T)), rng.standard_normal((Cout, Cin, K))
+    masked = orc.block_fwd_masked(x, w, [n], pad=pad)
+    alone = orc.block_fwd(x[:, :, :n], w, pad=pad)               # T_out = n
+    np.testing.assert_allclose(masked[:, :, :n], alone, rtol=1e-13, atol=1e-13)
+    # beyond n + (K-1) - pad the output depends on nothing but zeros
+    assert np.all(masked[:, :, n + K - 1 - pad:] == 0)
+    assert list(orc.out_lengths([n, 0, 5], K, 1, 1, pad)) == [n, 0, 5]
+    assert list(orc.out_lengths([20, 21], 11, 2, 1, 5)) == [10, 11]
+
+
+def test_masked_gradients_are_the_derivatives_of_the_masked_forward():
+    rng = np.random.default_rng(43)
+    B, Cin, Cout, T, K, pad = 2, 3, 2, 12, 3, 1
+    x, w = rng.standard_normal((B, Cin, T)), rng.standard_normal((Cout, Cin, K))
+    lengths = np.array([12, 7])
+    dz = rng.standard_normal((B, Cout, T))
+    loss = lambda xx, ww: float(np.sum(orc.block_fwd_masked(xx, ww, lengths, pad=pad) * dz))
+    dx, dw = orc.bwd_data_masked(dz, w, T, lengths, pad=pad), orc.bwd_weight_masked(x, dz, K, lengths, pad=pad)
+    eps = 1e-6
+    for idx in [(0, 1, 11), (1, 2, 6), (1, 0, 7), (1, 1, 11)]:      # the last two lie in the padding: derivative 0
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += eps
+        xm[idx] -= eps
+        np.testing.assert_allclose((loss(xp, w) - loss(xm, w)) / (2 * eps), dx[idx], rtol=1e-6, atol=1e-8)
+    assert dx[1, 0, 7] == 0 and dx[1, 1, 11] == 0
+    for idx in [(0, 0, 0), (1, 2, 2)]:
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += eps
+        wm[idx] -= eps
+        np.testing.assert_allclose((loss(x, wp) - loss(x, wm)) / (2 * eps), dw[idx], rtol=1e-6, atol=1e-8)
