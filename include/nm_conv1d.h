@@ -127,6 +127,29 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
                   void *dx, void *dres, float *dw, unsigned flags, int dtype,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The three passes on a padded batch (paper Section 4.1.1: the encoder takes the length of every
+ * utterance next to the padded batch).  lengths [B] int32 (device): samples of batch item b at
+ * t >= lengths[b] are padding; values are clipped to [0, T].
+ *   block_fwd_masked:   padding of x reads as zero (whatever the buffer holds there, NaN included);
+ *                       y is written for all T_out positions (the block does not mask its output;
+ *                       the valid length behind it is nm_conv1d_out_len(lengths[b], ...)).
+ *   bwd_weight_masked:  dw from x with its padding read as zero.
+ *   bwd_data_masked:    dx is zero on the padding.
+ * All other arguments, the workspace size and the error behaviour are those of the unmasked calls;
+ * lengths == NULL is NM_ERR_BAD_ARG. */
+int nm_conv1d_block_fwd_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                               const int *lengths, const void *x, const void *w, const float *scale,
+                               const float *shift, const void *residual, void *y, unsigned flags,
+                               int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+int nm_conv1d_bwd_data_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                              const int *lengths, const void *dy, const void *y, const float *scale,
+                              const void *w, void *dx, void *dres, unsigned flags, int dtype,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+int nm_conv1d_bwd_weight_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                                const int *lengths, const void *x, const void *dy, const void *y,
+                                const float *scale, float *dw, unsigned flags, int dtype,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Decoder tail (paper Section 4.1.1: the CTC decoder module turns the encoder output into per-frame
  * log-probabilities over the vocabulary): a 1x1 convolution to Ncls classes followed by a log-softmax
  * over the classes of every frame,

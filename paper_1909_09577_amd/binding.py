@@ -21,7 +21,8 @@ NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
 NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
-           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -53,6 +54,12 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_data.restype = i
         L.nm_conv1d_bwd_weight.argtypes = [i] * 8 + [vp] * 5 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd_weight.restype = i
+        L.nm_conv1d_block_fwd_masked.argtypes = [i] * 8 + [vp] * 7 + [u, i, vp, sz, vp]
+        L.nm_conv1d_block_fwd_masked.restype = i
+        L.nm_conv1d_bwd_data_masked.argtypes = [i] * 8 + [vp] * 7 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd_data_masked.restype = i
+        L.nm_conv1d_bwd_weight_masked.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd_weight_masked.restype = i
         L.nm_conv1d_bwd.argtypes = [i] * 8 + [vp] * 8 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd.restype = i
         L.nm_decoder_logsoftmax_fwd.argtypes = [i] * 4 + [vp] * 4 + [u, i, vp]
@@ -127,8 +134,9 @@ def _workspace(op, dims, dtype_code, flags, workspace, device):
 
 
 def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, stride=1, dilation=1,
-                        pad=0, relu=False, force_direct=False, workspace=None, stream=None):
-    """y = relu?(scale*conv1d(x,w)+shift+residual); returns y (allocated if not given)."""
+                        pad=0, relu=False, force_direct=False, workspace=None, stream=None, lengths=None):
+    """y = relu?(scale*conv1d(x,w)+shift+residual); returns y (allocated if not given).
+    lengths (int32 [B], optional): valid length of every sample, the rest of x reads as zero."""
     torch = _torch()
     B, Cin, T = x.shape
     Cout, _, K = w.shape
@@ -141,8 +149,10 @@ def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, 
     flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_FWD, dims, code, flags, workspace, x.device)
-    st = lib().nm_conv1d_block_fwd(
-        *dims, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
+    fn, extra = (lib().nm_conv1d_block_fwd, ()) if lengths is None else (
+        lib().nm_conv1d_block_fwd_masked, (_ptr(lengths, torch.int32, (B,), "lengths"),))
+    st = fn(
+        *dims, *extra, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
         _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(shift, torch.float32, (Cout,), "shift"),
         _ptr(residual, x.dtype, (B, Cout, To), "residual"), _ptr(y, x.dtype, (B, Cout, To), "y"),
         flags, code, ws_ptr, ws_bytes, _stream(stream))
@@ -152,8 +162,9 @@ def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, 
 
 
 def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stride=1, dilation=1, pad=0,
-                       relu=False, want_dres=False, force_direct=False, workspace=None, stream=None):
-    """dx (and optionally dres) from the upstream gradient dy; returns (dx, dres)."""
+                       relu=False, want_dres=False, force_direct=False, workspace=None, stream=None, lengths=None):
+    """dx (and optionally dres) from the upstream gradient dy; returns (dx, dres).
+    lengths (int32 [B], optional): valid input length of every sample; dx is zero beyond it."""
     torch = _torch()
     B, Cout, To = dy.shape
     _, Cin, K = w.shape
@@ -165,8 +176,10 @@ def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stri
     flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD_DATA, dims, code, flags, workspace, dy.device)
-    st = lib().nm_conv1d_bwd_data(
-        *dims, _ptr(dy, name="dy"), _ptr(y, dy.dtype, (B, Cout, To), "y"),
+    fn, extra = (lib().nm_conv1d_bwd_data, ()) if lengths is None else (
+        lib().nm_conv1d_bwd_data_masked, (_ptr(lengths, torch.int32, (B,), "lengths"),))
+    st = fn(
+        *dims, *extra, _ptr(dy, name="dy"), _ptr(y, dy.dtype, (B, Cout, To), "y"),
         _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(w, dy.dtype, (Cout, Cin, K), "w"),
         _ptr(dx, dy.dtype, (B, Cin, T), "dx"), _ptr(dres, dy.dtype, (B, Cout, To), "dres"),
         flags, code, ws_ptr, ws_bytes, _stream(stream))
@@ -176,8 +189,9 @@ def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stri
 
 
 def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dilation=1, pad=0,
-                         relu=False, accumulate=False, force_direct=False, workspace=None, stream=None):
-    """dw [Cout,Cin,K] float32 from x and the upstream gradient dy; returns dw."""
+                         relu=False, accumulate=False, force_direct=False, workspace=None, stream=None, lengths=None):
+    """dw [Cout,Cin,K] float32 from x and the upstream gradient dy; returns dw.
+    lengths (int32 [B], optional): valid length of every sample, the rest of x reads as zero."""
     torch = _torch()
     B, Cin, T = x.shape
     _, Cout, To = dy.shape
@@ -189,8 +203,10 @@ def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dil
     flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD_WEIGHT, dims, code, flags, workspace, x.device)
-    st = lib().nm_conv1d_bwd_weight(
-        *dims, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+    fn, extra = (lib().nm_conv1d_bwd_weight, ()) if lengths is None else (
+        lib().nm_conv1d_bwd_weight_masked, (_ptr(lengths, torch.int32, (B,), "lengths"),))
+    st = fn(
+        *dims, *extra, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
         _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(dw, torch.float32, (Cout, Cin, K), "dw"),
         flags, code, ws_ptr, ws_bytes, _stream(stream))
     if st != NM_OK:

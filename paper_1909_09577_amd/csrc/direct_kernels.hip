@@ -27,6 +27,7 @@ __global__ __launch_bounds__(kThreads) void direct_fwd_kernel(Geom g, const TS *
     if (t >= g.To) return;
     const TS *xb = x + (size_t)b * g.Cin * g.T;
     const int tau0 = t * g.stride - g.pad;
+    const int len = valid_len(g, b);
     float acc[kChanPerThread];
 #pragma unroll
     for (int c = 0; c < kChanPerThread; ++c) acc[c] = 0.f;
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void direct_fwd_kernel(Geom g, const TS *
         for (int ci = ci0; ci < ci1; ++ci) {
             for (int k = 0; k < g.K; ++k) {
                 const int tau = tau0 + k * g.dil;
-                if (tau < 0 || tau >= g.T) continue;
+                if (tau < 0 || tau >= len) continue;
                 const float xv = load_as_f32(xb, (size_t)ci * g.T + tau);
 #pragma unroll
                 for (int c = 0; c < kChanPerThread; ++c) {
@@ -120,10 +121,11 @@ __global__ __launch_bounds__(kThreads) void direct_dgrad_kernel(Geom g, const TS
 #pragma unroll
         for (int c = 0; c < kChanPerThread; ++c) acc[c] += part[c];
     }
+    const bool padding = tau >= valid_len(g, b);
 #pragma unroll
     for (int c = 0; c < kChanPerThread; ++c) {
         if (ci0 + c >= g.Cin) break;
-        store_from_f32(dx, ((size_t)b * g.Cin + ci0 + c) * g.T + tau, acc[c]);
+        store_from_f32(dx, ((size_t)b * g.Cin + ci0 + c) * g.T + tau, padding ? 0.f : acc[c]);
     }
 }
 
@@ -149,8 +151,11 @@ __global__ __launch_bounds__(kThreads) void direct_wgrad_kernel(Geom g, const TS
     for (int b = 0; b < g.B; ++b) {
         const TS *dzr = dz + ((size_t)b * g.Cout + co) * g.To;
         const TS *xr = x + ((size_t)b * g.Cin + ci) * g.T;
-        for (int t0 = t_lo; t0 < t_hi; t0 += 64) {
-            const int t1 = min(t0 + 64, t_hi);
+        // with lengths: t*stride + off < len[b]
+        const int len = valid_len(g, b);
+        const int t_hi_b = len - 1 - off < 0 ? 0 : min(t_hi, (len - 1 - off) / g.stride + 1);
+        for (int t0 = t_lo; t0 < t_hi_b; t0 += 64) {
+            const int t1 = min(t0 + 64, t_hi_b);
             float part = 0.f;
             for (int t = t0; t < t1; ++t)
                 part = fmaf(load_as_f32(dzr, t), load_as_f32(xr, (size_t)(t * g.stride + off)), part);

@@ -11,7 +11,17 @@ namespace nm {
 // Geometry of one conv1d sub-block; To is T_out.
 struct Geom {
     int B, Cin, Cout, T, K, stride, dil, pad, To;
+    // valid input length of every batch item (device pointer, [B]) or NULL: samples at t >= len[b] are
+    // padding -- read as zero by the forward pass and the weight gradient, given a zero input gradient
+    const int *len;
 };
+// length of batch item b clipped to [0, T] (T without lengths)
+__device__ __forceinline__ int valid_len(const Geom &g, int b)
+{
+    if (!g.len) return g.T;
+    const int n = g.len[b];
+    return n < 0 ? 0 : (n > g.T ? g.T : n);
+}
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 

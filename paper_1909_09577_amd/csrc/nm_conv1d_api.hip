@@ -60,6 +60,7 @@ int check_geometry(int B, int Cin, int Cout, int T, int K, int stride, int dil, 
     if ((long long)pad + (long long)dil * K > (1 << 28) || stride > (1 << 20)) return NM_ERR_UNSUPPORTED;
     g->B = B; g->Cin = Cin; g->Cout = Cout; g->T = T; g->K = K;
     g->stride = stride; g->dil = dil; g->pad = pad; g->To = to;
+    g->len = nullptr;
     return NM_OK;
 }
 
@@ -87,6 +88,10 @@ bool use_mfma(int op, const Geom &g, int dtype, unsigned flags)
 bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || scale != nullptr; }
 
 bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
+
+// Whether a call with per-sample lengths may take the matrix-core kernels (not yet: the plain kernels
+// apply the lengths; without lengths this is always true).
+bool masked_on_mfma(const Geom &g) { return g.len == nullptr; }
 
 // Scratch need of one operation on one path (mfma: matrix-core kernels, else plain kernels).
 size_t workspace_for(int op, const Geom &g, int dtype, bool mfma, bool scale_or_relu)
@@ -165,10 +170,10 @@ const char *nm_strerror(int status)
     }
 }
 
-int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
-                        const void *x, const void *w, const float *scale, const float *shift,
-                        const void *residual, void *y, unsigned flags, int dtype, void *workspace,
-                        size_t workspace_bytes, void *hip_stream)
+static int block_fwd_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                          const void *x, const void *w, const float *scale, const float *shift,
+                          const void *residual, void *y, unsigned flags, int dtype, void *workspace,
+                          size_t workspace_bytes, void *hip_stream)
 {
     DisarmOnExit disarm;
     Geom g;
@@ -176,12 +181,14 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
                             NM_RELU | NM_FORCE_DIRECT, &g);
     if (st != NM_OK) return st;
     if (!x || !w || !y) return NM_ERR_BAD_ARG;
+    g.len = lengths;
     const size_t e = elt(dtype);
     const size_t ny = (size_t)g.B * g.Cout * g.To * e;
     if (overlap(y, ny, x, (size_t)g.B * g.Cin * g.T * e) || overlap(y, ny, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(y, ny, residual, ny))
         return NM_ERR_BAD_ARG;
-    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags) && aligned16(x) && aligned16(y) && aligned16(residual);
+    const bool mfma = use_mfma(NM_OP_FWD, g, dtype, flags) && aligned16(x) && aligned16(y) && aligned16(residual) &&
+                      masked_on_mfma(g);
     const size_t need = workspace_for(NM_OP_FWD, g, dtype, mfma, true);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
@@ -193,10 +200,10 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
     return dev(launch_direct_fwd(g, dtype == NM_BF16, x, w, scale, shift, residual, y, relu, s));
 }
 
-int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
-                       const void *dy, const void *y, const float *scale, const void *w, void *dx,
-                       void *dres, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
-                       void *hip_stream)
+static int bwd_data_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                         const void *dy, const void *y, const float *scale, const void *w, void *dx,
+                         void *dres, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                         void *hip_stream)
 {
     DisarmOnExit disarm;
     Geom g;
@@ -204,6 +211,7 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
                             NM_RELU | NM_FORCE_DIRECT, &g);
     if (st != NM_OK) return st;
     if (!dy || !w || !dx) return NM_ERR_BAD_ARG;
+    g.len = lengths;
     const bool relu = (flags & NM_RELU) != 0;
     if (relu && !y) return NM_ERR_BAD_ARG;
     const size_t e = elt(dtype);
@@ -212,7 +220,7 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
         overlap(dx, ndx, dres, ndy) || overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy))
         return NM_ERR_BAD_ARG;
     const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && aligned16(dy) && aligned16(dx) &&
-                      (!relu || aligned16(y));
+                      (!relu || aligned16(y)) && masked_on_mfma(g);
     const bool dzneeded = needs_dz(flags, scale);
     const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
@@ -231,16 +239,17 @@ int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int d
     return dev(launch_direct_dgrad(g, bf, dz, w, dx, s));
 }
 
-int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
-                         const void *x, const void *dy, const void *y, const float *scale, float *dw,
-                         unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
-                         void *hip_stream)
+static int bwd_weight_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                           const void *x, const void *dy, const void *y, const float *scale, float *dw,
+                           unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
 {
     DisarmOnExit disarm;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
     if (st != NM_OK) return st;
     if (!x || !dy || !dw) return NM_ERR_BAD_ARG;
+    g.len = lengths;
     const bool relu = (flags & NM_RELU) != 0;
     if (relu && !y) return NM_ERR_BAD_ARG;
     const size_t e = elt(dtype);
@@ -248,7 +257,7 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
     if (overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, (size_t)g.B * g.Cin * g.T * e))
         return NM_ERR_BAD_ARG;
     const bool mfma = use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) && aligned16(x) && aligned16(dy) &&
-                      (!relu || aligned16(y));
+                      (!relu || aligned16(y)) && masked_on_mfma(g);
     const bool dzneeded = needs_dz(flags, scale);
     const size_t need = workspace_for(NM_OP_BWD_WEIGHT, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
@@ -266,6 +275,60 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
     }
     MainKernelTimer timer(s);
     return dev(launch_direct_wgrad(g, bf, x, dz, dw, accum, s));
+}
+
+int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                        const void *w, const float *scale, const float *shift, const void *residual, void *y,
+                        unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return block_fwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, w, scale, shift, residual, y, flags, dtype,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *dy,
+                       const void *y, const float *scale, const void *w, void *dx, void *dres, unsigned flags, int dtype,
+                       void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return bwd_data_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, dy, y, scale, w, dx, dres, flags, dtype,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                         const void *dy, const void *y, const float *scale, float *dw, unsigned flags, int dtype,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return bwd_weight_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, dy, y, scale, dw, flags, dtype, workspace,
+                           workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_block_fwd_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                               const int *lengths, const void *x, const void *w, const float *scale, const float *shift,
+                               const void *residual, void *y, unsigned flags, int dtype, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    if (!lengths) return NM_ERR_BAD_ARG;
+    return block_fwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, x, w, scale, shift, residual, y, flags, dtype,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_bwd_data_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                              const int *lengths, const void *dy, const void *y, const float *scale, const void *w,
+                              void *dx, void *dres, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                              void *hip_stream)
+{
+    if (!lengths) return NM_ERR_BAD_ARG;
+    return bwd_data_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, dy, y, scale, w, dx, dres, flags, dtype,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_bwd_weight_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                                const int *lengths, const void *x, const void *dy, const void *y, const float *scale,
+                                float *dw, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                                void *hip_stream)
+{
+    if (!lengths) return NM_ERR_BAD_ARG;
+    return bwd_weight_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, x, dy, y, scale, dw, flags, dtype, workspace,
+                           workspace_bytes, hip_stream);
 }
 
 int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,

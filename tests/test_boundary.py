@@ -148,3 +148,18 @@ def test_decoder_tail_arguments_are_checked():
     assert f(2, 64, 29, 16, FAKE, FAKE2, None, FAKE3, 0, 9, None) == nm.NM_ERR_BAD_ARG      # dtype
     assert f(2, 64, 29, 16, FAKE, FAKE2, None, FAKE3, nm.NM_RELU, 0, None) == nm.NM_ERR_BAD_ARG  # foreign flag
     assert f(60000, 60000, 29, 60000, FAKE, FAKE2, None, FAKE3, 0, 0, None) == nm.NM_ERR_UNSUPPORTED
+
+
+def test_masked_entry_points_check_their_arguments():
+    L = nm.lib()
+    d = GOOD
+    dims = (d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"])
+    # no lengths
+    assert L.nm_conv1d_block_fwd_masked(*dims, None, FAKE2, FAKE3, None, None, None, FAKE4, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_conv1d_bwd_data_masked(*dims, None, FAKE2, None, None, FAKE3, FAKE4, None, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_conv1d_bwd_weight_masked(*dims, None, FAKE2, FAKE3, None, None, FAKE4, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+    # the other checks are those of the unmasked calls
+    assert L.nm_conv1d_block_fwd_masked(*dims, FAKE, None, FAKE3, None, None, None, FAKE4, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+    bad = (0,) + dims[1:]
+    assert L.nm_conv1d_bwd_weight_masked(*bad, FAKE, FAKE2, FAKE3, None, None, FAKE4, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_conv1d_bwd_data_masked(*dims, FAKE, FAKE2, None, None, FAKE3, FAKE4, None, nm.NM_RELU, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
