@@ -61,6 +61,9 @@ struct ConvGemmParams {
     int full;        // tiles every wavefront computes on its own, over the whole reduction, before the shared ones
     int relu;
     const bf16_t *in;       // [B][R][Tin]
+    const int *len_in;      // [B] valid input lengths (samples beyond read as zero) or NULL
+    const int *len_out;     // [B] lengths beyond which the output is written as zero, or NULL; the limit of
+    int len_out_sub, len_out_div;  // batch item b is ceil((len_out[b] - sub) / div) (phases of a strided gradient)
     const bf16x8 *wp;       // packed weights
     size_t wp_bytes;        // size of the packed weights including the zero pair (< 2 GiB)
     size_t wp_zero;         // offset (in fragments of 16 bytes) of one tap pair of zero weights
@@ -116,16 +119,29 @@ struct Epilogue {
     __amdgpu_buffer_rsrc_t rs_out, rs_res, rs_scale, rs_shift;
     int M, Tout;
     bool has_scale, relu;
+    const int *len_out;  // optional [B]: outputs at t >= ceil((len_out[b] - sub) / div) are written as zero
+    int len_sub, len_div;
 
     struct RowLoads {
         u32x4 rvec[kItems];
         float scv[kItems], shv[kItems];
         uint32_t ooff[kItems];
+        int tlim_rel;  // output limit of the batch item relative to the tile's first time step (wave-uniform)
     };
+    // first time step of batch item b that is written as zero (Tout without lengths)
+    __device__ __forceinline__ int out_limit(int b) const
+    {
+        if (!len_out) return Tout;
+        const int n = (len_out[b] - len_sub + len_div - 1) / len_div;
+        return n < 0 ? 0 : (n > Tout ? Tout : n);
+    }
 
     __device__ __forceinline__ void init(const bf16_t *out, const bf16_t *res, const float *scale, const float *shift, int B,
-                                         int M_, int Tout_, int relu_)
+                                         int M_, int Tout_, int relu_, const int *len_out_ = nullptr, int sub = 0, int div = 1)
     {
+        len_out = len_out_;
+        len_sub = sub;
+        len_div = div < 1 ? 1 : div;
         const int out_bytes = (int)((size_t)B * M_ * Tout_ * 2);
         M = M_;
         Tout = Tout_;
@@ -141,6 +157,7 @@ struct Epilogue {
     __device__ __forceinline__ RowLoads request_rows(int el, int b, int t0, int m0, bool split) const
     {
         RowLoads ld;
+        ld.tlim_rel = out_limit(b) - t0;
 #pragma unroll
         for (int q = 0; q < kItems; ++q) {
             const int idx = el + 64 * q;
@@ -178,6 +195,11 @@ struct Epilogue {
                 }
                 o[e] = pack_bf16x2(v0, v1);
             }
+            if (len_out) {  // zeros from the output limit on (a uniform branch: nothing to do without lengths)
+                const int nvalid = ld.tlim_rel - c8 * 8;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] &= nvalid >= 2 * e + 2 ? 0xffffffffu : (nvalid == 2 * e + 1 ? 0x0000ffffu : 0u);
+            }
             __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ld.ooff[q], 0, 0);
         }
     }
@@ -207,6 +229,14 @@ struct Epilogue {
         }
     }
 };
+
+// valid length of batch item b from an optional device array, clipped to [0, T]
+__device__ __forceinline__ int clipped_len(const int *len, int b, int T)
+{
+    if (!len) return T;
+    const int n = len[b];
+    return n < 0 ? 0 : (n > T ? T : n);
+}
 
 struct TileCoords {
     int mt, b, t0, ws_al, off0;
@@ -254,6 +284,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     struct StageAddr {
         uint32_t soff, va, vb;  // scalar offset; lane offsets of the even / odd channel (or out of range)
         int tq;                 // first time step of item 0 of this lane
+        int tlen;               // valid length of the batch item (Tin without lengths)
+        int ws_al;              // time step of window row 0
     };
     auto stage_addr = [&](int b, int c, int ws_al) {
         StageAddr a;
@@ -266,10 +298,15 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         a.va = 2 * pp < rem ? base : kOutOfRange;
         a.vb = 2 * pp + 1 < rem ? base + (uint32_t)(p.Tin * 2) : kOutOfRange;
         a.tq = tq;
+        a.tlen = __builtin_amdgcn_readfirstlane(clipped_len(p.len_in, b, p.Tin));
+        a.ws_al = ws_al;
         return a;
     };
     auto stage_load = [&](const StageAddr &a, int it, bool active, u32x4 &xa, u32x4 &xb) {
-        const bool t_ok = active && (unsigned)(a.tq + 32 * it) <= (unsigned)(p.Tin - 8);  // 0 <= t and t + 8 <= Tin
+        const int t = a.tq + 32 * it;
+        // a group is requested when it starts inside [0, tlen) (groups are 8-aligned and Tin % 8 == 0, so it
+        // then ends inside the row); what lies at or beyond tlen in it is cleared when it is written to LDS
+        const bool t_ok = active && (unsigned)t < (unsigned)a.tlen;
         // a lane of a missing channel holds kOutOfRange: adding 64*it keeps it beyond the buffer
         xa = __builtin_amdgcn_raw_buffer_load_b128(rs_in, t_ok ? a.va + (uint32_t)(64 * it) : kOutOfRange, a.soff, 0);
         xb = __builtin_amdgcn_raw_buffer_load_b128(rs_in, t_ok ? a.vb + (uint32_t)(64 * it) : kOutOfRange, a.soff, 0);
@@ -297,6 +334,18 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             dst[(2 * j + 1) * kRowDwords] = zip_hi16(xa[j], xb[j]);
         }
     };
+    // With lengths, the 8-step group that contains the first padding sample has been staged whole: its
+    // rows from the valid length on are cleared here, after the chunk's items are in LDS and before it
+    // is read (groups that start in the padding were never requested).  ws_al: time of buffer row 0.
+    auto clear_padding_rows = [&](unsigned char *buf, int tlen, int ws_al) {
+        const int r0 = tlen - ws_al;                 // first padding row of the window
+        const int nr = ((tlen + 7) & ~7) - tlen;     // rows up to the end of its group (0 when tlen % 8 == 0)
+        if (tlen < p.Tin && nr > 0 && r0 >= 0 && r0 < nitems * 32) {
+            const int l = fresh_lane();
+            for (int r = l >> 4; r < nr; r += 4)
+                *reinterpret_cast<uint32_t *>(buf + (size_t)(r0 + r) * kRowBytes + (l & 15) * 4) = 0u;
+        }
+    };
     constexpr int kSlots = KT > 0 ? unrolled_slots(KT) : 6;  // staging items of the next chunk held in registers
     u32x4 sxa[kSlots], sxb[kSlots];
     // a whole chunk, nothing to overlap with (first tile, or every tile without cross-tile staging)
@@ -308,6 +357,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 #pragma unroll
             for (int q = 0; q < kSlots; ++q) stage_write(buf, it0 + q, it0 + q < nitems, sxa[q], sxb[q]);
         }
+        clear_padding_rows(buf, sa.tlen, sa.ws_al);
     };
 
     // ---- weight fragment stream: buffer loads whose scalar offset is a cursor into the packed weights
@@ -376,7 +426,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     uint32_t w_cur = 0;
 
     Epilogue<NT> epi;
-    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu);
+    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu, p.len_out, p.len_out_sub, p.len_out_div);
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     // accumulators: zero here, and again in the epilogue as soon as a tile's values have been handed over
@@ -501,6 +551,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                         __builtin_amdgcn_sched_barrier(0);
                     };
                     for_each_index(tap, std::make_integer_sequence<int, (KT > 0 ? KT : 1)>{});
+                    if (has_t) clear_padding_rows(nxt, sa.tlen, sa.ws_al);
                     w_cur = w_nxt;
                     ++cc;
                 }
@@ -577,9 +628,11 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
                         // windows longer than the register slots, or everything when chunks are short
                         for (int it = async_stage ? kSlots : 0; it < nitems; ++it) {
                             u32x4 ya, yb;
-                            stage_load(stage_addr(t_b, t_c, t_ws), it, true, ya, yb);
+                            const StageAddr sl = stage_addr(t_b, t_c, t_ws);
+                            stage_load(sl, it, true, ya, yb);
                             stage_write(nxt, it, true, ya, yb);
                         }
+                        clear_padding_rows(nxt, clipped_len(p.len_in, t_b, p.Tin), t_ws);
                     }
                     ++ci_ord;
                     ++cc;
@@ -736,12 +789,13 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)((size_t)p.B * p.R * T * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
     Epilogue<NT> epi;
-    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu);
+    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu, p.len_out, p.len_out_sub, p.len_out_div);
 
     // position in the stream: tile coordinates and stage; advanced without divisions except at a tile change
     struct Pos {
         bool valid;
         int tile, mt4, b, t0, s;  // tile: which turn of this workgroup
+        int tlen;                 // valid input length of batch item b (T without lengths)
     };
     auto decode = [&](Pos &q) {  // (mt4, b, t0) of turn q.tile; wave-uniform, pinned to scalar registers
         int ntile, mt4;
@@ -760,6 +814,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         q.mt4 = __builtin_amdgcn_readfirstlane(mt4);
         q.b = __builtin_amdgcn_readfirstlane(b);
         q.t0 = __builtin_amdgcn_readfirstlane((ntile - b * p.ntt) * TN);
+        q.tlen = __builtin_amdgcn_readfirstlane(clipped_len(p.len_in, b, T));
     };
     auto advance = [&](Pos &q) {
         if (++q.s == nst) {
@@ -779,7 +834,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         const int blk = wave * kPwItems + it;
         const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
         const int t = q.t0 + 8 * tg;
-        const bool ok = q.valid && t + 8 <= T;
+        const bool ok = q.valid && t < q.tlen;  // groups that start inside the valid length (T % 8 == 0: they end inside the row)
         const uint32_t off = (uint32_t)(((2 * pair) * T + t) * 2);
         xa = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (ok && 2 * pair < rem) ? off : kOutOfRange, soff, 0);
         xb = __builtin_amdgcn_raw_buffer_load_b128(rs_in, (ok && 2 * pair + 1 < rem) ? off + (uint32_t)(T * 2) : kOutOfRange, soff, 0);
@@ -788,14 +843,16 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
 #pragma unroll
         for (int it = 0; it < kPwItems; ++it) x_load_item(q, it, xa[it], xb[it]);
     };
-    auto x_write_item = [&](unsigned char *buf, int it, const u32x4 &xa, const u32x4 &xb) {
+    // (time steps at or beyond the valid length of the stage's batch item are written as zeros)
+    auto x_write_item = [&](unsigned char *buf, const Pos &q, int it, const u32x4 &xa, const u32x4 &xb) {
         const int blk = wave * kPwItems + it;
         const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
         uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (8 * tg) * kPwRowBytes + pair * 4);
+        const int nvalid = q.tlen - (q.t0 + 8 * tg);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            dst[(2 * j) * (kPwRowBytes / 4)] = zip_lo16(xa[j], xb[j]);
-            dst[(2 * j + 1) * (kPwRowBytes / 4)] = zip_hi16(xa[j], xb[j]);
+            dst[(2 * j) * (kPwRowBytes / 4)] = nvalid > 2 * j ? zip_lo16(xa[j], xb[j]) : 0u;
+            dst[(2 * j + 1) * (kPwRowBytes / 4)] = nvalid > 2 * j + 1 ? zip_hi16(xa[j], xb[j]) : 0u;
         }
     };
     // ---- weights of this wavefront's 64 rows: [chunk of the stage][ks][mi], reloaded in place
@@ -839,7 +896,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         x_load(q0, xa0, xb0);
         x_load(q1, xa1, xb1);
 #pragma unroll
-        for (int it = 0; it < kPwItems; ++it) x_write_item(smem, it, xa0[it], xb0[it]);
+        for (int it = 0; it < kPwItems; ++it) x_write_item(smem, q0, it, xa0[it], xb0[it]);
         __syncthreads();
     }
     const int lane_off = (lane & 31) * kPwRowBytes + (lane >> 5) * 16;
@@ -870,7 +927,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
             constexpr int first = 2 * kPwChunks - kPwItems;
             const int step = 2 * j + ks;
             if (step < kPwItems) x_load_item(q2, step, xa[step], xb[step]);  // the stage after the next, one item per k-step
-            if (step >= first) x_write_item(nxt, step - first, xo_a[step - first], xo_b[step - first]);
+            if (step >= first) x_write_item(nxt, q1, step - first, xo_a[step - first], xo_b[step - first]);
             __builtin_amdgcn_sched_barrier(0);  // keeps every load where it is written
         };
 #pragma unroll
@@ -1304,6 +1361,7 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
     fill_common(p, pl, g.B, g.Cout, g.Cin, g.T, g.To, g.K, g.dil, g.pad);
     p.relu = relu ? 1 : 0;
     p.in = (const bf16_t *)x;
+    p.len_in = g.len;
     p.wp = (const bf16x8 *)ws;
     p.scale = scale; p.shift = shift; p.res = (const bf16_t *)res;
     p.out = (bf16_t *)y;
@@ -1403,6 +1461,9 @@ hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *
         p.in = (const bf16_t *)dz;
         p.wp = (const bf16x8 *)packed[r];
         p.out = (bf16_t *)phase_out[r];
+        p.len_out = g.len;  // dx[2u+r] is padding from 2u+r >= len on: u >= ceil((len - r) / 2)
+        p.len_out_sub = r;
+        p.len_out_div = 2;
         e = launch_plan(pl, p, s);  // the first of the two carries the one-shot timer
         if (e != hipSuccess) return e;
     }
@@ -1458,6 +1519,8 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
     p.in = (const bf16_t *)dz;
     p.wp = (const bf16x8 *)ws;
     p.out = (bf16_t *)dx;
+    p.len_out = g.len;
+    p.len_out_div = 1;
     return launch_plan(pl, p, s);
 }
 
@@ -1493,6 +1556,8 @@ hipError_t launch_mfma_dgrad_prepared(const Geom &g, void *dx, void *ws, hipStre
     p.in = (const bf16_t *)((unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K));
     p.wp = (const bf16x8 *)ws;
     p.out = (bf16_t *)dx;
+    p.len_out = g.len;
+    p.len_out_div = 1;
     return launch_plan(pl, p, s);
 }
 

@@ -89,9 +89,9 @@ bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || 
 
 bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
 
-// Whether a call with per-sample lengths may take the matrix-core kernels (not yet: the plain kernels
-// apply the lengths; without lengths this is always true).
-bool masked_on_mfma(const Geom &g) { return g.len == nullptr; }
+// Whether a call with per-sample lengths may take the matrix-core kernels: the forward pass and the
+// input gradient apply them there; the weight gradient with lengths runs on the plain kernel.
+bool masked_on_mfma(const Geom &g, int op = NM_OP_FWD) { return g.len == nullptr || op != NM_OP_BWD_WEIGHT; }
 
 // Scratch need of one operation on one path (mfma: matrix-core kernels, else plain kernels).
 size_t workspace_for(int op, const Geom &g, int dtype, bool mfma, bool scale_or_relu)
@@ -257,7 +257,7 @@ static int bwd_weight_impl(int B, int Cin, int Cout, int T, int K, int stride, i
     if (overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, (size_t)g.B * g.Cin * g.T * e))
         return NM_ERR_BAD_ARG;
     const bool mfma = use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) && aligned16(x) && aligned16(dy) &&
-                      (!relu || aligned16(y)) && masked_on_mfma(g);
+                      (!relu || aligned16(y)) && masked_on_mfma(g, NM_OP_BWD_WEIGHT);
     const bool dzneeded = needs_dz(flags, scale);
     const size_t need = workspace_for(NM_OP_BWD_WEIGHT, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
