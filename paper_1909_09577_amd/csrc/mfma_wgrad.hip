@@ -51,6 +51,7 @@ struct WgradParams {
     int dz_row_bytes, dz_bytes, x_bytes, buf_bytes;
     int total, per_xcd, CL;    // work-item numbering (CL == 0: plain order)
     const bf16_t *x;           // [B][Cin][T]
+    const int *len;            // [B] valid lengths of x (samples beyond read as zero) or NULL
     const bf16_t *dz;          // [B][Cout][To]
     float *part;               // [S][K][Cout][Cin]
     // stride-1, dilation-1 kernel only: dz in MFMA A-fragment order [B][ncm][nst][64 lanes][8]
@@ -374,6 +375,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradParams p)
 //     64-byte rows (any 4 consecutive rows cover all 64 banks, so the transposing reads are
 //     conflict-free) and every fragment read is `base + immediate`.
 // A last tap group that is one tap short skips that tap; shorter ones multiply unused taps.
+// valid length of batch item b from an optional device array, clipped to [0, T]
+__device__ __forceinline__ int clipped_len(const int *len, int b, int T)
+{
+    if (!len) return T;
+    const int n = len[b];
+    return n < 0 ? 0 : (n > T ? T : n);
+}
 constexpr int kFastTCH = 80;
 constexpr int kFastSteps = kFastTCH / 16;
 constexpr int kFastXRowBytes = 64;
@@ -455,6 +463,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         uint32_t xs;  // scalar byte offset of the unit's batch item in x
         int tbase;    // first output step
         uint32_t as;  // scalar byte offset of the unit's dz fragments (channel block 0, step 0)
+        int tlen;     // valid length of the unit's batch item (T without lengths)
         bool live;
     };
     auto unit_addr = [&](int u) {
@@ -465,11 +474,12 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         a.tbase = chunk * kFastTCH;
         a.xs = (uint32_t)((size_t)b * p.Cin * p.T * 2);
         a.as = (uint32_t)((((size_t)b * p.ncm + (co0 >> 5)) * p.nst + (size_t)chunk * kFastSteps) * 1024);
+        a.tlen = p.len ? __builtin_amdgcn_readfirstlane(clipped_len(p.len, b, p.T)) : p.T;
         return a;
     };
     auto x_load_item = [&](const UnitAddr &a, int q, u32x4 &xa, u32x4 &xb) {
         const int t = a.tbase + x_t0 + 32 * q;
-        const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);  // 0 <= t and t + 8 <= T
+        const bool t_ok = a.live && (unsigned)t < (unsigned)a.tlen;  // groups that start inside [0, tlen)
         // the lane offset carries the time (it is negative only where t is, and those lanes are masked)
         xa = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
         xb = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2 + 64 * q) : kFar, a.xs);
@@ -490,6 +500,18 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
 #pragma unroll
         for (int q = 0; q < kFastXItems; ++q) x_write_item(buf, q, xa[q], xb[q]);
     };
+    // With lengths the group that contains the first padding sample was staged whole: its rows from the
+    // valid length on are cleared after the window has been written.
+    const bool masked = p.len != nullptr;
+    auto clear_padding_rows = [&](unsigned char *buf, int tlen, int tbase) {
+        if (!masked) return;
+        const int r0 = tlen - (tbase + xs_rel_al);
+        const int nr = ((tlen + 7) & ~7) - tlen;
+        if (tlen < p.T && nr > 0 && r0 >= 0 && r0 < kRows) {
+            for (int r = lane >> 4; r < nr; r += 4)
+                *reinterpret_cast<uint32_t *>(buf + (size_t)(r0 + r) * kFastXRowBytes + (lane & 15) * 4) = 0u;
+        }
+    };
     // A fragments of one unit: [mi][step], 1 KiB contiguous per wavefront and fragment
     const uint32_t a_lane = (uint32_t)lane * 16;
     const uint32_t a_mi = (uint32_t)p.nst * 1024;  // from channel block mi to mi + 1
@@ -508,6 +530,7 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
     const int my_units = slot_id < p.units ? (p.units - slot_id + slots - 1) / slots : 0;
     if (my_units == 0) return;
     u32x4 xa0[kFastXItems], xb0r[kFastXItems], xa1[kFastXItems], xb1r[kFastXItems];
+    int pend_tlen = 0, pend_tbase = 0;  // of the unit whose x window waits in registers for its LDS write
     {
         const UnitAddr a0 = unit_addr(slot_id), a1 = unit_addr(slot_id + slots);
 #pragma unroll
@@ -520,6 +543,9 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
         x_load(a0, xa0, xb0r);
         x_load(a1, xa1, xb1r);   // written at the end of the first unit
         x_write(wbuf0, xa0, xb0r);
+        clear_padding_rows(wbuf0, a0.tlen, a0.tbase);
+        pend_tlen = a1.tlen;
+        pend_tbase = a1.tbase;
     }
     // one unit: multiply from LDS buffer `par` and the fragment set afr; request the dz fragments and
     // the x window of unit u + 2*slots into afr and (xa, xb) -- the x set that was written before
@@ -588,6 +614,9 @@ __device__ __forceinline__ void fast_units(const WgradParams &p, unsigned char *
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        clear_padding_rows(wr, pend_tlen, pend_tbase);
+        pend_tlen = an.tlen;
+        pend_tbase = an.tbase;
     };
     const int npairs = (my_units + 1) >> 1;
     int u = slot_id;
@@ -672,6 +701,7 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     struct UnitAddr {
         uint32_t xs, as;
         int tbase;
+        int tlen;  // valid length of the unit's batch item (T without lengths)
         bool live;
     };
     // units of this workgroup: sp, sp + S, sp + 2S, ...; (batch item, chunk) advance without divisions
@@ -694,11 +724,12 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         a.tbase = q.c * kFastTCH;
         a.xs = (uint32_t)b * (uint32_t)(p.Cin * p.T * 2);
         a.as = (uint32_t)((b * p.ncm + (co0 >> 5)) * p.nst + q.c * kFastSteps) * 1024u;
+        a.tlen = p.len ? __builtin_amdgcn_readfirstlane(clipped_len(p.len, b, p.T)) : p.T;
         return a;
     };
     auto x_load_item = [&](const UnitAddr &a, u32x4 &xa, u32x4 &xb) {
         const int t = a.tbase + x_t0;
-        const bool t_ok = a.live && (unsigned)t <= (unsigned)(p.T - 8);
+        const bool t_ok = a.live && (unsigned)t < (unsigned)a.tlen;  // groups that start inside [0, tlen)
         xa = buf_load16(rs_x, t_ok ? x_lane_a + (uint32_t)(a.tbase * 2) : kFar, a.xs);
         xb = buf_load16(rs_x, t_ok ? x_lane_b + (uint32_t)(a.tbase * 2) : kFar, a.xs);
     };
@@ -708,6 +739,18 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         for (int e = 0; e < 4; ++e) {
             dst[(2 * e) * (kFastXRowBytes / 4)] = zip_lo16(xa[e], xb[e]);
             dst[(2 * e + 1) * (kFastXRowBytes / 4)] = zip_hi16(xa[e], xb[e]);
+        }
+    };
+    // With lengths the group that contains the first padding sample was staged whole: the wavefront
+    // whose item holds it clears its rows from the valid length on (after its write, before the barrier).
+    const bool masked = p.len != nullptr;
+    auto clear_padding_rows = [&](unsigned char *buf, int tlen, int tbase) {
+        if (!masked) return;
+        const int r0 = tlen - (tbase + xs_rel_al);   // first padding row of the window
+        const int nr = ((tlen + 7) & ~7) - tlen;
+        if (tlen < p.T && nr > 0 && r0 >= 32 * W && r0 < 32 * W + 32) {
+            for (int r = lane >> 4; r < nr; r += 4)
+                *reinterpret_cast<uint32_t *>(buf + (size_t)(r0 + r) * kFastXRowBytes + (lane & 15) * 4) = 0u;
         }
     };
     const uint32_t a_lane = (uint32_t)lane * 16;
@@ -729,6 +772,7 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
 
     const int my_units = sp < p.units ? (p.units - sp + S - 1) / S : 0;  // the same for all four wavefronts
     u32x4 xa0, xb0r, xa1, xb1r;
+    int pend_tlen = 0, pend_tbase = 0;  // of the unit whose x item waits in registers for its LDS write
     {
         UnitPos q0 = unit_pos(sp), q1 = q0;
         advance(q1);
@@ -743,6 +787,9 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         x_load_item(a0, xa0, xb0r);
         x_load_item(a1, xa1, xb1r);  // written during the first unit
         x_write_item(smem, xa0, xb0r);
+        clear_padding_rows(smem, a0.tlen, a0.tbase);
+        pend_tlen = a1.tlen;
+        pend_tbase = a1.tbase;
         __syncthreads();
     }
     // one unit: multiply from window `par`; request the dz fragments and this wavefront's x item of
@@ -800,6 +847,9 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        clear_padding_rows(wr, pend_tlen, pend_tbase);
+        pend_tlen = an.tlen;
+        pend_tbase = an.tbase;
         __syncthreads();  // the other window is complete; this one may be overwritten
     };
     const int npairs = (my_units + 1) >> 1;
@@ -1083,6 +1133,7 @@ hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, b
     number_work_items(p);
     if (f.shared) p.CL = -1;
     p.x = (const bf16_t *)x; p.dzf = dzf; p.part = part;
+    p.len = g.len;
     const int grid = p.per_xcd * 8;
     hipError_t e;
     if (f.shared) {

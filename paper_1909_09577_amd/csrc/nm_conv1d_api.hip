@@ -89,9 +89,13 @@ bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || 
 
 bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
 
-// Whether a call with per-sample lengths may take the matrix-core kernels: the forward pass and the
-// input gradient apply them there; the weight gradient with lengths runs on the plain kernel.
-bool masked_on_mfma(const Geom &g, int op = NM_OP_FWD) { return g.len == nullptr || op != NM_OP_BWD_WEIGHT; }
+// Whether a call with per-sample lengths may take the matrix-core kernels: the forward pass, the input
+// gradient and the stride-1 weight-gradient kernels apply them; the general weight-gradient kernel
+// does not (lengths then go to the plain kernel).
+bool masked_on_mfma(const Geom &g, int op = NM_OP_FWD)
+{
+    return g.len == nullptr || op != NM_OP_BWD_WEIGHT || mfma_wgrad_fast_supported(g);
+}
 
 // Scratch need of one operation on one path (mfma: matrix-core kernels, else plain kernels).
 size_t workspace_for(int op, const Geom &g, int dtype, bool mfma, bool scale_or_relu)

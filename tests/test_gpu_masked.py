@@ -27,6 +27,9 @@ CASES = [
     (L("k_dil2", 2, 96, 80, 248, 9, dilation=2, pad=8), [248, 100]),
     (L("k_zero_len", 2, 16, 16, 64, 5, pad=2), [0, 64]),
     (L("k_odd_len", 2, 40, 48, 333, 7, pad=3, residual=True), [333, 150]),
+    # the weight-gradient kernel with shared staging (8 x 32 = 256 output tiles) and the K=1 kernel at full width
+    (L("k_shared_wgrad", 2, 1024, 512, 160, 17, pad=8, affine=False, relu=False), [160, 77]),
+    (L("k_shared_wgrad_k13", 3, 1024, 512, 240, 13, pad=6, affine=False, relu=False), [1, 239, 100]),
 ]
 
 
