@@ -4,19 +4,27 @@
 A step is one pass of the whole hot path over one synthetic batch of the headline workload
 (Jasper B3-shaped block: B=32, Cin=Cout=512, T=800, K=17, stride 1, pad 8, bf16 storage,
 float32 accumulation, folded-BN affine + residual + ReLU):
-    nm_conv1d_block_fwd  ->  nm_conv1d_bwd_data (dx and dres)  ->  nm_conv1d_bwd_weight
-with every helper kernel of those calls (weight packing, dz pass, dw reduction) inside the timed
-region and all inputs resident in HBM before it starts.  The same step with both gradients from one
-call (nm_conv1d_bwd) is timed afterwards and reported as an extra object, not as the headline.  The metric is
+    nm_conv1d_block_fwd  ->  nm_conv1d_bwd (input gradient with dres, and weight gradient)
+with every helper kernel of those calls (weight packing, the mask pass over dy and y, the dw
+reduction) inside the timed region and all inputs resident in HBM before it starts.  The same step with
+the two gradients from separate calls (nm_conv1d_bwd_data, nm_conv1d_bwd_weight: bit-identical results,
+the mask pass runs twice) is timed afterwards and reported as an extra object.  The metric is
 3 * 2*B*Cout*T_out*Cin*K flop per step divided by the measured time, in TFLOP/s.
+
+Protocol: W warm-up steps (events around each main kernel find the dominant one), then an untimed
+settling phase (`settle_steps` in the JSON line: the chip's clocks and power state take some tens of
+milliseconds of load to settle, which a short timed region would otherwise measure), then exactly K
+timed steps between two device synchronisations, timed with the host clock (`ms_per_step`, the
+headline) and with an event pair around the whole loop (`ms_per_step_device`).
 
 The JSON line also carries
   roofline     -- the dominant kernel (largest share of the step) against the bf16 dense MFMA
                   peak; its average duration is measured in the timed region with HIP events
                   recorded on the launch stream right around that kernel (the library's
                   nm_conv1d_time_next_main_kernel hook) in every fourth step;
-  cpu_baseline -- the fp64 CPU oracle, untuned, timed on the host cores on the first 8 of the
-                  32 batch items of the same workload (a baseline, not the target).
+  main_kernels -- duration, TFLOP/s, algorithmic bytes and GB/s of the three main kernels (warm-up events);
+  cpu_baseline -- the fp64 CPU oracle, untuned, timed on the host cores on the full workload
+                  (a baseline, not the target).
 """
 import argparse
 import json
@@ -26,27 +34,55 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
 
 
-def cpu_baseline(cfg_full):
-    """Oracle forward + both gradients on a bounded sample (first 8 batch items)."""
+WORKLOADS = {"b1": "JASPER_B1", "b3": "JASPER_B3", "epilog_a": "EPILOG_A", "epilog_b": "EPILOG_B", "epilog_c": "EPILOG_C"}
+METRIC_NAMES = {
+    "b3": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), C=512 K=17 T=800",
+    "b1": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), C=256 K=11 T=800",
+    "epilog_a": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), 768->896 K=29 dilation 2 T=800",
+    "epilog_b": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), 896->1024 K=1 T=800",
+    "epilog_c": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), 1024->29 K=1 T=800",
+}
+
+
+def describe(cfg):
+    epi = "+".join(n for n, on in (("affine", cfg.affine), ("residual", cfg.residual), ("ReLU", cfg.relu)) if on) or "no epilogue"
+    return (f"{cfg.name}: B={cfg.B} Cin={cfg.Cin} Cout={cfg.Cout} T={cfg.T} K={cfg.K} stride {cfg.stride} "
+            f"dilation {cfg.dilation} pad {cfg.pad}, {epi}, fwd+dgrad(+dres)+wgrad")
+
+
+def kernel_names_for(cfg):
+    """Names of the three main kernels as a profiler lists them (for matching against profiles/)."""
+    if cfg.K == 1:
+        conv = "pointwise_gemm_kernel" if cfg.Cout > 64 else "conv_gemm_kernel<5, 1, 0>"
+        conv_d = "pointwise_gemm_kernel" if cfg.Cin > 64 else "conv_gemm_kernel<5, 1, 0>"
+        return {"fwd": conv + " (forward)", "dgrad": conv_d + " (input gradient)", "wgrad": "wgrad_fast_kernel<1, 1>"}
+    conv = f"conv_gemm_kernel<5, 1, {cfg.K}>"
+    wg = {17: "wgrad_shared_kernel<17, 1>", 11: "wgrad_shared_kernel<11, 1>", 29: "wgrad_shared_kernel<15, 2>"}.get(cfg.K, "wgrad kernel")
+    return {"fwd": conv + " (forward)", "dgrad": conv + " (input gradient)", "wgrad": wg}
+
+
+def cpu_baseline(cfg):
+    """Oracle forward + both gradients on the whole workload (about ten seconds on 16 cores)."""
     import numpy as np
-    import _util as U
     from oracle import conv1d_oracle as orc
     from paper_1909_09577_amd import inputs as syn
-    nb = min(8, cfg_full.B)
-    cfg = syn.shrink(cfg_full, B=nb)
+    from paper_1909_09577_amd.device_inputs import geom_kw
     inp = syn.make_inputs(cfg, "bf16")
+    kw = geom_kw(cfg)
     t0 = time.perf_counter()
-    y = U.oracle_fwd(cfg, inp)
-    dx, dw, dres = U.oracle_bwd(cfg, inp, y)
+    y = orc.block_fwd(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["residual"], True, **kw)
+    dz, dres = orc.epilogue_bwd(inp["dy"], y, inp["scale"], True)
+    dx = orc.bwd_data(dz, inp["w"], cfg.T, **kw)
+    dw = orc.bwd_weight(inp["x"], dz, cfg.K, **kw)
     dt = time.perf_counter() - t0
+    assert np.isfinite(dx).all() and np.isfinite(dw).all() and dres.shape == y.shape
     flops = 3 * cfg.flops_per_pass
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"first {nb} of {cfg_full.B} batch items of the same workload, fp64, fwd+dgrad+wgrad, {dt:.1f} s"}
+            "sample": f"the whole workload (all {cfg.B} batch items), fp64, fwd+dgrad+wgrad, {dt:.1f} s"}
 
 
 def recorded_traffic(kernel_key):
@@ -72,10 +108,43 @@ def recorded_traffic(kernel_key):
     return float(m.group(1)) * 1e6 if m else None
 
 
-def stack_report():
-    """Time of one forward+backward step of the whole 64-layer 10x5-shaped stack (B=32, T=1600->800):
-    every distinct layer shape is timed on its own (block forward + nm_conv1d_bwd) and weighted with
-    the number of times it occurs; prints one JSON line.  Not the headline: `--stack` only."""
+def stack_report(steps, warmup):
+    """One forward+backward step of the whole 64-layer 10x5-shaped stack (B=32, T=1600->800), chained by the
+    product's stack driver (every layer's block forward, then every layer's fused backward, activations kept
+    for backward, block-input gradients summed by NM_ACCUM_DX), timed as one thing with an event pair around
+    `steps` steps.  Prints one JSON line.  Not the headline: `--stack` only."""
+    import torch
+    from paper_1909_09577_amd import inputs as syn
+    from paper_1909_09577_amd import stack as nmstack
+    layers = syn.jasper_10x5_layers()
+    st = nmstack.EncoderStack(layers, nmstack.random_parameters(layers, seed=4))
+    c0, cl = layers[0]["cfg"], layers[-1]["cfg"]
+    x = torch.randn(c0.B, c0.Cin, c0.T, device="cuda").bfloat16()
+    dy = torch.randn(cl.B, cl.Cout, cl.T_out, device="cuda").bfloat16()
+    for _ in range(max(warmup, 2)):
+        st.step(x, dy)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        st.step(x, dy)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_host = (time.perf_counter() - t0) / steps * 1e3
+    ms = e0.elapsed_time(e1) / steps
+    flop = st.flops_per_step
+    print(json.dumps({"metric": "10x5 encoder stack fwd+bwd, 64 layers chained (bf16)", "ms_per_step": round(ms_host, 3),
+                      "ms_per_step_device": round(ms, 3), "steps": steps, "warmup": max(warmup, 2),
+                      "value": round(flop / ms_host / 1e9, 1), "unit": "TFLOP/s",
+                      "frac_of_bf16_mfma_peak": round(flop / ms_host / 1e9 / PEAK_BF16_TFLOPS, 4),
+                      "flop_per_step": flop, "config": {"workload": "Jasper 10x5-shaped stack, B=32, input [32,64,1600]"}}),
+          flush=True)
+
+
+def stack_layers_report():
+    """Every distinct layer shape of the 64-layer stack timed on its own (block forward + nm_conv1d_bwd) and
+    weighted with the number of times it occurs; prints one JSON line.  `--stack-layers` only."""
     import torch
     from paper_1909_09577_amd import binding as nm
     from paper_1909_09577_amd import inputs as syn
@@ -110,12 +179,14 @@ def stack_report():
         for _ in range(3):
             step()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         n = 10
+        e0.record()
         for _ in range(n):
             step()
+        e1.record()
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) / n * 1e3
+        ms = e0.elapsed_time(e1) / n
         total_ms += ms * cnt
         total_flop += 3 * c.flops_per_pass * cnt
         rows.append({"layer": f"{c.Cin}->{c.Cout} K={c.K} s={c.stride} d={c.dilation}" + (" +res" if c.residual else ""),
@@ -173,73 +244,96 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--settle-steps", type=int, default=100,
+                    help="untimed steps between warm-up and the timed region (reported as settle_steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="run this many plain 256 MiB copy kernels (dst = src + 1) before the steps (counter runs only: "
                          "the copy kernel's FETCH_SIZE / WRITE_SIZE per byte moved scale the other kernels' counters)")
     ap.add_argument("--stack", action="store_true",
-                    help="instead of the headline: time every layer shape of the 64-layer stack (one extra JSON line)")
+                    help="instead of the headline: the chained 64-layer stack step (one extra JSON line)")
+    ap.add_argument("--stack-layers", action="store_true",
+                    help="instead of the headline: every layer shape of the 64-layer stack timed on its own")
     ap.add_argument("--decoder", action="store_true",
                     help="instead of the headline: the decoder tail (1x1 conv + log-softmax), an HBM-bound step")
+    ap.add_argument("--workload", default="b3", choices=sorted(WORKLOADS),
+                    help="single-layer workload to time (default: the headline, b3); the others are for profiles")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch
-    import _util as U
     from paper_1909_09577_amd import binding as nm
     from paper_1909_09577_amd import inputs as syn
+    from paper_1909_09577_amd.device_inputs import geom_kw, to_dev
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     nm.lib()  # fails loudly if the HIP library has not been built
     if args.stack:
-        stack_report()
+        stack_report(max(args.steps // 10, 5), args.warmup // 5)
+        return
+    if args.stack_layers:
+        stack_layers_report()
         return
     if args.decoder:
         decoder_report(args.steps, args.warmup, not args.no_cpu_baseline)
         return
 
-    cfg = syn.HEADLINE
+    cfg = getattr(syn, WORKLOADS[args.workload])
+    headline = cfg is syn.HEADLINE
     dt = "bf16"
     inp = syn.make_inputs(cfg, dt)
-    kw = U.geom_kw(cfg)
-    x, w = U.to_dev(inp, "x", dt), U.to_dev(inp, "w", dt)
-    scale, shift = U.to_dev(inp, "scale", dt), U.to_dev(inp, "shift", dt)
-    res, dy = U.to_dev(inp, "residual", dt), U.to_dev(inp, "dy", dt)
-    To = cfg.T_out
+    kw = geom_kw(cfg)
+    relu = cfg.relu
+    x, w = to_dev(inp, "x", dt), to_dev(inp, "w", dt)
+    scale = to_dev(inp, "scale", dt) if cfg.affine else None
+    shift = to_dev(inp, "shift", dt) if cfg.affine else None
+    res = to_dev(inp, "residual", dt) if cfg.residual else None
+    dy = to_dev(inp, "dy", dt)
+    To = nm.nm_conv1d_out_len(cfg.T, cfg.K, cfg.stride, cfg.dilation, cfg.pad)
+    assert To == cfg.T_out
     y = torch.empty((cfg.B, cfg.Cout, To), dtype=torch.bfloat16, device="cuda")
     dx = torch.empty_like(x)
-    dres = torch.empty_like(y)
+    dres = torch.empty_like(y) if cfg.residual else None
     dw = torch.empty((cfg.Cout, cfg.Cin, cfg.K), dtype=torch.float32, device="cuda")
-    ws_bytes = max(nm.nm_conv1d_workspace_bytes(op, *cfg.dims(), nm.NM_BF16, nm.NM_RELU) for op in (0, 1, 2))
+    ws_bytes = max(nm.nm_conv1d_workspace_bytes(op, *cfg.dims(), nm.NM_BF16, nm.NM_RELU) for op in (0, 1, 2, 3))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ysv = y if relu else None
 
     def ev():
         e = torch.cuda.Event(enable_timing=True)
         e.record()  # torch creates the handle on first record
         return e
 
-    names = ("fwd", "dgrad", "wgrad")
-    # Events around a kernel split the stream's back-to-back dispatch (a few microseconds per pair), so
-    # the timed region carries them only around the dominant kernel and only in every fourth step; which
-    # kernel dominates is found with events around all three during the warmup steps.
-    every = 4
-    warm_pairs = {n: [(ev(), ev()) for _ in range(max(args.warmup, 1))] for n in names}
-    timed_steps = list(range(0, args.steps, every))
-    pairs = [(ev(), ev()) for _ in timed_steps]
+    def fwd(xs=x, rs=res, ys=y):
+        nm.nm_conv1d_block_fwd(xs, w, scale, shift, rs, y=ys, relu=relu, workspace=ws, **kw)
 
-    def step(hook=None):
-        if hook and "fwd" in hook:
+    def bwd(xs=x, dys=dy, ys=ysv, dxs=dx, drs=dres):
+        nm.nm_conv1d_bwd(xs, dys, w, y=ys, scale=scale, dx=dxs, dres=drs, dw=dw, relu=relu, workspace=ws, **kw)
+
+    def bwd_data():
+        nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, dx=dx, dres=dres, relu=relu, workspace=ws, **kw)
+
+    def bwd_weight():
+        nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=ysv, scale=scale, dw=dw, relu=relu, workspace=ws, **kw)
+
+    def step():
+        fwd()
+        bwd()
+
+    def step_three_calls(hook=None):
+        # the one-shot timer brackets the main kernel of the next call: here each of the three in turn
+        if hook:
             nm.nm_conv1d_time_next_main_kernel(*hook["fwd"])
-        nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw)
-        if hook and "dgrad" in hook:
+        fwd()
+        if hook:
             nm.nm_conv1d_time_next_main_kernel(*hook["dgrad"])
-        nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=y, scale=scale, dx=dx, dres=dres, relu=True, workspace=ws, **kw)
-        if hook and "wgrad" in hook:
+        bwd_data()
+        if hook:
             nm.nm_conv1d_time_next_main_kernel(*hook["wgrad"])
-        nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
+        bwd_weight()
 
     if args.calibration_copies:
         # an elementwise kernel that reads 256 MiB and writes 256 MiB (a device-to-device memcpy may go
@@ -251,40 +345,50 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(max(args.warmup, 1)):
-        step({n: warm_pairs[n][i] for n in names})
+    # ---- warm-up: the three main kernels are timed one by one (separate calls, so that the hook reaches each)
+    names = ("fwd", "dgrad", "wgrad")
+    nwarm = max(args.warmup, 1)
+    warm_pairs = {n: [(ev(), ev()) for _ in range(nwarm)] for n in names}
+    for i in range(nwarm):
+        step_three_calls({n: warm_pairs[n][i] for n in names})
     torch.cuda.synchronize()
-    warm_ms = {n: sorted(a.elapsed_time(b) for a, b in warm_pairs[n])[len(warm_pairs[n]) // 2] for n in names}
+    warm_ms = {n: sorted(a.elapsed_time(b) for a, b in warm_pairs[n])[nwarm // 2] for n in names}
     dominant = max(warm_ms, key=warm_ms.get)
 
+    # ---- settling phase (untimed, disclosed), then the timed region
+    for _ in range(max(args.settle_steps, 0)):
+        step()
+    # Events around a kernel split the stream's back-to-back dispatch (a few microseconds per pair), so the
+    # timed region carries them only around the dominant kernel and only in every fourth step.
+    every = 4
+    pairs = [(ev(), ev()) for _ in range(0, args.steps, every)]
+    op_of = {"fwd": nm.NM_OP_FWD, "dgrad": nm.NM_OP_BWD_DATA, "wgrad": nm.NM_OP_BWD_WEIGHT}
+
+    def timed_step(pair):
+        if dominant == "fwd":
+            nm.nm_conv1d_time_next_kernel_of(*pair, nm.NM_OP_FWD)
+            fwd()
+            bwd()
+        else:
+            fwd()
+            nm.nm_conv1d_time_next_kernel_of(*pair, op_of[dominant])
+            bwd()
+
+    loop_a, loop_b = ev(), ev()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    loop_a.record()
     for i in range(args.steps):
-        step({dominant: pairs[i // every]} if i % every == 0 else None)
+        if i % every == 0:
+            timed_step(pairs[i // every])
+        else:
+            step()
+    loop_b.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step_device = loop_a.elapsed_time(loop_b) / args.steps
 
-    # the same step with both gradients from one call (nm_conv1d_bwd): reported beside the headline
-    ws_f = torch.empty(max(nm.nm_conv1d_workspace_bytes(nm.NM_OP_BWD, *cfg.dims(), nm.NM_BF16, nm.NM_RELU), 256),
-                       dtype=torch.uint8, device="cuda")
-
-    def step_fused():
-        nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw)
-        nm.nm_conv1d_bwd(x, dy, w, y=y, scale=scale, dx=dx, dres=dres, dw=dw, relu=True, workspace=ws_f, **kw)
-
-    for _ in range(max(args.warmup, 1)):
-        step_fused()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step_fused()
-    torch.cuda.synchronize()
-    ms_fused = (time.perf_counter() - t1) / args.steps * 1e3
-
-    # per-pass times (event pairs around each call, helper kernels included) and a cold variant of the
-    # step: six buffer sets (about 1 GB, four times the 256 MB Infinity Cache) used in rotation, so that
-    # no tensor is found in a cache from the previous step.  Reported beside the headline, which is the
-    # warm step above (the tensors of one layer stay resident between its forward and backward pass).
     def timed(fn, n):
         a, b = ev(), ev()
         a.record()
@@ -294,59 +398,71 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
+    # the same step with the two gradients from separate calls: reported beside the headline
+    n_side = max(args.steps, 20)
+    ms_three = timed(step_three_calls, n_side)
+    # per-call times (helper kernels included)
     n_pass = max(args.steps // 4, 10)
-    per_pass = {
-        "fwd": timed(lambda: nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, **kw), n_pass),
-        "dgrad": timed(lambda: nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=y, scale=scale, dx=dx, dres=dres, relu=True,
-                                                     workspace=ws, **kw), n_pass),
-        "wgrad": timed(lambda: nm.nm_conv1d_bwd_weight(x, dy, cfg.K, y=y, scale=scale, dw=dw, relu=True, workspace=ws,
-                                                       **kw), n_pass),
-    }
-    sets = [tuple(torch.empty_like(t).copy_(t) for t in (x, res, dy, y, dx, dres)) for _ in range(6)]
+    per_call = {"block_fwd": timed(fwd, n_pass), "bwd": timed(bwd, n_pass), "bwd_data": timed(bwd_data, n_pass),
+                "bwd_weight": timed(bwd_weight, n_pass)}
+    # a cold variant of the step: six buffer sets (about 1 GB, four times the 256 MB Infinity Cache) used in
+    # rotation, so that no tensor is found in a cache from the previous step
+    sets = [tuple(None if t is None else torch.empty_like(t).copy_(t) for t in (x, res, dy, y, dx, dres)) for _ in range(6)]
     state = {"i": 0}
 
     def cold_step():
         xs, rs, dys, ys, dxs, drs = sets[state["i"] % len(sets)]
         state["i"] += 1
-        nm.nm_conv1d_block_fwd(xs, w, scale, shift, rs, y=ys, relu=True, workspace=ws, **kw)
-        nm.nm_conv1d_bwd_data(dys, w, cfg.T, y=ys, scale=scale, dx=dxs, dres=drs, relu=True, workspace=ws, **kw)
-        nm.nm_conv1d_bwd_weight(xs, dys, cfg.K, y=ys, scale=scale, dw=dw, relu=True, workspace=ws, **kw)
+        fwd(xs, rs, ys)
+        bwd(xs, dys, ys if relu else None, dxs, drs)
 
     for _ in range(len(sets)):
         cold_step()
     ms_cold = timed(cold_step, max(args.steps // 4, 12))
     del sets
 
-    ms_per_step = elapsed / args.steps * 1e3
     flops_step = 3 * cfg.flops_per_pass
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     dom_ms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
-    kernel_names = {"fwd": "conv_gemm_kernel<5,1,17> (forward)", "dgrad": "conv_gemm_kernel<5,1,17> (input gradient)",
-                    "wgrad": "wgrad_shared_kernel<17, 1>"}
+    e2 = 2  # bytes per bf16
+    n_x, n_y, n_w = cfg.B * cfg.Cin * cfg.T * e2, cfg.B * cfg.Cout * To * e2, cfg.Cout * cfg.Cin * cfg.K * e2
+    # algorithmic bytes per launch: each operand read once, each result written once
+    alg_bytes = {"fwd": n_x + n_w + (n_y if cfg.residual else 0) + n_y,        # x, w, residual -> y
+                 "dgrad": n_y + n_w + n_x,                                      # g = dy*[y>0], w -> dx
+                 "wgrad": n_x + n_y + 2 * n_w}                                  # x, g -> dw (float32)
+    kernel_names = kernel_names_for(cfg)
     achieved = cfg.flops_per_pass / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": recorded_traffic(dominant),
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": recorded_traffic(dominant) if headline else None,
                 "kernel": kernel_names[dominant],
-                "flops_per_launch": cfg.flops_per_pass,
-                "avg_launch_ms": round(dom_ms, 4), "timed_launches": len(pairs),
-                "warmup_main_kernels_ms": {n: round(v, 4) for n, v in warm_ms.items()}}
+                "flops_per_launch": cfg.flops_per_pass, "algorithmic_bytes_per_launch": alg_bytes[dominant],
+                "avg_launch_ms": round(dom_ms, 4), "timed_launches": len(pairs)}
+    main_kernels = {kernel_names[n]: {"ms": round(warm_ms[n], 4),
+                                      "tflops": round(cfg.flops_per_pass / (warm_ms[n] * 1e-3) / 1e12, 1),
+                                      "algorithmic_bytes": alg_bytes[n],
+                                      "algorithmic_gb_per_s": round(alg_bytes[n] / (warm_ms[n] * 1e-3) / 1e9, 1)}
+                    for n in names}
 
     out = {
-        "metric": "conv1d fwd+dgrad+wgrad TFLOP/s (bf16), C=512 K=17 T=800",
+        "metric": METRIC_NAMES[args.workload],
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "settle_steps": max(args.settle_steps, 0),
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_device": round(ms_per_step_device, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "Jasper B3-shaped block: B=32 Cin=Cout=512 T=800 K=17 stride 1 dilation 1 pad 8, "
-                               "affine+residual+ReLU, fwd+dgrad(+dres)+wgrad", "seed": cfg.seed},
+        "config": {"workload": describe(cfg), "seed": cfg.seed,
+                   "step": "nm_conv1d_block_fwd + nm_conv1d_bwd (dx, dres, dw)"},
         "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
-        "per_pass_ms": {n: round(v, 4) for n, v in per_pass.items()},
-        "per_pass_tflops": {n: round(cfg.flops_per_pass / (v * 1e-3) / 1e12, 1) for n, v in per_pass.items()},
+        "per_call_ms": {n: round(v, 4) for n, v in per_call.items()},
+        "three_call_step": {"ms_per_step": round(ms_three, 4), "value": round(flops_step / (ms_three * 1e-3) / 1e12, 2),
+                            "unit": "TFLOP/s",
+                            "note": "same step with nm_conv1d_bwd_data + nm_conv1d_bwd_weight instead of nm_conv1d_bwd "
+                                    "(device time over %d steps)" % n_side},
         "cold": {"ms_per_step": round(ms_cold, 4), "value": round(flops_step / (ms_cold * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
                  "note": "six rotating sets of activation tensors (about 1 GB), nothing cached from the previous step"},
-        "fused_backward": {"ms_per_step": round(ms_fused, 4), "value": round(flops_step / (ms_fused * 1e-3) / 1e12, 2),
-                           "unit": "TFLOP/s", "note": "same step with nm_conv1d_bwd (one dz pass for both gradients)"},
         "roofline": roofline,
+        "main_kernels": main_kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

@@ -60,8 +60,11 @@ enum {
     NM_RELU = 1u,        /* forward: apply max(.,0); backward: mask with [y > 0] (y required) */
     NM_ACCUM_DW = 2u,    /* bwd_weight: dw += result instead of dw = result (gradient
                             accumulation over several batches, paper Section 3.3) */
-    NM_FORCE_DIRECT = 4u /* use the plain one-thread-per-output kernels instead of the
+    NM_FORCE_DIRECT = 4u, /* use the plain one-thread-per-output kernels instead of the
                             matrix-core kernels (always used for NM_F32) */
+    NM_ACCUM_DX = 8u     /* bwd_data / bwd: dx = round(dx + gradient), one rounding, instead of dx = gradient:
+                            sums the two gradients that meet at the input of a residual block (the first
+                            sub-block's and the residual projection's) without a pass of its own */
 };
 
 enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2, NM_OP_BWD = 3 };
@@ -99,7 +102,11 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
  *   w     [Cout][Cin][K]    in,  dtype
  *   dx    [B][Cin][T]       out, dtype
  *   dres  [B][Cout][T_out]  out, dtype, or NULL: gradient with respect to the residual
- * In NM_BF16 mode dz = dy*m*scale is rounded to bfloat16 before it is contracted.
+ * In NM_BF16 mode the matrix-core kernels contract g = dy*m (exact in bfloat16) with the weights
+ * bf16(w[co,ci,k]*scale[co]): the affine factor is folded into the weight operand, rounded once per weight.
+ * The weight gradient contracts the same g and multiplies its float32 sums by scale[co].  The plain
+ * kernels (NM_FORCE_DIRECT, NM_F32) form dz = g*scale in the storage type instead.
+ * With lengths and NM_ACCUM_DX, positions at or beyond a sample's length keep their old value.
  */
 int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
                        const void *dy, const void *y, const float *scale, const void *w,
@@ -120,8 +127,7 @@ int nm_conv1d_bwd_weight(int B, int Cin, int Cout, int T, int K, int stride, int
  * Same results as nm_conv1d_bwd_data followed by nm_conv1d_bwd_weight on the same arguments,
  * bit for bit; where the matrix-core kernels apply, the mask-and-scale pass over dy and y that
  * forms dz runs once and feeds both gradients.  Arguments as for those two calls; dres may be
- * NULL; workspace of nm_conv1d_workspace_bytes(NM_OP_BWD, ...) bytes.  The one-shot timer of
- * nm_conv1d_time_next_main_kernel brackets the input-gradient kernel of this call. */
+ * NULL; workspace of nm_conv1d_workspace_bytes(NM_OP_BWD, ...) bytes. */
 int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
                   const void *x, const void *dy, const void *y, const float *scale, const void *w,
                   void *dx, void *dres, float *dw, unsigned flags, int dtype,
@@ -164,14 +170,19 @@ int nm_decoder_logsoftmax_fwd(int B, int Cin, int Ncls, int T, const void *x, co
                               const float *bias, float *logp, unsigned flags, int dtype,
                               void *hip_stream);
 
-/* Measurement aid (no effect on results).  Arms a one-shot timer for the calling thread: the
- * next nm_conv1d_block_fwd / nm_conv1d_bwd_data / nm_conv1d_bwd_weight call made by this thread
- * records `start_event` immediately before and `stop_event` immediately after its main
- * convolution kernel, on that call's stream (helper kernels of the call -- weight packing, the
- * dz = dy*m*scale pass, the final dw reduction -- stay outside the pair).  Both arguments are
- * hipEvent_t handles created by the caller with timing enabled; passing NULL for either
- * disarms.  The pair is consumed by that call whether it succeeds or not.  Returns NM_OK. */
+/* Measurement aid (no effect on results; the only state the library keeps, and
+ * it is per thread).  Arms a one-shot timer for the calling thread: the next entry-point call made by this
+ * thread records `start_event` immediately before and `stop_event` immediately after a main convolution
+ * kernel of that call, on the call's stream (helper kernels -- weight packing, the mask pass, the final dw
+ * reduction -- stay outside the pair).  Which kernel: the first main kernel the call launches
+ * (nm_conv1d_time_next_main_kernel: the input-gradient kernel of an nm_conv1d_bwd call), or the main
+ * kernel of pass `op` (nm_conv1d_time_next_kernel_of: NM_OP_FWD, NM_OP_BWD_DATA or NM_OP_BWD_WEIGHT; other
+ * values return NM_ERR_BAD_ARG), which reaches the weight-gradient kernel inside nm_conv1d_bwd.  Both
+ * arguments are hipEvent_t handles created by the caller with timing enabled; passing NULL for either
+ * disarms.  The pair is consumed by that call whether it succeeds, runs such a kernel, or not.
+ * Returns NM_OK. */
 int nm_conv1d_time_next_main_kernel(void *start_event, void *stop_event);
+int nm_conv1d_time_next_kernel_of(void *start_event, void *stop_event, int op);
 
 #ifdef __cplusplus
 }

@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_PKG, "libnmconv1d.so")
 
 NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE = 0, -1, -2, -3, -4
 NM_BF16, NM_F32 = 0, 1
-NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT = 1, 2, 4
+NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT, NM_ACCUM_DX = 1, 2, 4, 8
 NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
-           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_kernel_of", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.nm_decoder_logsoftmax_fwd.restype = i
         L.nm_conv1d_time_next_main_kernel.argtypes = [vp, vp]
         L.nm_conv1d_time_next_main_kernel.restype = i
+        L.nm_conv1d_time_next_kernel_of.argtypes = [vp, vp, i]
+        L.nm_conv1d_time_next_kernel_of.restype = i
         _lib = L
     return _lib
 
@@ -90,6 +92,14 @@ def nm_conv1d_time_next_main_kernel(start_event, stop_event) -> None:
         lib().nm_conv1d_time_next_main_kernel(None, None)
         return
     lib().nm_conv1d_time_next_main_kernel(ctypes.c_void_p(start_event.cuda_event), ctypes.c_void_p(stop_event.cuda_event))
+
+
+def nm_conv1d_time_next_kernel_of(start_event, stop_event, op: int) -> None:
+    """Like nm_conv1d_time_next_main_kernel for the main kernel of pass `op` (NM_OP_FWD / _BWD_DATA / _BWD_WEIGHT)."""
+    st = lib().nm_conv1d_time_next_kernel_of(ctypes.c_void_p(start_event.cuda_event), ctypes.c_void_p(stop_event.cuda_event),
+                                             int(op))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_time_next_kernel_of")
 
 
 # ---- tensor marshalling -----------------------------------------------------------------
@@ -162,7 +172,8 @@ def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, 
 
 
 def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stride=1, dilation=1, pad=0,
-                       relu=False, want_dres=False, force_direct=False, workspace=None, stream=None, lengths=None):
+                       relu=False, want_dres=False, force_direct=False, workspace=None, stream=None, lengths=None,
+                       accumulate_dx=False):
     """dx (and optionally dres) from the upstream gradient dy; returns (dx, dres).
     lengths (int32 [B], optional): valid input length of every sample; dx is zero beyond it."""
     torch = _torch()
@@ -170,10 +181,12 @@ def nm_conv1d_bwd_data(dy, w, T, y=None, scale=None, dx=None, dres=None, *, stri
     _, Cin, K = w.shape
     code = _dtype_code(dy)
     if dx is None:
+        if accumulate_dx:
+            raise ValueError("accumulate_dx needs an existing dx")
         dx = torch.empty((B, Cin, T), dtype=dy.dtype, device=dy.device)
     if dres is None and want_dres:
         dres = torch.empty_like(dy)
-    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0) | (NM_ACCUM_DX if accumulate_dx else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD_DATA, dims, code, flags, workspace, dy.device)
     fn, extra = (lib().nm_conv1d_bwd_data, ()) if lengths is None else (
@@ -215,7 +228,8 @@ def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dil
 
 
 def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, stride=1, dilation=1, pad=0,
-                  relu=False, want_dres=False, accumulate=False, force_direct=False, workspace=None, stream=None):
+                  relu=False, want_dres=False, accumulate=False, force_direct=False, workspace=None, stream=None,
+                  accumulate_dx=False):
     """Both gradients in one call; returns (dx, dres, dw)."""
     torch = _torch()
     B, Cin, T = x.shape
@@ -223,6 +237,8 @@ def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, 
     To = dy.shape[2]
     code = _dtype_code(x)
     if dx is None:
+        if accumulate_dx:
+            raise ValueError("accumulate_dx needs an existing dx")
         dx = torch.empty((B, Cin, T), dtype=x.dtype, device=x.device)
     if dres is None and want_dres:
         dres = torch.empty_like(dy)
@@ -230,7 +246,8 @@ def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, 
         if accumulate:
             raise ValueError("accumulate needs an existing dw")
         dw = torch.empty((Cout, Cin, K), dtype=torch.float32, device=x.device)
-    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0) | \
+        (NM_ACCUM_DX if accumulate_dx else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD, dims, code, flags, workspace, x.device)
     st = lib().nm_conv1d_bwd(

@@ -4,13 +4,15 @@ from __future__ import annotations
 import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
+OBJ_DIR = os.path.join(_PKG, "_build")
 LIB_PATH = os.path.join(_PKG, "libnmconv1d.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -22,33 +24,29 @@ def sources():
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every .hip source into one shared library; returns its path."""
+    """Compile every .hip source (one hipcc process per file, side by side) and link them into one
+    shared library; returns its path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + sources()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    jobs = []
+    for src in sources():
+        obj = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(src))[0] + ".o")
+        jobs.append((src, obj, [hipcc] + HIPCC_FLAGS + ["-c", "-o", obj, src]))
+
+    def run(job):
+        if verbose:
+            print(" ".join(job[2]), flush=True)
+        subprocess.run(job[2], check=True)
+        return job[1]
+
+    with ThreadPoolExecutor(max_workers=min(8, max(len(jobs), 1))) as pool:
+        objs = list(pool.map(run, jobs))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", LIB_PATH] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB_PATH
 
 
-PROBE_SRC = os.path.join(_PKG, "probes", "mfma_rate.hip")
-PROBE_BIN = os.path.join(_PKG, "probes", "mfma_rate")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """Compile the stand-alone MFMA rate probe (an executable, not part of the library)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-o", PROBE_BIN, PROBE_SRC]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return PROBE_BIN
-
-
 if __name__ == "__main__":
-    import sys
-    if len(sys.argv) > 1 and sys.argv[1] == "probe":
-        print(build_probe(verbose=True))
-    else:
-        print(build_library(verbose=True))
+    print(build_library(verbose=True))

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void epilogue_bwd_kernel(size_t n, int Co
 template <typename TS>
 __global__ __launch_bounds__(kThreads) void direct_dgrad_kernel(Geom g, const TS *__restrict__ dz,
                                                                 const TS *__restrict__ w,
-                                                                TS *__restrict__ dx)
+                                                                TS *__restrict__ dx, int accumulate)
 {
     const int tau = blockIdx.x * kThreads + threadIdx.x;
     const int ci0 = blockIdx.y * kChanPerThread;
@@ -125,7 +125,9 @@ __global__ __launch_bounds__(kThreads) void direct_dgrad_kernel(Geom g, const TS
 #pragma unroll
     for (int c = 0; c < kChanPerThread; ++c) {
         if (ci0 + c >= g.Cin) break;
-        store_from_f32(dx, ((size_t)b * g.Cin + ci0 + c) * g.T + tau, padding ? 0.f : acc[c]);
+        const size_t o = ((size_t)b * g.Cin + ci0 + c) * g.T + tau;
+        const float v = padding ? 0.f : acc[c];
+        store_from_f32(dx, o, accumulate ? load_as_f32(dx, o) + v : v);
     }
 }
 
@@ -133,6 +135,7 @@ __global__ __launch_bounds__(kThreads) void direct_dgrad_kernel(Geom g, const TS
 template <typename TS>
 __global__ __launch_bounds__(kThreads) void direct_wgrad_kernel(Geom g, const TS *__restrict__ x,
                                                                 const TS *__restrict__ dz,
+                                                                const float *__restrict__ scale,
                                                                 float *__restrict__ dw, int accumulate)
 {
     const int n = blockIdx.x * kThreads + threadIdx.x;
@@ -163,6 +166,7 @@ __global__ __launch_bounds__(kThreads) void direct_wgrad_kernel(Geom g, const TS
         }
     }
     const size_t o = ((size_t)co * g.Cin + ci) * g.K + k;
+    if (scale) acc *= scale[co];
     dw[o] = accumulate ? dw[o] + acc : acc;
 }
 
@@ -190,20 +194,21 @@ hipError_t fwd_t(const Geom &g, const void *x, const void *w, const float *scale
 }
 
 template <typename TS>
-hipError_t dgrad_t(const Geom &g, const void *dz, const void *w, void *dx, hipStream_t s)
+hipError_t dgrad_t(const Geom &g, const void *dz, const void *w, void *dx, bool accumulate, hipStream_t s)
 {
     dim3 grid((g.T + kThreads - 1) / kThreads, (g.Cin + kChanPerThread - 1) / kChanPerThread, g.B);
     hipLaunchKernelGGL(direct_dgrad_kernel<TS>, grid, dim3(kThreads), 0, s, g, (const TS *)dz,
-                       (const TS *)w, (TS *)dx);
+                       (const TS *)w, (TS *)dx, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 
 template <typename TS>
-hipError_t wgrad_t(const Geom &g, const void *x, const void *dz, float *dw, bool accumulate, hipStream_t s)
+hipError_t wgrad_t(const Geom &g, const void *x, const void *dz, const float *scale, float *dw, bool accumulate,
+                   hipStream_t s)
 {
     dim3 grid((g.Cin * g.K + kThreads - 1) / kThreads, g.Cout, 1);
     hipLaunchKernelGGL(direct_wgrad_kernel<TS>, grid, dim3(kThreads), 0, s, g, (const TS *)x,
-                       (const TS *)dz, dw, accumulate ? 1 : 0);
+                       (const TS *)dz, scale, dw, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -245,16 +250,17 @@ hipError_t launch_epilogue_bwd_vec8(const Geom &g, const void *dy, const void *y
     return hipGetLastError();
 }
 
-hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx,
+hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx, bool accumulate,
                                hipStream_t s)
 {
-    return is_bf16 ? dgrad_t<bf16_t>(g, dz, w, dx, s) : dgrad_t<float>(g, dz, w, dx, s);
+    return is_bf16 ? dgrad_t<bf16_t>(g, dz, w, dx, accumulate, s) : dgrad_t<float>(g, dz, w, dx, accumulate, s);
 }
 
-hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, float *dw,
+hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, const float *scale, float *dw,
                                bool accumulate, hipStream_t s)
 {
-    return is_bf16 ? wgrad_t<bf16_t>(g, x, dz, dw, accumulate, s) : wgrad_t<float>(g, x, dz, dw, accumulate, s);
+    return is_bf16 ? wgrad_t<bf16_t>(g, x, dz, scale, dw, accumulate, s)
+                   : wgrad_t<float>(g, x, dz, scale, dw, accumulate, s);
 }
 
 }  // namespace nm

@@ -967,7 +967,9 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
 // Packed weights: [mt][chunk][tap < Kp][ks][mi][lane][8] (Kp = K rounded up to even, the extra
 // tap is zero); element (lane, j) of fragment (ks, mi) is
 // W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside,
-// with W'[m][r][k] = w[m][r][k] (forward) or w[r][m][K-1-k] (input gradient: FLIP).
+// with W'[m][r][k] = w[m][r][k] (forward) or w[r][m][K-1-k] * rscale[r] (input gradient: FLIP; r is the
+// block's output channel co, rscale its folded-BatchNorm factor or NULL for 1; the product is rounded to
+// bf16, so the input gradient contracts the exact dy*[y>0] with bf16(w*scale)).
 // One block packs 16 of the 64 channels of one (mt, chunk): it copies that 16x32xK block of w
 // into LDS with coalesced reads (runs of 32*K, resp. 16*K, contiguous elements) and gathers the
 // fragments from there.
@@ -978,7 +980,8 @@ __host__ __device__ constexpr int pack_m_stride(int K) { return kChunk * K + 2; 
 template <bool FLIP>
 __device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem, const bf16_t *__restrict__ w,
                                               u32x4 *__restrict__ wp, int M, int R, int K, int nch,
-                                              int ld /* row length of w */, size_t zero_off, int vec /* 16-byte aligned runs */)
+                                              int ld /* row length of w */, size_t zero_off, int vec /* 16-byte aligned runs */,
+                                              const float *__restrict__ rscale = nullptr)
 {
     bf16_t *tile = reinterpret_cast<bf16_t *>(smem);  // [16 m][32 r][K] as m*ms + r*K + k
     const int ms = pack_m_stride(K);
@@ -999,10 +1002,14 @@ __device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem,
     auto row_off = [&](int row) {  // element offset of the run in w
         return FLIP ? (size_t)(r0 + row) * ld + (size_t)m0 * K : (size_t)(m0 + row) * ld + (size_t)r0 * K;
     };
-    auto put = [&](int row, int o, bf16_t v) {  // element o of run `row`
+    auto row_factor = [&](int row) {  // FLIP only: a run belongs to one reduction channel
+        return (FLIP && rscale && r0 + row < R) ? rscale[r0 + row] : 1.f;
+    };
+    const bool scaled = FLIP && rscale != nullptr;
+    auto put = [&](int row, int o, bf16_t v, float f) {  // element o of run `row`
         if (FLIP) {
             const int m = o / K, k = o - m * K;
-            tile[m * ms + row * K + (K - 1 - k)] = v;
+            tile[m * ms + row * K + (K - 1 - k)] = scaled ? f32_to_bf16(bf16_to_f32(v) * f) : v;
         } else {
             tile[row * ms + o] = v;
         }
@@ -1023,11 +1030,12 @@ __device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem,
                 const int v = v0 + u * 256;
                 if (v < nvec) {
                     const int row = v / vpr, o = (v - row * vpr) * 8;
+                    const float f = row_factor(row);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const uint32_t word = d[u][e >> 1];
                         const bf16_t val = (bf16_t)((e & 1) ? word >> 16 : word & 0xffffu);
-                        put(row, o + e, (o + e < valid) ? val : (bf16_t)0);
+                        put(row, o + e, (o + e < valid) ? val : (bf16_t)0, f);
                     }
                 }
             }
@@ -1036,7 +1044,8 @@ __device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem,
         for (int row = wv; row < nrows; row += 4) {
             const bool ok = row_ok(row);
             const bf16_t *src = w + (ok ? row_off(row) : (size_t)0);
-            for (int o = lane; o < run; o += 64) put(row, o, (ok && o < valid) ? src[o] : (bf16_t)0);
+            const float f = row_factor(row);
+            for (int o = lane; o < run; o += 64) put(row, o, (ok && o < valid) ? src[o] : (bf16_t)0, f);
         }
     }
     __syncthreads();
@@ -1057,46 +1066,60 @@ __device__ __forceinline__ void prepack_block(unsigned blk, unsigned char *smem,
 
 template <bool FLIP>
 __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__ w, u32x4 *__restrict__ wp, int M,
-                                                      int R, int K, int nch, int ld, size_t zero_off, int vec)
+                                                      int R, int K, int nch, int ld, size_t zero_off, int vec,
+                                                      const float *__restrict__ rscale)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    prepack_block<FLIP>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+    prepack_block<FLIP>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec, rscale);
+}
+
+// g = dy * [y > 0] for one 16-byte group (8 bf16): the mask works on the bits, so g is exact.
+__device__ __forceinline__ u32x4 masked_grad8(u32x4 g, const u32x4 yv)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
+        g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
+    }
+    return g;
 }
 
 // Everything the input-gradient engine needs, in one launch: the first npack blocks pack the
-// flipped weights (a latency-bound job), the others run the elementwise epilogue backward
-// (dz and dres; bandwidth bound), so the two overlap instead of following each other.
+// flipped weights times the affine factor of their output channel (a latency-bound job), the others
+// run the elementwise mask pass g = dy*[y>0] (bandwidth bound), so the two overlap instead of
+// following each other.  g is what the engine contracts; it is also the residual gradient, so it
+// is written straight into dres when the caller asked for that, into the workspace otherwise.
 __global__ __launch_bounds__(256) void dgrad_prepare_kernel(unsigned npack, const bf16_t *__restrict__ w,
                                                             u32x4 *__restrict__ wp, int M, int R, int K, int nch,
-                                                            int ld, size_t zero_off, int vec, size_t n8, int Cout,
-                                                            int To8, const u32x4_t *__restrict__ dy,
-                                                            const u32x4_t *__restrict__ y, const float *__restrict__ scale,
-                                                            int relu, u32x4_t *__restrict__ dz, u32x4_t *__restrict__ dres)
+                                                            int ld, size_t zero_off, int vec,
+                                                            const float *__restrict__ rscale, size_t n8,
+                                                            const u32x4 *__restrict__ dy, const u32x4 *__restrict__ y,
+                                                            int relu, u32x4 *__restrict__ gout)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     if (blockIdx.x < npack) {
-        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec, rscale);
     } else {
         const size_t i = (size_t)(blockIdx.x - npack) * 256 + threadIdx.x;
-        if (i < n8) epilogue_bwd_vec8_item(i, Cout, To8, dy, y, scale, relu, dz, dres);
+        if (i < n8) gout[i] = relu ? masked_grad8(dy[i], y[i]) : dy[i];
     }
 }
 
-// The same for a fused backward call: the elementwise part also writes dz in the fragment order
+// The same for a fused backward call: the elementwise part also writes g in the fragment order
 // of the stride-1 weight-gradient kernel, so dy and y are read once for both gradients.  Its
 // threads are laid out like the fragments (one wavefront per 32 channels x 16 time steps: lane l
 // handles channel l%32, time steps 8*(l/32) .. +7), which makes the fragment stores contiguous.
+// gplain may be NULL (no ReLU and no residual gradient wanted: the engine then reads dy itself).
 __global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const bf16_t *__restrict__ w,
                                                           u32x4 *__restrict__ wp, int M, int R, int K, int nch, int ld,
-                                                          size_t zero_off, int vec, int B, int Cout, int To, int ncm,
-                                                          int nst, const bf16_t *__restrict__ dy,
-                                                          const bf16_t *__restrict__ y, const float *__restrict__ scale,
-                                                          int relu, u32x4 *__restrict__ dz, u32x4 *__restrict__ dzf,
-                                                          u32x4 *__restrict__ dres)
+                                                          size_t zero_off, int vec, const float *__restrict__ rscale,
+                                                          int B, int Cout, int To, int ncm, int nst,
+                                                          const bf16_t *__restrict__ dy, const bf16_t *__restrict__ y,
+                                                          int relu, u32x4 *__restrict__ gplain, u32x4 *__restrict__ gf)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     if (blockIdx.x < npack) {
-        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec);
+        prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec, rscale);
         return;
     }
     const int lane = threadIdx.x & 63;
@@ -1106,29 +1129,14 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const 
     const int st = frag % nst, cm = (frag / nst) % ncm, b = frag / ((unsigned)nst * ncm);
     const int co = cm * 32 + (lane & 31);
     const int t = 16 * st + 8 * (lane >> 5);
-    u32x4 g = {0u, 0u, 0u, 0u}, r = {0u, 0u, 0u, 0u};
+    u32x4 g = {0u, 0u, 0u, 0u};
     if (co < Cout && t + 8 <= To) {
         const size_t i = (((size_t)b * Cout + co) * To + t) / 8;  // 16-byte group index
         g = reinterpret_cast<const u32x4 *>(dy)[i];
-        if (relu) {
-            const u32x4 yv = reinterpret_cast<const u32x4 *>(y)[i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
-                g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
-            }
-        }
-        r = g;
-        if (scale) {
-            const float sc = scale[co];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                r[j] = pack_bf16x2(__uint_as_float(g[j] << 16) * sc, __uint_as_float(g[j] & 0xffff0000u) * sc);
-        }
-        if (dres) dres[i] = g;
-        dz[i] = r;
+        if (relu) g = masked_grad8(g, reinterpret_cast<const u32x4 *>(y)[i]);
+        if (gplain) gplain[i] = g;
     }
-    dzf[(size_t)frag * 64 + lane] = r;
+    gf[(size_t)frag * 64 + lane] = g;
 }
 
 // ---- input gradient of a stride-2 convolution (the encoder's first layer) -------------------------
@@ -1235,14 +1243,10 @@ template <int NT, int STRIDE, int KT>
 hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 {
     auto kern = conv_gemm_kernel<NT, STRIDE, KT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), kMaxLds);
     if (e != hipSuccess) return e;
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-    }
+    const int cus = current_device_info().cus;
     const int grid = p.num_tiles < cus ? p.num_tiles : cus;
     ConvGemmParams q = p;
     // private tiles per wavefront (unrolled kernels only); a remainder of more than three shared rounds
@@ -1255,14 +1259,10 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 
 hipError_t launch_pointwise(const ConvGemmParams &p, hipStream_t s)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pointwise_gemm_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPwLds);
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(pointwise_gemm_kernel), (int)kPwLds);
     if (e != hipSuccess) return e;
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-    }
+    const int cus = current_device_info().cus;
     const int ntiles = (p.nmt + kWaves - 1) / kWaves * p.ntt * p.B;
     MainKernelTimer timer(s);
     hipLaunchKernelGGL(pointwise_gemm_kernel, dim3(ntiles < cus ? ntiles : cus), dim3(kThreads), kPwLds, s, p);
@@ -1276,13 +1276,11 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
     if (p.K == 1 && p.nmt >= 2 && pl.nt == 5 && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout) return launch_pointwise(p, s);
     if (pl.unrolled) {
         switch (p.K) {
-#ifndef NM_ONLY_K17
         case 11: return launch_t<5, 1, 11>(p, pl.lds, s);
         case 13: return launch_t<5, 1, 13>(p, pl.lds, s);
         case 21: return launch_t<5, 1, 21>(p, pl.lds, s);
         case 25: return launch_t<5, 1, 25>(p, pl.lds, s);
         case 29: return launch_t<5, 1, 29>(p, pl.lds, s);
-#endif
         case 17: return launch_t<5, 1, 17>(p, pl.lds, s);
         default: return hipErrorInvalidValue;
         }
@@ -1296,30 +1294,44 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 
 size_t prepack_lds(int K) { return (size_t)kPackRows * pack_m_stride(K) * sizeof(bf16_t); }
 
-// flip == false: W'[m][r][k] = w[m][r][k] (w is [M][R][K]); flip == true: W'[m][r][k] = w[r][m][K-1-k]
-// (w is [R][M][K]).
-hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, bool flip, hipStream_t s)
+// flip == false: W'[m][r][k] = w[m][r][k] (w is [M][R][K]); flip == true: W'[m][r][k] = w[r][m][K-1-k] * rscale[r]
+// (w is [R][M][K]; rscale NULL: 1).
+struct PackGeom {
+    int nmt, nch, vec;
+    size_t lds, zero_off;
+    unsigned blocks;
+};
+PackGeom pack_geom(const void *w, int M, int R, int K, bool flip)
 {
-    const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
-    const size_t lds = prepack_lds(K);
-    const size_t zero_off = (size_t)nmt * nch * ((K + 1) & ~1) * 256;
+    PackGeom q;
+    q.nmt = (M + kTileM - 1) / kTileM;
+    q.nch = (R + kChunk - 1) / kChunk;
+    q.lds = prepack_lds(K);
+    q.zero_off = (size_t)q.nmt * q.nch * ((K + 1) & ~1) * 256;
     // runs start at multiples of 2*K*(row length) bytes from w: 16-byte aligned when w is and the other
     // channel count is a multiple of 8 (the tensor must also fit a 32-bit byte offset)
     const int other = flip ? M : R;
-    const int vec = ((uintptr_t)w % 16 == 0 && other % 8 == 0 && (size_t)M * R * K * 2 < ((size_t)1 << 31)) ? 1 : 0;
+    q.vec = ((uintptr_t)w % 16 == 0 && other % 8 == 0 && (size_t)M * R * K * 2 < ((size_t)1 << 31)) ? 1 : 0;
+    q.blocks = (unsigned)(q.nmt * q.nch * 4);
+    return q;
+}
+
+hipError_t run_prepack(const void *w, void *wp, int M, int R, int K, bool flip, const float *rscale, hipStream_t s)
+{
+    const PackGeom q = pack_geom(w, M, R, K, flip);
     hipError_t e;
     if (flip) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static LdsOptIn opt_in;
+        e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(prepack_kernel<true>), kMaxLds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prepack_kernel<true>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, M * K, zero_off, vec);
+        hipLaunchKernelGGL(prepack_kernel<true>, dim3(q.blocks), dim3(256), q.lds, s, (const bf16_t *)w, (u32x4 *)wp,
+                           M, R, K, q.nch, M * K, q.zero_off, q.vec, rscale);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(prepack_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static LdsOptIn opt_in;
+        e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(prepack_kernel<false>), kMaxLds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(prepack_kernel<false>, dim3(nmt * nch * 4), dim3(256), lds, s, (const bf16_t *)w, (u32x4 *)wp,
-                           M, R, K, nch, R * K, zero_off, vec);
+        hipLaunchKernelGGL(prepack_kernel<false>, dim3(q.blocks), dim3(256), q.lds, s, (const bf16_t *)w, (u32x4 *)wp,
+                           M, R, K, q.nch, R * K, q.zero_off, q.vec, (const float *)nullptr);
     }
     return hipGetLastError();
 }
@@ -1355,7 +1367,7 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 {
     const Plan pl = make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil);
     if (!pl.ok || !mfma_fwd_supported(g)) return hipErrorInvalidValue;
-    hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, s);
+    hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, nullptr, s);
     if (e != hipSuccess) return e;
     ConvGemmParams p = {};
     fill_common(p, pl, g.B, g.Cout, g.Cin, g.T, g.To, g.K, g.dil, g.pad);
@@ -1417,13 +1429,35 @@ size_t mfma_dgrad_workspace(const Geom &g)
 }
 
 namespace {
+// The elementwise pass in front of an input gradient whose weights are packed separately: g = dy*[y>0]
+// into `gbuf` (when there is a ReLU) and/or `dres`.  Returns the tensor the engine contracts in *g_used.
+hipError_t mask_pass(const Geom &g, const void *dy, const void *y, bool relu, void *gbuf, void *dres, const void **g_used,
+                     hipStream_t s)
+{
+    *g_used = dy;
+    if (!relu && !dres) return hipSuccess;
+    hipError_t e;
+    if (dres && ((uintptr_t)dres % 16) == 0) {
+        // the residual gradient is g itself: write it once and contract it from there
+        e = launch_epilogue_bwd_vec8(g, dy, y, nullptr, relu, nullptr, dres, s);
+        if (relu) *g_used = dres;
+    } else if (!dres) {
+        e = launch_epilogue_bwd_vec8(g, dy, y, nullptr, relu, gbuf, nullptr, s);
+        *g_used = gbuf;
+    } else {  // a misaligned dres: the 2-byte kernel writes it and an aligned copy for the engine
+        e = launch_epilogue_bwd(g, true, dy, y, nullptr, relu, relu ? gbuf : nullptr, dres, s);
+        if (relu) *g_used = gbuf;
+    }
+    return e;
+}
+
 hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
                                      void *dx, void *dres, bool relu, void *ws, hipStream_t s)
 {
     const Phase2 ph = phases_of_stride2(g);
     if (!ph.ok) return hipErrorInvalidValue;
     unsigned char *cur = (unsigned char *)ws;
-    void *dzbuf = cur;
+    void *gbuf = cur;
     cur += dz_bytes_of(g);
     void *wsub[2], *packed[2], *phase_out[2];
     for (int r = 0; r < 2; ++r) {
@@ -1434,17 +1468,9 @@ hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *
         phase_out[r] = cur;
         cur += align_up((size_t)g.B * g.Cin * ph.U * sizeof(bf16_t), 256);
     }
-    hipError_t e;
-    const void *dz = dy;
-    const bool need_dz = relu || scale != nullptr;
-    if (need_dz || dres) {
-        if (!dres || ((uintptr_t)dres % 16) == 0)
-            e = launch_epilogue_bwd_vec8(g, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
-        else
-            e = launch_epilogue_bwd(g, true, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
-        if (e != hipSuccess) return e;
-        if (need_dz) dz = dzbuf;
-    }
+    const void *gin = dy;
+    hipError_t e = mask_pass(g, dy, y, relu, gbuf, dres, &gin, s);
+    if (e != hipSuccess) return e;
     const size_t rows = (size_t)g.Cout * g.Cin;
     hipLaunchKernelGGL(tap_subsample_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, (const bf16_t *)w,
                        (bf16_t *)wsub[0], (bf16_t *)wsub[1], rows, g.K, ph.kp[0], ph.K[0], ph.kp[1], ph.K[1]);
@@ -1452,13 +1478,13 @@ hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *
     if (e != hipSuccess) return e;
     for (int r = 0; r < 2; ++r) {
         const Plan pl = make_plan(g.To, ph.U, g.Cout, ph.K[r], 1, 1);
-        e = run_prepack(wsub[r], packed[r], g.Cin, g.Cout, ph.K[r], true, s);
+        e = run_prepack(wsub[r], packed[r], g.Cin, g.Cout, ph.K[r], true, scale, s);
         if (e != hipSuccess) return e;
         ConvGemmParams p = {};
-        // out[u] = sum_j W'[j] * dz[u - padL + j] with j = K_r-1-k'  ->  padL = K_r - 1 - c_r
+        // out[u] = sum_j W'[j] * g[u - padL + j] with j = K_r-1-k'  ->  padL = K_r - 1 - c_r
         fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, ph.U, ph.K[r], 1, ph.K[r] - 1 - ph.c[r]);
         p.relu = 0;
-        p.in = (const bf16_t *)dz;
+        p.in = (const bf16_t *)gin;
         p.wp = (const bf16x8 *)packed[r];
         p.out = (bf16_t *)phase_out[r];
         p.len_out = g.len;  // dx[2u+r] is padding from 2u+r >= len on: u >= ceil((len - r) / 2)
@@ -1472,92 +1498,92 @@ hipError_t launch_mfma_dgrad_stride2(const Geom &g, const void *dy, const void *
                        (const u32x4 *)phase_out[1], (u32x4 *)dx, n8);
     return hipGetLastError();
 }
-}  // namespace
 
-hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
-                             void *dx, void *dres, bool relu, void *ws, hipStream_t s)
+// parameters of the stride-1 input gradient as a run of the forward engine
+void fill_dgrad(ConvGemmParams &p, const Plan &pl, const Geom &g, const void *gin, const void *packed, void *dx, bool accumulate)
 {
-    if (g.stride == 2) return launch_mfma_dgrad_stride2(g, dy, y, scale, w, dx, dres, relu, ws, s);
-    const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
-    if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
-    // dz = dy*[y>0]*scale (bf16) and dres = dy*[y>0] come from one elementwise pass; when it can use
-    // 16-byte accesses (To % 8 == 0 on this path, dres aligned) it shares a launch with the weight packing
-    hipError_t e;
-    const void *dz = dy;
-    const bool need_dz = relu || scale != nullptr;
-    void *dzbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
-    if ((need_dz || dres) && (!dres || ((uintptr_t)dres % 16) == 0)) {
-        const int M = g.Cin, R = g.Cout;  // the engine's roles for this pass
-        const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
-        const size_t lds = prepack_lds(g.K);
-        const size_t zero_off = (size_t)nmt * nch * ((g.K + 1) & ~1) * 256;
-        const int vec = ((uintptr_t)w % 16 == 0 && M % 8 == 0 && (size_t)M * R * g.K * 2 < ((size_t)1 << 31)) ? 1 : 0;
-        const unsigned npack = (unsigned)(nmt * nch * 4);
-        const size_t n8 = (size_t)g.B * g.Cout * g.To / 8;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(dgrad_prepare_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(npack + (unsigned)((n8 + 255) / 256)), dim3(256), lds, s, npack,
-                           (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, nch, M * g.K, zero_off, vec, n8, g.Cout, g.To / 8,
-                           (const u32x4_t *)dy, (const u32x4_t *)y, scale, relu ? 1 : 0,
-                           (u32x4_t *)(need_dz ? dzbuf : nullptr), (u32x4_t *)dres);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        if (need_dz) dz = dzbuf;
-    } else {
-        e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, s);
-        if (e != hipSuccess) return e;
-        if (need_dz || dres) {  // a misaligned dres: the 2-byte kernel
-            e = launch_epilogue_bwd(g, true, dy, y, scale, relu, need_dz ? dzbuf : nullptr, dres, s);
-            if (e != hipSuccess) return e;
-            if (need_dz) dz = dzbuf;
-        }
-    }
-    ConvGemmParams p = {};
     fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad);
     p.relu = 0;
-    p.in = (const bf16_t *)dz;
-    p.wp = (const bf16x8 *)ws;
+    p.in = (const bf16_t *)gin;
+    p.wp = (const bf16x8 *)packed;
     p.out = (bf16_t *)dx;
+    p.res = accumulate ? (const bf16_t *)dx : nullptr;  // dx += : every lane reads the 16 bytes it then overwrites
     p.len_out = g.len;
     p.len_out_div = 1;
+}
+}  // namespace
+
+// accumulate (stride 1 only): dx = bf16(dx + gradient), one rounding.
+hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
+                             void *dx, void *dres, bool relu, bool accumulate, void *ws, hipStream_t s)
+{
+    if (g.stride == 2) {
+        if (accumulate) return hipErrorInvalidValue;
+        return launch_mfma_dgrad_stride2(g, dy, y, scale, w, dx, dres, relu, ws, s);
+    }
+    const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
+    if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
+    // g = dy*[y>0] (exact in bf16) comes from one elementwise pass, which shares a launch with the weight
+    // packing when it can use 16-byte accesses (To % 8 == 0 on this path; dres aligned); the affine
+    // factor scale[co] is folded into the packed weights.
+    hipError_t e;
+    const void *gin = dy;
+    void *gbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
+    if (!dres || ((uintptr_t)dres % 16) == 0) {
+        const int M = g.Cin, R = g.Cout;  // the engine's roles for this pass
+        const PackGeom q = pack_geom(w, M, R, g.K, true);
+        void *gout = dres ? dres : (relu ? gbuf : nullptr);
+        const size_t n8 = gout ? (size_t)g.B * g.Cout * g.To / 8 : 0;
+        static LdsOptIn opt_in;
+        e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(dgrad_prepare_kernel), kMaxLds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(dgrad_prepare_kernel, dim3(q.blocks + (unsigned)((n8 + 255) / 256)), dim3(256), q.lds, s, q.blocks,
+                           (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, q.nch, M * g.K, q.zero_off, q.vec, scale, n8,
+                           (const u32x4 *)dy, (const u32x4 *)y, relu ? 1 : 0, (u32x4 *)gout);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (relu) gin = gout;
+    } else {
+        e = run_prepack(w, ws, g.Cin, g.Cout, g.K, true, scale, s);
+        if (e != hipSuccess) return e;
+        e = mask_pass(g, dy, y, relu, gbuf, dres, &gin, s);
+        if (e != hipSuccess) return e;
+    }
+    ConvGemmParams p = {};
+    fill_dgrad(p, pl, g, gin, ws, dx, accumulate);
     return launch_plan(pl, p, s);
 }
 
 // ---- fused backward -------------------------------------------------------------------------
+// Packs the flipped, scaled weights into ws and, in the same launch, forms g = dy*[y>0] in the two
+// layouts the gradients read: plain (into dres when the caller wants the residual gradient, else into
+// the workspace behind the packed weights; skipped when there is no ReLU and no dres) and in fragment
+// order (gf).  *g_plain receives the tensor the input-gradient engine has to contract.
 hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
-                              bool relu, void *ws, void *dzf, const DzfLayout &layout, void *dres, hipStream_t s)
+                              bool relu, void *ws, void *gf, const DzfLayout &layout, void *dres, const void **g_plain,
+                              hipStream_t s)
 {
     const int M = g.Cin, R = g.Cout;  // the engine's roles for the input gradient
-    const int nmt = (M + kTileM - 1) / kTileM, nch = (R + kChunk - 1) / kChunk;
-    const size_t lds = prepack_lds(g.K);
-    const size_t zero_off = (size_t)nmt * nch * ((g.K + 1) & ~1) * 256;
-    const int vec = ((uintptr_t)w % 16 == 0 && M % 8 == 0 && (size_t)M * R * g.K * 2 < ((size_t)1 << 31)) ? 1 : 0;
-    const unsigned npack = (unsigned)(nmt * nch * 4);
+    const PackGeom q = pack_geom(w, M, R, g.K, true);
     const size_t nfrag = (size_t)g.B * layout.ncm * layout.nst;
-    void *dzbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_prepare_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    void *gbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
+    void *gout = dres ? dres : (relu ? gbuf : nullptr);
+    *g_plain = gout ? gout : dy;
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(bwd_prepare_kernel), kMaxLds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_prepare_kernel, dim3(npack + (unsigned)((nfrag + 3) / 4)), dim3(256), lds, s, npack,
-                       (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, nch, M * g.K, zero_off, vec, g.B, g.Cout, g.To,
-                       layout.ncm, layout.nst, (const bf16_t *)dy, (const bf16_t *)y, scale, relu ? 1 : 0,
-                       (u32x4 *)dzbuf, (u32x4 *)dzf, (u32x4 *)dres);
+    hipLaunchKernelGGL(bwd_prepare_kernel, dim3(q.blocks + (unsigned)((nfrag + 3) / 4)), dim3(256), q.lds, s, q.blocks,
+                       (const bf16_t *)w, (u32x4 *)ws, M, R, g.K, q.nch, M * g.K, q.zero_off, q.vec, scale, g.B, g.Cout, g.To,
+                       layout.ncm, layout.nst, (const bf16_t *)dy, (const bf16_t *)y, relu ? 1 : 0, (u32x4 *)gout, (u32x4 *)gf);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_dgrad_prepared(const Geom &g, void *dx, void *ws, hipStream_t s)
+hipError_t launch_mfma_dgrad_prepared(const Geom &g, const void *g_plain, void *dx, bool accumulate, void *ws, hipStream_t s)
 {
     const Plan pl = make_plan(g.To, g.T, g.Cout, g.K, 1, g.dil);
     if (!pl.ok || !mfma_dgrad_supported(g)) return hipErrorInvalidValue;
     ConvGemmParams p = {};
-    fill_common(p, pl, g.B, g.Cin, g.Cout, g.To, g.T, g.K, g.dil, g.dil * (g.K - 1) - g.pad);
-    p.relu = 0;
-    p.in = (const bf16_t *)((unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K));
-    p.wp = (const bf16x8 *)ws;
-    p.out = (bf16_t *)dx;
-    p.len_out = g.len;
-    p.len_out_div = 1;
+    fill_dgrad(p, pl, g, g_plain, ws, dx, accumulate);
     return launch_plan(pl, p, s);
 }
 

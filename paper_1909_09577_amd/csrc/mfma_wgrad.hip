@@ -18,8 +18,10 @@
 //     a row offset; a B fragment needs 8 consecutive *time steps* of one channel, i.e. a column
 //     of that layout, which the gfx950 transposing LDS read (ds_read_b64_tr_b16: 16 lanes read a
 //     4x16 block, lane i receives column i) delivers in two reads.
-// dz itself (dy * [y>0] * scale, rounded to bf16) is materialised once per call by a
-// vectorised elementwise kernel when it differs from dy.
+// The kernels contract g = dy * [y>0] (exact in bf16: a value of dy or zero; materialised once per call
+// by a vectorised elementwise kernel) and the affine factor scale[co] multiplies the float32 sums in
+// the final reduction, so the operand carries no rounding of its own:
+//   dw[co,ci,k] = scale[co] * sum_b sum_t g[b,co,t] * x[b,ci,tau(t,k)].
 #include "nm_common.h"
 
 namespace nm {
@@ -389,8 +391,7 @@ constexpr int kFastXRowBytes = 64;
 constexpr int fast_x_items(int dil) { return dil == 1 ? 3 : 4; }  // 92 rows -> 3, 97 rows (dilation 2, 6 taps) -> 4
 
 __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm, int nst, const bf16_t *__restrict__ dy,
-                                                      const bf16_t *__restrict__ y, const float *__restrict__ scale,
-                                                      int relu, u32x4 *__restrict__ dzf)
+                                                      const bf16_t *__restrict__ y, int relu, u32x4 *__restrict__ dzf)
 {
     const int lane = threadIdx.x & 63;
     const int st = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -408,14 +409,6 @@ __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm,
             for (int j = 0; j < 4; ++j) {
                 const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
                 g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
-            }
-        }
-        if (scale) {
-            const float sc = scale[co];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float g0 = __uint_as_float(g[j] << 16) * sc, g1 = __uint_as_float(g[j] & 0xffff0000u) * sc;
-                g[j] = pack_bf16x2(g0, g1);
             }
         }
     }
@@ -893,9 +886,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_shared_kernel(const WgradParam
     }
 }
 
-// dw[co][ci][k] = (accumulate ? dw : 0) + sum_s part[s][k][co][ci]; one block per (co, 64 ci).
+// dw[co][ci][k] = (accumulate ? dw : 0) + scale[co] * sum_s part[s][k][co][ci]; one block per (co, 64 ci).
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw,
-                                                           int S, int K, int Cout, int Cin, int accumulate)
+                                                           const float *__restrict__ scale, int S, int K, int Cout,
+                                                           int Cin, int accumulate)
 {
     extern __shared__ float tile[];  // [64][K+1]
     const int co = blockIdx.y;
@@ -903,13 +897,14 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     const int l = threadIdx.x & 63, kq = threadIdx.x >> 6;
     const int ci = ci0 + l;
     const size_t plane = (size_t)Cout * Cin;
+    const float factor = scale ? scale[co] : 1.f;
     for (int k = kq; k < K; k += 4) {
         float s = 0.f;
         if (ci < Cin) {
             const float *src = part + ((size_t)k * Cout + co) * Cin + ci;
             for (int sp = 0; sp < S; ++sp) s += src[(size_t)sp * K * plane];
         }
-        tile[l * (K + 1) + k] = s;
+        tile[l * (K + 1) + k] = s * factor;
     }
     __syncthreads();
     const int nci = min(64, Cin - ci0);
@@ -1045,8 +1040,8 @@ template <int KT, int DIL>
 hipError_t launch_fast_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 {
     auto kern = wgrad_fast_kernel<KT, DIL>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), kMaxLds);
     if (e != hipSuccess) return e;
     MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
@@ -1080,17 +1075,28 @@ template <int KT>
 hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 {
     auto kern = wgrad_kernel<KT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), kMaxLds);
     if (e != hipSuccess) return e;
     MainKernelTimer timer(s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
     return hipGetLastError();
 }
 
+// the reduction's LDS tile is [64][K+1] floats: the default 64 KiB limit bounds the tap count
+constexpr int kMaxReduceTaps = 64 * 1024 / (64 * (int)sizeof(float)) - 1;  // 255
+hipError_t launch_reduce(const Geom &g, const float *part, float *dw, const float *scale, int S, bool accumulate,
+                         hipStream_t s)
+{
+    dim3 rgrid((g.Cin + 63) / 64, g.Cout);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, scale, S, g.K,
+                       g.Cout, g.Cin, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
 }  // namespace
 
-bool mfma_wgrad_supported(const Geom &g) { return fast_ok(g) || make_wplan(g).ok; }
+bool mfma_wgrad_supported(const Geom &g) { return g.K <= kMaxReduceTaps && (fast_ok(g) || make_wplan(g).ok); }
 
 size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
 {
@@ -1117,7 +1123,8 @@ DzfLayout mfma_wgrad_dzf_layout(const Geom &g)
     return l;
 }
 
-hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, bool accumulate, void *ws, hipStream_t s)
+hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, const float *scale, float *dw, bool accumulate, void *ws,
+                                      hipStream_t s)
 {
     const FastPlan f = make_fast_plan(g);
     float *part = (float *)ws;
@@ -1165,10 +1172,7 @@ hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, b
         }
     }
     if (e != hipSuccess) return e;
-    dim3 rgrid((g.Cin + 63) / 64, g.Cout);
-    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, f.S, g.K,
-                       g.Cout, g.Cin, accumulate ? 1 : 0);
-    return hipGetLastError();
+    return launch_reduce(g, part, dw, scale, f.S, accumulate, s);
 }
 
 hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y, const float *scale,
@@ -1178,19 +1182,19 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
         const FastPlan f = make_fast_plan(g);
         u32x4 *dzf = (u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
         hipLaunchKernelGGL(dz_pack_kernel, dim3((f.nst + 3) / 4, f.ncm, g.B), dim3(256), 0, s, g.Cout, g.To, f.ncm,
-                           f.nst, (const bf16_t *)dy, (const bf16_t *)y, scale, relu ? 1 : 0, dzf);
+                           f.nst, (const bf16_t *)dy, (const bf16_t *)y, relu ? 1 : 0, dzf);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_mfma_wgrad_prepared(g, x, dw, accumulate, ws, s);
+        return launch_mfma_wgrad_prepared(g, x, scale, dw, accumulate, ws, s);
     }
     const WPlan w = make_wplan(g);
     if (!w.ok) return hipErrorInvalidValue;
     float *part = (float *)ws;
     const void *dz = dy;
-    if (relu || scale) {
+    if (relu) {
         void *dzbuf = (unsigned char *)ws + part_bytes(g, w.S);
         // rows are 16-byte aligned here: To % 8 == 0 and the caller checked the pointers
-        hipError_t e = launch_epilogue_bwd_vec8(g, dy, y, scale, relu, dzbuf, nullptr, s);
+        hipError_t e = launch_epilogue_bwd_vec8(g, dy, y, nullptr, relu, dzbuf, nullptr, s);
         if (e != hipSuccess) return e;
         dz = dzbuf;
     }
@@ -1217,10 +1221,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
     default: e = launch_kt<6>(p, w.lds, grid, s); break;
     }
     if (e != hipSuccess) return e;
-    dim3 rgrid((g.Cin + 63) / 64, g.Cout);
-    hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, w.S, g.K,
-                       g.Cout, g.Cin, accumulate ? 1 : 0);
-    return hipGetLastError();
+    return launch_reduce(g, part, dw, scale, w.S, accumulate, s);
 }
 
 }  // namespace nm

@@ -94,6 +94,22 @@ __device__ __forceinline__ void epilogue_bwd_vec8_item(size_t i, int Cout, int T
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ---- per-device facts and one-time kernel set-up (host) -----------------------------------------
+// Launches sit on the hot path of a training step, so nothing below queries the runtime more than
+// once per device and kernel: the compute-unit count is cached, and the opt-in to more than 64 KiB
+// of dynamic LDS (a per-device function attribute) is made on a kernel's first launch on a device.
+constexpr int kMaxDevices = 64;
+struct DeviceInfo {
+    int dev;  // current device, or -1 when the runtime could not say
+    int cus;  // its compute units (256 when unknown)
+};
+DeviceInfo current_device_info();
+struct LdsOptIn {
+    unsigned char done[kMaxDevices] = {};  // written once per device; a racing second write stores the same value
+};
+// Raise the dynamic-LDS limit of `fn` to `bytes` on the current device unless that was done before.
+hipError_t ensure_dynamic_lds(LdsOptIn &state, const void *fn, int bytes);
+
 // One-shot event pair armed by nm_conv1d_time_next_main_kernel (thread local, nm_conv1d_api.hip).
 // Construct right before the launch of a call's main kernel, destroy right after it.
 struct MainKernelTimer {
@@ -113,9 +129,11 @@ hipError_t launch_epilogue_bwd(const Geom &g, bool is_bf16, const void *dy, cons
 // Same for bf16 tensors with To % 8 == 0 and 16-byte aligned pointers (8 elements per thread).
 hipError_t launch_epilogue_bwd_vec8(const Geom &g, const void *dy, const void *y, const float *scale, bool relu,
                                     void *dz, void *dres, hipStream_t s);
-hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx,
+// accumulate: dx = storage(dx + gradient) (positions at or beyond a sample's length keep their value)
+hipError_t launch_direct_dgrad(const Geom &g, bool is_bf16, const void *dz, const void *w, void *dx, bool accumulate,
                                hipStream_t s);
-hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, float *dw,
+// dw = (accumulate ? dw : 0) + scale[co] * sum (scale may be NULL: 1)
+hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const void *dz, const float *scale, float *dw,
                                bool accumulate, hipStream_t s);
 
 // ---- matrix-core kernels (mfma_*.hip), bf16 storage only -------------------------------
@@ -130,7 +148,8 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 bool mfma_dgrad_supported(const Geom &g);
 size_t mfma_dgrad_workspace(const Geom &g);
 hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale,
-                             const void *w, void *dx, void *dres, bool relu, void *ws, hipStream_t s);
+                             const void *w, void *dx, void *dres, bool relu, bool accumulate, void *ws,
+                             hipStream_t s);
 
 bool mfma_wgrad_supported(const Geom &g);
 size_t mfma_wgrad_workspace(const Geom &g, bool need_dz);
@@ -139,7 +158,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
                              hipStream_t s);
 
 // ---- fused backward: one pass over dy / y feeds both gradients --------------------------------
-// The stride-1 weight-gradient kernel reads dz in MFMA fragment order
+// The stride-1 weight-gradient kernels read g = dy*[y>0] in MFMA fragment order
 // [B][ncm = 2*ceil(Cout/64)][nst][64 lanes][8]: lane l of block (b, cm, st) holds channel cm*32 + l%32,
 // time steps 16*st + 8*(l/32) .. +7 (zeros outside the tensor).  It lives `offset` bytes into that
 // kernel's workspace (mfma_wgrad_workspace(g, true) bytes in all).
@@ -149,14 +168,18 @@ struct DzfLayout {
 };
 bool mfma_wgrad_fast_supported(const Geom &g);
 DzfLayout mfma_wgrad_dzf_layout(const Geom &g);
-// weight gradient from a workspace whose dz has been written already
-hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, float *dw, bool accumulate, void *ws,
-                                      hipStream_t s);
-// packs the flipped weights into ws (as launch_mfma_dgrad does) and, in the same launch, forms
-// dz (plain, behind the packed weights in ws), dz in fragment order (dzf) and dres (may be NULL)
+// weight gradient from a workspace whose fragment-order g has been written already; scale[co] (or NULL)
+// multiplies the float32 sums
+hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, const float *scale, float *dw, bool accumulate,
+                                      void *ws, hipStream_t s);
+// packs the flipped weights times scale into ws (as launch_mfma_dgrad does) and, in the same launch, forms
+// g plain (into dres, else behind the packed weights in ws, else nowhere) and in fragment order (gf);
+// *g_plain: the tensor the input gradient contracts
 hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
-                              bool relu, void *ws, void *dzf, const DzfLayout &layout, void *dres, hipStream_t s);
+                              bool relu, void *ws, void *gf, const DzfLayout &layout, void *dres, const void **g_plain,
+                              hipStream_t s);
 // input gradient from a workspace prepared by launch_bwd_prepare
-hipError_t launch_mfma_dgrad_prepared(const Geom &g, void *dx, void *ws, hipStream_t s);
+hipError_t launch_mfma_dgrad_prepared(const Geom &g, const void *g_plain, void *dx, bool accumulate, void *ws,
+                                      hipStream_t s);
 
 }  // namespace nm

@@ -10,15 +10,44 @@ using namespace nm;
 namespace {
 thread_local hipEvent_t t_start_event = nullptr;
 thread_local hipEvent_t t_stop_event = nullptr;
+thread_local int t_timed_op = -1;    // pass whose main kernel the armed pair is for (-1: the first one launched)
+thread_local int t_current_op = -1;  // pass the calling entry point is launching right now
 }  // namespace
 
 namespace nm {
+DeviceInfo current_device_info()
+{
+    static int cached_cus[kMaxDevices] = {};  // 0: not asked yet
+    DeviceInfo d = {-1, 256};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return d;
+    d.dev = dev;
+    if (dev < 0 || dev >= kMaxDevices) return d;
+    if (cached_cus[dev] == 0) {
+        int v = 0;
+        cached_cus[dev] =
+            (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+    }
+    d.cus = cached_cus[dev];
+    return d;
+}
+
+hipError_t ensure_dynamic_lds(LdsOptIn &state, const void *fn, int bytes)
+{
+    const DeviceInfo d = current_device_info();
+    const bool known = d.dev >= 0 && d.dev < kMaxDevices;
+    if (known && state.done[d.dev]) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && known) state.done[d.dev] = 1;
+    return e;
+}
+
 MainKernelTimer::MainKernelTimer(hipStream_t s) : stream(s), stop(nullptr)
 {
-    if (t_start_event && t_stop_event) {
-        (void)hipEventRecord(t_start_event, s);
-        stop = t_stop_event;
-    }
+    if (!(t_start_event && t_stop_event)) return;
+    if (t_timed_op >= 0 && t_timed_op != t_current_op) return;  // armed for another pass of this call
+    (void)hipEventRecord(t_start_event, s);
+    stop = t_stop_event;
     t_start_event = nullptr;
     t_stop_event = nullptr;
 }
@@ -30,7 +59,7 @@ MainKernelTimer::~MainKernelTimer()
 
 namespace {
 
-constexpr unsigned kAllFlags = NM_RELU | NM_ACCUM_DW | NM_FORCE_DIRECT;
+constexpr unsigned kAllFlags = NM_RELU | NM_ACCUM_DW | NM_FORCE_DIRECT | NM_ACCUM_DX;
 constexpr size_t kWsAlign = 256;
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
@@ -84,7 +113,8 @@ bool use_mfma(int op, const Geom &g, int dtype, unsigned flags)
     }
 }
 
-// Whether dz differs from dy (then backward passes on the plain path materialise it).
+// Whether dz = dy*[y>0]*scale differs from dy (the plain input-gradient kernel contracts a materialised dz;
+// the plain weight-gradient kernel contracts dy*[y>0] and applies scale to its sums).
 bool needs_dz(unsigned flags, const float *scale) { return (flags & NM_RELU) || scale != nullptr; }
 
 bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
@@ -124,6 +154,7 @@ struct DisarmOnExit {
     {
         t_start_event = nullptr;
         t_stop_event = nullptr;
+        t_current_op = -1;
     }
 };
 
@@ -159,6 +190,15 @@ int nm_conv1d_time_next_main_kernel(void *start_event, void *stop_event)
 {
     t_start_event = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
     t_stop_event = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
+    t_timed_op = -1;
+    return NM_OK;
+}
+
+int nm_conv1d_time_next_kernel_of(void *start_event, void *stop_event, int op)
+{
+    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT) return NM_ERR_BAD_ARG;
+    nm_conv1d_time_next_main_kernel(start_event, stop_event);
+    t_timed_op = op;
     return NM_OK;
 }
 
@@ -199,6 +239,7 @@ static int block_fwd_impl(int B, int Cin, int Cout, int T, int K, int stride, in
     if (overlap(y, ny, workspace, need)) return NM_ERR_BAD_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
     const bool relu = (flags & NM_RELU) != 0;
+    t_current_op = NM_OP_FWD;
     if (mfma) return dev(launch_mfma_fwd(g, x, w, scale, shift, residual, y, relu, workspace, s));
     MainKernelTimer timer(s);
     return dev(launch_direct_fwd(g, dtype == NM_BF16, x, w, scale, shift, residual, y, relu, s));
@@ -212,7 +253,7 @@ static int bwd_data_impl(int B, int Cin, int Cout, int T, int K, int stride, int
     DisarmOnExit disarm;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
-                            NM_RELU | NM_FORCE_DIRECT, &g);
+                            NM_RELU | NM_FORCE_DIRECT | NM_ACCUM_DX, &g);
     if (st != NM_OK) return st;
     if (!dy || !w || !dx) return NM_ERR_BAD_ARG;
     g.len = lengths;
@@ -223,15 +264,18 @@ static int bwd_data_impl(int B, int Cin, int Cout, int T, int K, int stride, int
     if (overlap(dx, ndx, dy, ndy) || overlap(dx, ndx, y, ndy) || overlap(dx, ndx, w, (size_t)g.Cout * g.Cin * g.K * e) ||
         overlap(dx, ndx, dres, ndy) || overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy))
         return NM_ERR_BAD_ARG;
+    const bool accum = (flags & NM_ACCUM_DX) != 0;
+    // accumulation into dx: the matrix-core engine adds the old value in its epilogue (stride 1, no lengths)
     const bool mfma = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && aligned16(dy) && aligned16(dx) &&
-                      (!relu || aligned16(y)) && masked_on_mfma(g);
+                      (!relu || aligned16(y)) && masked_on_mfma(g) && !(accum && (g.stride != 1 || g.len));
     const bool dzneeded = needs_dz(flags, scale);
     const size_t need = workspace_for(NM_OP_BWD_DATA, g, dtype, mfma, dzneeded);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != NM_OK) return st;
     if (overlap(dx, ndx, workspace, need) || overlap(dres, ndy, workspace, need)) return NM_ERR_BAD_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
-    if (mfma) return dev(launch_mfma_dgrad(g, dy, y, scale, w, dx, dres, relu, workspace, s));
+    t_current_op = NM_OP_BWD_DATA;
+    if (mfma) return dev(launch_mfma_dgrad(g, dy, y, scale, w, dx, dres, relu, accum, workspace, s));
     const bool bf = dtype == NM_BF16;
     const void *dz = dy;
     if (dzneeded || dres) {
@@ -240,7 +284,7 @@ static int bwd_data_impl(int B, int Cin, int Cout, int T, int K, int stride, int
         if (dzneeded) dz = workspace;
     }
     MainKernelTimer timer(s);
-    return dev(launch_direct_dgrad(g, bf, dz, w, dx, s));
+    return dev(launch_direct_dgrad(g, bf, dz, w, dx, accum, s));
 }
 
 static int bwd_weight_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
@@ -250,7 +294,8 @@ static int bwd_weight_impl(int B, int Cin, int Cout, int T, int K, int stride, i
 {
     DisarmOnExit disarm;
     Geom g;
-    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
+                            NM_RELU | NM_ACCUM_DW | NM_FORCE_DIRECT, &g);
     if (st != NM_OK) return st;
     if (!x || !dy || !dw) return NM_ERR_BAD_ARG;
     g.len = lengths;
@@ -269,16 +314,17 @@ static int bwd_weight_impl(int B, int Cin, int Cout, int T, int K, int stride, i
     if (overlap(dw, ndw, workspace, need)) return NM_ERR_BAD_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
     const bool accum = (flags & NM_ACCUM_DW) != 0;
+    t_current_op = NM_OP_BWD_WEIGHT;
     if (mfma) return dev(launch_mfma_wgrad(g, x, dy, y, scale, dw, relu, accum, workspace, s));
     const bool bf = dtype == NM_BF16;
     const void *dz = dy;
-    if (dzneeded) {
-        hipError_t err = launch_epilogue_bwd(g, bf, dy, y, scale, relu, workspace, nullptr, s);
+    if (relu) {  // the kernel contracts dy*[y>0]; scale multiplies its float32 sums
+        hipError_t err = launch_epilogue_bwd(g, bf, dy, y, nullptr, relu, workspace, nullptr, s);
         if (err != hipSuccess) return NM_ERR_DEVICE;
         dz = workspace;
     }
     MainKernelTimer timer(s);
-    return dev(launch_direct_wgrad(g, bf, x, dz, dw, accum, s));
+    return dev(launch_direct_wgrad(g, bf, x, dz, scale, dw, accum, s));
 }
 
 int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
@@ -352,17 +398,24 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
     }
     const bool relu = (flags & NM_RELU) != 0;
     const bool fused = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) &&
-                       mfma_wgrad_fast_supported(g) && needs_dz(flags, scale) && aligned16(x) && aligned16(dy) &&
+                       g.stride == 1 && mfma_wgrad_fast_supported(g) && aligned16(x) && aligned16(dy) &&
                        aligned16(dx) && (!relu || aligned16(y)) && (!dres || aligned16(dres));
     const size_t ws_data = mfma_dgrad_workspace(g);  // only meaningful when fused
     if (!fused) {
         // two calls sharing the workspace one after the other (their own argument checks apply)
         const size_t w1 = nm_conv1d_workspace_bytes(NM_OP_BWD_DATA, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
+        // a timer armed for the weight-gradient kernel outlives the first of the two calls
+        hipEvent_t keep_start = t_start_event, keep_stop = t_stop_event;
+        const bool keep = t_timed_op == NM_OP_BWD_WEIGHT;
         st = nm_conv1d_bwd_data(B, Cin, Cout, T, K, stride, dilation, pad, dy, y, scale, w, dx, dres, flags & ~NM_ACCUM_DW,
                                 dtype, workspace, w1, hip_stream);
         if (st != NM_OK) return st;
-        return nm_conv1d_bwd_weight(B, Cin, Cout, T, K, stride, dilation, pad, x, dy, y, scale, dw, flags, dtype,
-                                    workspace, workspace_bytes, hip_stream);
+        if (keep) {
+            t_start_event = keep_start;
+            t_stop_event = keep_stop;
+        }
+        return nm_conv1d_bwd_weight(B, Cin, Cout, T, K, stride, dilation, pad, x, dy, y, scale, dw, flags & ~NM_ACCUM_DX,
+                                    dtype, workspace, workspace_bytes, hip_stream);
     }
     DisarmOnExit disarm;
     const size_t e = elt(dtype);
@@ -377,14 +430,15 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
     hipStream_t s = (hipStream_t)hip_stream;
     void *ws_w = (unsigned char *)workspace + ws_data;  // the weight gradient's workspace: partials, then dz fragments
     const DzfLayout layout = mfma_wgrad_dzf_layout(g);
+    const void *g_plain = nullptr;
     hipError_t err = launch_bwd_prepare(g, dy, y, scale, w, relu, workspace, (unsigned char *)ws_w + layout.offset, layout,
-                                        dres, s);
+                                        dres, &g_plain, s);
     if (err != hipSuccess) return NM_ERR_DEVICE;
-    err = launch_mfma_dgrad_prepared(g, dx, workspace, s);  // carries the one-shot timer
+    t_current_op = NM_OP_BWD_DATA;
+    err = launch_mfma_dgrad_prepared(g, g_plain, dx, (flags & NM_ACCUM_DX) != 0, workspace, s);
     if (err != hipSuccess) return NM_ERR_DEVICE;
-    t_start_event = nullptr;
-    t_stop_event = nullptr;
-    return dev(launch_mfma_wgrad_prepared(g, x, dw, (flags & NM_ACCUM_DW) != 0, ws_w, s));
+    t_current_op = NM_OP_BWD_WEIGHT;
+    return dev(launch_mfma_wgrad_prepared(g, x, scale, dw, (flags & NM_ACCUM_DW) != 0, ws_w, s));
 }
 
 }  // extern "C"

@@ -40,11 +40,14 @@ class LayerCfg:
     relu: bool = True
     residual: bool = False
     seed: int = 0
+    # Length of the layer's output rows.  It is part of the workload's shape and is given as data by
+    # whoever builds the workload (the named ones below state it; tests take it from the oracle, the
+    # benchmark from the library): this module shapes random draws with it and computes nothing.
+    T_out: int = -1
 
-    @property
-    def T_out(self) -> int:
-        span = self.T + 2 * self.pad - self.dilation * (self.K - 1) - 1
-        return span // self.stride + 1 if span >= 0 else -1
+    def __post_init__(self):
+        if self.T_out < 1:
+            raise ValueError(f"{self.name}: T_out (the output length of the layer) must be given")
 
     @property
     def flops_per_pass(self) -> int:
@@ -56,14 +59,14 @@ class LayerCfg:
 
 
 # The single-layer workloads.
-TINY = LayerCfg("tiny_64to256_k11", B=2, Cin=64, Cout=256, T=200, K=11, pad=5, residual=False, seed=0)
-JASPER_B1 = LayerCfg("b1_256_k11", B=32, Cin=256, Cout=256, T=800, K=11, pad=5, residual=True, seed=1)
-JASPER_B3 = LayerCfg("b3_512_k17", B=32, Cin=512, Cout=512, T=800, K=17, pad=8, residual=True, seed=2)
+TINY = LayerCfg("tiny_64to256_k11", B=2, Cin=64, Cout=256, T=200, K=11, pad=5, residual=False, seed=0, T_out=200)
+JASPER_B1 = LayerCfg("b1_256_k11", B=32, Cin=256, Cout=256, T=800, K=11, pad=5, residual=True, seed=1, T_out=800)
+JASPER_B3 = LayerCfg("b3_512_k17", B=32, Cin=512, Cout=512, T=800, K=17, pad=8, residual=True, seed=2, T_out=800)
 EPILOG_A = LayerCfg("epilog_768to896_k29_d2", B=32, Cin=768, Cout=896, T=800, K=29, dilation=2,
-                    pad=28, seed=3)
-EPILOG_B = LayerCfg("epilog_896to1024_k1", B=32, Cin=896, Cout=1024, T=800, K=1, seed=4)
+                    pad=28, seed=3, T_out=800)
+EPILOG_B = LayerCfg("epilog_896to1024_k1", B=32, Cin=896, Cout=1024, T=800, K=1, seed=4, T_out=800)
 EPILOG_C = LayerCfg("epilog_1024to29_k1", B=32, Cin=1024, Cout=29, T=800, K=1, affine=False,
-                    relu=False, seed=5)
+                    relu=False, seed=5, T_out=800)
 
 SINGLE_LAYER_CFGS = [TINY, JASPER_B1, JASPER_B3, EPILOG_A, EPILOG_B, EPILOG_C]
 HEADLINE = JASPER_B3
@@ -87,21 +90,23 @@ def jasper_10x5_layers(B: int = 32, T_in: int = 1600, seed: int = 4) -> List[dic
         n += 1
         return cfg
 
-    c = add("prolog", -1, Cin=64, Cout=256, T=T_in, K=11, stride=2, pad=5)
-    T = c.T_out
+    if T_in % 2:
+        raise ValueError("T_in must be even (the stride-2 prolog halves it)")
+    T = T_in // 2  # K=11, stride 2, pad 5 on an even length; every later layer keeps the length ("same" padding)
+    add("prolog", -1, Cin=64, Cout=256, T=T_in, K=11, stride=2, pad=5, T_out=T)
     cin = 256
     spec = [(256, 11), (256, 11), (384, 13), (384, 13), (512, 17), (512, 17), (640, 21), (640, 21),
             (768, 25), (768, 25)]
     for bi, (ch, k) in enumerate(spec):
-        add("proj", bi, Cin=cin, Cout=ch, T=T, K=1, pad=0, relu=False)
+        add("proj", bi, Cin=cin, Cout=ch, T=T, K=1, pad=0, relu=False, T_out=T)
         c_in = cin
         for j in range(5):
-            add("sub", bi, Cin=c_in, Cout=ch, T=T, K=k, pad=(k - 1) // 2, residual=(j == 4))
+            add("sub", bi, Cin=c_in, Cout=ch, T=T, K=k, pad=(k - 1) // 2, residual=(j == 4), T_out=T)
             c_in = ch
         cin = ch
-    add("epilog", 10, Cin=cin, Cout=896, T=T, K=29, dilation=2, pad=28)
-    add("epilog", 10, Cin=896, Cout=1024, T=T, K=1)
-    add("epilog", 10, Cin=1024, Cout=29, T=T, K=1, affine=False, relu=False)
+    add("epilog", 10, Cin=cin, Cout=896, T=T, K=29, dilation=2, pad=28, T_out=T)
+    add("epilog", 10, Cin=896, Cout=1024, T=T, K=1, T_out=T)
+    add("epilog", 10, Cin=1024, Cout=29, T=T, K=1, affine=False, relu=False, T_out=T)
     return layers
 
 

@@ -37,33 +37,8 @@ def assert_close(got, ref, dtype: str, what: str, rms_bound: float | None = None
     return mx, rr
 
 
-# ---- host <-> device ---------------------------------------------------------------------
-def to_dev(inp: dict, name: str, dtype: str):
-    """Device tensor holding exactly the bits of inp[name] in the storage dtype."""
-    import torch
-    if name in ("scale", "shift") or dtype == "f32":
-        return torch.from_numpy(np.ascontiguousarray(inp[name], dtype=np.float32)).cuda()
-    bits = inp[name + "_bits"]
-    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def arr_to_dev(a: np.ndarray, dtype: str):
-    """Device tensor of a float array; for bf16 the values must already be representable."""
-    import torch
-    if dtype == "f32":
-        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-    bits = syn.f32_to_bf16_bits(np.ascontiguousarray(a, dtype=np.float32))
-    assert np.array_equal(syn.bf16_bits_to_f32(bits), np.asarray(a, dtype=np.float32)), "not bf16-representable"
-    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def to_host_f64(t) -> np.ndarray:
-    import torch
-    torch.cuda.synchronize()
-    if t.dtype == torch.bfloat16:
-        bits = t.view(torch.int16).cpu().numpy().view(np.uint16)
-        return syn.bf16_bits_to_f64(bits)
-    return t.cpu().numpy().astype(np.float64)
+# ---- host <-> device (shared with the benchmark: paper_1909_09577_amd/device_inputs.py) ---------
+from paper_1909_09577_amd.device_inputs import arr_to_dev, geom_kw, to_dev, to_host_f64  # noqa: E402,F401
 
 
 def round_to_storage(a: np.ndarray, dtype: str) -> np.ndarray:
@@ -75,10 +50,6 @@ def round_to_storage(a: np.ndarray, dtype: str) -> np.ndarray:
 
 
 # ---- oracle on a LayerCfg --------------------------------------------------------------------
-def geom_kw(cfg):
-    return dict(stride=cfg.stride, dilation=cfg.dilation, pad=cfg.pad)
-
-
 def oracle_fwd(cfg, inp):
     return orc.block_fwd(inp["x"], inp["w"], inp["scale"] if cfg.affine else None,
                          inp["shift"] if cfg.affine else None, inp["residual"] if cfg.residual else None,

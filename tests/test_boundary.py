@@ -163,3 +163,12 @@ def test_masked_entry_points_check_their_arguments():
     bad = (0,) + dims[1:]
     assert L.nm_conv1d_bwd_weight_masked(*bad, FAKE, FAKE2, FAKE3, None, None, FAKE4, 0, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
     assert L.nm_conv1d_bwd_data_masked(*dims, FAKE, FAKE2, None, None, FAKE3, FAKE4, None, nm.NM_RELU, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
+
+
+def test_declared_output_lengths_of_the_workloads_are_the_oracles():
+    from paper_1909_09577_amd import inputs as syn
+    cfgs = list(syn.SINGLE_LAYER_CFGS) + [e["cfg"] for e in syn.jasper_10x5_layers()] + \
+        [e["cfg"] for e in syn.jasper_10x5_layers(B=1, T_in=320)]
+    for c in cfgs:
+        assert c.T_out == orc.out_len(c.T, c.K, c.stride, c.dilation, c.pad), c.name
+        assert c.T_out == nm.nm_conv1d_out_len(c.T, c.K, c.stride, c.dilation, c.pad), c.name

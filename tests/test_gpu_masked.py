@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 
 
 def L(name, B, Cin, Cout, T, K, stride=1, dilation=1, pad=0, affine=True, relu=True, residual=False, seed=31):
-    return LayerCfg(name, B, Cin, Cout, T, K, stride, dilation, pad, affine, relu, residual, seed)
+    return LayerCfg(name, B, Cin, Cout, T, K, stride, dilation, pad, affine, relu, residual, seed,
+                    T_out=orc.out_len(T, K, stride, dilation, pad))
 
 
 CASES = [

@@ -44,7 +44,8 @@ def run_bwd(cfg, inp, dtype, force_direct, y_saved_dev):
 
 
 def L(name, B, Cin, Cout, T, K, stride=1, dilation=1, pad=0, affine=True, relu=True, residual=False, seed=11):
-    return LayerCfg(name, B, Cin, Cout, T, K, stride, dilation, pad, affine, relu, residual, seed)
+    return LayerCfg(name, B, Cin, Cout, T, K, stride, dilation, pad, affine, relu, residual, seed,
+                    T_out=orc.out_len(T, K, stride, dilation, pad))
 
 
 # Odd shapes: ragged channel counts and lengths, strides, dilations, pad 0 / larger than needed,
@@ -152,9 +153,13 @@ SHARED_WGRAD = [
     L("w_k25", 1, 1024, 512, 160, 25, pad=12, affine=False, relu=False),
     L("w_k29_d2", 1, 1024, 512, 160, 29, dilation=2, pad=28, affine=False, relu=False),
 ]
-# (no affine, no ReLU: dz is dy itself, so the 5.6 million weight gradients of each case carry no bf16
-# rounding of dz, whose 6-sigma tail would sit right at the 1e-2 gate; that rounding is covered by
-# every other case)
+# the same geometries with the whole epilogue on (affine + ReLU + residual): the mask and the scale
+# factor of dz then pass through the weight-gradient kernel's operand path
+SHARED_WGRAD += [
+    L(c.name + "_epi", c.B, c.Cin, c.Cout, c.T, c.K, dilation=c.dilation, pad=c.pad, affine=True, relu=True, residual=True,
+      seed=12)
+    for c in list(SHARED_WGRAD)
+]
 
 
 @pytest.mark.parametrize("cfg", SHARED_WGRAD, ids=lambda c: c.name)
@@ -213,8 +218,16 @@ def check_sampled(cfg, n_act=4096, n_w=2048, seed=99):
 
 
 @pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
+def test_full_size_workloads_full_tensor(cfg):
+    """The named full-size bf16 workloads (B=32, T=800) in the launch configuration the benchmark times:
+    every element of y, dx, dres and dw against the oracle (tens of seconds of oracle time each)."""
+    check_layer(cfg, "bf16", False)
+
+
+@pytest.mark.parametrize("cfg", FULL, ids=lambda c: c.name)
 def test_full_size_workloads_sampled(cfg):
-    """Full-size bf16 workloads in the launch configuration the benchmark times."""
+    """The same workloads with the saved output taken from the input recipe (not from the oracle's
+    forward), on sampled elements plus corners and tile edges."""
     check_sampled(cfg)
 
 
@@ -261,6 +274,37 @@ def test_full_size_f32_mode_sampled():
     U.assert_close(dw[idx], orc.bwd_weight_at(x64, dz, cfg.K, idx, **kw), dtype, "f32 dw")
 
 
+def check_f32_sampled(cfg, n_act, n_w, seed):
+    """float32 storage (plain kernels), sampled outputs against the oracle at the 1e-5 gate."""
+    dtype = "f32"
+    rng = np.random.default_rng(seed)
+    inp = syn.make_inputs(cfg, dtype)
+    x64, w64 = inp["x"].astype(np.float64), inp["w"].astype(np.float64)
+    scale = inp["scale"] if cfg.affine else None
+    shift = inp["shift"] if cfg.affine else None
+    res = inp["residual"] if cfg.residual else None
+    kw = U.geom_kw(cfg)
+    y = U.to_host_f64(run_fwd(cfg, inp, dtype, True)).reshape(-1)
+    idx = sample_indices(y.size, n_act, rng, edge_indices((cfg.B, cfg.Cout, cfg.T_out)))
+    U.assert_close(y[idx], orc.block_fwd_at(x64, w64, idx, scale, shift, res, cfg.relu, **kw), dtype, f"{cfg.name} f32 y")
+    dx, dw, dres = run_bwd(cfg, inp, dtype, True, U.to_dev(inp, "y_saved", dtype))
+    dz, dres_ref = orc.epilogue_bwd(inp["dy"], inp["y_saved"] if cfg.relu else None, scale, cfg.relu)
+    np.testing.assert_array_equal(U.to_host_f64(dres), dres_ref)
+    dx = U.to_host_f64(dx).reshape(-1)
+    idx = sample_indices(dx.size, n_act, rng, edge_indices((cfg.B, cfg.Cin, cfg.T)))
+    U.assert_close(dx[idx], orc.bwd_data_at(dz, w64, cfg.T, idx, **kw), dtype, f"{cfg.name} f32 dx")
+    dw = U.to_host_f64(dw).reshape(-1)
+    idx = sample_indices(dw.size, n_w, rng, [0, dw.size - 1, cfg.K - 1, cfg.Cin * cfg.K - 1])
+    U.assert_close(dw[idx], orc.bwd_weight_at(x64, dz, cfg.K, idx, **kw), dtype, f"{cfg.name} f32 dw")
+
+
+@pytest.mark.parametrize("cfg", [syn.JASPER_B3, syn.EPILOG_A], ids=lambda c: c.name)
+def test_f32_mode_at_the_long_reduction_lengths(cfg):
+    """float32 mode where its 1e-5 gate is hardest: 8 704-term (512 channels x 17 taps) and 22 272-term
+    (768 x 29) forward / input-gradient sums, 25 600-term weight-gradient sums (full batch, B=32, T=800)."""
+    check_f32_sampled(cfg, n_act=2048, n_w=1024, seed=7)
+
+
 def test_pure_gradients_without_epilogue_and_accumulate():
     """y=NULL, scale=NULL: the backward entry points are plain convolution gradients;
     NM_ACCUM_DW adds into dw."""
@@ -277,6 +321,33 @@ def test_pure_gradients_without_epilogue_and_accumulate():
         acc = nm.nm_conv1d_bwd_weight(U.to_dev(inp, "x", dtype), U.to_dev(inp, "dy", dtype), cfg.K, dw=base.clone(),
                                       accumulate=True, force_direct=fd, **U.geom_kw(cfg))
         U.assert_close(U.to_host_f64(acc), dw_ref + 0.5, dtype, "accumulated dw")
+
+
+@pytest.mark.parametrize("cfg", [
+    L("acc_k1_proj", 2, 256, 384, 320, 1, relu=False),                   # a residual projection: the K=1 kernel
+    L("acc_k11", 2, 72, 100, 336, 11, pad=5, residual=True),             # unrolled engine, ragged channel tiles
+    L("acc_k5", 2, 64, 64, 176, 5, pad=2),                               # tap-pair engine
+    L("acc_odd_len", 2, 40, 48, 333, 7, pad=3),                          # plain kernels
+    L("acc_stride2", 2, 64, 96, 400, 11, stride=2, pad=5),               # stride 2: accumulation on the plain kernel
+], ids=lambda c: c.name)
+def test_input_gradient_accumulation(cfg):
+    """NM_ACCUM_DX: dx = round(dx_old + gradient), through nm_conv1d_bwd_data and nm_conv1d_bwd."""
+    dtype = "bf16"
+    inp = syn.make_inputs(cfg, dtype)
+    kw = U.geom_kw(cfg)
+    scale = U.to_dev(inp, "scale", dtype) if cfg.affine else None
+    x, dy, w = U.to_dev(inp, "x", dtype), U.to_dev(inp, "dy", dtype), U.to_dev(inp, "w", dtype)
+    ysv = U.to_dev(inp, "y_saved", dtype) if cfg.relu else None
+    old = U.to_dev(inp, "x", dtype)  # any bf16 tensor of dx's shape serves as the old value
+    dz, _ = orc.epilogue_bwd(inp["dy"], inp["y_saved"] if cfg.relu else None, inp["scale"] if cfg.affine else None, cfg.relu)
+    ref = inp["x"].astype(np.float64) + orc.bwd_data(dz, inp["w"], cfg.T, **kw)
+    dx1, _ = nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, dx=old.clone(), relu=cfg.relu, accumulate_dx=True, **kw)
+    U.assert_close(U.to_host_f64(dx1), ref, dtype, f"{cfg.name} accumulated dx")
+    dx2, _, _ = nm.nm_conv1d_bwd(x, dy, w, y=ysv, scale=scale, dx=old.clone(), relu=cfg.relu, accumulate_dx=True, **kw)
+    assert np.array_equal(U.to_host_f64(dx1), U.to_host_f64(dx2)), "fused call differs from nm_conv1d_bwd_data"
+    dx3, _ = nm.nm_conv1d_bwd_data(dy, w, cfg.T, y=ysv, scale=scale, dx=old.clone(), relu=cfg.relu, accumulate_dx=True,
+                                   force_direct=True, **kw)
+    U.assert_close(U.to_host_f64(dx3), ref, dtype, f"{cfg.name} accumulated dx (plain kernel)")
 
 
 def test_impulse_recovers_weights_on_gpu():

@@ -1,36 +1,38 @@
-"""End-to-end run of the 64-layer 10x5-shaped encoder stack (prolog, ten blocks of five sub-blocks
-with a K=1 residual projection each, three epilog layers) through the C ABI, forward and backward,
-at a reduced size (B=1, 320 -> 160 time steps), against the fp64 oracle run over the same stack.
+"""The 64-layer 10x5-shaped encoder stack (prolog, ten blocks of five sub-blocks with a K=1 residual
+projection each, three epilog layers), run forward and backward by the product's stack driver
+(paper_1909_09577_amd/stack.py: every layer through the C ABI) and checked against the fp64 oracle.
 
-Both chains start from the same seeded tensors (input, per-layer weights/scale/shift, final
-gradient) and neither sees the other's intermediate results.  The oracle chain rounds every tensor
-that the GPU path stores in bf16 (layer outputs, dx, dres, the sum of the two block-input
-gradients) to bf16 at the same places, so that the comparison measures the kernels and not 64
-layers of compounded storage rounding.  Even so the two chains do not stay within the single-kernel
-tolerance: an output that falls next to a bf16 rounding boundary rounds differently after float32
-and after float64 accumulation (one unit in the last place, 2^-8 relative), the following layers
-amplify such flips, and the difference between the chains grows from 2e-6 (relative rms) after the
-first layer to a plateau of about 5e-3 after some 25 layers -- the level of the bf16 storage noise
-itself -- where it stays.  The forward gates here are therefore those of that plateau (relative rms
-error <= 1e-2, max scaled error <= 6e-2), the backward ones direction and size only (see below);
-the single-kernel gate (1e-2 max) is applied layer by layer in test_gpu_parity.py on every
-distinct layer shape of this stack.  Residual wiring: the projection r = affine(conv1x1(block
-input)) (no ReLU) is the residual of the block's fifth sub-block; in backward dres of that
-sub-block is the projection's dy and the block-input gradient is dx(first sub-block) + dx(projection).
+Two kinds of check:
+
+* teacher-forced, layer by layer (the parity gate proper): the GPU chain runs once; then, for every one
+  of the 64 layers, the oracle takes the tensors the GPU chain actually fed to that layer -- its bf16
+  input, residual, upstream gradient and saved output, read back bit-exactly -- and the layer's y, dx,
+  dres and dw are held to the single-kernel gate (1e-2 max scaled error, 3e-3 relative rms).  No error
+  compounds that way and every layer of the real chain, with its real post-ReLU, residual-summed data
+  and its wiring (which tensor feeds which port, the dres -> projection -> summed block-input
+  gradient path), is pinned.  Sizes: B=2 at full length (1600 -> 800 frames) on whole tensors, and
+  the full B=32 on sampled elements;
+* free-running at a reduced size: GPU chain and an fp64 oracle chain (which rounds to bf16 wherever the
+  GPU stores bf16) both run end to end from the same seeded tensors.  Two such chains cannot stay
+  within the single-kernel tolerance: values next to a bf16 rounding boundary round differently after
+  float32 and after float64 accumulation, later layers amplify the flips until the relative rms
+  difference plateaus near 5e-3, and each ReLU mask taken from such an output flips a fraction of a
+  percent of its elements.  That test therefore only asks the forward tensors to stay at the plateau
+  and the gradients to agree in direction and size; it is a smoke check of the whole, not the gate.
 """
 import numpy as np
 import pytest
 
 import _util as U
 from oracle import conv1d_oracle as orc
-from paper_1909_09577_amd import binding as nm
 from paper_1909_09577_amd import inputs as syn
+from paper_1909_09577_amd import stack as nmstack
 
 pytestmark = pytest.mark.gpu
 DT = "bf16"
-RMS_CHAIN = 1e-2   # relative rms error of any tensor of the two chains (plateau observed: about 5e-3)
-MAX_CHAIN = 6e-2   # max |g-o| / (|o| + rms(o)) (observed: up to about 4e-2)
-COS_CHAIN = 0.95   # cosine between the two chains' gradients (observed: about 0.98)
+RMS_CHAIN = 1e-2   # free-running chains: relative rms error of any forward tensor (plateau observed: about 5e-3)
+MAX_CHAIN = 6e-2   # free-running chains: max |g-o| / (|o| + rms(o)) (observed: up to about 4e-2)
+COS_CHAIN = 0.95   # free-running chains: cosine between the two chains' gradients (observed: about 0.98)
 
 
 def r16(a):
@@ -38,27 +40,112 @@ def r16(a):
     return U.round_to_storage(a, DT).astype(np.float64)
 
 
-class GpuLayer:
-    def __init__(self, cfg, inp):
-        self.cfg = cfg
-        self.kw = U.geom_kw(cfg)
-        self.w = U.to_dev(inp, "w", DT)
-        self.scale = U.to_dev(inp, "scale", DT) if cfg.affine else None
-        self.shift = U.to_dev(inp, "shift", DT) if cfg.affine else None
-
-    def fwd(self, x, residual=None):
-        self.x = x
-        self.y = nm.nm_conv1d_block_fwd(x, self.w, self.scale, self.shift, residual, relu=self.cfg.relu, **self.kw)
-        return self.y
-
-    def bwd(self, dy, want_dres=False):
-        ysv = self.y if self.cfg.relu else None
-        dx, dres = nm.nm_conv1d_bwd_data(dy, self.w, self.cfg.T, y=ysv, scale=self.scale, relu=self.cfg.relu,
-                                         want_dres=want_dres, **self.kw)
-        self.dw = nm.nm_conv1d_bwd_weight(self.x, dy, self.cfg.K, y=ysv, scale=self.scale, relu=self.cfg.relu, **self.kw)
-        return dx, dres
+def stack_inputs(B, T_in):
+    """Layer list with seeded parameters (drawn per layer with a one-item batch: only w, scale and shift of
+    those draws are used), the stack input and the gradient of the stack output."""
+    layers = syn.jasper_10x5_layers(B=B, T_in=T_in)
+    assert len(layers) == 64
+    for e in layers:
+        e["inp"] = syn.make_inputs(syn.shrink(e["cfg"], B=1), DT)
+    x0 = syn.make_inputs(layers[0]["cfg"], DT)
+    dy = syn.make_inputs(layers[-1]["cfg"], DT)
+    return layers, x0, dy
 
 
+def device_params(layers):
+    return [{"w": U.to_dev(e["inp"], "w", DT),
+             "scale": U.to_dev(e["inp"], "scale", DT) if e["cfg"].affine else None,
+             "shift": U.to_dev(e["inp"], "shift", DT) if e["cfg"].affine else None} for e in layers]
+
+
+# ---- teacher-forced, layer by layer -------------------------------------------------------------------
+class Chain:
+    """The GPU chain of one size, run once per test session."""
+    cache = {}
+
+    @classmethod
+    def get(cls, B, T_in):
+        key = (B, T_in)
+        if key not in cls.cache:
+            cls.cache.clear()  # one size at a time on the device
+            layers, x0, dy = stack_inputs(B, T_in)
+            st = nmstack.EncoderStack(layers, device_params(layers), record_partial_dx=True)
+            st.step(U.to_dev(x0, "x", DT), U.to_dev(dy, "dy", DT))
+            cls.cache[key] = (layers, st)
+        return cls.cache[key]
+
+
+def test_stack_wiring_of_the_chain():
+    """Which tensor feeds which port (identity of device buffers, after the teacher-forced run)."""
+    layers, st = Chain.get(2, 1600)
+    L = st.layers
+    assert L[1].x is L[0].y and L[2].x is L[0].y            # projection and first sub-block read the block input
+    for proj, subs in st.blocks:
+        assert subs[4].residual is proj.y and proj.dy is subs[4].dres
+        assert all(subs[j + 1].x is subs[j].y and subs[j].dy is subs[j + 1].dx for j in range(4))
+        assert proj.dx is subs[0].dx
+    for a, b in zip(st.blocks[:-1], st.blocks[1:]):
+        assert b[0].x is a[1][4].y and a[1][4].dy is b[1][0].dx
+    assert st.epilog[0].x is st.blocks[-1][1][4].y and st.blocks[-1][1][4].dy is st.epilog[0].dx
+    assert L[0].dy is st.blocks[0][1][0].dx
+
+
+SIZES = {"b2_full_tensors": (2, 1600, None), "b32_sampled": (32, 1600, 1024)}
+LAYER_IDS = [f"L{i:02d}" for i in range(64)]
+
+
+@pytest.mark.parametrize("li", range(64), ids=LAYER_IDS)
+@pytest.mark.parametrize("size", list(SIZES), ids=list(SIZES))
+def test_stack_teacher_forced(size, li):
+    B, T_in, nsample = SIZES[size]
+    layers, st = Chain.get(B, T_in)
+    e, l = layers[li], st.layers[li]
+    cfg, kw = e["cfg"], U.geom_kw(e["cfg"])
+    w64 = e["inp"]["w"].astype(np.float64)
+    scale = e["inp"]["scale"] if cfg.affine else None
+    shift = e["inp"]["shift"] if cfg.affine else None
+    H = U.to_host_f64
+    x, res, y_gpu, dy = H(l.x), (H(l.residual) if l.residual is not None else None), H(l.y), H(l.dy)
+    assert (res is not None) == cfg.residual
+    rng = np.random.default_rng(1000 + li)
+    what = f"{size} {cfg.name} ({cfg.Cin}->{cfg.Cout} K={cfg.K} s={cfg.stride} d={cfg.dilation})"
+
+    def pick(n_total):
+        return None if nsample is None else np.unique(rng.choice(n_total, size=min(nsample, n_total), replace=False))
+
+    # forward from the GPU chain's own inputs
+    idx = pick(y_gpu.size)
+    if idx is None:
+        U.assert_close(y_gpu, orc.block_fwd(x, w64, scale, shift, res, cfg.relu, **kw), DT, f"{what} y")
+    else:
+        U.assert_close(y_gpu.reshape(-1)[idx], orc.block_fwd_at(x, w64, idx, scale, shift, res, cfg.relu, **kw), DT,
+                       f"{what} y")
+    # backward from the GPU chain's own upstream gradient and saved output
+    dz, dres_ref = orc.epilogue_bwd(dy, y_gpu if cfg.relu else None, scale, cfg.relu)
+    if cfg.residual:
+        np.testing.assert_array_equal(H(l.dres), dres_ref)
+    # dx: a block's first sub-block and its projection share one tensor (the projection's call adds into it)
+    dx_gpu, base = H(l.dx), 0.0
+    if l.role == "sub" and st.blocks[l.block][1][0] is l:
+        dx_gpu = H(st.partial_dx[l.block])
+    elif l.role == "proj":
+        base = H(st.partial_dx[l.block])
+    idx = pick(dx_gpu.size)
+    if idx is None:
+        U.assert_close(dx_gpu, base + orc.bwd_data(dz, w64, cfg.T, **kw), DT, f"{what} dx")
+    else:
+        b = base.reshape(-1)[idx] if l.role == "proj" else 0.0
+        U.assert_close(dx_gpu.reshape(-1)[idx], b + orc.bwd_data_at(dz, w64, cfg.T, idx, **kw), DT, f"{what} dx")
+    dw_gpu = H(l.dw)
+    idx = pick(dw_gpu.size)
+    if idx is None:
+        U.assert_close(dw_gpu, orc.bwd_weight(x, dz, cfg.K, **kw), DT, f"{what} dw", rms_bound=U.RMS_DW_BF16)
+    else:
+        U.assert_close(dw_gpu.reshape(-1)[idx], orc.bwd_weight_at(x, dz, cfg.K, idx, **kw), DT, f"{what} dw",
+                       rms_bound=U.RMS_DW_BF16)
+
+
+# ---- free-running chains at a reduced size ----------------------------------------------------------------
 class OracleLayer:
     def __init__(self, cfg, inp):
         self.cfg = cfg
@@ -74,16 +161,15 @@ class OracleLayer:
 
     def bwd(self, dy, want_dres=False):
         dz, dres = orc.epilogue_bwd(dy, self.y if self.cfg.relu else None, self.scale, self.cfg.relu)
-        dx = r16(orc.bwd_data(dz, self.w, self.cfg.T, **self.kw))
+        self.dx_exact = orc.bwd_data(dz, self.w, self.cfg.T, **self.kw)
         self.dw = orc.bwd_weight(self.x, dz, self.cfg.K, **self.kw)
-        return dx, (dres if want_dres else None)
+        return r16(self.dx_exact), (dres if want_dres else None)
 
 
-def run_stack(layers, make_layer, x0, dy_final, add):
-    """Forward then backward over the layer list; returns (final output, input gradient, layer objects)."""
-    objs = [make_layer(e["cfg"], e["inp"]) for e in layers]
+def run_oracle_stack(layers, x0, dy_final):
+    """The same wiring as the product's driver, on the oracle (stores rounded to bf16 where the GPU stores bf16)."""
+    objs = [OracleLayer(e["cfg"], e["inp"]) for e in layers]
     roles = [e["role"] for e in layers]
-    # ---- forward
     h = objs[0].fwd(x0)
     i = 1
     blocks = []
@@ -99,7 +185,6 @@ def run_stack(layers, make_layer, x0, dy_final, add):
     for ep in objs[i:]:
         h = ep.fwd(h)
     y_final = h
-    # ---- backward
     g = dy_final
     for ep in reversed(objs[i:]):
         g, _ = ep.bwd(g)
@@ -107,47 +192,29 @@ def run_stack(layers, make_layer, x0, dy_final, add):
         g, dres = subs[4].bwd(g, want_dres=True)
         for sub in reversed(subs[:4]):
             g, _ = sub.bwd(g)
-        gp, _ = proj.bwd(dres)
-        g = add(g, gp)
+        proj.bwd(dres)
+        g = r16(g + proj.dx_exact)  # the projection's call adds its float sums to the stored gradient, rounds once
     dx0, _ = objs[0].bwd(g)
     return y_final, dx0, objs
 
 
 def test_encoder_stack_end_to_end_reduced_size():
-    layers = syn.jasper_10x5_layers(B=1, T_in=320)
-    assert len(layers) == 64
-    for e in layers:
-        e["inp"] = syn.make_inputs(e["cfg"], DT)
-    first, last = layers[0], layers[-1]
-    x0_host, dy_host = first["inp"]["x"].astype(np.float64), last["inp"]["dy"].astype(np.float64)
+    layers, x0, dy = stack_inputs(1, 320)
+    st = nmstack.EncoderStack(layers, device_params(layers))
+    y_g, dx_g = st.step(U.to_dev(x0, "x", DT), U.to_dev(dy, "dy", DT))
+    gl = st.layers
+    y_o, dx_o, ol = run_oracle_stack(layers, x0["x"].astype(np.float64), dy["dy"].astype(np.float64))
 
-    y_g, dx_g, gl = run_stack(layers, GpuLayer, U.to_dev(first["inp"], "x", DT), U.to_dev(last["inp"], "dy", DT),
-                              lambda a, b: a + b)  # one bf16 add per block (float32 inside, rounded once)
-    y_o, dx_o, ol = run_stack(layers, OracleLayer, x0_host, dy_host, lambda a, b: r16(a + b))
-
-    import os
-    if os.environ.get("NM_STACK_VERBOSE"):
-        for e, g, o in zip(layers, gl, ol):
-            mx, rr = U.err_metrics(U.to_host_f64(g.y), o.y)
-            mw, rw = U.err_metrics(U.to_host_f64(g.dw), o.dw)
-            print(f"{e['cfg'].name:12s} y: max {mx:.2e} rms {rr:.2e}   dw: max {mw:.2e} rms {rw:.2e}")
     # the first layer's output has seen no compounding yet: single-kernel gate
     U.assert_close(U.to_host_f64(gl[0].y), ol[0].y, DT, "prolog output")
-    # forward tensors: the plateau gates
     worst_mx = worst_rr = 0.0
-    checks = [(f"{e['cfg'].name} y", U.to_host_f64(g.y), o.y) for e, g, o in zip(layers, gl, ol)]
-    for what, got, ref in checks:
-        mx, rr = U.err_metrics(got, ref)
+    for e, g, o in zip(layers, gl, ol):
+        mx, rr = U.err_metrics(U.to_host_f64(g.y), o.y)
         worst_mx, worst_rr = max(worst_mx, mx), max(worst_rr, rr)
-        assert mx <= MAX_CHAIN and rr <= RMS_CHAIN, f"{what}: max scaled error {mx:.3e}, rel rms {rr:.3e}"
+        assert mx <= MAX_CHAIN and rr <= RMS_CHAIN, f"{e['cfg'].name} y: max scaled error {mx:.3e}, rel rms {rr:.3e}"
     # the last layer has no ReLU: its weight gradient only sees the forward plateau
     mx, rr = U.err_metrics(U.to_host_f64(gl[-1].dw), ol[-1].dw)
     assert mx <= MAX_CHAIN and rr <= 2 * RMS_CHAIN, f"last layer dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
-    # Gradients further back: each ReLU layer whose saved output differs at the plateau level has
-    # its mask y > 0 flipped for the few elements whose pre-activation lies within that noise of
-    # zero (about 0.4 % of them), which alone perturbs the gradient by sqrt(0.004) = 6 % per
-    # layer; the two backward chains settle at a relative difference of 0.1-0.2.  What can still
-    # be asked of them is that they point the same way and have the same size.
     worst_cos = 1.0
     grads = [("stack input gradient", U.to_host_f64(dx_g), dx_o)]
     grads += [(f"{e['cfg'].name} dw", U.to_host_f64(g.dw), o.dw) for e, g, o in zip(layers, gl, ol)]
