@@ -50,7 +50,9 @@ typedef enum {
     NM_ERR_BAD_ARG = -1,     /* NULL required pointer, non-positive size, unknown flag/dtype, T_out <= 0 */
     NM_ERR_UNSUPPORTED = -2, /* valid request this build cannot serve (e.g. a tensor of 2^31 elements or more) */
     NM_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned or smaller than required */
-    NM_ERR_DEVICE = -4       /* the HIP runtime refused a launch */
+    NM_ERR_DEVICE = -4,      /* the HIP runtime refused a launch */
+    NM_ERR_SCRATCH_LIMIT = -5 /* nm_conv1d_block_fwd_static only: the geometry needs more scratch than
+                                 NM_STATIC_SCRATCH_BYTES */
 } nm_status;
 
 typedef enum { NM_BF16 = 0, NM_F32 = 1 } nm_dtype;
@@ -170,7 +172,21 @@ int nm_decoder_logsoftmax_fwd(int B, int Cin, int Ncls, int T, const void *x, co
                               const float *bias, float *logp, unsigned flags, int dtype,
                               void *hip_stream);
 
-/* Measurement aid (no effect on results; the only state the library keeps, and
+/* Block forward for callers that cannot allocate device memory or size a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments,
+ * results (bit for bit) and error behaviour as nm_conv1d_block_fwd, without the workspace arguments: the
+ * scratch its kernels need (the weights in matrix-core fragment order) lives in a fixed array of
+ * NM_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing.  A geometry whose nm_conv1d_workspace_bytes(NM_OP_FWD, ...) exceeds
+ * NM_STATIC_SCRATCH_BYTES returns NM_ERR_SCRATCH_LIMIT before anything is launched.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap in time on one GPU (different streams or threads) race on
+ * it and must be serialised by the caller.  Nothing in the array has to survive between calls. */
+#define NM_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int nm_conv1d_block_fwd_static(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                               const void *x, const void *w, const float *scale, const float *shift,
+                               const void *residual, void *y, unsigned flags, int dtype, void *hip_stream);
+
+/* Measurement aid (no effect on results; the only state the library keeps besides the array above, and
  * it is per thread).  Arms a one-shot timer for the calling thread: the next entry-point call made by this
  * thread records `start_event` immediately before and `stop_event` immediately after a main convolution
  * kernel of that call, on the call's stream (helper kernels -- weight packing, the mask pass, the final dw

@@ -15,14 +15,15 @@ from typing import Optional
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libnmconv1d.so")
 
-NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE = 0, -1, -2, -3, -4
+NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE, NM_ERR_SCRATCH_LIMIT = 0, -1, -2, -3, -4, -5
+NM_STATIC_SCRATCH_BYTES = 32 << 20
 NM_BF16, NM_F32 = 0, 1
 NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT, NM_ACCUM_DX = 1, 2, 4, 8
 NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
-           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_time_next_kernel_of", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -50,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.nm_strerror.restype = ctypes.c_char_p
         L.nm_conv1d_block_fwd.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp, sz, vp]
         L.nm_conv1d_block_fwd.restype = i
+        L.nm_conv1d_block_fwd_static.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp]
+        L.nm_conv1d_block_fwd_static.restype = i
         L.nm_conv1d_bwd_data.argtypes = [i] * 8 + [vp] * 6 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd_data.restype = i
         L.nm_conv1d_bwd_weight.argtypes = [i] * 8 + [vp] * 5 + [u, i, vp, sz, vp]
@@ -168,6 +171,25 @@ def nm_conv1d_block_fwd(x, w, scale=None, shift=None, residual=None, y=None, *, 
         flags, code, ws_ptr, ws_bytes, _stream(stream))
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_block_fwd")
+    return y
+
+
+def nm_conv1d_block_fwd_static(x, w, scale=None, shift=None, residual=None, *, y, stride=1, dilation=1, pad=0,
+                               relu=False, force_direct=False, stream=None):
+    """nm_conv1d_block_fwd without a workspace: scratch is the library's fixed array.  The caller passes
+    the output tensor y (this wrapper allocates nothing either); returns y."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = y.shape[2]
+    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    st = lib().nm_conv1d_block_fwd_static(
+        B, Cin, Cout, T, K, stride, dilation, pad, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(shift, torch.float32, (Cout,), "shift"),
+        _ptr(residual, x.dtype, (B, Cout, To), "residual"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+        flags, _dtype_code(x), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_block_fwd_static")
     return y
 
 

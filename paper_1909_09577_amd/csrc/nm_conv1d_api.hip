@@ -5,9 +5,36 @@
 #include "../../include/nm_conv1d.h"
 #include "nm_common.h"
 
+#include <mutex>
+
 using namespace nm;
 
+// Scratch of nm_conv1d_block_fwd_static.  The name is a host-side handle only: device code and
+// launches use the address hipGetSymbolAddress returns for the current device (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[NM_STATIC_SCRATCH_BYTES];
+
 namespace {
+// Address of `scratch` on the current device, looked up once per device.
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 thread_local hipEvent_t t_start_event = nullptr;
 thread_local hipEvent_t t_stop_event = nullptr;
 thread_local int t_timed_op = -1;    // pass whose main kernel the armed pair is for (-1: the first one launched)
@@ -210,6 +237,7 @@ const char *nm_strerror(int status)
     case NM_ERR_UNSUPPORTED: return "unsupported size";
     case NM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case NM_ERR_DEVICE: return "HIP runtime error";
+    case NM_ERR_SCRATCH_LIMIT: return "geometry needs more scratch than the fixed array of the no-allocation entry point";
     default: return "unknown status";
     }
 }
@@ -333,6 +361,28 @@ int nm_conv1d_block_fwd(int B, int Cin, int Cout, int T, int K, int stride, int 
 {
     return block_fwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, w, scale, shift, residual, y, flags, dtype,
                           workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_block_fwd_static(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                               const void *w, const float *scale, const float *shift, const void *residual, void *y,
+                               unsigned flags, int dtype, void *hip_stream)
+{
+    // Size the scratch like nm_conv1d_workspace_bytes does (0 for invalid arguments: the shared
+    // implementation below then reports them, before any device call).
+    const size_t need = nm_conv1d_workspace_bytes(NM_OP_FWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
+    if (need > NM_STATIC_SCRATCH_BYTES) {
+        DisarmOnExit disarm;
+        return NM_ERR_SCRATCH_LIMIT;
+    }
+    void *ptr = nullptr;
+    if (need > 0 && x && w && y) {  // (missing tensors: no device call before the argument error)
+        if (static_scratch(&ptr) != hipSuccess) {
+            DisarmOnExit disarm;
+            return NM_ERR_DEVICE;
+        }
+    }
+    return block_fwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, w, scale, shift, residual, y, flags, dtype,
+                          ptr, ptr ? (size_t)NM_STATIC_SCRATCH_BYTES : 0, hip_stream);
 }
 
 int nm_conv1d_bwd_data(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *dy,

@@ -165,6 +165,28 @@ def test_masked_entry_points_check_their_arguments():
     assert L.nm_conv1d_bwd_data_masked(*dims, FAKE, FAKE2, None, None, FAKE3, FAKE4, None, nm.NM_RELU, 0, None, 0, None) == nm.NM_ERR_BAD_ARG
 
 
+# ---- the forward entry point without a workspace ---------------------------------------------------
+def fwd_static(dims=None, x=FAKE2, w=FAKE3, y=FAKE4, flags=0, dtype=0):
+    d = dict(GOOD, **(dims or {}))
+    return nm.lib().nm_conv1d_block_fwd_static(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"],
+                                               d["pad"], x, w, None, None, None, y, flags, dtype, None)
+
+
+def test_static_forward_reports_argument_errors_and_its_scratch_limit_before_any_device_call():
+    assert fwd_static(x=None) == nm.NM_ERR_BAD_ARG
+    assert fwd_static(dims=dict(T=0)) == nm.NM_ERR_BAD_ARG
+    assert fwd_static(flags=1 << 9) == nm.NM_ERR_BAD_ARG
+    assert fwd_static(dtype=7) == nm.NM_ERR_BAD_ARG
+    # 768 -> 896 channels with 29 taps: 41 MB of packed weights against a 32 MiB array
+    big = dict(B=1, Cin=768, Cout=896, T=160, K=29, stride=1, dilation=2, pad=28)
+    assert nm.nm_conv1d_workspace_bytes(nm.NM_OP_FWD, *big.values()) > nm.NM_STATIC_SCRATCH_BYTES
+    assert fwd_static(dims=big) == nm.NM_ERR_SCRATCH_LIMIT
+    assert "scratch" in nm.strerror(nm.NM_ERR_SCRATCH_LIMIT)
+    text = open(os.path.join(ROOT, "include", "nm_conv1d.h")).read()
+    m = re.search(r"#define NM_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << (\d+)\)", text)
+    assert m and int(m.group(1)) << int(m.group(2)) == nm.NM_STATIC_SCRATCH_BYTES
+
+
 def test_declared_output_lengths_of_the_workloads_are_the_oracles():
     from paper_1909_09577_amd import inputs as syn
     cfgs = list(syn.SINGLE_LAYER_CFGS) + [e["cfg"] for e in syn.jasper_10x5_layers()] + \
