@@ -11,9 +11,9 @@ the two gradients from separate calls (nm_conv1d_bwd_data, nm_conv1d_bwd_weight:
 the mask pass runs twice) is timed afterwards and reported as an extra object.  The metric is
 3 * 2*B*Cout*T_out*Cin*K flop per step divided by the measured time, in TFLOP/s.
 
-Protocol: W warm-up steps (events around each main kernel find the dominant one), then an untimed
-settling phase (`settle_steps` in the JSON line: the chip's clocks and power state take some tens of
-milliseconds of load to settle, which a short timed region would otherwise measure), then exactly K
+Protocol: W warm-up steps, then an untimed settling phase (`settle_steps` in the JSON line: the chip's
+clocks and power state take some tens of milliseconds of load to settle, which a short timed region
+would otherwise measure), then exactly K
 timed steps between two device synchronisations, timed with the host clock (`ms_per_step`, the
 headline) and with an event pair around the whole loop (`ms_per_step_device`).
 
@@ -22,7 +22,8 @@ The JSON line also carries
                   peak; its average duration is measured in the timed region with HIP events
                   recorded on the launch stream right around that kernel (the library's
                   nm_conv1d_time_next_main_kernel hook) in every fourth step;
-  main_kernels -- duration, TFLOP/s, algorithmic bytes and GB/s of the three main kernels (warm-up events);
+  main_kernels -- duration, TFLOP/s, algorithmic bytes and GB/s of the three main kernels (events in the last
+                  steps of the settling phase);
   cpu_baseline -- the fp64 CPU oracle, untuned, timed on the host cores on the full workload
                   (a baseline, not the target).
 """
@@ -345,19 +346,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- warm-up: the three main kernels are timed one by one (separate calls, so that the hook reaches each)
+    # ---- warm-up, then the settling phase (untimed, disclosed).  Its last steps run the backward as two calls
+    # with an event pair around each of the three main kernels: that finds the dominant kernel on a chip
+    # that has reached its steady clocks.
     names = ("fwd", "dgrad", "wgrad")
-    nwarm = max(args.warmup, 1)
-    warm_pairs = {n: [(ev(), ev()) for _ in range(nwarm)] for n in names}
-    for i in range(nwarm):
-        step_three_calls({n: warm_pairs[n][i] for n in names})
-    torch.cuda.synchronize()
-    warm_ms = {n: sorted(a.elapsed_time(b) for a, b in warm_pairs[n])[nwarm // 2] for n in names}
-    dominant = max(warm_ms, key=warm_ms.get)
-
-    # ---- settling phase (untimed, disclosed), then the timed region
-    for _ in range(max(args.settle_steps, 0)):
+    for _ in range(max(args.warmup, 1)):
         step()
+    nprobe = 10
+    for _ in range(max(args.settle_steps - nprobe, 0)):
+        step()
+    probe_pairs = {n: [(ev(), ev()) for _ in range(nprobe)] for n in names}
+    for i in range(nprobe):
+        step_three_calls({n: probe_pairs[n][i] for n in names})
+    torch.cuda.synchronize()
+    warm_ms = {n: sorted(a.elapsed_time(b) for a, b in probe_pairs[n])[nprobe // 2] for n in names}
+    dominant = max(warm_ms, key=warm_ms.get)
+    settle_steps = max(args.settle_steps - nprobe, 0) + nprobe
+
     # Events around a kernel split the stream's back-to-back dispatch (a few microseconds per pair), so the
     # timed region carries them only around the dominant kernel and only in every fourth step.
     every = 4
@@ -447,7 +452,7 @@ def main():
     out = {
         "metric": METRIC_NAMES[args.workload],
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "settle_steps": max(args.settle_steps, 0),
+        "settle_steps": settle_steps,
         "ms_per_step": round(ms_per_step, 4), "ms_per_step_device": round(ms_per_step_device, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

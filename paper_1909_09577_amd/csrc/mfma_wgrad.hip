@@ -24,6 +24,8 @@
 //   dw[co,ci,k] = scale[co] * sum_b sum_t g[b,co,t] * x[b,ci,tau(t,k)].
 #include "nm_common.h"
 
+#include <type_traits>
+
 namespace nm {
 namespace {
 
@@ -656,22 +658,76 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradParams 
 // costs a quarter of the main loop.  Here the four wavefronts of a workgroup walk through the SAME
 // units and share one staged window that covers all KG taps of the group (128 rows: each wavefront
 // loads and writes one 32-row item, a quarter of the work), and split the 2*KG accumulator blocks
-// (tap, 32-channel half of the 64 output channels) evenly: ceil(2*KG/4) consecutive blocks each, in
-// tap-major order, so a wavefront reads only the 4-6 taps it owns.  A block is owned by one wavefront
-// for the whole reduction, so there is no exchange at the end: every wavefront stores its blocks to
-// the [S][K][Cout][Cin] scratch.  One workgroup barrier per unit (double-buffered window).  The dz
-// fragments stream as in wgrad_fast_kernel (all four wavefronts read the same ones: L1 hits).
+// (tap, 32-channel half of the 64 output channels) among themselves.  A block is owned by one
+// wavefront for the whole reduction, so there is no exchange at the end: every wavefront stores its
+// blocks to the [S][K][Cout][Cin] scratch.
+//
+// Which blocks a wavefront owns.  The B fragment of tap t at a step is two transposing LDS reads, of
+// rows t*DIL and t*DIL + 4 (relative to the step): taps that are 4/DIL apart share a read.  So the taps
+// are dealt out in chains of that stride -- dilation 1: tap t belongs to wavefront t mod 4 (the K mod 4
+// taps that are left over are dealt out half by half); dilation 2: even taps form one chain, odd taps
+// the other, each cut in two -- and a wavefront reads each row once per step: K = 17 needs 6, 7, 5, 5 reads
+// per step in the four wavefronts for 9, 9, 8, 8 blocks, where consecutive taps would need 10 to 12.
+//
+// Pipeline.  Three window buffers: during unit u (window u in buffer u mod 3) every wavefront writes its
+// item of window u+2 (requested one unit earlier) and requests window u+3; the barrier at the end of a
+// unit therefore orders things that are a whole unit apart, and the fragments of the next unit's first
+// step are read from LDS before it, so the matrix pipe has its operands when the barrier opens.  The
+// g = dy*[y>0] fragments stream from L2 straight into registers, two units ahead (all four wavefronts
+// read the same ones: L1 hits).
+struct TapPlan {
+    int nb;                // accumulator blocks of this wavefront
+    int tap[16], half[16];
+    int nrow;              // distinct rows (relative to the step's first row, in units of DIL-less rows) it reads
+    int row[32];
+    int lo[16], hi[16];    // per block: positions in row[] of its two reads
+};
+template <int KG, int DIL>
+constexpr int block_owner(int tap, int half)
+{
+    if (DIL == 1) {
+        constexpr int Q4 = (KG / 4) * 4;
+        return tap < Q4 ? tap % 4 : (2 * (tap - Q4) + half) % 4;
+    }
+    const int pos = tap / 2;
+    if (tap % 2 == 0) return pos < ((KG + 1) / 2 + 1) / 2 ? 0 : 1;
+    return pos < (KG / 2 + 1) / 2 ? 2 : 3;
+}
+template <int KG, int DIL, int W>
+constexpr TapPlan make_tap_plan()
+{
+    TapPlan q = {};
+    for (int tap = 0; tap < KG; ++tap)
+        for (int half = 0; half < 2; ++half)
+            if (block_owner<KG, DIL>(tap, half) == W) {
+                q.tap[q.nb] = tap;
+                q.half[q.nb] = half;
+                ++q.nb;
+            }
+    for (int j = 0; j < q.nb; ++j) {
+        for (int e = 0; e < 2; ++e) {
+            const int r = q.tap[j] * DIL + 4 * e;
+            int at = -1;
+            for (int i = 0; i < q.nrow; ++i)
+                if (q.row[i] == r) at = i;
+            if (at < 0) {
+                at = q.nrow;
+                q.row[q.nrow++] = r;
+            }
+            (e == 0 ? q.lo[j] : q.hi[j]) = at;
+        }
+    }
+    return q;
+}
+
 template <int KG, int DIL, int W>
 __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char *smem, int sp, int k0, int kt, int co0,
                                              int ci0)
 {
-    constexpr int NB = (2 * KG + kWaves - 1) / kWaves;         // accumulator blocks per wavefront
-    constexpr int J0 = W * NB < 2 * KG ? W * NB : 2 * KG;      // this wavefront's blocks [J0, J1), block j = (tap j/2, half j%2)
-    constexpr int J1 = J0 + NB < 2 * KG ? J0 + NB : 2 * KG;
-    constexpr int NBW = J1 - J0;
-    constexpr int T0 = J0 / 2, T1 = (J1 + 1) / 2;              // taps [T0, T1)
-    constexpr int NTAP = T1 - T0 > 0 ? T1 - T0 : 1;
-    constexpr int kRows = 128, kBufBytes = kRows * kFastXRowBytes;
+    constexpr TapPlan plan = make_tap_plan<KG, DIL, W>();
+    constexpr int NBW = plan.nb, NROW = plan.nrow;
+    static_assert(NBW >= 1 && NBW <= 16 && NROW <= 32, "tap plan out of range");
+    constexpr int kRows = 128, kBufBytes = kRows * kFastXRowBytes;  // three such windows in LDS
     const int lane = threadIdx.x & 63;
     const int S = p.S;
     const __amdgpu_buffer_rsrc_t rs_x =
@@ -752,24 +808,39 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     auto a_load = [&](const UnitAddr &a, int mi, int st) {
         return buf_load16(rs_dz, a.live ? a_lane + (uint32_t)(st * 1024) : kFar, a.as + (uint32_t)mi * a_mi);
     };
+    // transposing reads: this lane addresses 4 channels 16*((lane/16)&1) + 4*(lane&3) at time row
+    // 8*(lane/32) + (lane&15)/4 of the block it reads
     const int g4 = lane >> 4, i16 = lane & 15;
     const int trow = 8 * (g4 >> 1) + (i16 >> 2) + off0;
     const int tcol = 16 * (g4 & 1) + 4 * (i16 & 3);
     const unsigned char *xb0 = smem + trow * kFastXRowBytes + tcol * 2;
-
-    f32x16 acc[NBW > 0 ? NBW : 1];
+    // rows of step st, from the window whose bytes start at xw (a pointer that already carries the lane part)
+    auto read_rows = [&](const unsigned char *xw, int st, s16x4(&dst)[NROW]) {
 #pragma unroll
-    for (int j = 0; j < (NBW > 0 ? NBW : 1); ++j)
+        for (int i = 0; i < NROW; ++i)
+            dst[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xw + (st * 16 + plan.row[i]) * kFastXRowBytes));
+    };
+
+    f32x16 acc[NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
     const int my_units = sp < p.units ? (p.units - sp + S - 1) / S : 0;  // the same for all four wavefronts
+    // x items in flight: two register sets; set X(u mod 2) is written to LDS during unit u (it holds this
+    // wavefront's item of window u+2), set X((u+1) mod 2) is requested during unit u (window u+3)
     u32x4 xa0, xb0r, xa1, xb1r;
-    int pend_tlen = 0, pend_tbase = 0;  // of the unit whose x item waits in registers for its LDS write
+    int tlen0 = 0, tbase0 = 0, tlen1 = 0, tbase1 = 0;  // of the windows waiting in the two sets
+    s16x4 rd[2][NROW];                                  // rows of the current / the next step
+    UnitPos ahead = unit_pos(sp);                       // the unit whose window is requested next
     {
-        UnitPos q0 = unit_pos(sp), q1 = q0;
-        advance(q1);
-        const UnitAddr a0 = unit_addr(q0), a1 = unit_addr(q1);
+        const UnitAddr a0 = unit_addr(ahead);
+        advance(ahead);
+        const UnitAddr a1 = unit_addr(ahead);
+        advance(ahead);
+        const UnitAddr a2 = unit_addr(ahead);
+        advance(ahead);
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -778,58 +849,67 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
                 afr1[mi][st] = a_load(a1, mi, st);
             }
         x_load_item(a0, xa0, xb0r);
-        x_load_item(a1, xa1, xb1r);  // written during the first unit
+        x_load_item(a1, xa1, xb1r);
         x_write_item(smem, xa0, xb0r);
         clear_padding_rows(smem, a0.tlen, a0.tbase);
-        pend_tlen = a1.tlen;
-        pend_tbase = a1.tbase;
+        x_write_item(smem + kBufBytes, xa1, xb1r);
+        clear_padding_rows(smem + kBufBytes, a1.tlen, a1.tbase);
+        x_load_item(a2, xa0, xb0r);  // window 2: written during unit 0
+        tlen0 = a2.tlen;
+        tbase0 = a2.tbase;
         __syncthreads();
+        read_rows(xb0, 0, rd[0]);
     }
-    // one unit: multiply from window `par`; request the dz fragments and this wavefront's x item of
-    // unit u + 2S; write the x item of unit u + S (other register set) into the other window
-    UnitPos ahead = unit_pos(sp);  // the unit two ahead of the one being multiplied
-    advance(ahead);
-    advance(ahead);
-    auto unit = [&](int par, u32x4(&afr)[2][kFastSteps], u32x4 &xa, u32x4 &xb, const u32x4 &xo_a, const u32x4 &xo_b) {
-        const UnitAddr an = unit_addr(ahead);
+    // byte offsets of the buffers holding window u, u+1 and the one being written (window u+2)
+    int cur = 0, nxt = kBufBytes, wr = 2 * kBufBytes;
+    // one unit; PAR: which of rd[] holds its first step (units alternate, a unit has five steps)
+    auto unit = [&](auto par_c, u32x4(&afr)[2][kFastSteps], u32x4 &xa, u32x4 &xb, int &tlen_req, int &tbase_req,
+                    const u32x4 &xo_a, const u32x4 &xo_b, int tlen_wr, int tbase_wr) {
+        constexpr int PAR = decltype(par_c)::value;
+        // the dz fragments requested in this unit are those of the unit after the next; the x item is one further
+        UnitPos two = ahead;  // `ahead` is three units on
+        two.b -= step_b;
+        two.c -= step_c;
+        if (two.c < 0) {
+            two.c += p.nchunk;
+            two.b -= 1;
+        }
+        const UnitAddr an2 = unit_addr(two);
+        const UnitAddr an3 = unit_addr(ahead);
         advance(ahead);
-        const unsigned char *xb_ = xb0 + par * kBufBytes;
-        unsigned char *wr = smem + (par ^ 1) * kBufBytes;
-        auto read_b = [&](int st, bf16x8(&bfr)[NTAP]) {
-#pragma unroll
-            for (int i = 0; i < NTAP; ++i) {
-                const unsigned char *xp = xb_ + (st * 16 + (T0 + i) * DIL) * kFastXRowBytes;
-                union {
-                    s16x4 h[2];
-                    bf16x8 v;
-                } cvt;
-                cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp));
-                cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(xp + 4 * kFastXRowBytes));
-                bfr[i] = cvt.v;
-            }
-        };
-        bf16x8 bq[2][NTAP];
-        read_b(0, bq[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *xw = xb0 + cur, *xn = xb0 + nxt;
+        unsigned char *wbuf = smem + wr;
 #pragma unroll
         for (int st = 0; st < kFastSteps; ++st) {
-            if (st + 1 < kFastSteps) read_b(st + 1, bq[(st + 1) & 1]);
+            constexpr int dummy = 0;
+            (void)dummy;
+            s16x4(&rc)[NROW] = rd[(PAR + st) & 1];
+            s16x4(&rn)[NROW] = rd[(PAR + st + 1) & 1];
+            if (st + 1 < kFastSteps)
+                read_rows(xw, st + 1, rn);
+            else
+                read_rows(xn, 0, rn);  // first step of the next unit: its window was complete a barrier ago
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
-                const int blk = J0 + j;
                 union {
                     u32x4 u;
                     bf16x8 v;
                 } af;
-                af.u = afr[blk & 1][st];
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bq[st & 1][(blk >> 1) - T0], acc[j], 0, 0, 0);
+                af.u = afr[plan.half[j]][st];
+                union {
+                    s16x4 h[2];
+                    bf16x8 v;
+                } bf;
+                bf.h[0] = rc[plan.lo[j]];
+                bf.h[1] = rc[plan.hi[j]];
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bf.v, acc[j], 0, 0, 0);
             }
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an, mi, st);
-            if (st == 0) x_load_item(an, xa, xb);
-            if (st == kFastSteps - 1) x_write_item(wr, xo_a, xo_b);
+            for (int mi = 0; mi < 2; ++mi) afr[mi][st] = a_load(an2, mi, st);
+            if (st == 0) x_load_item(an3, xa, xb);
+            if (st == kFastSteps - 1) x_write_item(wbuf, xo_a, xo_b);
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
+            for (int i = 0; i < NBW; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // VALU
@@ -840,15 +920,19 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        clear_padding_rows(wr, pend_tlen, pend_tbase);
-        pend_tlen = an.tlen;
-        pend_tbase = an.tbase;
-        __syncthreads();  // the other window is complete; this one may be overwritten
+        clear_padding_rows(wbuf, tlen_wr, tbase_wr);
+        tlen_req = an3.tlen;
+        tbase_req = an3.tbase;
+        const int old = cur;
+        cur = nxt;
+        nxt = wr;
+        wr = old;
+        __syncthreads();  // window u+2 is complete; window u may be overwritten from the next unit on
     };
     const int npairs = (my_units + 1) >> 1;
     for (int i = 0; i < npairs; ++i) {
-        unit(0, afr0, xa0, xb0r, xa1, xb1r);
-        unit(1, afr1, xa1, xb1r, xa0, xb0r);
+        unit(std::integral_constant<int, 0>{}, afr0, xa1, xb1r, tlen1, tbase1, xa0, xb0r, tlen0, tbase0);
+        unit(std::integral_constant<int, 1>{}, afr1, xa0, xb0r, tlen0, tbase0, xa1, xb1r, tlen1, tbase1);
     }
 
     // ---- every block goes straight to the scratch: register r of a block is output channel
@@ -857,7 +941,7 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     if (ci < p.Cin) {
 #pragma unroll
         for (int j = 0; j < NBW; ++j) {
-            const int blk = J0 + j, tap = blk >> 1, half = blk & 1;
+            const int tap = plan.tap[j], half = plan.half[j];
             if (tap >= kt) continue;  // a group shorter than KG
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -1023,7 +1107,7 @@ FastPlan make_fast_plan(const Geom &g)
                     f.KTg = KG;
                     f.ntg = (g.K + KG - 1) / KG;
                     f.S = (int)Ss;
-                    f.lds = 2 * 128 * kFastXRowBytes;
+                    f.lds = 3 * 128 * kFastXRowBytes;
                     break;
                 }
             }
