@@ -1073,17 +1073,6 @@ __global__ __launch_bounds__(256) void prepack_kernel(const bf16_t *__restrict__
     prepack_block<FLIP>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec, rscale);
 }
 
-// g = dy * [y > 0] for one 16-byte group (8 bf16): the mask works on the bits, so g is exact.
-__device__ __forceinline__ u32x4 masked_grad8(u32x4 g, const u32x4 yv)
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
-        g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
-    }
-    return g;
-}
-
 // Everything the input-gradient engine needs, in one launch: the first npack blocks pack the
 // flipped weights times the affine factor of their output channel (a latency-bound job), the others
 // run the elementwise mask pass g = dy*[y>0] (bandwidth bound), so the two overlap instead of
@@ -1106,9 +1095,7 @@ __global__ __launch_bounds__(256) void dgrad_prepare_kernel(unsigned npack, cons
 }
 
 // The same for a fused backward call: the elementwise part also writes g in the fragment order
-// of the stride-1 weight-gradient kernel, so dy and y are read once for both gradients.  Its
-// threads are laid out like the fragments (one wavefront per 32 channels x 16 time steps: lane l
-// handles channel l%32, time steps 8*(l/32) .. +7), which makes the fragment stores contiguous.
+// of the stride-1 weight-gradient kernels (mask_pack_wave), so dy and y are read once for both gradients.
 // gplain may be NULL (no ReLU and no residual gradient wanted: the engine then reads dy itself).
 __global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const bf16_t *__restrict__ w,
                                                           u32x4 *__restrict__ wp, int M, int R, int K, int nch, int ld,
@@ -1122,21 +1109,11 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(unsigned npack, const 
         prepack_block<true>(blockIdx.x, smem, w, wp, M, R, K, nch, ld, zero_off, vec, rscale);
         return;
     }
-    const int lane = threadIdx.x & 63;
-    const unsigned frag = (blockIdx.x - npack) * 4 + (threadIdx.x >> 6);  // (b, cm, st), st fastest
-    const unsigned nfrag = (unsigned)B * ncm * nst;
-    if (frag >= nfrag) return;
-    const int st = frag % nst, cm = (frag / nst) % ncm, b = frag / ((unsigned)nst * ncm);
-    const int co = cm * 32 + (lane & 31);
-    const int t = 16 * st + 8 * (lane >> 5);
-    u32x4 g = {0u, 0u, 0u, 0u};
-    if (co < Cout && t + 8 <= To) {
-        const size_t i = (((size_t)b * Cout + co) * To + t) / 8;  // 16-byte group index
-        g = reinterpret_cast<const u32x4 *>(dy)[i];
-        if (relu) g = masked_grad8(g, reinterpret_cast<const u32x4 *>(y)[i]);
-        if (gplain) gplain[i] = g;
-    }
-    gf[(size_t)frag * 64 + lane] = g;
+    const unsigned nst4 = (unsigned)(nst + 3) / 4;
+    const unsigned item = (blockIdx.x - npack) * 4 + (threadIdx.x >> 6);  // (b, cm, st4), st4 fastest
+    if (item >= (unsigned)B * ncm * nst4) return;
+    const int st4 = item % nst4, cm = (item / nst4) % ncm, b = item / (nst4 * ncm);
+    mask_pack_wave(threadIdx.x & 63, b, cm, st4, Cout, To, ncm, nst, dy, y, relu, gplain, gf);
 }
 
 // ---- input gradient of a stride-2 convolution (the encoder's first layer) -------------------------
@@ -1565,7 +1542,7 @@ hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, cons
 {
     const int M = g.Cin, R = g.Cout;  // the engine's roles for the input gradient
     const PackGeom q = pack_geom(w, M, R, g.K, true);
-    const size_t nfrag = (size_t)g.B * layout.ncm * layout.nst;
+    const size_t nfrag = (size_t)g.B * layout.ncm * ((layout.nst + 3) / 4);  // items of four fragments, one per wavefront
     void *gbuf = (unsigned char *)ws + packed_bytes(g.Cin, g.Cout, g.K);
     void *gout = dres ? dres : (relu ? gbuf : nullptr);
     *g_plain = gout ? gout : dy;

@@ -395,26 +395,9 @@ constexpr int fast_x_items(int dil) { return dil == 1 ? 3 : 4; }  // 92 rows -> 
 __global__ __launch_bounds__(256) void dz_pack_kernel(int Cout, int To, int ncm, int nst, const bf16_t *__restrict__ dy,
                                                       const bf16_t *__restrict__ y, int relu, u32x4 *__restrict__ dzf)
 {
-    const int lane = threadIdx.x & 63;
-    const int st = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int cm = blockIdx.y, b = blockIdx.z;
-    if (st >= nst) return;
-    const int co = cm * 32 + (lane & 31);
-    const int t = 16 * st + 8 * (lane >> 5);
-    u32x4 g = {0u, 0u, 0u, 0u};
-    if (co < Cout && t + 8 <= To) {
-        const size_t off = ((size_t)b * Cout + co) * To + t;
-        g = *reinterpret_cast<const u32x4 *>(dy + off);
-        if (relu) {
-            const u32x4 yv = *reinterpret_cast<const u32x4 *>(y + off);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
-                g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
-            }
-        }
-    }
-    dzf[(((size_t)b * ncm + cm) * nst + st) * 64 + lane] = g;
+    const int st4 = blockIdx.x * 4 + (threadIdx.x >> 6);  // four 16-step fragments per wavefront
+    if (st4 * 4 >= nst) return;
+    mask_pack_wave(threadIdx.x & 63, blockIdx.z, blockIdx.y, st4, Cout, To, ncm, nst, dy, y, relu, nullptr, dzf);
 }
 
 // The unit loop of the stride-1 kernel for KA active taps (KA == KT, or KT - 1 for a short last
@@ -1001,6 +984,45 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     }
 }
 
+// The same for Cin % 4 == 0 and 16-byte aligned dw: one block per (co, 256 ci), 16-byte loads along ci
+// (a wavefront reads 1 KiB contiguous per partial row) and 16-byte stores of the transposed tile.
+constexpr int kReduce4Ci = 256;
+__global__ __launch_bounds__(256) void wgrad_reduce4_kernel(const float *__restrict__ part, float *__restrict__ dw,
+                                                            const float *__restrict__ scale, int S, int K, int Cout,
+                                                            int Cin, int accumulate)
+{
+    extern __shared__ float tile[];  // [256][K+1]
+    const int co = blockIdx.y;
+    const int ci0 = blockIdx.x * kReduce4Ci;
+    const int l = threadIdx.x & 63, kq = threadIdx.x >> 6;
+    const int ci = ci0 + 4 * l;
+    const size_t plane = (size_t)Cout * Cin;
+    const float factor = scale ? scale[co] : 1.f;
+    for (int k = kq; k < K; k += 4) {
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        if (ci < Cin) {
+            const float *src = part + ((size_t)k * Cout + co) * Cin + ci;
+            for (int sp = 0; sp < S; ++sp) sum += *reinterpret_cast<const f32x4 *>(src + (size_t)sp * K * plane);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[(4 * l + e) * (K + 1) + k] = sum[e] * factor;
+    }
+    __syncthreads();
+    const int nci = min(kReduce4Ci, Cin - ci0);
+    const int n = nci * K;  // a multiple of 4
+    float *dst = dw + ((size_t)co * Cin + ci0) * K;
+    for (int e0 = threadIdx.x * 4; e0 < n; e0 += 1024) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int c = (e0 + e) / K, k = (e0 + e) - c * K;
+            v[e] = tile[c * (K + 1) + k];
+        }
+        f32x4 *o = reinterpret_cast<f32x4 *>(dst + e0);
+        *o = accumulate ? *o + v : v;
+    }
+}
+
 struct WPlan {
     bool ok;
     int KTg, ntg, TCH, NRX, S;
@@ -1172,6 +1194,12 @@ constexpr int kMaxReduceTaps = 64 * 1024 / (64 * (int)sizeof(float)) - 1;  // 25
 hipError_t launch_reduce(const Geom &g, const float *part, float *dw, const float *scale, int S, bool accumulate,
                          hipStream_t s)
 {
+    if (g.Cin % 4 == 0 && ((uintptr_t)dw % 16) == 0 && (size_t)kReduce4Ci * (g.K + 1) * sizeof(float) <= 64 * 1024) {
+        dim3 grid4((g.Cin + kReduce4Ci - 1) / kReduce4Ci, g.Cout);
+        hipLaunchKernelGGL(wgrad_reduce4_kernel, grid4, dim3(256), kReduce4Ci * (g.K + 1) * sizeof(float), s, part, dw, scale,
+                           S, g.K, g.Cout, g.Cin, accumulate ? 1 : 0);
+        return hipGetLastError();
+    }
     dim3 rgrid((g.Cin + 63) / 64, g.Cout);
     hipLaunchKernelGGL(wgrad_reduce_kernel, rgrid, dim3(256), 64 * (g.K + 1) * sizeof(float), s, part, dw, scale, S, g.K,
                        g.Cout, g.Cin, accumulate ? 1 : 0);
@@ -1265,7 +1293,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
     if (fast_ok(g)) {
         const FastPlan f = make_fast_plan(g);
         u32x4 *dzf = (u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
-        hipLaunchKernelGGL(dz_pack_kernel, dim3((f.nst + 3) / 4, f.ncm, g.B), dim3(256), 0, s, g.Cout, g.To, f.ncm,
+        hipLaunchKernelGGL(dz_pack_kernel, dim3(((f.nst + 3) / 4 + 3) / 4, f.ncm, g.B), dim3(256), 0, s, g.Cout, g.To, f.ncm,
                            f.nst, (const bf16_t *)dy, (const bf16_t *)y, relu ? 1 : 0, dzf);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

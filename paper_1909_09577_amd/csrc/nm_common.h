@@ -92,6 +92,57 @@ __device__ __forceinline__ void epilogue_bwd_vec8_item(size_t i, int Cout, int T
     }
 }
 
+// g = dy * [y > 0] for one 16-byte group (8 bf16): the mask works on the bits, so g is exact.
+__device__ __forceinline__ u32x4_t masked_grad8(u32x4_t g, const u32x4_t yv)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = yv[j] & 0xffffu, hi = yv[j] >> 16;  // y > 0 on bf16 bits: 0x0001..0x7f80
+        g[j] &= ((lo - 1u < 0x7f80u) ? 0x0000ffffu : 0u) | ((hi - 1u < 0x7f80u) ? 0xffff0000u : 0u);
+    }
+    return g;
+}
+
+// One wavefront's share of the pass that forms g = dy*[y>0] for the weight-gradient kernels: 32 channels
+// (block cm) x 64 time steps (four 16-step fragments from st4*4 on) of batch item b.  Reads are whole
+// 128-byte lines (lane = 8 rows x 8 groups of 8 steps, four times); g goes out in MFMA A-fragment order
+// [B][ncm][nst][64 lanes][8] (lane l of a fragment: channel l%32, steps 8*(l/32) .. +7; zeros outside the
+// tensor), again in whole lines, and, when gplain is given, also in the layout of dy.
+__device__ __forceinline__ void mask_pack_wave(int lane, int b, int cm, int st4, int Cout, int To, int ncm, int nst,
+                                               const bf16_t *__restrict__ dy, const bf16_t *__restrict__ y, int relu,
+                                               u32x4_t *__restrict__ gplain, u32x4_t *__restrict__ gf)
+{
+    const int tg = lane & 7, st = st4 * 4 + (tg >> 1);
+    const int t = 64 * st4 + 8 * tg;
+    u32x4_t g[4];
+    size_t idx[4];
+    bool ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int co = cm * 32 + 8 * i + (lane >> 3);
+        ok[i] = co < Cout && t + 8 <= To;
+        idx[i] = (((size_t)b * Cout + co) * To + t) / 8;  // 16-byte group index
+        g[i] = u32x4_t{0u, 0u, 0u, 0u};
+        if (ok[i]) g[i] = reinterpret_cast<const u32x4_t *>(dy)[idx[i]];
+    }
+    if (relu) {
+        u32x4_t yv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (ok[i]) yv[i] = reinterpret_cast<const u32x4_t *>(y)[idx[i]];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (ok[i]) g[i] = masked_grad8(g[i], yv[i]);
+    }
+    if (st < nst) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (gplain && ok[i]) gplain[idx[i]] = g[i];
+            gf[(((size_t)b * ncm + cm) * nst + st) * 64 + (tg & 1) * 32 + 8 * i + (lane >> 3)] = g[i];
+        }
+    }
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- per-device facts and one-time kernel set-up (host) -----------------------------------------
