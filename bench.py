@@ -198,6 +198,49 @@ def stack_layers_report():
                       "layers": sorted(rows, key=lambda r: -r["ms"] * r["count"])}), flush=True)
 
 
+def bn_report(steps, warmup):
+    """The headline block with training-mode BatchNorm (nm_conv1d_bn_fwd + nm_conv1d_bn_bwd): batch statistics,
+    normalise pass, backward through the statistics, both convolution gradients.  One JSON line; `--bn` only."""
+    import torch
+    from paper_1909_09577_amd import binding as nm
+    from paper_1909_09577_amd import inputs as syn
+    c = syn.HEADLINE
+    kw = dict(stride=c.stride, dilation=c.dilation, pad=c.pad)
+    x = torch.randn(c.B, c.Cin, c.T, device="cuda").bfloat16()
+    w = (torch.randn(c.Cout, c.Cin, c.K, device="cuda") / (c.Cin * c.K) ** 0.5).bfloat16()
+    res = torch.randn(c.B, c.Cout, c.T_out, device="cuda").bfloat16()
+    dy = torch.randn(c.B, c.Cout, c.T_out, device="cuda").bfloat16()
+    gamma, beta = torch.rand(c.Cout, device="cuda") + 0.5, torch.randn(c.Cout, device="cuda") * 0.1
+    z, y = torch.empty_like(res), torch.empty_like(res)
+    mean, invstd = torch.empty(c.Cout, device="cuda"), torch.empty(c.Cout, device="cuda")
+    dx, dres = torch.empty_like(x), torch.empty_like(res)
+    dw = torch.empty(c.Cout, c.Cin, c.K, device="cuda")
+    dgamma, dbeta = torch.empty(c.Cout, device="cuda"), torch.empty(c.Cout, device="cuda")
+    ws = torch.empty(max(nm.nm_conv1d_workspace_bytes(op, *c.dims(), nm.NM_BF16, nm.NM_RELU)
+                         for op in (nm.NM_OP_BN_FWD, nm.NM_OP_BN_BWD)), dtype=torch.uint8, device="cuda")
+
+    def step():
+        nm.nm_conv1d_bn_fwd(x, w, gamma, beta, res, relu=True, z=z, y=y, mean=mean, invstd=invstd, workspace=ws, **kw)
+        nm.nm_conv1d_bn_bwd(x, w, gamma, z, y, mean, invstd, dy, relu=True, dx=dx, dres=dres, dw=dw, dgamma=dgamma,
+                            dbeta=dbeta, workspace=ws, **kw)
+
+    for _ in range(max(warmup, 1) + 50):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    flop = 3 * c.flops_per_pass
+    print(json.dumps({"metric": "conv1d block with training-mode BatchNorm, fwd+bwd TFLOP/s (bf16), C=512 K=17 T=800",
+                      "value": round(flop / ms / 1e9, 1), "unit": "TFLOP/s", "ms_per_step": round(ms, 4), "steps": steps,
+                      "frac_of_bf16_mfma_peak": round(flop / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                      "config": {"workload": describe(c) + ", batch statistics"}}), flush=True)
+
+
 def decoder_report(steps, warmup, with_cpu):
     """Decoder tail (1x1 convolution to 29 classes + log-softmax) at the encoder's output size; an
     HBM-bound step: one JSON line with the achieved bandwidth on its algorithmic bytes.  `--decoder` only."""
@@ -255,6 +298,8 @@ def main():
                     help="instead of the headline: the chained 64-layer stack step (one extra JSON line)")
     ap.add_argument("--stack-layers", action="store_true",
                     help="instead of the headline: every layer shape of the 64-layer stack timed on its own")
+    ap.add_argument("--bn", action="store_true",
+                    help="instead of the headline: the same block with training-mode BatchNorm (batch statistics)")
     ap.add_argument("--decoder", action="store_true",
                     help="instead of the headline: the decoder tail (1x1 conv + log-softmax), an HBM-bound step")
     ap.add_argument("--workload", default="b3", choices=sorted(WORKLOADS),
@@ -277,6 +322,9 @@ def main():
         return
     if args.stack_layers:
         stack_layers_report()
+        return
+    if args.bn:
+        bn_report(args.steps, args.warmup)
         return
     if args.decoder:
         decoder_report(args.steps, args.warmup, not args.no_cpu_baseline)

@@ -69,7 +69,7 @@ enum {
                             sub-block's and the residual projection's) without a pass of its own */
 };
 
-enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2, NM_OP_BWD = 3 };
+enum { NM_OP_FWD = 0, NM_OP_BWD_DATA = 1, NM_OP_BWD_WEIGHT = 2, NM_OP_BWD = 3, NM_OP_BN_FWD = 4, NM_OP_BN_BWD = 5 };
 
 /* T_out of the convolution (formula above), or NM_ERR_BAD_ARG (<0) if any argument is
  * out of range or no output position exists.  Host only. */
@@ -134,6 +134,31 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
                   const void *x, const void *dy, const void *y, const float *scale, const void *w,
                   void *dx, void *dres, float *dw, unsigned flags, int dtype,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The block with training-mode BatchNorm (paper Section 4.1.1 trains the encoder with the `train` action;
+ * Section 3: a trainable module computes its outputs and its gradient flows).  Instead of a given affine the
+ * normalisation uses the statistics of the batch, taken per output channel over batch and time
+ * (N = B*T_out elements):
+ *   z = conv(x, w), stored in `dtype`;  mean[c] = (1/N) sum z;  var[c] = (1/N) sum (z-mean)^2 (biased);
+ *   invstd[c] = 1/sqrt(var[c]+eps);  zhat = (z-mean)*invstd;  y = relu?( gamma[c]*zhat + beta[c] + residual ).
+ * The statistics and y are computed from the stored z (in NM_BF16 mode: the rounded values).
+ *   nm_conv1d_bn_fwd:  x, w, residual (or NULL) in; gamma, beta [Cout] float in (NULL: 1 / 0);
+ *                      z, y [B][Cout][T_out] out (dtype); mean, invstd [Cout] float out (saved for backward).
+ *   nm_conv1d_bn_bwd:  x, w, gamma, the saved z, y (y required iff NM_RELU), mean, invstd and dy in;
+ *                      g = dy*[y>0];  dres = g (or NULL);  dbeta[c] = sum g;  dgamma[c] = sum g*zhat (NULL: not wanted);
+ *                      dz = gamma*invstd*( g - dbeta/N - zhat*dgamma/N ), rounded to dtype, is then contracted:
+ *                      dx [B][Cin][T] and dw [Cout][Cin][K] float as by nm_conv1d_bwd on dz.
+ *                      NM_ACCUM_DW adds into dw, dgamma and dbeta; NM_ACCUM_DX into dx.
+ * Workspace: nm_conv1d_workspace_bytes(NM_OP_BN_FWD / NM_OP_BN_BWD, ...).  Sums are deterministic.  Other
+ * conventions and errors as for the calls above. */
+int nm_conv1d_bn_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                     const void *w, const float *gamma, const float *beta, float eps, const void *residual, void *z,
+                     void *y, float *mean, float *invstd, unsigned flags, int dtype, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
+int nm_conv1d_bn_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                     const void *w, const float *gamma, const void *z, const void *y, const float *mean,
+                     const float *invstd, const void *dy, void *dx, void *dres, float *dw, float *dgamma, float *dbeta,
+                     unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* The three passes on a padded batch (paper Section 4.1.1: the encoder takes the length of every
  * utterance next to the padded batch).  lengths [B] int32 (device): samples of batch item b at

@@ -19,11 +19,11 @@ NM_OK, NM_ERR_BAD_ARG, NM_ERR_UNSUPPORTED, NM_ERR_WORKSPACE, NM_ERR_DEVICE, NM_E
 NM_STATIC_SCRATCH_BYTES = 32 << 20
 NM_BF16, NM_F32 = 0, 1
 NM_RELU, NM_ACCUM_DW, NM_FORCE_DIRECT, NM_ACCUM_DX = 1, 2, 4, 8
-NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD = 0, 1, 2, 3
+NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD, NM_OP_BN_FWD, NM_OP_BN_BWD = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
-           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_weight_masked.restype = i
         L.nm_conv1d_bwd.argtypes = [i] * 8 + [vp] * 8 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd.restype = i
+        L.nm_conv1d_bn_fwd.argtypes = [i] * 8 + [vp] * 4 + [ctypes.c_float] + [vp] * 5 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bn_fwd.restype = i
+        L.nm_conv1d_bn_bwd.argtypes = [i] * 8 + [vp] * 13 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bn_bwd.restype = i
         L.nm_decoder_logsoftmax_fwd.argtypes = [i] * 4 + [vp] * 4 + [u, i, vp]
         L.nm_decoder_logsoftmax_fwd.restype = i
         L.nm_conv1d_time_next_main_kernel.argtypes = [vp, vp]
@@ -280,6 +284,67 @@ def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, 
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_bwd")
     return dx, dres, dw
+
+
+def nm_conv1d_bn_fwd(x, w, gamma=None, beta=None, residual=None, *, eps=1e-3, stride=1, dilation=1, pad=0, relu=False,
+                     force_direct=False, z=None, y=None, mean=None, invstd=None, workspace=None, stream=None):
+    """Block forward with training-mode BatchNorm; returns (z, y, mean, invstd)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = nm_conv1d_out_len(T, K, stride, dilation, pad)
+    if To <= 0:
+        raise NmError(NM_ERR_BAD_ARG, "nm_conv1d_bn_fwd")
+    code = _dtype_code(x)
+    z = torch.empty((B, Cout, To), dtype=x.dtype, device=x.device) if z is None else z
+    y = torch.empty((B, Cout, To), dtype=x.dtype, device=x.device) if y is None else y
+    mean = torch.empty((Cout,), dtype=torch.float32, device=x.device) if mean is None else mean
+    invstd = torch.empty((Cout,), dtype=torch.float32, device=x.device) if invstd is None else invstd
+    flags = (NM_RELU if relu else 0) | (NM_FORCE_DIRECT if force_direct else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_BN_FWD, dims, code, flags, workspace, x.device)
+    st = lib().nm_conv1d_bn_fwd(
+        *dims, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"), _ptr(gamma, torch.float32, (Cout,), "gamma"),
+        _ptr(beta, torch.float32, (Cout,), "beta"), float(eps), _ptr(residual, x.dtype, (B, Cout, To), "residual"),
+        _ptr(z, x.dtype, (B, Cout, To), "z"), _ptr(y, x.dtype, (B, Cout, To), "y"), _ptr(mean, torch.float32, (Cout,), "mean"),
+        _ptr(invstd, torch.float32, (Cout,), "invstd"), flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bn_fwd")
+    return z, y, mean, invstd
+
+
+def nm_conv1d_bn_bwd(x, w, gamma, z, y, mean, invstd, dy, *, stride=1, dilation=1, pad=0, relu=False, want_dres=False,
+                     force_direct=False, accumulate=False, accumulate_dx=False, dx=None, dres=None, dw=None, dgamma=None,
+                     dbeta=None, workspace=None, stream=None):
+    """Backward of nm_conv1d_bn_fwd; returns (dx, dres, dw, dgamma, dbeta)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = dy.shape[2]
+    code = _dtype_code(x)
+    if (accumulate and (dw is None or dgamma is None or dbeta is None)) or (accumulate_dx and dx is None):
+        raise ValueError("accumulation needs existing output tensors")
+    dx = torch.empty((B, Cin, T), dtype=x.dtype, device=x.device) if dx is None else dx
+    if dres is None and want_dres:
+        dres = torch.empty_like(dy)
+    dw = torch.empty((Cout, Cin, K), dtype=torch.float32, device=x.device) if dw is None else dw
+    dgamma = torch.empty((Cout,), dtype=torch.float32, device=x.device) if dgamma is None else dgamma
+    dbeta = torch.empty((Cout,), dtype=torch.float32, device=x.device) if dbeta is None else dbeta
+    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0) | (NM_FORCE_DIRECT if force_direct else 0) | \
+        (NM_ACCUM_DX if accumulate_dx else 0)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    ws, ws_ptr, ws_bytes = _workspace(NM_OP_BN_BWD, dims, code, flags, workspace, x.device)
+    act = (B, Cout, To)
+    st = lib().nm_conv1d_bn_bwd(
+        *dims, _ptr(x, name="x"), _ptr(w, x.dtype, (Cout, Cin, K), "w"), _ptr(gamma, torch.float32, (Cout,), "gamma"),
+        _ptr(z, x.dtype, act, "z"), _ptr(y, x.dtype, act, "y"), _ptr(mean, torch.float32, (Cout,), "mean"),
+        _ptr(invstd, torch.float32, (Cout,), "invstd"), _ptr(dy, x.dtype, act, "dy"), _ptr(dx, x.dtype, (B, Cin, T), "dx"),
+        _ptr(dres, x.dtype, act, "dres"), _ptr(dw, torch.float32, (Cout, Cin, K), "dw"),
+        _ptr(dgamma, torch.float32, (Cout,), "dgamma"), _ptr(dbeta, torch.float32, (Cout,), "dbeta"),
+        flags, code, ws_ptr, ws_bytes, _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bn_bwd")
+    return dx, dres, dw, dgamma, dbeta
 
 
 def nm_decoder_logsoftmax_fwd(x, w, bias=None, logp=None, *, force_direct=False, stream=None):

@@ -233,4 +233,13 @@ hipError_t launch_bwd_prepare(const Geom &g, const void *dy, const void *y, cons
 hipError_t launch_mfma_dgrad_prepared(const Geom &g, const void *g_plain, void *dx, bool accumulate, void *ws,
                                       hipStream_t s);
 
+// ---- training-mode BatchNorm passes (bn_train.hip) ---------------------------------------------
+size_t bn_fwd_scratch_bytes(int B, int C);
+size_t bn_bwd_scratch_bytes(int B, int C);
+hipError_t launch_bn_fwd(int B, int C, int T, bool is_bf16, const void *z, const float *gamma, const float *beta, float eps,
+                         const void *residual, bool relu, void *y, float *mean, float *invstd, void *scratch, hipStream_t s);
+hipError_t launch_bn_bwd(int B, int C, int T, bool is_bf16, const void *dy, const void *y, const void *z, const float *gamma,
+                         const float *mean, const float *invstd, bool relu, void *dz, void *dres, float *dgamma,
+                         float *dbeta, bool accumulate, void *scratch, hipStream_t s);
+
 }  // namespace nm

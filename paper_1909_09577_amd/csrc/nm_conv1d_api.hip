@@ -198,9 +198,18 @@ size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K,
                                  int pad, int dtype, unsigned flags)
 {
     Geom g;
-    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT && op != NM_OP_BWD) return 0;
+    if (op != NM_OP_FWD && op != NM_OP_BWD_DATA && op != NM_OP_BWD_WEIGHT && op != NM_OP_BWD && op != NM_OP_BN_FWD &&
+        op != NM_OP_BN_BWD)
+        return 0;
     if (check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g) != NM_OK)
         return 0;
+    // the BatchNorm calls keep their own scratch (and, backward, the dz tensor) in front of the inner call's workspace
+    if (op == NM_OP_BN_FWD)
+        return bn_fwd_scratch_bytes(g.B, g.Cout) +
+               nm_conv1d_workspace_bytes(NM_OP_FWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
+    if (op == NM_OP_BN_BWD)
+        return bn_bwd_scratch_bytes(g.B, g.Cout) + align_up((size_t)g.B * g.Cout * g.To * elt(dtype), kWsAlign) +
+               nm_conv1d_workspace_bytes(NM_OP_BWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
     // The query sees neither the scale pointer nor the alignment of the tensors (misaligned
     // tensors take the plain kernels); it sizes for the larger of the cases.
     auto one = [&](int o) {
@@ -489,6 +498,72 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
     if (err != hipSuccess) return NM_ERR_DEVICE;
     t_current_op = NM_OP_BWD_WEIGHT;
     return dev(launch_mfma_wgrad_prepared(g, x, scale, dw, (flags & NM_ACCUM_DW) != 0, ws_w, s));
+}
+
+int nm_conv1d_bn_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                     const void *w, const float *gamma, const float *beta, float eps, const void *residual, void *z,
+                     void *y, float *mean, float *invstd, unsigned flags, int dtype, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, NM_RELU | NM_FORCE_DIRECT, &g);
+    if (st == NM_OK && (!x || !w || !z || !y || !mean || !invstd || !(eps >= 0.f))) st = NM_ERR_BAD_ARG;
+    const size_t e = st == NM_OK ? elt(dtype) : 0;
+    const size_t ny = st == NM_OK ? (size_t)g.B * g.Cout * g.To * e : 0;
+    if (st == NM_OK && (overlap(y, ny, z, ny) || overlap(y, ny, residual, ny) || overlap(z, ny, residual, ny) ||
+                        overlap(y, ny, x, (size_t)g.B * g.Cin * g.T * e) || overlap(y, ny, w, (size_t)g.Cout * g.Cin * g.K * e)))
+        st = NM_ERR_BAD_ARG;
+    const size_t need =
+        st == NM_OK ? nm_conv1d_workspace_bytes(NM_OP_BN_FWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags) : 0;
+    if (st == NM_OK) st = check_workspace(workspace, workspace_bytes, need);
+    if (st == NM_OK && (overlap(y, ny, workspace, need) || overlap(z, ny, workspace, need))) st = NM_ERR_BAD_ARG;
+    if (st != NM_OK) {
+        DisarmOnExit disarm;
+        return st;
+    }
+    const size_t own = bn_fwd_scratch_bytes(g.B, g.Cout);
+    // the convolution itself: z = conv(x, w), no epilogue (its own argument checks apply once more)
+    st = nm_conv1d_block_fwd(B, Cin, Cout, T, K, stride, dilation, pad, x, w, nullptr, nullptr, nullptr, z,
+                             flags & NM_FORCE_DIRECT, dtype, (unsigned char *)workspace + own, workspace_bytes - own, hip_stream);
+    if (st != NM_OK) return st;
+    return dev(launch_bn_fwd(g.B, g.Cout, g.To, dtype == NM_BF16, z, gamma, beta, eps, residual, (flags & NM_RELU) != 0, y, mean,
+                             invstd, workspace, (hipStream_t)hip_stream));
+}
+
+int nm_conv1d_bn_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                     const void *w, const float *gamma, const void *z, const void *y, const float *mean,
+                     const float *invstd, const void *dy, void *dx, void *dres, float *dw, float *dgamma, float *dbeta,
+                     unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Geom g;
+    int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
+    if (st == NM_OK && (!x || !w || !z || !mean || !invstd || !dy || !dx || !dw)) st = NM_ERR_BAD_ARG;
+    if (st == NM_OK && (flags & NM_RELU) && !y) st = NM_ERR_BAD_ARG;
+    const size_t e = st == NM_OK ? elt(dtype) : 0;
+    const size_t ny = st == NM_OK ? (size_t)g.B * g.Cout * g.To * e : 0;
+    if (st == NM_OK && (overlap(dres, ny, dy, ny) || overlap(dres, ny, y, ny) || overlap(dres, ny, z, ny))) st = NM_ERR_BAD_ARG;
+    const size_t need =
+        st == NM_OK ? nm_conv1d_workspace_bytes(NM_OP_BN_BWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags) : 0;
+    if (st == NM_OK) st = check_workspace(workspace, workspace_bytes, need);
+    if (st == NM_OK && overlap(dres, ny, workspace, need)) st = NM_ERR_BAD_ARG;
+    if (st != NM_OK) {
+        DisarmOnExit disarm;
+        return st;
+    }
+    const size_t own = bn_bwd_scratch_bytes(g.B, g.Cout);
+    void *dz = (unsigned char *)workspace + own;
+    const size_t used = own + align_up(ny, kWsAlign);
+    const bool relu = (flags & NM_RELU) != 0;
+    hipError_t err = launch_bn_bwd(g.B, g.Cout, g.To, dtype == NM_BF16, dy, y, z, gamma, mean, invstd, relu, dz, dres, dgamma,
+                                   dbeta, (flags & NM_ACCUM_DW) != 0, workspace, (hipStream_t)hip_stream);
+    if (err != hipSuccess) {
+        DisarmOnExit disarm;
+        return NM_ERR_DEVICE;
+    }
+    // both convolution gradients of the corrected dz (no mask, no scale left to apply)
+    return nm_conv1d_bwd(B, Cin, Cout, T, K, stride, dilation, pad, x, dz, nullptr, nullptr, w, dx, nullptr, dw,
+                         flags & (NM_ACCUM_DW | NM_ACCUM_DX | NM_FORCE_DIRECT), dtype, (unsigned char *)workspace + used,
+                         workspace_bytes - used, hip_stream);
 }
 
 }  // extern "C"

@@ -194,3 +194,33 @@ def test_declared_output_lengths_of_the_workloads_are_the_oracles():
     for c in cfgs:
         assert c.T_out == orc.out_len(c.T, c.K, c.stride, c.dilation, c.pad), c.name
         assert c.T_out == nm.nm_conv1d_out_len(c.T, c.K, c.stride, c.dilation, c.pad), c.name
+
+
+# ---- the block with training-mode BatchNorm -----------------------------------------------------------
+def test_bn_entry_points_report_argument_errors_before_any_device_call():
+    L_ = nm.lib()
+    d = dict(GOOD)
+    dims = (d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"])
+    eps = ctypes.c_float(1e-3)
+
+    def bn_fwd(x=FAKE2, z=FAKE3, y=FAKE4, mean=FAKE5, dims=dims, flags=0, eps=eps, ws=None, ws_bytes=0):
+        return L_.nm_conv1d_bn_fwd(*dims, x, FAKE, None, None, eps, None, z, y, mean, FAKE, flags, 0, ws, ws_bytes, None)
+
+    assert bn_fwd(x=None) == nm.NM_ERR_BAD_ARG
+    assert bn_fwd(mean=None) == nm.NM_ERR_BAD_ARG
+    assert bn_fwd(eps=ctypes.c_float(-1.0)) == nm.NM_ERR_BAD_ARG
+    assert bn_fwd(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG
+    assert bn_fwd(dims=(0,) + dims[1:]) == nm.NM_ERR_BAD_ARG
+    assert bn_fwd() == nm.NM_ERR_WORKSPACE  # it always needs scratch for the statistics
+    need = nm.nm_conv1d_workspace_bytes(nm.NM_OP_BN_FWD, *dims)
+    assert need >= 3 * 8 * d["B"] * d["Cout"] and need % 256 == 0
+    assert nm.nm_conv1d_workspace_bytes(nm.NM_OP_BN_BWD, *dims) > nm.nm_conv1d_workspace_bytes(nm.NM_OP_BWD, *dims)
+
+    def bn_bwd(x=FAKE2, y=FAKE3, dy=FAKE4, dx=FAKE5, flags=nm.NM_RELU):
+        return L_.nm_conv1d_bn_bwd(*dims, x, FAKE, None, FAKE, y, FAKE, FAKE, dy, dx, None, FAKE, None, None, flags, 0,
+                                   None, 0, None)
+
+    assert bn_bwd(x=None) == nm.NM_ERR_BAD_ARG
+    assert bn_bwd(y=None) == nm.NM_ERR_BAD_ARG      # NM_RELU needs the saved output
+    assert bn_bwd(dx=None) == nm.NM_ERR_BAD_ARG
+    assert bn_bwd() == nm.NM_ERR_WORKSPACE
