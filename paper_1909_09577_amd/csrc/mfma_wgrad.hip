@@ -1191,7 +1191,9 @@ hipError_t launch_kt(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 
 // the reduction's LDS tile is [64][K+1] floats: the default 64 KiB limit bounds the tap count
 constexpr int kMaxReduceTaps = 64 * 1024 / (64 * (int)sizeof(float)) - 1;  // 255
-hipError_t launch_reduce(const Geom &g, const float *part, float *dw, const float *scale, int S, bool accumulate,
+}  // namespace
+
+hipError_t launch_wgrad_reduce(const Geom &g, const float *part, float *dw, const float *scale, int S, bool accumulate,
                          hipStream_t s)
 {
     if (g.Cin % 4 == 0 && ((uintptr_t)dw % 16) == 0 && (size_t)kReduce4Ci * (g.K + 1) * sizeof(float) <= 64 * 1024) {
@@ -1206,12 +1208,19 @@ hipError_t launch_reduce(const Geom &g, const float *part, float *dw, const floa
     return hipGetLastError();
 }
 
-}  // namespace
-
 bool mfma_wgrad_supported(const Geom &g) { return g.K <= kMaxReduceTaps && (fast_ok(g) || make_wplan(g).ok); }
 
 size_t mfma_wgrad_workspace(const Geom &g, bool need_dz)
 {
+    // (sized without looking at lengths: a call with lengths never takes the pointwise kernel)
+    Geom g0 = g;
+    g0.len = nullptr;
+    if (wgrad_k1_supported(g0)) {
+        const FastPlan f = make_fast_plan(g);
+        const size_t fast = part_bytes(g, f.S) + dzf_bytes(g, f);
+        const size_t k1 = wgrad_k1_part_bytes(g0) + dz_buf_bytes(g);
+        return fast > k1 ? fast : k1;
+    }
     if (fast_ok(g)) {
         const FastPlan f = make_fast_plan(g);
         return part_bytes(g, f.S) + dzf_bytes(g, f);
@@ -1284,12 +1293,23 @@ hipError_t launch_mfma_wgrad_prepared(const Geom &g, const void *x, const float 
         }
     }
     if (e != hipSuccess) return e;
-    return launch_reduce(g, part, dw, scale, f.S, accumulate, s);
+    return launch_wgrad_reduce(g, part, dw, scale, f.S, accumulate, s);
 }
 
 hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const void *y, const float *scale,
                              float *dw, bool relu, bool accumulate, void *ws, hipStream_t s)
 {
+    if (wgrad_k1_supported(g)) {
+        // pointwise layers: a GEMM over rows as they lie in memory; g = dy*[y>0] only has to be formed with a ReLU
+        const void *gplain = dy;
+        if (relu) {
+            void *gbuf = (unsigned char *)ws + wgrad_k1_part_bytes(g);
+            hipError_t e = launch_epilogue_bwd_vec8(g, dy, y, nullptr, relu, gbuf, nullptr, s);
+            if (e != hipSuccess) return e;
+            gplain = gbuf;
+        }
+        return launch_wgrad_k1(g, x, gplain, scale, dw, accumulate, ws, s);
+    }
     if (fast_ok(g)) {
         const FastPlan f = make_fast_plan(g);
         u32x4 *dzf = (u32x4 *)((unsigned char *)ws + part_bytes(g, f.S));
@@ -1333,7 +1353,7 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
     default: e = launch_kt<6>(p, w.lds, grid, s); break;
     }
     if (e != hipSuccess) return e;
-    return launch_reduce(g, part, dw, scale, w.S, accumulate, s);
+    return launch_wgrad_reduce(g, part, dw, scale, w.S, accumulate, s);
 }
 
 }  // namespace nm

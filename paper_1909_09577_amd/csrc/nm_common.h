@@ -208,6 +208,15 @@ hipError_t launch_mfma_wgrad(const Geom &g, const void *x, const void *dy, const
                              const float *scale, float *dw, bool relu, bool accumulate, void *ws,
                              hipStream_t s);
 
+// dw[co][ci][k] = (accumulate ? dw : 0) + scale[co] * sum_s part[s][k][co][ci] (scale NULL: 1), fixed order
+hipError_t launch_wgrad_reduce(const Geom &g, const float *part, float *dw, const float *scale, int S, bool accumulate,
+                               hipStream_t s);
+// pointwise (K = 1) weight gradient as a GEMM over plain rows (mfma_wgrad_k1.hip); never with lengths
+bool wgrad_k1_supported(const Geom &g);
+size_t wgrad_k1_part_bytes(const Geom &g);
+hipError_t launch_wgrad_k1(const Geom &g, const void *x, const void *gplain, const float *scale, float *dw, bool accumulate,
+                           void *ws, hipStream_t s);
+
 // ---- fused backward: one pass over dy / y feeds both gradients --------------------------------
 // The stride-1 weight-gradient kernels read g = dy*[y>0] in MFMA fragment order
 // [B][ncm = 2*ceil(Cout/64)][nst][64 lanes][8]: lane l of block (b, cm, st) holds channel cm*32 + l%32,

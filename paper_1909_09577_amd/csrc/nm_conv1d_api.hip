@@ -457,7 +457,7 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
     }
     const bool relu = (flags & NM_RELU) != 0;
     const bool fused = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) &&
-                       g.stride == 1 && mfma_wgrad_fast_supported(g) && aligned16(x) && aligned16(dy) &&
+                       g.stride == 1 && mfma_wgrad_fast_supported(g) && !wgrad_k1_supported(g) && aligned16(x) && aligned16(dy) &&
                        aligned16(dx) && (!relu || aligned16(y)) && (!dres || aligned16(dres));
     const size_t ws_data = mfma_dgrad_workspace(g);  // only meaningful when fused
     if (!fused) {

@@ -78,6 +78,11 @@ MEDIUM = [
     L("m_k13", 2, 96, 64, 320, 13, pad=6, residual=True),
     L("m_k21", 1, 160, 72, 328, 21, pad=10),
     L("m_k25", 1, 64, 128, 336, 25, pad=12, residual=True),
+    # pointwise layers on the K=1 GEMM kernels: ragged channel tiles, a length that is no multiple of the 80-step unit,
+    # with and without the mask pass
+    L("m_k1_ragged", 3, 136, 200, 336, 1, residual=True),
+    L("m_k1_proj", 5, 320, 264, 88, 1, relu=False),
+    L("m_k1_tiles", 2, 384, 520, 400, 1),
 ]
 
 
