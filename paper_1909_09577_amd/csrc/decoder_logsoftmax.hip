@@ -45,9 +45,15 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// BLOCK == false: the decoder tail (bias, log-softmax, float32 out).  BLOCK == true: the same load stream as the
+// forward pass of a pointwise conv1d sub-block with at most 32 output channels (the 1024 -> 29 projection in
+// front of the decoder): `bias` is the shift, and the epilogue is scale, shift, residual, ReLU, bf16 out.
+template <bool BLOCK>
 __global__ __launch_bounds__(256) void decoder_mfma_kernel(int B, int Cin, int Ncls, int T, const bf16_t *__restrict__ x,
                                                            const bf16_t *__restrict__ w, const float *__restrict__ bias,
-                                                           float *__restrict__ logp)
+                                                           float *__restrict__ logp, const float *__restrict__ scale,
+                                                           const bf16_t *__restrict__ res, int relu,
+                                                           bf16_t *__restrict__ y)
 {
     __shared__ __align__(16) unsigned char smem[4 * 2 * kStepBytes];
     const int lane = threadIdx.x & 63;
@@ -117,9 +123,27 @@ __global__ __launch_bounds__(256) void decoder_mfma_kernel(int B, int Cin, int N
         }
     }
 
-    // ---- log-softmax over the classes of this lane's frame.  Register r of the accumulator is class
-    // 8*(r/4) + 4*(lane/32) + r%4, frame lane%32: a frame's classes sit in two lanes, 32 apart.
+    // Register r of the accumulator is class 8*(r/4) + 4*(lane/32) + r%4, frame lane%32.
     const int t = t0 + (lane & 31);
+    if constexpr (BLOCK) {
+        if (t < T) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int c = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (c < Ncls) {
+                    const size_t o = ((size_t)b * Ncls + c) * T + t;
+                    float v = acc[r];
+                    if (scale) v *= scale[c];
+                    if (bias) v += bias[c];
+                    if (res) v += bf16_to_f32(res[o]);
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    y[o] = f32_to_bf16(v);
+                }
+            }
+        }
+        return;
+    }
+    // ---- log-softmax over the classes of this lane's frame: a frame's classes sit in two lanes, 32 apart.
     float z[16];
     float m = -INFINITY;
 #pragma unroll
@@ -177,6 +201,24 @@ __global__ __launch_bounds__(256) void decoder_plain_kernel(int B, int Cin, int 
 }
 
 }  // namespace
+
+// Forward of a pointwise sub-block with few output channels on the decoder's load stream.
+bool skinny_fwd_supported(const Geom &g)
+{
+    return g.K == 1 && g.stride == 1 && g.pad == 0 && g.To == g.T && g.len == nullptr && g.Cout <= 32 && g.Cin % 16 == 0 &&
+           g.T % 8 == 0 && (size_t)g.B * g.Cin * g.T * 2 <= ((size_t)1 << 30);
+}
+
+hipError_t launch_skinny_fwd(const Geom &g, const void *x, const void *w, const float *scale, const float *shift,
+                             const void *res, void *y, bool relu, hipStream_t s)
+{
+    dim3 grid((g.T + 4 * kFramesPerWave - 1) / (4 * kFramesPerWave), g.B);
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL(decoder_mfma_kernel<true>, grid, dim3(256), 0, s, g.B, g.Cin, g.Cout, g.T, (const bf16_t *)x,
+                       (const bf16_t *)w, shift, (float *)nullptr, scale, (const bf16_t *)res, relu ? 1 : 0, (bf16_t *)y);
+    return hipGetLastError();
+}
+
 }  // namespace nm
 
 using namespace nm;
@@ -197,8 +239,8 @@ extern "C" int nm_decoder_logsoftmax_fwd(int B, int Cin, int Ncls, int T, const 
                       (size_t)B * Cin * T * 2 <= ((size_t)1 << 30);
     if (fast) {
         dim3 grid((T + 4 * kFramesPerWave - 1) / (4 * kFramesPerWave), B);
-        hipLaunchKernelGGL(decoder_mfma_kernel, grid, dim3(256), 0, s, B, Cin, Ncls, T, (const bf16_t *)x, (const bf16_t *)w,
-                           bias, logp);
+        hipLaunchKernelGGL(decoder_mfma_kernel<false>, grid, dim3(256), 0, s, B, Cin, Ncls, T, (const bf16_t *)x,
+                           (const bf16_t *)w, bias, logp, (const float *)nullptr, (const bf16_t *)nullptr, 0, (bf16_t *)nullptr);
     } else {
         dim3 grid((T + 255) / 256, B);
         if (dtype == NM_BF16)

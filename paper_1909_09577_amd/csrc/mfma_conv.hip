@@ -1346,6 +1346,8 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
 {
     const Plan pl = make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil);
     if (!pl.ok || !mfma_fwd_supported(g)) return hipErrorInvalidValue;
+    // a pointwise layer with a handful of output channels is a stream over x: no packing, no tiles
+    if (skinny_fwd_supported(g) && ((uintptr_t)w % 16) == 0) return launch_skinny_fwd(g, x, w, scale, shift, res, y, relu, s);
     hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, nullptr, s);
     if (e != hipSuccess) return e;
     ConvGemmParams p = {};

@@ -196,6 +196,11 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
                            const float *shift, const void *res, void *y, bool relu, void *ws,
                            hipStream_t s);
 
+// pointwise forward with at most 32 output channels: bound by reading x once (decoder_logsoftmax.hip)
+bool skinny_fwd_supported(const Geom &g);
+hipError_t launch_skinny_fwd(const Geom &g, const void *x, const void *w, const float *scale, const float *shift,
+                             const void *res, void *y, bool relu, hipStream_t s);
+
 bool mfma_dgrad_supported(const Geom &g);
 size_t mfma_dgrad_workspace(const Geom &g);
 hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale,

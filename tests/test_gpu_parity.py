@@ -83,6 +83,10 @@ MEDIUM = [
     L("m_k1_ragged", 3, 136, 200, 336, 1, residual=True),
     L("m_k1_proj", 5, 320, 264, 88, 1, relu=False),
     L("m_k1_tiles", 2, 384, 520, 400, 1),
+    # pointwise layers with at most 32 output channels: the forward pass streams x once (decoder-style kernel)
+    L("m_k1_skinny", 3, 96, 29, 328, 1, residual=True),
+    L("m_k1_skinny32", 2, 160, 32, 136, 1, relu=False),
+    L("m_k1_skinny5", 2, 64, 5, 264, 1),
 ]
 
 
