@@ -168,6 +168,7 @@ int nm_conv1d_bn_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dil
  *                       the valid length behind it is nm_conv1d_out_len(lengths[b], ...)).
  *   bwd_weight_masked:  dw from x with its padding read as zero.
  *   bwd_data_masked:    dx is zero on the padding.
+ *   bwd_masked:         both of these in one call.
  * All other arguments, the workspace size and the error behaviour are those of the unmasked calls;
  * lengths == NULL is NM_ERR_BAD_ARG. */
 int nm_conv1d_block_fwd_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
@@ -182,6 +183,11 @@ int nm_conv1d_bwd_weight_masked(int B, int Cin, int Cout, int T, int K, int stri
                                 const int *lengths, const void *x, const void *dy, const void *y,
                                 const float *scale, float *dw, unsigned flags, int dtype,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+/* nm_conv1d_bwd on a padded batch: the results of bwd_data_masked and bwd_weight_masked, bit for bit, from one call. */
+int nm_conv1d_bwd_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                         const void *x, const void *dy, const void *y, const float *scale, const void *w, void *dx,
+                         void *dres, float *dw, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
 
 /* Decoder tail (paper Section 4.1.1: the CTC decoder module turns the encoder output into per-frame
  * log-probabilities over the vocabulary): a 1x1 convolution to Ncls classes followed by a log-softmax

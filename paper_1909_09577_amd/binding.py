@@ -23,7 +23,7 @@ NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD, NM_OP_BN_FWD, NM_OP_BN_B
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
-           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_bwd_masked", "nm_conv1d_time_next_main_kernel")
 
 _lib = None
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_weight_masked.restype = i
         L.nm_conv1d_bwd.argtypes = [i] * 8 + [vp] * 8 + [u, i, vp, sz, vp]
         L.nm_conv1d_bwd.restype = i
+        L.nm_conv1d_bwd_masked.argtypes = [i] * 8 + [vp] * 9 + [u, i, vp, sz, vp]
+        L.nm_conv1d_bwd_masked.restype = i
         L.nm_conv1d_bn_fwd.argtypes = [i] * 8 + [vp] * 4 + [ctypes.c_float] + [vp] * 5 + [u, i, vp, sz, vp]
         L.nm_conv1d_bn_fwd.restype = i
         L.nm_conv1d_bn_bwd.argtypes = [i] * 8 + [vp] * 13 + [u, i, vp, sz, vp]
@@ -255,8 +257,8 @@ def nm_conv1d_bwd_weight(x, dy, K, y=None, scale=None, dw=None, *, stride=1, dil
 
 def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, stride=1, dilation=1, pad=0,
                   relu=False, want_dres=False, accumulate=False, force_direct=False, workspace=None, stream=None,
-                  accumulate_dx=False):
-    """Both gradients in one call; returns (dx, dres, dw)."""
+                  accumulate_dx=False, lengths=None):
+    """Both gradients in one call; returns (dx, dres, dw).  lengths (int32 [B], optional): padded batch."""
     torch = _torch()
     B, Cin, T = x.shape
     Cout, _, K = w.shape
@@ -276,8 +278,10 @@ def nm_conv1d_bwd(x, dy, w, y=None, scale=None, dx=None, dres=None, dw=None, *, 
         (NM_ACCUM_DX if accumulate_dx else 0)
     dims = (B, Cin, Cout, T, K, stride, dilation, pad)
     ws, ws_ptr, ws_bytes = _workspace(NM_OP_BWD, dims, code, flags, workspace, x.device)
-    st = lib().nm_conv1d_bwd(
-        *dims, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
+    fn, extra = (lib().nm_conv1d_bwd, ()) if lengths is None else (
+        lib().nm_conv1d_bwd_masked, (_ptr(lengths, torch.int32, (B,), "lengths"),))
+    st = fn(
+        *dims, *extra, _ptr(x, name="x"), _ptr(dy, x.dtype, (B, Cout, To), "dy"), _ptr(y, x.dtype, (B, Cout, To), "y"),
         _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(w, x.dtype, (Cout, Cin, K), "w"),
         _ptr(dx, x.dtype, (B, Cin, T), "dx"), _ptr(dres, x.dtype, (B, Cout, To), "dres"),
         _ptr(dw, torch.float32, (Cout, Cin, K), "dw"), flags, code, ws_ptr, ws_bytes, _stream(stream))

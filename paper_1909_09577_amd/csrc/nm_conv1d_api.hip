@@ -440,9 +440,9 @@ int nm_conv1d_bwd_weight_masked(int B, int Cin, int Cout, int T, int K, int stri
                            workspace_bytes, hip_stream);
 }
 
-int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
-                  const void *dy, const void *y, const float *scale, const void *w, void *dx, void *dres, float *dw,
-                  unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+static int bwd_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                    const void *x, const void *dy, const void *y, const float *scale, const void *w, void *dx, void *dres,
+                    float *dw, unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags, kAllFlags, &g);
@@ -456,7 +456,9 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
         return st;
     }
     const bool relu = (flags & NM_RELU) != 0;
-    const bool fused = use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) &&
+    g.len = lengths;
+    const bool fused = !(lengths && (flags & NM_ACCUM_DX)) &&
+                       use_mfma(NM_OP_BWD_DATA, g, dtype, flags) && use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) &&
                        g.stride == 1 && mfma_wgrad_fast_supported(g) && !wgrad_k1_supported(g) && aligned16(x) && aligned16(dy) &&
                        aligned16(dx) && (!relu || aligned16(y)) && (!dres || aligned16(dres));
     const size_t ws_data = mfma_dgrad_workspace(g);  // only meaningful when fused
@@ -466,15 +468,15 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
         // a timer armed for the weight-gradient kernel outlives the first of the two calls
         hipEvent_t keep_start = t_start_event, keep_stop = t_stop_event;
         const bool keep = t_timed_op == NM_OP_BWD_WEIGHT;
-        st = nm_conv1d_bwd_data(B, Cin, Cout, T, K, stride, dilation, pad, dy, y, scale, w, dx, dres, flags & ~NM_ACCUM_DW,
-                                dtype, workspace, w1, hip_stream);
+        st = bwd_data_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, dy, y, scale, w, dx, dres, flags & ~NM_ACCUM_DW,
+                           dtype, workspace, w1, hip_stream);
         if (st != NM_OK) return st;
         if (keep) {
             t_start_event = keep_start;
             t_stop_event = keep_stop;
         }
-        return nm_conv1d_bwd_weight(B, Cin, Cout, T, K, stride, dilation, pad, x, dy, y, scale, dw, flags & ~NM_ACCUM_DX,
-                                    dtype, workspace, workspace_bytes, hip_stream);
+        return bwd_weight_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, x, dy, y, scale, dw, flags & ~NM_ACCUM_DX,
+                               dtype, workspace, workspace_bytes, hip_stream);
     }
     DisarmOnExit disarm;
     const size_t e = elt(dtype);
@@ -498,6 +500,24 @@ int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilati
     if (err != hipSuccess) return NM_ERR_DEVICE;
     t_current_op = NM_OP_BWD_WEIGHT;
     return dev(launch_mfma_wgrad_prepared(g, x, scale, dw, (flags & NM_ACCUM_DW) != 0, ws_w, s));
+}
+
+int nm_conv1d_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                  const void *dy, const void *y, const float *scale, const void *w, void *dx, void *dres, float *dw,
+                  unsigned flags, int dtype, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return bwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, dy, y, scale, w, dx, dres, dw, flags, dtype,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+int nm_conv1d_bwd_masked(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
+                         const void *x, const void *dy, const void *y, const float *scale, const void *w, void *dx,
+                         void *dres, float *dw, unsigned flags, int dtype, void *workspace, size_t workspace_bytes,
+                         void *hip_stream)
+{
+    if (!lengths) return NM_ERR_BAD_ARG;
+    return bwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, lengths, x, dy, y, scale, w, dx, dres, dw, flags, dtype,
+                    workspace, workspace_bytes, hip_stream);
 }
 
 int nm_conv1d_bn_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,

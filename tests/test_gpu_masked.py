@@ -78,4 +78,8 @@ def test_masked_passes(case, force_direct):
     valid_ref = np.concatenate([dx_ref[b, :, :n].reshape(-1) for b, n in enumerate(lens)])
     U.assert_close(valid, valid_ref, dtype, f"{cfg.name} dx")
     U.assert_close(U.to_host_f64(dw), dw_ref, dtype, f"{cfg.name} dw", rms_bound=U.RMS_DW_BF16)
+    # both gradients from one call: bit-identical to the two calls
+    dx1, dres1, dw1 = nm.nm_conv1d_bwd(xd, dyd, wd, y=ysv, scale=sc, relu=cfg.relu, want_dres=True, force_direct=force_direct,
+                                       lengths=ld, **kw)
+    assert torch.equal(dx1, dx) and torch.equal(dres1, dres) and torch.equal(dw1, dw), f"{cfg.name}: fused masked backward"
     np.testing.assert_array_equal(U.to_host_f64(dres), dres_ref)
