@@ -1,0 +1,72 @@
+/*
+ * nm_conv1d_fp8.h -- C ABI of the 8-bit floating-point variant of the conv1d block forward (gfx950).
+ *
+ * The paper's mixed-precision contract (Section 3.3) runs the convolutions on low-precision operands
+ * and keeps sums in float32; it names float16.  This variant applies the same contract with the E4M3
+ * format of the OCP 8-bit floating-point specification (1 sign, 4 exponent bits, bias 7, 3 mantissa
+ * bits, no infinities, largest finite value 448), which the gfx950 matrix cores multiply at twice the
+ * bfloat16 rate.  The paper gives no quantisation rule; the usual scaled one is used:
+ *
+ *   scale of a slice         s    = amax / 448            (1 when the slice is all zero), float32 division
+ *   code of an element       q    = E4M3( v * (1/s) )     1/s and the product in float32; round to nearest,
+ *                                                          ties to the even mantissa, saturating at +-448
+ *   block                    z    = sum_ci sum_k decode(wq[co,ci,k]) * decode(xq[b,ci,tau(t,k)])   (float32 sums)
+ *                            y    = relu?( scale[co]*sx*sw[co]*z + shift[co] + residual[b,co,t] )
+ *
+ * with one scale sx for the activation tensor and one scale sw[co] per output channel of the weights.
+ * The scales are inputs of the block (device memory), so a training loop may reuse those of an earlier
+ * step; nm_fp8_row_scales computes them from a tensor.
+ *
+ * Conventions (pointers, ownership, stream, status codes, determinism, argument checks before any device
+ * call) are those of nm_conv1d.h.  All tensors here are bfloat16 except where stated.
+ */
+#ifndef NM_CONV1D_FP8_H
+#define NM_CONV1D_FP8_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* scales[r] = max |x[r*row_len .. (r+1)*row_len)| / 448 (1 if that maximum is 0), r < rows.
+ *   x       [rows][row_len] bfloat16, device, in
+ *   scales  [rows] float, device, out
+ * rows >= 1, row_len >= 1, rows*row_len < 2^31.  Needs no workspace. */
+int nm_fp8_row_scales(const void *x, int rows, size_t row_len, float *scales, void *hip_stream);
+
+/* codes[i] = E4M3( x[i] * (1/scales[i / row_len]) ), same element order as x.
+ *   x       [rows][row_len] bfloat16, device, in
+ *   scales  [rows] float, device, in (positive, finite)
+ *   codes   [rows][row_len] bytes, device, out */
+int nm_fp8_quantize_rows(const void *x, int rows, size_t row_len, const float *scales, unsigned char *codes,
+                         void *hip_stream);
+
+/* 1 if nm_conv1d_block_fwd_fp8 serves this geometry, 0 if it returns NM_ERR_UNSUPPORTED (or the
+ * arguments are invalid).  Served: stride 1, Cin and Cout multiples of 64, and (K, dilation) one of
+ * (17,1) (21,1) (25,1) (29,2) -- the tap counts of the encoder's 512- to 896-channel blocks.  Host only. */
+int nm_conv1d_fp8_supported(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
+
+/* Bytes of device workspace of nm_conv1d_block_fwd_fp8 (0 for an unsupported or invalid geometry).  Host only. */
+size_t nm_conv1d_fp8_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
+
+/* Block forward on E4M3 operands.
+ *   x         [B][Cin][T]        bfloat16, in: quantised inside the call with x_scale
+ *   x_scale   [1] float          device, in
+ *   w         [Cout][Cin][K]     bfloat16, in: quantised inside the call, output channel co with w_scales[co]
+ *   w_scales  [Cout] float       device, in
+ *   scale, shift [Cout] float    in, NULL means 1 / 0
+ *   residual  [B][Cout][T_out]   bfloat16, in, or NULL
+ *   y         [B][Cout][T_out]   bfloat16, out (float32 result rounded to nearest even)
+ * flags: 0 or NM_RELU.  workspace: nm_conv1d_fp8_workspace_bytes(...) bytes, 256-byte aligned; it holds the
+ * codes of x (time-major in 64-channel groups, zero rows for the padding) and of w (matrix-core fragment
+ * order) and is scratch.  Returns NM_ERR_UNSUPPORTED for geometries outside nm_conv1d_fp8_supported. */
+int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                            const void *x, const float *x_scale, const void *w, const float *w_scales,
+                            const float *scale, const float *shift, const void *residual, void *y,
+                            unsigned flags, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_CONV1D_FP8_H */

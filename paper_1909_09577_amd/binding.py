@@ -23,7 +23,9 @@ NM_OP_FWD, NM_OP_BWD_DATA, NM_OP_BWD_WEIGHT, NM_OP_BWD, NM_OP_BN_FWD, NM_OP_BN_B
 
 EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_conv1d_block_fwd",
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
-           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_bwd_masked", "nm_conv1d_time_next_main_kernel")
+           "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_bwd_masked", "nm_conv1d_time_next_main_kernel",
+           "nm_fp8_row_scales", "nm_fp8_quantize_rows", "nm_conv1d_fp8_supported", "nm_conv1d_fp8_workspace_bytes",
+           "nm_conv1d_block_fwd_fp8")
 
 _lib = None
 
@@ -77,6 +79,16 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_time_next_main_kernel.restype = i
         L.nm_conv1d_time_next_kernel_of.argtypes = [vp, vp, i]
         L.nm_conv1d_time_next_kernel_of.restype = i
+        L.nm_fp8_row_scales.argtypes = [vp, i, sz, vp, vp]
+        L.nm_fp8_row_scales.restype = i
+        L.nm_fp8_quantize_rows.argtypes = [vp, i, sz, vp, vp, vp]
+        L.nm_fp8_quantize_rows.restype = i
+        L.nm_conv1d_fp8_supported.argtypes = [i] * 8
+        L.nm_conv1d_fp8_supported.restype = i
+        L.nm_conv1d_fp8_workspace_bytes.argtypes = [i] * 8
+        L.nm_conv1d_fp8_workspace_bytes.restype = sz
+        L.nm_conv1d_block_fwd_fp8.argtypes = [i] * 8 + [vp] * 8 + [u, vp, sz, vp]
+        L.nm_conv1d_block_fwd_fp8.restype = i
         _lib = L
     return _lib
 
@@ -365,3 +377,70 @@ def nm_decoder_logsoftmax_fwd(x, w, bias=None, logp=None, *, force_direct=False,
     if st != NM_OK:
         raise NmError(st, "nm_decoder_logsoftmax_fwd")
     return logp
+
+
+# ---- 8-bit floating-point (E4M3) variant of the block forward (include/nm_conv1d_fp8.h) ------------------
+def nm_fp8_row_scales(x, rows: int, *, stream=None):
+    """float32 [rows]: amax/448 of each of `rows` equal slices of the bfloat16 tensor x (1 for an all-zero slice)."""
+    torch = _torch()
+    if x.dtype != torch.bfloat16:
+        raise TypeError("x must be bfloat16")
+    n = x.numel()
+    if rows <= 0 or n % rows:
+        raise ValueError("rows must divide the number of elements")
+    scales = torch.empty(rows, dtype=torch.float32, device=x.device)
+    st = lib().nm_fp8_row_scales(_ptr(x, name="x"), rows, n // rows, _ptr(scales), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_fp8_row_scales")
+    return scales
+
+
+def nm_fp8_quantize_rows(x, scales, *, stream=None):
+    """uint8 tensor shaped like x: the E4M3 codes of x with slice r divided by scales[r]."""
+    torch = _torch()
+    if x.dtype != torch.bfloat16:
+        raise TypeError("x must be bfloat16")
+    rows = scales.numel()
+    n = x.numel()
+    if rows <= 0 or n % rows:
+        raise ValueError("len(scales) must divide the number of elements")
+    codes = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    st = lib().nm_fp8_quantize_rows(_ptr(x, name="x"), rows, n // rows, _ptr(scales, torch.float32, (rows,), "scales"),
+                                    _ptr(codes), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_fp8_quantize_rows")
+    return codes
+
+
+def nm_conv1d_fp8_supported(B, Cin, Cout, T, K, stride=1, dilation=1, pad=0) -> bool:
+    return bool(lib().nm_conv1d_fp8_supported(B, Cin, Cout, T, K, stride, dilation, pad))
+
+
+def nm_conv1d_fp8_workspace_bytes(B, Cin, Cout, T, K, stride=1, dilation=1, pad=0) -> int:
+    return int(lib().nm_conv1d_fp8_workspace_bytes(B, Cin, Cout, T, K, stride, dilation, pad))
+
+
+def nm_conv1d_block_fwd_fp8(x, x_scale, w, w_scales, scale=None, shift=None, residual=None, y=None, *, stride=1,
+                            dilation=1, pad=0, relu=False, workspace=None, stream=None):
+    """Block forward on E4M3 operands: x and w (bfloat16) are quantised inside the call with x_scale [1] and
+    w_scales [Cout] (float32 device tensors); returns y (bfloat16, allocated if not given)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    Cout, _, K = w.shape
+    To = nm_conv1d_out_len(T, K, stride, dilation, pad)
+    if To <= 0:
+        raise NmError(NM_ERR_BAD_ARG, "nm_conv1d_block_fwd_fp8")
+    if y is None:
+        y = torch.empty((B, Cout, To), dtype=torch.bfloat16, device=x.device)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    if workspace is None:
+        workspace = torch.empty(max(nm_conv1d_fp8_workspace_bytes(*dims), 256), dtype=torch.uint8, device=x.device)
+    st = lib().nm_conv1d_block_fwd_fp8(
+        *dims, _ptr(x, torch.bfloat16, name="x"), _ptr(x_scale, torch.float32, (1,), "x_scale"),
+        _ptr(w, torch.bfloat16, (Cout, Cin, K), "w"), _ptr(w_scales, torch.float32, (Cout,), "w_scales"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(shift, torch.float32, (Cout,), "shift"),
+        _ptr(residual, torch.bfloat16, (B, Cout, To), "residual"), _ptr(y, torch.bfloat16, (B, Cout, To), "y"),
+        NM_RELU if relu else 0, ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_block_fwd_fp8")
+    return y

@@ -1,0 +1,561 @@
+// Block forward on 8-bit floating-point (E4M3) operands: quantisation kernels, the matrix-core
+// convolution kernel and the entry points declared in include/nm_conv1d_fp8.h.
+//
+//   q = E4M3(v * (1/s))  (float32 arithmetic, round to nearest even, saturating at +-448)
+//   z[b,co,t] = sum_ci sum_k decode(wq[co,ci,k]) * decode(xq[b,ci,t - pad + k*dil])      (stride 1)
+//   y = relu?( scale[co]*sx*sw[co]*z + shift[co] + residual )
+//
+// The contraction runs on v_mfma_f32_32x32x64_f8f6f4 (both operands E4M3, no block scaling): one
+// instruction multiplies a 32x64 by a 64x32 tile, four times the work of the bfloat16 instruction at
+// twice its rate.  Products of two E4M3 values have at most 8 significant bits and are exact in float32.
+//
+// Data layout chosen for this kernel (both tensors are written by the quantisation kernels below, so
+// nothing has to follow the [B][C][T] order of the inputs):
+//   * activations  xq[B][Cin/64][Tp][64]: time-major rows of 64 channels, Tp = 160*ceil(T_out/160) +
+//     (K-1)*dil rows per (batch item, channel group), row r standing for input time r - pad; rows outside
+//     [0, T) are zero.  The window of a chunk (all rows the K taps of a 160-step tile touch) is one
+//     contiguous piece of memory, copied to LDS with 16-byte accesses and no shuffling, and every tap is
+//     a row offset;
+//   * weights  wq[Cout/64][Cin/64][K][2][64 lanes][32 B]: A fragments in register order, so a wavefront
+//     reads 2 KiB contiguous per fragment straight from L2 into registers.
+//
+// Work decomposition: an output tile is 64 channels x 160 time steps of one batch item, held by one
+// wavefront in ten 32x32 accumulators; a workgroup is four wavefronts that own four tiles of the same
+// channel tile (so their weight loads hit L1) with private LDS windows -- no workgroup barrier anywhere.
+// Wavefronts are persistent and run through their tiles with one pipeline: weight fragments live in
+// 4 (+ K mod 4) register sets, each reloaded right after its last use with the tap that needs it
+// next, four taps ahead, across chunk and tile boundaries; the window of the next chunk (or of the next
+// tile's first chunk) is requested piece by piece during the current chunk and written to the other LDS
+// buffer four taps later; a B fragment register is reloaded for the next tap right after the two
+// MFMAs that read it.
+#include "../../include/nm_conv1d.h"
+#include "../../include/nm_conv1d_fp8.h"
+#include "nm_common.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace nm {
+namespace {
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTileCo = 64;
+constexpr int kNT = 5;                     // 32-step blocks per tile
+constexpr int kTileT = 32 * kNT;           // 160
+constexpr int kChunk = 64;                 // reduction channels per chunk = bytes of a window row
+constexpr int kRowBytes = 80;              // LDS row: 64 B + 16 B pad
+constexpr int kFragBytes = 64 * 32;        // one A fragment
+constexpr int kTapBytes = 2 * kFragBytes;  // the two fragments (rows 0-31, 32-63) of one tap and chunk
+constexpr int kAhead = 4;                  // taps between the request of a window piece and its LDS write
+constexpr size_t kSlack = 8192;            // bytes behind each quantised tensor that prefetches may read
+constexpr float kE4M3Max = 448.0f;
+
+// ---------------------------------------------------------------------------------------------
+// E4M3 conversion (software: the rule is part of the result, so it is spelled out rather than left to
+// a conversion instruction).  Round to nearest, ties to even, saturate at +-448, NaN -> 0x7F.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    const uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return 0x7fu;
+    if (a >= 0x43e00000u) return sign | 0x7eu;  // |f| >= 448
+    if (a < 0x3c800000u) {                      // |f| < 2^-6: multiples of 2^-9 (8 of them reach 2^-6 = code 0x08)
+        const float r = __builtin_rintf(__uint_as_float(a) * 512.0f);
+        return sign | (uint32_t)r;
+    }
+    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);  // keep 3 mantissa bits
+    return sign | ((r >> 20) - (120u << 3));             // exponent bias 127 -> 7
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, int n, uint32_t v)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// amax[r] (as the bit pattern of a non-negative float, which orders like an unsigned integer)
+__global__ __launch_bounds__(256) void row_amax_kernel(const bf16_t *__restrict__ x, size_t row_len, uint32_t *amax)
+{
+    const int r = blockIdx.y;
+    const bf16_t *row = x + (size_t)r * row_len;
+    float m = 0.f;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < row_len; i += (size_t)gridDim.x * 256)
+        m = fmaxf(m, fabsf(bf16_to_f32(row[i])));
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) atomicMax(amax + r, __float_as_uint(m));
+}
+
+__global__ __launch_bounds__(256) void amax_to_scale_kernel(float *s, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float a = s[i];
+    s[i] = a == 0.f ? 1.f : a / kE4M3Max;
+}
+
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const bf16_t *__restrict__ x, size_t row_len, size_t total,
+                                                            const float *__restrict__ scales, unsigned char *__restrict__ q)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const float inv = 1.0f / scales[i / row_len];
+    q[i] = (unsigned char)f32_to_e4m3(bf16_to_f32(x[i]) * inv);
+}
+
+// x [B][Cin][T] bf16 -> xq[B][Cin/64][Tp][64] codes; row r stands for input time r - pad, zero outside [0,T).
+// grid (ceil(Tp/64), Cin/64, B); thread (tl, cg): row blockIdx.x*64 + tl, channels 16*cg .. 16*cg+15.
+__global__ __launch_bounds__(256) void quant_x_kernel(const bf16_t *__restrict__ x, const float *__restrict__ xs,
+                                                      unsigned char *__restrict__ xq, int Cin, int T, int Tp, int pad)
+{
+    const int tl = threadIdx.x & 63, cg = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + tl;
+    if (r >= Tp) return;
+    const int c = blockIdx.y, b = blockIdx.z;
+    const int t = r - pad;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (t >= 0 && t < T) {
+        const float inv = 1.0f / xs[0];
+        const bf16_t *src = x + ((size_t)b * Cin + c * 64 + cg * 16) * T + t;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t code = f32_to_e4m3(bf16_to_f32(src[(size_t)j * T]) * inv);
+            out[j >> 2] |= code << (8 * (j & 3));
+        }
+    }
+    *reinterpret_cast<u32x4 *>(xq + (((size_t)b * gridDim.y + c) * Tp + r) * 64 + cg * 16) = out;
+}
+
+// w [Cout][Cin][K] bf16 -> wq[Cout/64][Cin/64][K][2][64][32] codes.  One block per (channel tile, chunk,
+// row half): its 32 rows of 64*K weights are contiguous pieces of memory; they go through LDS as codes.
+// Lane l of a fragment holds row l%32 and the 32 channels 32*(l/32) .. +31 of the chunk.
+__global__ __launch_bounds__(256) void pack_w_kernel(const bf16_t *__restrict__ w, const float *__restrict__ wsc,
+                                                     unsigned char *__restrict__ wq, int Cin, int K)
+{
+    extern __shared__ __align__(16) unsigned char codes[];  // [32][pitch]
+    const int mi = blockIdx.x & 1, c = blockIdx.y, cot = blockIdx.z;
+    const int nck = gridDim.y;
+    const int rowlen = 64 * K;       // codes per row
+    const int pitch = rowlen + 8;    // keeps the 8-byte writes aligned
+    const int vec_per_row = rowlen / 8;
+    for (int v = threadIdx.x; v < 32 * vec_per_row; v += 256) {
+        const int row = v / vec_per_row, col = v - row * vec_per_row;
+        const int co = cot * 64 + mi * 32 + row;
+        const float inv = 1.0f / wsc[co];
+        const u32x4 raw = *reinterpret_cast<const u32x4 *>(w + ((size_t)co * Cin + c * 64) * K + col * 8);
+        u32x2 o = {0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bf16_t h = (bf16_t)((raw[j >> 1] >> (16 * (j & 1))) & 0xffffu);
+            o[j >> 2] |= f32_to_e4m3(bf16_to_f32(h) * inv) << (8 * (j & 3));
+        }
+        *reinterpret_cast<u32x2 *>(codes + row * pitch + col * 8) = o;
+    }
+    __syncthreads();
+    for (int it = threadIdx.x; it < K * 64; it += 256) {
+        const int k = it >> 6, lane = it & 63;
+        const unsigned char *src = codes + (lane & 31) * pitch + (32 * (lane >> 5)) * K + k;
+        u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            lo[j >> 2] |= (uint32_t)src[j * K] << (8 * (j & 3));
+            hi[j >> 2] |= (uint32_t)src[(16 + j) * K] << (8 * (j & 3));
+        }
+        u32x4 *dst = reinterpret_cast<u32x4 *>(wq + ((((size_t)(cot * nck + c) * K + k) * 2 + mi) * 64 + lane) * 32);
+        dst[0] = lo;
+        dst[1] = hi;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+struct Fp8Params {
+    int B, Cin, Cout, To, K;
+    int ncot, nck, ntt, Tp;
+    int nbt;     // B * ntt (batch item, time tile) pairs
+    int ntiles;  // ncot * 4 * ceil(nbt / 4): tile ids, some of them empty when nbt % 4 != 0
+    int relu;
+    const unsigned char *xq;
+    const unsigned char *wq;
+    const float *xs, *ws, *scale, *shift;
+    const bf16_t *res;
+    bf16_t *y;
+};
+
+struct TileCoords {
+    int cot, b, tt;
+    bool valid;
+};
+// tile ids are numbered so that four consecutive ids share the channel tile: id = (group*ncot + cot)*4 + j,
+// (b, tt) pair number group*4 + j
+__device__ __forceinline__ TileCoords decode_tile(const Fp8Params &p, int id)
+{
+    TileCoords c;
+    const int q = id >> 2, j = id & 3;
+    c.cot = q % p.ncot;
+    const int bt = (q / p.ncot) * 4 + j;
+    c.valid = id < p.ntiles && bt < p.nbt;
+    c.b = bt / p.ntt;
+    c.tt = bt - c.b * p.ntt;
+    return c;
+}
+
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wavefront execute in order; this only keeps the compiler from moving LDS
+    // accesses across the point where other lanes' data must be visible.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int KT, int DIL>
+struct Plan {
+    static constexpr int Q4 = (KT / 4) * 4, R = KT - Q4, NSETS = 4 + R;
+    static constexpr int ROWS = kTileT + (KT - 1) * DIL;
+    static constexpr int NIT = (ROWS * 4 + 63) / 64;  // 16-byte window pieces per lane
+    static constexpr int BUF = NIT * 16 * kRowBytes;  // one LDS window buffer of a wavefront
+    static constexpr int SPAN = KT - 1 - kAhead;      // taps over which the window requests are spread
+    static_assert(SPAN >= 1, "too few taps for the staging schedule");
+    static constexpr int set_of(int k) { return k < Q4 ? k % 4 : 4 + (k - Q4); }
+    static constexpr int load_tap(int i) { return i * SPAN / NIT; }
+};
+
+template <int KT, int DIL>
+__global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
+{
+    using P = Plan<KT, DIL>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wid = blockIdx.x * kWaves + wave;
+    const int nwaves = gridDim.x * kWaves;
+    if (wid >= p.ntiles) return;
+
+    unsigned char *const lds = smem + wave * (2 * P::BUF);
+    const int n = lane & 31, h = lane >> 5;
+    const int rd_lane = n * kRowBytes + 32 * h;                    // B fragment: row n, channels 32h..32h+31
+    const int wr_lane = (lane >> 2) * kRowBytes + (lane & 3) * 16;  // window piece: row lane/4, quarter lane%4
+    const size_t chunk_stride = (size_t)p.Tp * kChunk;              // bytes between the windows of consecutive chunks
+    const size_t wtile_bytes = (size_t)p.nck * KT * kTapBytes;
+
+    auto window_base = [&](const TileCoords &t) {
+        return p.xq + ((size_t)t.b * p.nck * p.Tp + (size_t)t.tt * kTileT) * kChunk + lane * 16;
+    };
+    auto weights_base = [&](const TileCoords &t) { return p.wq + (size_t)t.cot * wtile_bytes + lane * 32; };
+
+    // first valid tile of this wavefront
+    int id = wid;
+    TileCoords tc = decode_tile(p, id);
+    while (!tc.valid) {
+        id += nwaves;
+        if (id >= p.ntiles) return;
+        tc = decode_tile(p, id);
+    }
+
+    u32x4 stage[P::NIT];
+    i32x8 aset[P::NSETS][2];
+    i32x8 bfr[kNT];
+    f32x16 acc[2][kNT];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int tb = 0; tb < kNT; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][tb][r] = 0.f;
+
+    auto load_a = [&](i32x8(&dst)[2], const unsigned char *src) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            const u32x4 lo = *reinterpret_cast<const u32x4 *>(src + mi * kFragBytes);
+            const u32x4 hi = *reinterpret_cast<const u32x4 *>(src + mi * kFragBytes + 16);
+            dst[mi] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        }
+    };
+    auto load_b = [&](i32x8 &dst, const unsigned char *buf, int row_off) {
+        const u32x4 lo = *reinterpret_cast<const u32x4 *>(buf + rd_lane + row_off * kRowBytes);
+        const u32x4 hi = *reinterpret_cast<const u32x4 *>(buf + rd_lane + row_off * kRowBytes + 16);
+        dst = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+    };
+
+    // ---- prologue: the first tile's first window, weight sets and B fragments
+    const unsigned char *xcur = window_base(tc);
+    const unsigned char *wcur = weights_base(tc);
+    static_for<P::NIT>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        stage[i] = *reinterpret_cast<const u32x4 *>(xcur + i * 1024);
+    });
+    static_for<P::NIT>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        *reinterpret_cast<u32x4 *>(lds + wr_lane + i * 16 * kRowBytes) = stage[i];
+    });
+    static_for<KT>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < 4 || k >= P::Q4) load_a(aset[P::set_of(k)], wcur + k * kTapBytes);
+    });
+    wave_lds_fence();
+    static_for<kNT>([&](auto tc5) {
+        constexpr int tb = decltype(tc5)::value;
+        load_b(bfr[tb], lds, tb * 32);
+    });
+    int cur = 0;  // LDS buffer that holds the current chunk's window
+
+    for (;;) {
+        // the tile after this one (if any) supplies the "next chunk" of this tile's last chunk
+        int nid = id + nwaves;
+        TileCoords nt = decode_tile(p, nid);
+        while (nid < p.ntiles && !nt.valid) {
+            nid += nwaves;
+            nt = decode_tile(p, nid);
+        }
+        const bool has_next = nid < p.ntiles;
+        const unsigned char *xnext_tile = has_next ? window_base(nt) : window_base(tc);
+        const unsigned char *wnext_tile = has_next ? weights_base(nt) : weights_base(tc);
+
+        for (int c = 0; c < p.nck; ++c) {
+            const bool last = c + 1 == p.nck;
+            const unsigned char *xnxt = last ? xnext_tile : xcur + chunk_stride;
+            const unsigned char *wnxt = last ? wnext_tile : wcur + KT * kTapBytes;
+            unsigned char *const bcur = lds + cur * P::BUF;
+            unsigned char *const bnxt = lds + (cur ^ 1) * P::BUF;
+
+            static_for<KT>([&](auto kc) {
+                constexpr int k = decltype(kc)::value;
+                // window of the next chunk: request pieces, write the ones requested kAhead taps ago
+                static_for<P::NIT>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    if constexpr (P::load_tap(i) == k) stage[i] = *reinterpret_cast<const u32x4 *>(xnxt + i * 1024);
+                });
+                static_for<P::NIT>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    if constexpr (P::load_tap(i) + kAhead == k)
+                        *reinterpret_cast<u32x4 *>(bnxt + wr_lane + i * 16 * kRowBytes) = stage[i];
+                });
+                if constexpr (k == KT - 1) wave_lds_fence();  // the next window is complete before its first rows are read
+                __builtin_amdgcn_sched_barrier(0);
+                constexpr int s = P::set_of(k);
+                static_for<kNT>([&](auto tc5) {
+                    constexpr int tb = decltype(tc5)::value;
+                    acc[0][tb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aset[s][0], bfr[tb], acc[0][tb], 0, 0, 0, 0, 0, 0);
+                    acc[1][tb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(aset[s][1], bfr[tb], acc[1][tb], 0, 0, 0, 0, 0, 0);
+                    if constexpr (k + 1 < KT)
+                        load_b(bfr[tb], bcur, tb * 32 + (k + 1) * DIL);
+                    else
+                        load_b(bfr[tb], bnxt, tb * 32);
+                    __builtin_amdgcn_sched_barrier(0);  // keep the reload here: the scheduler would sink it to its use
+                });
+                // this tap's weight set is free: fetch the tap that uses it next
+                if constexpr (k + 4 < P::Q4)
+                    load_a(aset[s], wcur + (k + 4) * kTapBytes);
+                else if constexpr (k < P::Q4)
+                    load_a(aset[s], wnxt + (k % 4) * kTapBytes);
+                else
+                    load_a(aset[s], wnxt + k * kTapBytes);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            xcur = xnxt;
+            wcur = wnxt;
+            cur ^= 1;
+        }
+
+        // ---- epilogue: register r of block (mi, tb) is channel cot*64 + mi*32 + 8*(r/4) + 4*h + r%4, time tt*160 + tb*32 + n
+        const float sx = p.xs[0];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int co = tc.cot * kTileCo + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                const float eff = (p.scale ? p.scale[co] : 1.f) * (sx * p.ws[co]);
+                const float sh = p.shift ? p.shift[co] : 0.f;
+                const size_t row = ((size_t)tc.b * p.Cout + co) * p.To;
+#pragma unroll
+                for (int tb = 0; tb < kNT; ++tb) {
+                    const int t = tc.tt * kTileT + tb * 32 + n;
+                    if (t < p.To) {
+                        float v = acc[mi][tb][r] * eff + sh;
+                        if (p.res) v += bf16_to_f32(p.res[row + t]);
+                        if (p.relu) v = fmaxf(v, 0.f);
+                        p.y[row + t] = f32_to_bf16(v);
+                    }
+                    acc[mi][tb][r] = 0.f;
+                }
+            }
+        }
+        if (!has_next) break;
+        id = nid;
+        tc = nt;
+    }
+}
+
+template <int KT, int DIL>
+hipError_t launch_fp8_conv(const Fp8Params &p, hipStream_t s)
+{
+    using P = Plan<KT, DIL>;
+    static LdsOptIn opt_in;
+    constexpr int lds = kWaves * 2 * P::BUF;
+    static_assert(lds <= 160 * 1024, "LDS windows exceed the CU");
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(fp8_conv_kernel<KT, DIL>), lds);
+    if (e != hipSuccess) return e;
+    const int cus = current_device_info().cus;
+    const int grid = min(cus, (p.ntiles + kWaves - 1) / kWaves);
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL((fp8_conv_kernel<KT, DIL>), dim3(grid), dim3(kThreads), lds, s, p);
+    return hipGetLastError();
+}
+
+bool taps_supported(int K, int dil)
+{
+    return (dil == 1 && (K == 17 || K == 21 || K == 25)) || (dil == 2 && K == 29);
+}
+
+struct Fp8Layout {
+    int ncot, nck, ntt, Tp;
+    size_t xq_bytes, wq_bytes, total;
+};
+Fp8Layout fp8_layout(int B, int Cin, int Cout, int To, int K, int dil)
+{
+    Fp8Layout l;
+    l.ncot = Cout / kTileCo;
+    l.nck = Cin / kChunk;
+    l.ntt = (To + kTileT - 1) / kTileT;
+    l.Tp = l.ntt * kTileT + (K - 1) * dil;
+    l.xq_bytes = align_up((size_t)B * l.nck * l.Tp * kChunk + kSlack, 256);
+    l.wq_bytes = align_up((size_t)l.ncot * l.nck * K * kTapBytes + kSlack, 256);
+    l.total = l.xq_bytes + l.wq_bytes;
+    return l;
+}
+
+int fp8_check(int B, int Cin, int Cout, int T, int K, int stride, int dil, int pad, int *To)
+{
+    if (B <= 0 || Cin <= 0 || Cout <= 0 || T <= 0 || K <= 0 || stride <= 0 || dil <= 0 || pad < 0) return NM_ERR_BAD_ARG;
+    const long long span = (long long)T + 2LL * pad - (long long)dil * (K - 1) - 1;
+    if (span < 0) return NM_ERR_BAD_ARG;
+    const long long to = span / stride + 1;
+    if (to > (1LL << 31) - 1) return NM_ERR_BAD_ARG;
+    *To = (int)to;
+    if (stride != 1 || Cin % kChunk || Cout % kTileCo || !taps_supported(K, dil)) return NM_ERR_UNSUPPORTED;
+    if (pad > (K - 1) * dil) return NM_ERR_UNSUPPORTED;  // rows of xq before time 0 are the left padding only
+    if ((long long)B * Cin * T > (1LL << 31) - 1 || (long long)B * Cout * to > (1LL << 31) - 1 ||
+        (long long)Cout * Cin * K > (1LL << 31) - 1 || B > 65535)
+        return NM_ERR_UNSUPPORTED;
+    const Fp8Layout l = fp8_layout(B, Cin, Cout, (int)to, K, dil);
+    if (l.xq_bytes > (1ull << 31) || l.wq_bytes > (1ull << 31)) return NM_ERR_UNSUPPORTED;
+    return NM_OK;
+}
+
+bool overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b) return false;
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+}  // namespace
+}  // namespace nm
+
+using namespace nm;
+
+extern "C" int nm_fp8_row_scales(const void *x, int rows, size_t row_len, float *scales, void *hip_stream)
+{
+    if (!x || !scales || rows <= 0 || row_len == 0) return NM_ERR_BAD_ARG;
+    if ((unsigned long long)rows * row_len > (1ull << 31) - 1 || rows > 65535) return NM_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, reinterpret_cast<uint32_t *>(scales), rows, 0u);
+    const int bx = (int)std::min<size_t>((row_len + 2047) / 2048, 1024);
+    hipLaunchKernelGGL(row_amax_kernel, dim3(bx, rows), dim3(256), 0, s, (const bf16_t *)x, row_len,
+                       reinterpret_cast<uint32_t *>(scales));
+    hipLaunchKernelGGL(amax_to_scale_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, scales, rows);
+    return hipGetLastError() == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+}
+
+extern "C" int nm_fp8_quantize_rows(const void *x, int rows, size_t row_len, const float *scales, unsigned char *codes,
+                                    void *hip_stream)
+{
+    if (!x || !scales || !codes || rows <= 0 || row_len == 0) return NM_ERR_BAD_ARG;
+    if ((unsigned long long)rows * row_len > (1ull << 31) - 1) return NM_ERR_UNSUPPORTED;
+    const size_t total = (size_t)rows * row_len;
+    if (overlap(x, total * 2, codes, total)) return NM_ERR_BAD_ARG;
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const bf16_t *)x, row_len, total, scales, codes);
+    return hipGetLastError() == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+}
+
+extern "C" int nm_conv1d_fp8_supported(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad)
+{
+    int To = 0;
+    return fp8_check(B, Cin, Cout, T, K, stride, dilation, pad, &To) == NM_OK ? 1 : 0;
+}
+
+extern "C" size_t nm_conv1d_fp8_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad)
+{
+    int To = 0;
+    if (fp8_check(B, Cin, Cout, T, K, stride, dilation, pad, &To) != NM_OK) return 0;
+    return fp8_layout(B, Cin, Cout, To, K, dilation).total;
+}
+
+extern "C" int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                                       const void *x, const float *x_scale, const void *w, const float *w_scales,
+                                       const float *scale, const float *shift, const void *residual, void *y,
+                                       unsigned flags, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int To = 0;
+    const int st = fp8_check(B, Cin, Cout, T, K, stride, dilation, pad, &To);
+    if (st != NM_OK) return st;
+    if (!x || !x_scale || !w || !w_scales || !y) return NM_ERR_BAD_ARG;
+    if (flags & ~(unsigned)NM_RELU) return NM_ERR_BAD_ARG;
+    const Fp8Layout l = fp8_layout(B, Cin, Cout, To, K, dilation);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < l.total) return NM_ERR_WORKSPACE;
+    const size_t nx = (size_t)B * Cin * T * 2, ny = (size_t)B * Cout * To * 2, nw = (size_t)Cout * Cin * K * 2;
+    if (((uintptr_t)w & 15) || ((uintptr_t)x & 1) || ((uintptr_t)y & 1) || ((uintptr_t)residual & 1)) return NM_ERR_BAD_ARG;
+    if (overlap(y, ny, x, nx) || overlap(y, ny, w, nw) || overlap(y, ny, residual, ny) || overlap(y, ny, workspace, l.total) ||
+        overlap(x, nx, workspace, l.total) || overlap(w, nw, workspace, l.total) || overlap(residual, ny, workspace, l.total))
+        return NM_ERR_BAD_ARG;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    unsigned char *xq = (unsigned char *)workspace;
+    unsigned char *wq = xq + l.xq_bytes;
+    hipLaunchKernelGGL(quant_x_kernel, dim3((l.Tp + 63) / 64, l.nck, B), dim3(256), 0, s, (const bf16_t *)x, x_scale, xq,
+                       Cin, T, l.Tp, pad);
+    hipLaunchKernelGGL(pack_w_kernel, dim3(2, l.nck, l.ncot), dim3(256), (size_t)32 * (64 * K + 8), s, (const bf16_t *)w,
+                       w_scales, wq, Cin, K);
+    if (hipGetLastError() != hipSuccess) return NM_ERR_DEVICE;
+
+    Fp8Params p;
+    p.B = B; p.Cin = Cin; p.Cout = Cout; p.To = To; p.K = K;
+    p.ncot = l.ncot; p.nck = l.nck; p.ntt = l.ntt; p.Tp = l.Tp;
+    p.nbt = B * l.ntt;
+    p.ntiles = l.ncot * 4 * ((p.nbt + 3) / 4);
+    p.relu = (flags & NM_RELU) ? 1 : 0;
+    p.xq = xq; p.wq = wq;
+    p.xs = x_scale; p.ws = w_scales; p.scale = scale; p.shift = shift;
+    p.res = (const bf16_t *)residual;
+    p.y = (bf16_t *)y;
+    hipError_t e;
+    if (dilation == 2) e = launch_fp8_conv<29, 2>(p, s);
+    else if (K == 17) e = launch_fp8_conv<17, 1>(p, s);
+    else if (K == 21) e = launch_fp8_conv<21, 1>(p, s);
+    else e = launch_fp8_conv<25, 1>(p, s);
+    return e == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+}

@@ -224,3 +224,40 @@ def test_bn_entry_points_report_argument_errors_before_any_device_call():
     assert bn_bwd(y=None) == nm.NM_ERR_BAD_ARG      # NM_RELU needs the saved output
     assert bn_bwd(dx=None) == nm.NM_ERR_BAD_ARG
     assert bn_bwd() == nm.NM_ERR_WORKSPACE
+
+
+def test_fp8_entry_points_report_argument_errors_before_any_device_call():
+    L = nm.lib()
+    ok = dict(B=2, Cin=64, Cout=128, T=200, K=17, stride=1, dilation=1, pad=8)
+
+    def sup(**kw):
+        d = dict(ok, **kw)
+        return nm.nm_conv1d_fp8_supported(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"])
+
+    assert sup() and sup(K=21, pad=10) and sup(K=25, pad=12) and sup(K=29, dilation=2, pad=28) and sup(pad=0) and sup(pad=16)
+    assert not sup(K=11, pad=5) and not sup(K=3, pad=1) and not sup(stride=2) and not sup(dilation=2)
+    assert not sup(Cin=96) and not sup(Cout=100) and not sup(pad=17) and not sup(B=0) and not sup(T=10, pad=0)
+    need = nm.nm_conv1d_fp8_workspace_bytes(**ok)
+    # codes of x: 2 items x 1 chunk x (2*160 + 16) rows x 64 B; of w: 2 tiles x 1 chunk x 17 taps x 4 KiB; slack each
+    assert need >= 2 * 336 * 64 + 2 * 17 * 4096 and need % 256 == 0
+    assert nm.nm_conv1d_fp8_workspace_bytes(**dict(ok, K=5, pad=2)) == 0
+
+    def call(x=FAKE2, xs=FAKE, w=FAKE3, ws=FAKE, y=FAKE4, flags=0, wsp=FAKE5, wsb=None, res=None, **kw):
+        d = dict(ok, **kw)
+        return L.nm_conv1d_block_fwd_fp8(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"],
+                                         x, xs, w, ws, None, None, res, y, flags, wsp, need if wsb is None else wsb, None)
+
+    assert call(K=11, pad=5) == nm.NM_ERR_UNSUPPORTED and call(Cin=96) == nm.NM_ERR_UNSUPPORTED
+    assert call(B=0) == nm.NM_ERR_BAD_ARG and call(pad=-1) == nm.NM_ERR_BAD_ARG
+    for missing in ("x", "xs", "w", "ws", "y"):
+        assert call(**{missing: None}) == nm.NM_ERR_BAD_ARG, missing
+    assert call(flags=nm.NM_ACCUM_DW) == nm.NM_ERR_BAD_ARG
+    assert call(wsp=None) == nm.NM_ERR_WORKSPACE and call(wsb=need - 1) == nm.NM_ERR_WORKSPACE
+    assert call(wsp=ctypes.c_void_p(0x7C0000000010)) == nm.NM_ERR_WORKSPACE
+    assert call(y=FAKE2) == nm.NM_ERR_BAD_ARG and call(res=FAKE4) == nm.NM_ERR_BAD_ARG   # y aliases x / the residual
+    assert call(w=ctypes.c_void_p(0x7E0000000008)) == nm.NM_ERR_BAD_ARG                    # w not 16-byte aligned
+    assert L.nm_fp8_row_scales(None, 1, 8, FAKE, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_fp8_row_scales(FAKE2, 0, 8, FAKE, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_fp8_row_scales(FAKE2, 1 << 20, 1 << 20, FAKE, None) == nm.NM_ERR_UNSUPPORTED
+    assert L.nm_fp8_quantize_rows(FAKE2, 1, 0, FAKE, FAKE3, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_fp8_quantize_rows(FAKE2, 2, 8, FAKE, FAKE2, None) == nm.NM_ERR_BAD_ARG       # codes alias x

@@ -1,0 +1,153 @@
+"""GPU parity of the 8-bit floating-point (E4M3) variant against the oracle (oracle/fp8_oracle.py +
+conv1d_oracle).
+
+Scales and codes are integer-like results of a float32 rule that both sides state the same way (float32
+division and multiplication, round to nearest even, saturation): they are compared bit for bit.  The
+block output is compared with the oracle's block on the values the oracle's own codes stand for -- the
+inputs, scales and quantisation rule are shared, no GPU result feeds the oracle -- at the gate of the bf16
+block: products of two E4M3 values are exact in float32, so the GPU result differs from the fp64 one by
+float32 accumulation (about 1e-6 relative to the rms) and the final rounding to bf16 (unit roundoff 2^-8).
+"""
+import numpy as np
+import pytest
+
+import _util as U
+from oracle import conv1d_oracle as orc
+from oracle import fp8_oracle as f8
+from paper_1909_09577_amd import binding as nm
+from paper_1909_09577_amd import inputs as syn
+from paper_1909_09577_amd.inputs import LayerCfg
+
+pytestmark = pytest.mark.gpu
+DT = "bf16"
+
+
+def L(name, B, Cin, Cout, T, K, dilation=1, pad=None, affine=True, relu=True, residual=False, seed=51):
+    pad = dilation * (K - 1) // 2 if pad is None else pad
+    return LayerCfg(name, B, Cin, Cout, T, K, 1, dilation, pad, affine, relu, residual, seed,
+                    T_out=orc.out_len(T, K, 1, dilation, pad))
+
+
+def bf16_dev(a):
+    """device bf16 tensor holding float32 array a rounded to bf16, and the rounded values as float32"""
+    import torch
+    bits = syn.f32_to_bf16_bits(np.ascontiguousarray(a, dtype=np.float32))
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16), syn.bf16_bits_to_f32(bits)
+
+
+@pytest.mark.parametrize("shape,rows", [((3, 1000), 3), ((1, 77777), 1), ((64, 64, 17), 64), ((5, 8191), 5), ((2, 4, 333), 1)])
+def test_scales_and_codes_are_bit_exact(shape, rows):
+    rng = np.random.default_rng(7)
+    a = rng.normal(0, 1, shape).astype(np.float32)
+    a.reshape(rows, -1)[0, :5] = [0.0, -0.0, 1e-30, -3e-5, 2.5]           # zeros, underflow to zero, subnormal codes
+    if rows > 2:
+        a.reshape(rows, -1)[1] = 0.0                                      # an all-zero slice: scale 1
+        a.reshape(rows, -1)[2] *= 1e-3
+    d, a16 = bf16_dev(a)
+    s_gpu = nm.nm_fp8_row_scales(d, rows)
+    s_ref = f8.row_scales(a16, rows)
+    assert np.array_equal(s_gpu.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    q_gpu = nm.nm_fp8_quantize_rows(d, s_gpu).cpu().numpy()
+    q_ref = f8.quantize_rows(a16, s_ref)
+    assert np.array_equal(q_gpu, q_ref)
+    # a scale that is too small for the data: saturation at +-448 on both sides
+    import torch
+    tiny = (s_ref / np.float32(37.0)).astype(np.float32)
+    q_gpu = nm.nm_fp8_quantize_rows(d, torch.from_numpy(tiny).cuda()).cpu().numpy()
+    assert np.array_equal(q_gpu, f8.quantize_rows(a16, tiny))
+    assert (q_gpu & 0x7F).max() == 0x7E
+
+
+def test_every_tie_and_every_code_boundary():
+    """All 16-bit patterns of bf16 that are finite, quantised with scale 1: covers every tie point of E4M3
+    that bf16 can express, both signs, the subnormal range and the saturation boundary."""
+    import torch
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = syn.bf16_bits_to_f32(bits)
+    keep = np.isfinite(vals)
+    d = torch.from_numpy(bits[keep].view(np.int16)).cuda().view(torch.bfloat16)
+    one = torch.ones(1, dtype=torch.float32, device="cuda")
+    q = nm.nm_fp8_quantize_rows(d, one).cpu().numpy()
+    assert np.array_equal(q, f8.quantize_rows(vals[keep], np.ones(1, np.float32)))
+
+
+CASES = [
+    L("f8_two_tiles", 2, 64, 64, 200, 17, residual=True),                 # ragged second time tile
+    L("f8_nine_pairs", 3, 128, 192, 333, 21, residual=True),              # (b, tile) pairs not a multiple of 4, odd length
+    L("f8_k25", 2, 192, 128, 160, 25, relu=False),
+    L("f8_k29_d2", 2, 128, 64, 248, 29, dilation=2),
+    L("f8_short_pad", 2, 64, 128, 180, 17, pad=3, affine=False),          # T_out < T
+    L("f8_long_pad", 2, 64, 64, 100, 17, pad=16, residual=True),          # T_out > T
+    L("f8_one_frame_tile", 1, 64, 64, 161, 17),                           # a time tile with a single valid frame
+    L("f8_many_tiles", 32, 64, 256, 1600, 17, residual=True),             # 1280 tiles: every wavefront runs a second tile
+]
+
+
+def run_case(cfg):
+    inp = syn.make_inputs(cfg, DT)
+    kw = U.geom_kw(cfg)
+    sx = f8.row_scales(inp["x"], 1)
+    sw = f8.row_scales(inp["w"], cfg.Cout)
+    xq, wq = f8.quantize_rows(inp["x"], sx), f8.quantize_rows(inp["w"], sw)
+    scale = inp["scale"] if cfg.affine else None
+    shift = inp["shift"] if cfg.affine else None
+    res = inp["residual"] if cfg.residual else None
+    ref = f8.block_fwd_fp8(orc.block_fwd, xq, sx[0], wq, sw, scale, shift, res, cfg.relu, **kw)
+
+    xd, wd = U.to_dev(inp, "x", DT), U.to_dev(inp, "w", DT)
+    sxd = nm.nm_fp8_row_scales(xd, 1)
+    swd = nm.nm_fp8_row_scales(wd, cfg.Cout)
+    assert np.array_equal(sxd.cpu().numpy(), sx) and np.array_equal(swd.cpu().numpy(), sw)
+    y = nm.nm_conv1d_block_fwd_fp8(
+        xd, sxd, wd, swd, U.to_dev(inp, "scale", DT) if cfg.affine else None,
+        U.to_dev(inp, "shift", DT) if cfg.affine else None, U.to_dev(inp, "residual", DT) if cfg.residual else None,
+        relu=cfg.relu, **kw)
+    assert tuple(y.shape) == (cfg.B, cfg.Cout, cfg.T_out)
+    return U.to_host_f64(y), ref, inp
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
+def test_block_fwd_fp8(cfg):
+    assert nm.nm_conv1d_fp8_supported(cfg.B, cfg.Cin, cfg.Cout, cfg.T, cfg.K, 1, cfg.dilation, cfg.pad)
+    got, ref, _ = run_case(cfg)
+    U.assert_close(got, ref, DT, f"{cfg.name} y")
+
+
+@pytest.mark.parametrize("cfg", [
+    L("f8_b3_512_k17", 32, 512, 512, 800, 17, residual=True, seed=2),
+    L("f8_768_k25", 32, 768, 768, 800, 25, residual=True, seed=6),
+], ids=lambda c: c.name)
+def test_block_fwd_fp8_full_size_full_tensor(cfg):
+    got, ref, inp = run_case(cfg)
+    U.assert_close(got, ref, DT, f"{cfg.name} y")
+    # how far the 8-bit block is from the unquantised one (reported, loosely bounded: two 3-bit mantissas)
+    exact = U.oracle_fwd(cfg, inp)
+    rel = np.sqrt(np.mean((ref - exact) ** 2)) / np.sqrt(np.mean(exact ** 2))
+    print(f"{cfg.name}: relative rms distance of the E4M3 block from the fp64 block on unquantised inputs: {rel:.4f}")
+    assert rel < 0.06
+
+
+def test_impulse_recovers_the_quantised_weights():
+    """x = one unit sample in one channel: y[co, t] = decode(wq[co, ci, k]) * sw[co] * decode(xq) * sx at
+    t = t0 + pad - k, so every (chunk, lane half, byte) position of both operands is exercised on its own."""
+    import torch
+    B, Cin, Cout, T, K, pad = 1, 128, 64, 160, 17, 8
+    rng = np.random.default_rng(9)
+    w = syn.bf16_bits_to_f32(syn.f32_to_bf16_bits(rng.normal(0, 0.05, (Cout, Cin, K)).astype(np.float32)))
+    wd, _ = bf16_dev(w)
+    sw = f8.row_scales(w, Cout)
+    wq = f8.e4m3_decode(f8.quantize_rows(w, sw)) * sw.astype(np.float64)[:, None, None]
+    swd = torch.from_numpy(sw).cuda()
+    sxd = torch.ones(1, dtype=torch.float32, device="cuda")
+    t0 = 70
+    for ci in (0, 31, 32, 63, 64, 100, 127):
+        x = np.zeros((B, Cin, T), dtype=np.float32)
+        x[0, ci, t0] = 1.0
+        xd, _ = bf16_dev(x)
+        y = U.to_host_f64(nm.nm_conv1d_block_fwd_fp8(xd, sxd, wd, swd, stride=1, dilation=1, pad=pad))
+        expect = np.zeros((Cout, T))
+        for k in range(K):
+            expect[:, t0 + pad - k] = wq[:, ci, k]
+        got = y[0]
+        assert np.array_equal(got != 0, expect != 0), f"channel {ci}: support of the response"
+        np.testing.assert_allclose(got, expect, rtol=2.0 ** -8, atol=0)
