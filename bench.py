@@ -37,6 +37,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA peak (published)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak (published)
 
 
@@ -295,6 +296,79 @@ def decoder_report(steps, warmup, with_cpu):
     print(json.dumps(out), flush=True)
 
 
+def fp8_report(steps, warmup, shape, with_cpu):
+    """The block forward on E4M3 operands (nm_conv1d_block_fwd_fp8: both quantisation passes and the matrix-core
+    kernel in every step, scales taken once before the loop as a training loop with delayed scaling would).  One JSON
+    line: TFLOP/s of the call, and the main kernel against the dense fp8 MFMA peak.  `--fp8` only."""
+    import numpy as np
+    import torch
+    from paper_1909_09577_amd import binding as nm
+    B, C, K, T = {"512": (32, 512, 17, 800), "640": (32, 640, 21, 800), "768": (32, 768, 25, 800)}[shape]
+    pad = (K - 1) // 2
+    kw = dict(stride=1, dilation=1, pad=pad)
+    g = torch.Generator(device="cuda").manual_seed(8)
+    x = torch.randn(B, C, T, device="cuda", generator=g).bfloat16()
+    w = (torch.randn(C, C, K, device="cuda", generator=g) / (C * K) ** 0.5).bfloat16()
+    res = torch.randn(B, C, T, device="cuda", generator=g).bfloat16()
+    scale = torch.rand(C, device="cuda", generator=g) + 0.5
+    shift = torch.randn(C, device="cuda", generator=g) * 0.1
+    y = torch.empty_like(res)
+    sx, sw = nm.nm_fp8_row_scales(x, 1), nm.nm_fp8_row_scales(w, C)
+    ws = torch.empty(nm.nm_conv1d_fp8_workspace_bytes(B, C, C, T, K, 1, 1, pad), dtype=torch.uint8, device="cuda")
+
+    def step():
+        nm.nm_conv1d_block_fwd_fp8(x, sx, w, sw, scale, shift, res, y, relu=True, workspace=ws, **kw)
+
+    for _ in range(max(warmup, 1) + 100):
+        step()
+    torch.cuda.synchronize()
+    every = 4
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(0, steps, every)]
+    for a, b in pairs:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        if i % every == 0:
+            nm.nm_conv1d_time_next_main_kernel(*pairs[i // every])
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    ms_dev = e0.elapsed_time(e1) / steps
+    kms = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+    flop = 2 * B * C * T * C * K
+    alg = 2 * B * C * T + 2 * C * C * K + 2 * 2 * B * C * T  # x, w (bf16 in), residual, y
+    out = {"metric": f"conv1d block forward on E4M3 operands, TFLOP/s, C={C} K={K} T={T}", "value": round(flop / ms / 1e9, 1),
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+           "ms_per_step_device": round(ms_dev, 4), "higher_is_better": True, "dtype": "fp8 e4m3 operands, f32 accumulate, bf16 in/out",
+           "data": "synthetic",
+           "config": {"workload": f"B={B} Cin=Cout={C} T={T} K={K} stride 1 dilation 1 pad {pad}, affine+residual+ReLU, forward only",
+                      "step": "nm_conv1d_block_fwd_fp8 (quantise x, quantise+pack w, matrix-core kernel)"},
+           "frac_of_fp8_mfma_peak": round(flop / ms / 1e9 / PEAK_FP8_TFLOPS, 4),
+           "roofline": {"bound": "mfma", "achieved": round(flop / kms / 1e9, 1), "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(flop / kms / 1e9 / PEAK_FP8_TFLOPS, 4), "traffic": None,
+                        "kernel": f"fp8_conv_kernel<{K}, 1>", "flops_per_launch": flop, "algorithmic_bytes_per_launch": alg,
+                        "avg_launch_ms": round(kms, 4), "timed_launches": len(pairs)}}
+    if with_cpu:
+        from oracle import conv1d_oracle as orc
+        from oracle import fp8_oracle as f8
+        nb = 8
+        xs, wn = x[:nb].float().cpu().numpy(), w.float().cpu().numpy()
+        t0 = time.perf_counter()
+        sxo, swo = f8.row_scales(xs, 1), f8.row_scales(wn, C)
+        yo = f8.block_fwd_fp8(orc.block_fwd, f8.quantize_rows(xs, sxo), sxo[0], f8.quantize_rows(wn, swo), swo,
+                              scale.cpu().numpy(), shift.cpu().numpy(), res[:nb].float().cpu().numpy(), True, **kw)
+        dt = time.perf_counter() - t0
+        assert np.isfinite(yo).all()
+        out["cpu_baseline"] = {"value": round(flop * nb / B / dt / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(),
+                               "kind": "oracle", "sample": f"first {nb} of {B} batch items, quantisation + fp64 block, {dt:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -314,6 +388,8 @@ def main():
                     help="instead of the headline: the same block with training-mode BatchNorm (batch statistics)")
     ap.add_argument("--decoder", action="store_true",
                     help="instead of the headline: the decoder tail (1x1 conv + log-softmax), an HBM-bound step")
+    ap.add_argument("--fp8", choices=("512", "640", "768"), default=None,
+                    help="instead of the headline: the block forward on E4M3 operands at this channel count")
     ap.add_argument("--workload", default="b3", choices=sorted(WORKLOADS),
                     help="single-layer workload to time (default: the headline, b3); the others are for profiles")
     args = ap.parse_args()
@@ -340,6 +416,9 @@ def main():
         return
     if args.decoder:
         decoder_report(args.steps, args.warmup, not args.no_cpu_baseline)
+        return
+    if args.fp8:
+        fp8_report(args.steps, args.warmup, args.fp8, not args.no_cpu_baseline)
         return
 
     cfg = getattr(syn, WORKLOADS[args.workload])

@@ -42,6 +42,7 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
@@ -187,6 +188,7 @@ struct Fp8Params {
     int nbt;     // B * ntt (batch item, time tile) pairs
     int ntiles;  // ncot * 4 * ceil(nbt / 4): tile ids, some of them empty when nbt % 4 != 0
     int relu;
+    int vec_io;  // T_out % 8 == 0 and y, residual 16-byte aligned: rows are read and written in 16-byte pieces
     const unsigned char *xq;
     const unsigned char *wq;
     const float *xs, *ws, *scale, *shift;
@@ -380,28 +382,95 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
             cur ^= 1;
         }
 
-        // ---- epilogue: register r of block (mi, tb) is channel cot*64 + mi*32 + 8*(r/4) + 4*h + r%4, time tt*160 + tb*32 + n
-        const float sx = p.xs[0];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int co = tc.cot * kTileCo + mi * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                const float eff = (p.scale ? p.scale[co] : 1.f) * (sx * p.ws[co]);
-                const float sh = p.shift ? p.shift[co] : 0.f;
-                const size_t row = ((size_t)tc.b * p.Cout + co) * p.To;
-#pragma unroll
-                for (int tb = 0; tb < kNT; ++tb) {
-                    const int t = tc.tt * kTileT + tb * 32 + n;
-                    if (t < p.To) {
-                        float v = acc[mi][tb][r] * eff + sh;
-                        if (p.res) v += bf16_to_f32(p.res[row + t]);
-                        if (p.relu) v = fmaxf(v, 0.f);
-                        p.y[row + t] = f32_to_bf16(v);
-                    }
-                    acc[mi][tb][r] = 0.f;
-                }
+        // ---- epilogue: register r of block (mi, tb) is channel cot*64 + mi*32 + 8*(r/4) + 4*h + r%4, time tt*160 + tb*32 + n.
+        // The tile leaves in four quarters of 16 channels: every lane writes the float32 values scale*acc + shift of
+        // the 40 elements it owns to a [16][160] LDS tile, then each lane takes 8 consecutive time steps of a row (two
+        // 16-byte LDS reads), adds the residual (one 16-byte load, requested a quarter ahead), applies the ReLU, rounds
+        // and stores 16 bytes.  The LDS tile is the window of this tile's last chunk, which is dead (the other buffer
+        // holds the next tile's first window).
+        {
+            const float sx = p.xs[0];
+            unsigned char *const ebuf = lds + (cur ^ 1) * P::BUF;
+            constexpr int kQPitch = kTileT * 4 + 16;
+            static_assert(16 * kQPitch + 512 <= P::BUF, "the epilogue tile must fit a window buffer");
+            constexpr int kVecPerRow = kTileT / 8, kVec = 16 * kVecPerRow / 64;  // 20 per row, 5 per lane
+            // per-row factor and shift of the tile's 64 channels: one load per lane, parked behind the tile
+            float *const rowf = reinterpret_cast<float *>(ebuf + 16 * kQPitch);
+            {
+                const int co = tc.cot * kTileCo + lane;
+                rowf[lane] = (p.scale ? p.scale[co] : 1.f) * (sx * p.ws[co]);
+                rowf[64 + lane] = p.shift ? p.shift[co] : 0.f;
             }
+            const bool vec_res = p.res && p.vec_io;
+            u32x4 rv[2][kVec];
+            auto load_residual = [&](u32x4(&dst)[kVec], int q) {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) {
+                    const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
+                    const int t = tc.tt * kTileT + col * 8;
+                    const size_t off = ((size_t)tc.b * p.Cout + tc.cot * kTileCo + q * 16 + row) * p.To + t;
+                    dst[j] = t < p.To ? *reinterpret_cast<const u32x4 *>(p.res + off) : u32x4{0u, 0u, 0u, 0u};
+                }
+            };
+            if (vec_res) load_residual(rv[0], 0);
+            wave_lds_fence();
+            static_for<4>([&](auto qc) {
+                constexpr int q = decltype(qc)::value, mi = q / 2, r0 = 8 * (q % 2);
+                f32x4 e4[2], s4[2];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    e4[j] = *reinterpret_cast<const f32x4 *>(rowf + q * 16 + 8 * j + 4 * h);
+                    s4[j] = *reinterpret_cast<const f32x4 *>(rowf + 64 + q * 16 + 8 * j + 4 * h);
+                }
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int j = rr >> 2, i = rr & 3, rl = 8 * j + 4 * h + i;
+#pragma unroll
+                    for (int tb = 0; tb < kNT; ++tb) {
+                        *reinterpret_cast<float *>(ebuf + rl * kQPitch + (tb * 32 + n) * 4) = acc[mi][tb][r0 + rr] * e4[j][i] + s4[j][i];
+                        acc[mi][tb][r0 + rr] = 0.f;
+                    }
+                }
+                if constexpr (q < 3) {
+                    if (vec_res) load_residual(rv[(q + 1) & 1], q + 1);
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) {
+                    const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
+                    const int t = tc.tt * kTileT + col * 8;
+                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32);
+                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32 + 16);
+                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    const size_t off = ((size_t)tc.b * p.Cout + tc.cot * kTileCo + q * 16 + row) * p.To + t;
+                    if (p.vec_io) {
+                        if (t < p.To) {
+                            if (p.res) {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    v[e] += bf16_to_f32((bf16_t)((rv[q & 1][j][e >> 1] >> (16 * (e & 1))) & 0xffffu));
+                            }
+                            if (p.relu) {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                            }
+                            const u32x4 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                                             pack_bf16x2(v[6], v[7])};
+                            *reinterpret_cast<u32x4 *>(p.y + off) = o;
+                        }
+                    } else {  // rows that are not 16-byte pieces: element by element
+                        for (int e = 0; e < 8; ++e) {
+                            if (t + e < p.To) {
+                                float u = v[e];
+                                if (p.res) u += bf16_to_f32(p.res[off + e]);
+                                if (p.relu) u = fmaxf(u, 0.f);
+                                p.y[off + e] = f32_to_bf16(u);
+                            }
+                        }
+                    }
+                }
+                wave_lds_fence();
+            });
         }
         if (!has_next) break;
         id = nid;
@@ -548,6 +617,7 @@ extern "C" int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, i
     p.nbt = B * l.ntt;
     p.ntiles = l.ncot * 4 * ((p.nbt + 3) / 4);
     p.relu = (flags & NM_RELU) ? 1 : 0;
+    p.vec_io = (To % 8 == 0 && !((uintptr_t)y & 15) && !((uintptr_t)residual & 15)) ? 1 : 0;
     p.xq = xq; p.wq = wq;
     p.xs = x_scale; p.ws = w_scales; p.scale = scale; p.shift = shift;
     p.res = (const bf16_t *)residual;
