@@ -225,6 +225,14 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
 }
 
+// The lane number, recomputed where it is needed (two ALU operations).
+__device__ __forceinline__ int fresh_lane()
+{
+    int l = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(l));
+    return l;
+}
+
 __device__ __forceinline__ void wave_lds_fence()
 {
     // LDS operations of one wavefront execute in order; this only keeps the compiler from moving LDS
@@ -263,10 +271,12 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
     const size_t chunk_stride = (size_t)p.Tp * kChunk;              // bytes between the windows of consecutive chunks
     const size_t wtile_bytes = (size_t)p.nck * KT * kTapBytes;
 
+    // base pointers are the same for all lanes (scalar registers); the lane's share is a 32-bit offset
+    const uint32_t lane16 = lane * 16, lane32 = lane * 32;
     auto window_base = [&](const TileCoords &t) {
-        return p.xq + ((size_t)t.b * p.nck * p.Tp + (size_t)t.tt * kTileT) * kChunk + lane * 16;
+        return p.xq + ((size_t)t.b * p.nck * p.Tp + (size_t)t.tt * kTileT) * kChunk;
     };
-    auto weights_base = [&](const TileCoords &t) { return p.wq + (size_t)t.cot * wtile_bytes + lane * 32; };
+    auto weights_base = [&](const TileCoords &t) { return p.wq + (size_t)t.cot * wtile_bytes; };
 
     // first valid tile of this wavefront
     int id = wid;
@@ -291,8 +301,8 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
     auto load_a = [&](i32x8(&dst)[2], const unsigned char *src) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) {
-            const u32x4 lo = *reinterpret_cast<const u32x4 *>(src + mi * kFragBytes);
-            const u32x4 hi = *reinterpret_cast<const u32x4 *>(src + mi * kFragBytes + 16);
+            const u32x4 lo = *reinterpret_cast<const u32x4 *>(src + lane32 + mi * kFragBytes);
+            const u32x4 hi = *reinterpret_cast<const u32x4 *>(src + lane32 + mi * kFragBytes + 16);
             dst[mi] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
         }
     };
@@ -307,7 +317,7 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
     const unsigned char *wcur = weights_base(tc);
     static_for<P::NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        stage[i] = *reinterpret_cast<const u32x4 *>(xcur + i * 1024);
+        stage[i] = *reinterpret_cast<const u32x4 *>(xcur + lane16 + i * 1024);
     });
     static_for<P::NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
@@ -348,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                 // window of the next chunk: request pieces, write the ones requested kAhead taps ago
                 static_for<P::NIT>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
-                    if constexpr (P::load_tap(i) == k) stage[i] = *reinterpret_cast<const u32x4 *>(xnxt + i * 1024);
+                    if constexpr (P::load_tap(i) == k) stage[i] = *reinterpret_cast<const u32x4 *>(xnxt + lane16 + i * 1024);
                 });
                 static_for<P::NIT>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
@@ -389,8 +399,12 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
         // and stores 16 bytes.  The LDS tile is the window of this tile's last chunk, which is dead (the other buffer
         // holds the next tile's first window).
         {
+            // lane-dependent values are recomputed here: kept alive across the main loop they would be spilled, and
+            // the reload of a spilled value waits for every memory operation in flight
+            const int lane = fresh_lane();
+            const int n = lane & 31, h = lane >> 5;
             const float sx = p.xs[0];
-            unsigned char *const ebuf = lds + (cur ^ 1) * P::BUF;
+            unsigned char *const ebuf = smem + wave * (2 * P::BUF) + (cur ^ 1) * P::BUF;
             constexpr int kQPitch = kTileT * 4 + 16;
             static_assert(16 * kQPitch + 512 <= P::BUF, "the epilogue tile must fit a window buffer");
             constexpr int kVecPerRow = kTileT / 8, kVec = 16 * kVecPerRow / 64;  // 20 per row, 5 per lane
