@@ -187,6 +187,9 @@ struct Fp8Params {
     int ncot, nck, ntt, Tp;
     int nbt;     // B * ntt (batch item, time tile) pairs
     int ntiles;  // ncot * 4 * ceil(nbt / 4): tile ids, some of them empty when nbt % 4 != 0
+    int priv_rounds;    // tiles below shared_first are private: wavefront w takes w, w + nwaves, ... (this many rounds)
+    int shared_first;   // tiles from here on are shared by the four wavefronts of a workgroup (ntiles: none)
+    int shared_rounds;  // ceil((ntiles - shared_first) / grid)
     int relu;
     int vec_io;  // T_out % 8 == 0 and y, residual 16-byte aligned: rows are read and written in 16-byte pieces
     const unsigned char *xq;
@@ -249,6 +252,9 @@ struct Plan {
     static constexpr int BUF = NIT * 16 * kRowBytes;  // one LDS window buffer of a wavefront
     static constexpr int SPAN = KT - 1 - kAhead;      // taps over which the window requests are spread
     static_assert(SPAN >= 1, "too few taps for the staging schedule");
+    static constexpr int XCH = 4 * 40 * 64 * 4;  // LDS for the exchange of partial tiles: 4 wavefronts x 40 floats per lane
+    static constexpr bool kShared = kWaves * 2 * BUF + XCH <= 160 * 1024;
+    static constexpr int LDS = kWaves * 2 * BUF + (kShared ? XCH : 0);
     static constexpr int set_of(int k) { return k < Q4 ? k % 4 : 4 + (k - Q4); }
     static constexpr int load_tap(int i) { return i * SPAN / NIT; }
 };
@@ -262,30 +268,56 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wid = blockIdx.x * kWaves + wave;
     const int nwaves = gridDim.x * kWaves;
-    if (wid >= p.ntiles) return;
-
     unsigned char *const lds = smem + wave * (2 * P::BUF);
     const int n = lane & 31, h = lane >> 5;
     const int rd_lane = n * kRowBytes + 32 * h;                    // B fragment: row n, channels 32h..32h+31
     const int wr_lane = (lane >> 2) * kRowBytes + (lane & 3) * 16;  // window piece: row lane/4, quarter lane%4
     const size_t chunk_stride = (size_t)p.Tp * kChunk;              // bytes between the windows of consecutive chunks
-    const size_t wtile_bytes = (size_t)p.nck * KT * kTapBytes;
+    const size_t wchunk_bytes = (size_t)KT * kTapBytes;
 
     // base pointers are the same for all lanes (scalar registers); the lane's share is a 32-bit offset
     const uint32_t lane16 = lane * 16, lane32 = lane * 32;
-    auto window_base = [&](const TileCoords &t) {
-        return p.xq + ((size_t)t.b * p.nck * p.Tp + (size_t)t.tt * kTileT) * kChunk;
-    };
-    auto weights_base = [&](const TileCoords &t) { return p.wq + (size_t)t.cot * wtile_bytes; };
 
-    // first valid tile of this wavefront
-    int id = wid;
-    TileCoords tc = decode_tile(p, id);
-    while (!tc.valid) {
-        id += nwaves;
-        if (id >= p.ntiles) return;
-        tc = decode_tile(p, id);
-    }
+    // ---- the wavefront's work items, in order: private tiles (sequence numbers below priv_rounds: tile
+    // wid + s*nwaves, all chunks), then the workgroup's shared tiles (tile shared_first + blockIdx + j*grid: the
+    // four wavefronts take chunks wave, wave+4, ... and sum their partial tiles through LDS).  Everything here
+    // is the same for all lanes, and the list of shared tiles is the same for the four wavefronts of a workgroup.
+    struct Item {
+        TileCoords t;
+        int c0, cs;
+        bool shared;
+        const unsigned char *x0, *w0;  // window and weights of the item's first chunk
+    };
+    const int nseq = p.priv_rounds + p.shared_rounds;
+    auto item_at = [&](int sq, Item &it) -> bool {
+        int id;
+        if (sq < p.priv_rounds) {
+            id = wid + sq * nwaves;
+            if (id >= p.shared_first) return false;
+            it.shared = false;
+            it.c0 = 0;
+            it.cs = 1;
+        } else {
+            id = p.shared_first + (int)blockIdx.x + (sq - p.priv_rounds) * (int)gridDim.x;
+            if (id >= p.ntiles) return false;
+            it.shared = true;
+            it.c0 = wave;
+            it.cs = kWaves;
+        }
+        it.t = decode_tile(p, id);
+        if (!it.t.valid) return false;
+        it.x0 = p.xq + (((size_t)it.t.b * p.nck + it.c0) * p.Tp + (size_t)it.t.tt * kTileT) * kChunk;
+        it.w0 = p.wq + ((size_t)it.t.cot * p.nck + it.c0) * wchunk_bytes;
+        return true;
+    };
+    auto next_item = [&](int from, Item &it) -> int {  // first sequence number >= from with an item, or nseq
+        int sq = from;
+        while (sq < nseq && !item_at(sq, it)) ++sq;
+        return sq;
+    };
+    Item item;
+    int seq = next_item(0, item);
+    if (seq >= nseq) return;  // nothing to do (then the workgroup has no shared tile either)
 
     u32x4 stage[P::NIT];
     i32x8 aset[P::NSETS][2];
@@ -312,9 +344,9 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
         dst = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
     };
 
-    // ---- prologue: the first tile's first window, weight sets and B fragments
-    const unsigned char *xcur = window_base(tc);
-    const unsigned char *wcur = weights_base(tc);
+    // ---- prologue: the first item's first window, weight sets and B fragments
+    const unsigned char *xcur = item.x0;
+    const unsigned char *wcur = item.w0;
     static_for<P::NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
         stage[i] = *reinterpret_cast<const u32x4 *>(xcur + lane16 + i * 1024);
@@ -335,21 +367,18 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
     int cur = 0;  // LDS buffer that holds the current chunk's window
 
     for (;;) {
-        // the tile after this one (if any) supplies the "next chunk" of this tile's last chunk
-        int nid = id + nwaves;
-        TileCoords nt = decode_tile(p, nid);
-        while (nid < p.ntiles && !nt.valid) {
-            nid += nwaves;
-            nt = decode_tile(p, nid);
-        }
-        const bool has_next = nid < p.ntiles;
-        const unsigned char *xnext_tile = has_next ? window_base(nt) : window_base(tc);
-        const unsigned char *wnext_tile = has_next ? weights_base(nt) : weights_base(tc);
+        // the item after this one (if any) supplies the "next chunk" of this item's last chunk
+        Item nxt;
+        const int nseq_next = next_item(seq + 1, nxt);
+        const bool has_next = nseq_next < nseq;
+        const unsigned char *xnext_item = has_next ? nxt.x0 : item.x0;
+        const unsigned char *wnext_item = has_next ? nxt.w0 : item.w0;
+        const TileCoords tc = item.t;
 
-        for (int c = 0; c < p.nck; ++c) {
-            const bool last = c + 1 == p.nck;
-            const unsigned char *xnxt = last ? xnext_tile : xcur + chunk_stride;
-            const unsigned char *wnxt = last ? wnext_tile : wcur + KT * kTapBytes;
+        for (int c = item.c0; c < p.nck; c += item.cs) {
+            const bool last = c + item.cs >= p.nck;
+            const unsigned char *xnxt = last ? xnext_item : xcur + item.cs * chunk_stride;
+            const unsigned char *wnxt = last ? wnext_item : wcur + item.cs * wchunk_bytes;
             unsigned char *const bcur = lds + cur * P::BUF;
             unsigned char *const bnxt = lds + (cur ^ 1) * P::BUF;
 
@@ -392,12 +421,44 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
             cur ^= 1;
         }
 
+        // ---- a shared tile: the four partial tiles are summed in four rounds, one quarter (16 channels: block row
+        // mi = q/2, registers 8*(q%2) .. +7 of every time block) per round -- the other three wavefronts park their
+        // 40 values per lane in LDS and wavefront q adds them in a fixed order, position by position.
+        if constexpr (P::kShared) {
+            if (item.shared) {
+                const int l = fresh_lane();
+                float *const xch = reinterpret_cast<float *>(smem + kWaves * 2 * P::BUF);
+                static_for<4>([&](auto qc) {
+                    constexpr int q = decltype(qc)::value, mi = q / 2, r0 = 8 * (q % 2);
+                    if (wave != q) {
+#pragma unroll
+                        for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+                            for (int tb = 0; tb < kNT; ++tb) xch[((wave * 40) + rr * kNT + tb) * 64 + l] = acc[mi][tb][r0 + rr];
+                    }
+                    __syncthreads();
+                    if (wave == q) {
+                        static_for<4>([&](auto wc) {
+                            constexpr int w2 = decltype(wc)::value;
+                            if constexpr (w2 != q) {
+#pragma unroll
+                                for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+                                    for (int tb = 0; tb < kNT; ++tb) acc[mi][tb][r0 + rr] += xch[((w2 * 40) + rr * kNT + tb) * 64 + l];
+                            }
+                        });
+                    }
+                    __syncthreads();
+                });
+            }
+        }
+
         // ---- epilogue: register r of block (mi, tb) is channel cot*64 + mi*32 + 8*(r/4) + 4*h + r%4, time tt*160 + tb*32 + n.
-        // The tile leaves in four quarters of 16 channels: every lane writes the float32 values scale*acc + shift of
-        // the 40 elements it owns to a [16][160] LDS tile, then each lane takes 8 consecutive time steps of a row (two
-        // 16-byte LDS reads), adds the residual (one 16-byte load, requested a quarter ahead), applies the ReLU, rounds
-        // and stores 16 bytes.  The LDS tile is the window of this tile's last chunk, which is dead (the other buffer
-        // holds the next tile's first window).
+        // The tile leaves in quarters of 16 channels (all four for a private tile, quarter `wave` for a shared one): every
+        // lane writes the float32 values scale*acc + shift of the 40 elements it owns to a [16][160] LDS tile, then each
+        // lane takes 8 consecutive time steps of a row (two 16-byte LDS reads), adds the residual (one 16-byte load,
+        // requested a quarter ahead), applies the ReLU, rounds and stores 16 bytes.  The LDS tile is the window of this
+        // item's last chunk, which is dead (the other buffer holds the next item's first window).
         {
             // lane-dependent values are recomputed here: kept alive across the main loop they would be spilled, and
             // the reload of a spilled value waits for every memory operation in flight
@@ -426,10 +487,13 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                     dst[j] = t < p.To ? *reinterpret_cast<const u32x4 *>(p.res + off) : u32x4{0u, 0u, 0u, 0u};
                 }
             };
-            if (vec_res) load_residual(rv[0], 0);
             wave_lds_fence();
-            static_for<4>([&](auto qc) {
+            // one quarter; LOAD_OWN: request its residual first, LOAD_NEXT: request the next quarter's in the middle
+            auto quarter = [&](auto qc, auto load_own, auto load_next) {
                 constexpr int q = decltype(qc)::value, mi = q / 2, r0 = 8 * (q % 2);
+                if constexpr (decltype(load_own)::value) {
+                    if (vec_res) load_residual(rv[q & 1], q);
+                }
                 f32x4 e4[2], s4[2];
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
@@ -440,12 +504,10 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                 for (int rr = 0; rr < 8; ++rr) {
                     const int j = rr >> 2, i = rr & 3, rl = 8 * j + 4 * h + i;
 #pragma unroll
-                    for (int tb = 0; tb < kNT; ++tb) {
+                    for (int tb = 0; tb < kNT; ++tb)
                         *reinterpret_cast<float *>(ebuf + rl * kQPitch + (tb * 32 + n) * 4) = acc[mi][tb][r0 + rr] * e4[j][i] + s4[j][i];
-                        acc[mi][tb][r0 + rr] = 0.f;
-                    }
                 }
-                if constexpr (q < 3) {
+                if constexpr (decltype(load_next)::value) {
                     if (vec_res) load_residual(rv[(q + 1) & 1], q + 1);
                 }
                 wave_lds_fence();
@@ -484,27 +546,69 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                     }
                 }
                 wave_lds_fence();
-            });
+            };
+            using T = std::true_type;
+            using F = std::false_type;
+            using std::integral_constant;
+            if (!item.shared) {
+                quarter(integral_constant<int, 0>{}, T{}, T{});
+                quarter(integral_constant<int, 1>{}, F{}, T{});
+                quarter(integral_constant<int, 2>{}, F{}, T{});
+                quarter(integral_constant<int, 3>{}, F{}, F{});
+            } else if (wave == 0) {
+                quarter(integral_constant<int, 0>{}, T{}, F{});
+            } else if (wave == 1) {
+                quarter(integral_constant<int, 1>{}, T{}, F{});
+            } else if (wave == 2) {
+                quarter(integral_constant<int, 2>{}, T{}, F{});
+            } else {
+                quarter(integral_constant<int, 3>{}, T{}, F{});
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int tb = 0; tb < kNT; ++tb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mi][tb][r] = 0.f;
         }
         if (!has_next) break;
-        id = nid;
-        tc = nt;
+        seq = nseq_next;
+        item = nxt;
     }
 }
 
 template <int KT, int DIL>
-hipError_t launch_fp8_conv(const Fp8Params &p, hipStream_t s)
+hipError_t launch_fp8_conv(Fp8Params p, hipStream_t s)
 {
     using P = Plan<KT, DIL>;
     static LdsOptIn opt_in;
-    constexpr int lds = kWaves * 2 * P::BUF;
-    static_assert(lds <= 160 * 1024, "LDS windows exceed the CU");
-    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(fp8_conv_kernel<KT, DIL>), lds);
+    static_assert(P::LDS <= 160 * 1024, "LDS windows exceed the CU");
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(fp8_conv_kernel<KT, DIL>), P::LDS);
     if (e != hipSuccess) return e;
-    const int cus = current_device_info().cus;
-    const int grid = min(cus, (p.ntiles + kWaves - 1) / kWaves);
+    // Tiles are dealt in rounds of one per wavefront.  A last partial round of at most two tiles per workgroup is
+    // run in shared form (four wavefronts per tile, a quarter of the reduction each) so that the chip stays full;
+    // a larger remainder is cheaper as one more private round.
+    const int G = current_device_info().cus, nw_max = G * kWaves;
+    const bool can_share = P::kShared && p.nck >= kWaves;
+    int grid;
+    if (p.ntiles >= nw_max) {
+        grid = G;
+        const int full = p.ntiles / nw_max, rem = p.ntiles - full * nw_max;
+        const bool share = can_share && rem <= 2 * G;
+        p.priv_rounds = share ? full : full + (rem > 0 ? 1 : 0);
+        p.shared_first = share ? full * nw_max : p.ntiles;
+    } else if (can_share && p.ntiles <= 2 * G) {
+        grid = min(G, p.ntiles);
+        p.priv_rounds = 0;
+        p.shared_first = 0;
+    } else {
+        grid = (p.ntiles + kWaves - 1) / kWaves;
+        p.priv_rounds = 1;
+        p.shared_first = p.ntiles;
+    }
+    p.shared_rounds = (p.ntiles - p.shared_first + grid - 1) / grid;
     MainKernelTimer timer(s);
-    hipLaunchKernelGGL((fp8_conv_kernel<KT, DIL>), dim3(grid), dim3(kThreads), lds, s, p);
+    hipLaunchKernelGGL((fp8_conv_kernel<KT, DIL>), dim3(grid), dim3(kThreads), P::LDS, s, p);
     return hipGetLastError();
 }
 

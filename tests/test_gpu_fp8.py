@@ -80,6 +80,12 @@ CASES = [
     L("f8_long_pad", 2, 64, 64, 100, 17, pad=16, residual=True),          # T_out > T
     L("f8_one_frame_tile", 1, 64, 64, 161, 17),                           # a time tile with a single valid frame
     L("f8_many_tiles", 32, 64, 256, 1600, 17, residual=True),             # 1280 tiles: every wavefront runs a second tile
+    # few tiles and at least four chunks: every tile is shared by the four wavefronts of a workgroup
+    L("f8_shared_8", 2, 256, 128, 200, 17, residual=True),
+    L("f8_shared_uneven_chunks", 3, 320, 64, 333, 21, residual=True),     # 5 chunks over 4 wavefronts, empty tile ids, odd length
+    L("f8_shared_k25", 2, 512, 192, 320, 25, relu=False),
+    # more tiles than wavefronts with a small remainder: private rounds followed by a shared one
+    L("f8_private_then_shared", 33, 256, 256, 1280, 17, residual=True),   # 33*8*4 = 1056 tiles = 1024 + 32
 ]
 
 
