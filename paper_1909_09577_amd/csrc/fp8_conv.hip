@@ -140,11 +140,59 @@ __global__ __launch_bounds__(256) void quant_x_kernel(const bf16_t *__restrict__
     *reinterpret_cast<u32x4 *>(xq + (((size_t)b * gridDim.y + c) * Tp + r) * 64 + cg * 16) = out;
 }
 
+// The same for T % 8 == 0 and 16-byte aligned x: 16-byte loads along T, the transposition to time-major rows goes
+// through LDS.  grid (ceil(T/128), Cin/64, B); a block converts 64 channels x 128 time steps.  Thread (g, tv) loads 8
+// time steps of the four channels 4g..4g+3 and writes eight dwords (four channel codes of one time step each); then
+// every thread copies 16-byte pieces of finished rows out.  The first and the last block of a row of blocks also
+// write the zero rows before time 0 and behind time T.
+constexpr int kQxT = 128;
+__global__ __launch_bounds__(256) void quant_x_vec_kernel(const bf16_t *__restrict__ x, const float *__restrict__ xs,
+                                                          unsigned char *__restrict__ xq, int Cin, int T, int Tp, int pad)
+{
+    __shared__ __align__(16) unsigned char tile[kQxT * kRowBytes];
+    const int c = blockIdx.y, b = blockIdx.z, nck = gridDim.y;
+    const int t0 = blockIdx.x * kQxT;
+    const int g = threadIdx.x & 15, tv = threadIdx.x >> 4;
+    const float inv = 1.0f / xs[0];
+    const int t = t0 + tv * 8;
+    if (t < T) {
+        const bf16_t *src = x + ((size_t)b * Cin + c * 64 + g * 4) * T + t;
+        u32x4 raw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4 *>(src + (size_t)j * T);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t d = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bf16_t hv = (bf16_t)((raw[j][e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                d |= f32_to_e4m3(bf16_to_f32(hv) * inv) << (8 * j);
+            }
+            *reinterpret_cast<uint32_t *>(tile + (tv * 8 + e) * kRowBytes + g * 4) = d;
+        }
+    }
+    __syncthreads();
+    unsigned char *const slab = xq + ((size_t)b * nck + c) * Tp * 64;
+    const int rows = min(kQxT, T - t0);
+    for (int i = threadIdx.x; i < rows * 4; i += 256) {
+        const int row = i >> 2, q = i & 3;
+        *reinterpret_cast<u32x4 *>(slab + (size_t)(t0 + row + pad) * 64 + q * 16) =
+            *reinterpret_cast<const u32x4 *>(tile + row * kRowBytes + q * 16);
+    }
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < pad * 4; i += 256) *reinterpret_cast<u32x4 *>(slab + (size_t)i * 16) = zero;
+    if (blockIdx.x == gridDim.x - 1)
+        for (int i = threadIdx.x; i < (Tp - T - pad) * 4; i += 256)
+            *reinterpret_cast<u32x4 *>(slab + (size_t)(T + pad) * 64 + (size_t)i * 16) = zero;
+}
+
 // w [Cout][Cin][K] bf16 -> wq[Cout/64][Cin/64][K][2][64][32] codes.  One block per (channel tile, chunk,
 // row half): its 32 rows of 64*K weights are contiguous pieces of memory; they go through LDS as codes.
 // Lane l of a fragment holds row l%32 and the 32 channels 32*(l/32) .. +31 of the chunk.
-__global__ __launch_bounds__(256) void pack_w_kernel(const bf16_t *__restrict__ w, const float *__restrict__ wsc,
-                                                     unsigned char *__restrict__ wq, int Cin, int K)
+constexpr int kPackThreads = 1024;
+__global__ __launch_bounds__(kPackThreads) void pack_w_kernel(const bf16_t *__restrict__ w, const float *__restrict__ wsc,
+                                                              unsigned char *__restrict__ wq, int Cin, int K)
 {
     extern __shared__ __align__(16) unsigned char codes[];  // [32][pitch]
     const int mi = blockIdx.x & 1, c = blockIdx.y, cot = blockIdx.z;
@@ -152,21 +200,33 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const bf16_t *__restrict__ 
     const int rowlen = 64 * K;       // codes per row
     const int pitch = rowlen + 8;    // keeps the 8-byte writes aligned
     const int vec_per_row = rowlen / 8;
-    for (int v = threadIdx.x; v < 32 * vec_per_row; v += 256) {
-        const int row = v / vec_per_row, col = v - row * vec_per_row;
-        const int co = cot * 64 + mi * 32 + row;
-        const float inv = 1.0f / wsc[co];
-        const u32x4 raw = *reinterpret_cast<const u32x4 *>(w + ((size_t)co * Cin + c * 64) * K + col * 8);
-        u32x2 o = {0u, 0u};
+    const int nvec = 32 * vec_per_row;
+    for (int base = 0; base < nvec; base += 4 * kPackThreads) {
+        u32x4 raw[4];
+        int row[4], col[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bf16_t h = (bf16_t)((raw[j >> 1] >> (16 * (j & 1))) & 0xffffu);
-            o[j >> 2] |= f32_to_e4m3(bf16_to_f32(h) * inv) << (8 * (j & 3));
+        for (int u = 0; u < 4; ++u) {  // four loads in flight
+            const int v = base + u * kPackThreads + threadIdx.x;
+            row[u] = v / vec_per_row;
+            col[u] = v - row[u] * vec_per_row;
+            if (v < nvec)
+                raw[u] = *reinterpret_cast<const u32x4 *>(w + ((size_t)(cot * 64 + mi * 32 + row[u]) * Cin + c * 64) * K + col[u] * 8);
         }
-        *reinterpret_cast<u32x2 *>(codes + row * pitch + col * 8) = o;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (base + u * kPackThreads + (int)threadIdx.x >= nvec) continue;
+            const float inv = 1.0f / wsc[cot * 64 + mi * 32 + row[u]];
+            u32x2 o = {0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bf16_t hv = (bf16_t)((raw[u][j >> 1] >> (16 * (j & 1))) & 0xffffu);
+                o[j >> 2] |= f32_to_e4m3(bf16_to_f32(hv) * inv) << (8 * (j & 3));
+            }
+            *reinterpret_cast<u32x2 *>(codes + row[u] * pitch + col[u] * 8) = o;
+        }
     }
     __syncthreads();
-    for (int it = threadIdx.x; it < K * 64; it += 256) {
+    for (int it = threadIdx.x; it < K * 64; it += kPackThreads) {
         const int k = it >> 6, lane = it & 63;
         const unsigned char *src = codes + (lane & 31) * pitch + (32 * (lane >> 5)) * K + k;
         u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
@@ -723,10 +783,14 @@ extern "C" int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, i
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char *xq = (unsigned char *)workspace;
     unsigned char *wq = xq + l.xq_bytes;
-    hipLaunchKernelGGL(quant_x_kernel, dim3((l.Tp + 63) / 64, l.nck, B), dim3(256), 0, s, (const bf16_t *)x, x_scale, xq,
-                       Cin, T, l.Tp, pad);
-    hipLaunchKernelGGL(pack_w_kernel, dim3(2, l.nck, l.ncot), dim3(256), (size_t)32 * (64 * K + 8), s, (const bf16_t *)w,
-                       w_scales, wq, Cin, K);
+    if (T % 8 == 0 && !((uintptr_t)x & 15))
+        hipLaunchKernelGGL(quant_x_vec_kernel, dim3((T + kQxT - 1) / kQxT, l.nck, B), dim3(256), 0, s, (const bf16_t *)x,
+                           x_scale, xq, Cin, T, l.Tp, pad);
+    else
+        hipLaunchKernelGGL(quant_x_kernel, dim3((l.Tp + 63) / 64, l.nck, B), dim3(256), 0, s, (const bf16_t *)x, x_scale, xq,
+                           Cin, T, l.Tp, pad);
+    hipLaunchKernelGGL(pack_w_kernel, dim3(2, l.nck, l.ncot), dim3(kPackThreads), (size_t)32 * (64 * K + 8), s,
+                       (const bf16_t *)w, w_scales, wq, Cin, K);
     if (hipGetLastError() != hipSuccess) return NM_ERR_DEVICE;
 
     Fp8Params p;
