@@ -58,22 +58,18 @@ constexpr size_t kSlack = 8192;            // bytes behind each quantised tensor
 constexpr float kE4M3Max = 448.0f;
 
 // ---------------------------------------------------------------------------------------------
-// E4M3 conversion (software: the rule is part of the result, so it is spelled out rather than left to
-// a conversion instruction).  Round to nearest, ties to even, saturate at +-448, NaN -> 0x7F.
-__device__ __forceinline__ uint32_t f32_to_e4m3(float f)
+// E4M3 conversion: round to nearest, ties to even, saturating at +-448.  The hardware conversion
+// (v_cvt_pk_fp8_f32, two values per instruction) rounds to nearest even; the saturation is made explicit by
+// clamping first.  Inputs are finite by contract (a NaN gives a NaN code).
+__device__ __forceinline__ float clamp_e4m3(float v) { return __builtin_fminf(__builtin_fmaxf(v, -448.0f), 448.0f); }
+// codes of a, b, c, d in bytes 0..3
+__device__ __forceinline__ uint32_t e4m3_pack4(float a, float b, float c, float d)
 {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t sign = (u >> 24) & 0x80u;
-    const uint32_t a = u & 0x7fffffffu;
-    if (a > 0x7f800000u) return 0x7fu;
-    if (a >= 0x43e00000u) return sign | 0x7eu;  // |f| >= 448
-    if (a < 0x3c800000u) {                      // |f| < 2^-6: multiples of 2^-9 (8 of them reach 2^-6 = code 0x08)
-        const float r = __builtin_rintf(__uint_as_float(a) * 512.0f);
-        return sign | (uint32_t)r;
-    }
-    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);  // keep 3 mantissa bits
-    return sign | ((r >> 20) - (120u << 3));             // exponent bias 127 -> 7
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(a), clamp_e4m3(b), 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(c), clamp_e4m3(d), r, true);
+    return (uint32_t)r;
 }
+__device__ __forceinline__ uint32_t f32_to_e4m3(float f) { return e4m3_pack4(f, 0.f, 0.f, 0.f) & 0xffu; }
 
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -132,10 +128,9 @@ __global__ __launch_bounds__(256) void quant_x_kernel(const bf16_t *__restrict__
         const float inv = 1.0f / xs[0];
         const bf16_t *src = x + ((size_t)b * Cin + c * 64 + cg * 16) * T + t;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const uint32_t code = f32_to_e4m3(bf16_to_f32(src[(size_t)j * T]) * inv);
-            out[j >> 2] |= code << (8 * (j & 3));
-        }
+        for (int j = 0; j < 4; ++j)
+            out[j] = e4m3_pack4(bf16_to_f32(src[(size_t)(4 * j) * T]) * inv, bf16_to_f32(src[(size_t)(4 * j + 1) * T]) * inv,
+                                bf16_to_f32(src[(size_t)(4 * j + 2) * T]) * inv, bf16_to_f32(src[(size_t)(4 * j + 3) * T]) * inv);
     }
     *reinterpret_cast<u32x4 *>(xq + (((size_t)b * gridDim.y + c) * Tp + r) * 64 + cg * 16) = out;
 }
@@ -162,13 +157,10 @@ __global__ __launch_bounds__(256) void quant_x_vec_kernel(const bf16_t *__restri
         for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4 *>(src + (size_t)j * T);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            uint32_t d = 0;
+            float v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bf16_t hv = (bf16_t)((raw[j][e >> 1] >> (16 * (e & 1))) & 0xffffu);
-                d |= f32_to_e4m3(bf16_to_f32(hv) * inv) << (8 * j);
-            }
-            *reinterpret_cast<uint32_t *>(tile + (tv * 8 + e) * kRowBytes + g * 4) = d;
+            for (int j = 0; j < 4; ++j) v[j] = bf16_to_f32((bf16_t)((raw[j][e >> 1] >> (16 * (e & 1))) & 0xffffu)) * inv;
+            *reinterpret_cast<uint32_t *>(tile + (tv * 8 + e) * kRowBytes + g * 4) = e4m3_pack4(v[0], v[1], v[2], v[3]);
         }
     }
     __syncthreads();
@@ -216,12 +208,10 @@ __global__ __launch_bounds__(kPackThreads) void pack_w_kernel(const bf16_t *__re
         for (int u = 0; u < 4; ++u) {
             if (base + u * kPackThreads + (int)threadIdx.x >= nvec) continue;
             const float inv = 1.0f / wsc[cot * 64 + mi * 32 + row[u]];
-            u32x2 o = {0u, 0u};
+            float v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bf16_t hv = (bf16_t)((raw[u][j >> 1] >> (16 * (j & 1))) & 0xffffu);
-                o[j >> 2] |= f32_to_e4m3(bf16_to_f32(hv) * inv) << (8 * (j & 3));
-            }
+            for (int j = 0; j < 8; ++j) v[j] = bf16_to_f32((bf16_t)((raw[u][j >> 1] >> (16 * (j & 1))) & 0xffffu)) * inv;
+            const u32x2 o = {e4m3_pack4(v[0], v[1], v[2], v[3]), e4m3_pack4(v[4], v[5], v[6], v[7])};
             *reinterpret_cast<u32x2 *>(codes + row[u] * pitch + col[u] * 8) = o;
         }
     }
