@@ -491,10 +491,15 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                         static_for<4>([&](auto wc) {
                             constexpr int w2 = decltype(wc)::value;
                             if constexpr (w2 != q) {
+                                float part[8 * kNT];  // all reads of one partial tile first, then the additions
+#pragma unroll
+                                for (int e = 0; e < 8 * kNT; ++e) part[e] = xch[((w2 * 40) + e) * 64 + l];
+                                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                                 for (int rr = 0; rr < 8; ++rr)
 #pragma unroll
-                                    for (int tb = 0; tb < kNT; ++tb) acc[mi][tb][r0 + rr] += xch[((w2 * 40) + rr * kNT + tb) * 64 + l];
+                                    for (int tb = 0; tb < kNT; ++tb) acc[mi][tb][r0 + rr] += part[rr * kNT + tb];
+                                __builtin_amdgcn_sched_barrier(0);
                             }
                         });
                     }
@@ -561,15 +566,23 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                     if (vec_res) load_residual(rv[(q + 1) & 1], q + 1);
                 }
                 wave_lds_fence();
+                if (p.vec_io) {
+                    // all LDS reads first, then the arithmetic and the stores: with the reads inside the loop every
+                    // piece would wait for its own LDS round trip
+                    f32x4 lo[kVec], hi[kVec];
 #pragma unroll
-                for (int j = 0; j < kVec; ++j) {
-                    const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
-                    const int t = tc.tt * kTileT + col * 8;
-                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32);
-                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32 + 16);
-                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    const size_t off = ((size_t)tc.b * p.Cout + tc.cot * kTileCo + q * 16 + row) * p.To + t;
-                    if (p.vec_io) {
+                    for (int j = 0; j < kVec; ++j) {
+                        const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
+                        lo[j] = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32);
+                        hi[j] = *reinterpret_cast<const f32x4 *>(ebuf + row * kQPitch + col * 32 + 16);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < kVec; ++j) {
+                        const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
+                        const int t = tc.tt * kTileT + col * 8;
+                        float v[8] = {lo[j][0], lo[j][1], lo[j][2], lo[j][3], hi[j][0], hi[j][1], hi[j][2], hi[j][3]};
+                        const size_t off = ((size_t)tc.b * p.Cout + tc.cot * kTileCo + q * 16 + row) * p.To + t;
                         if (t < p.To) {
                             if (p.res) {
 #pragma unroll
@@ -584,7 +597,13 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
                                              pack_bf16x2(v[6], v[7])};
                             *reinterpret_cast<u32x4 *>(p.y + off) = o;
                         }
-                    } else {  // rows that are not 16-byte pieces: element by element
+                    }
+                } else {  // rows that are not 16-byte pieces: element by element
+                    for (int j = 0; j < kVec; ++j) {
+                        const int idx = j * 64 + lane, row = idx / kVecPerRow, col = idx - row * kVecPerRow;
+                        const int t = tc.tt * kTileT + col * 8;
+                        const float *v = reinterpret_cast<const float *>(ebuf + row * kQPitch + col * 32);
+                        const size_t off = ((size_t)tc.b * p.Cout + tc.cot * kTileCo + q * 16 + row) * p.To + t;
                         for (int e = 0; e < 8; ++e) {
                             if (t + e < p.To) {
                                 float u = v[e];
@@ -624,6 +643,19 @@ __global__ __launch_bounds__(kThreads) void fp8_conv_kernel(const Fp8Params p)
         if (!has_next) break;
         seq = nseq_next;
         item = nxt;
+        // The weight sets and B fragments of the next item's first taps are fetched again here rather than kept
+        // across the epilogue (120 registers that the epilogue needs; the window itself stays in LDS).
+        static_for<KT>([&](auto kc) {
+            constexpr int k = decltype(kc)::value;
+            if constexpr (k < 4 || k >= P::Q4) load_a(aset[P::set_of(k)], wcur + k * kTapBytes);
+        });
+        {
+            const unsigned char *const bfirst = lds + cur * P::BUF;
+            static_for<kNT>([&](auto tc5) {
+                constexpr int tb = decltype(tc5)::value;
+                load_b(bfr[tb], bfirst, tb * 32);
+            });
+        }
     }
 }
 
