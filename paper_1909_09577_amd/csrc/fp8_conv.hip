@@ -27,7 +27,8 @@
 // next, four taps ahead, across chunk and tile boundaries; the window of the next chunk (or of the next
 // tile's first chunk) is requested piece by piece during the current chunk and written to the other LDS
 // buffer four taps later; a B fragment register is reloaded for the next tap right after the two
-// MFMAs that read it.
+// MFMAs that read it.  A small last round of tiles is shared by the four wavefronts of a workgroup: each
+// takes every fourth chunk of the tile and the partial tiles are summed through LDS in a fixed order.
 #include "../../include/nm_conv1d.h"
 #include "../../include/nm_conv1d_fp8.h"
 #include "nm_common.h"
