@@ -369,6 +369,53 @@ def fp8_report(steps, warmup, shape, with_cpu):
     print(json.dumps(out), flush=True)
 
 
+def masked_report(steps, warmup):
+    """The headline block on a ragged batch (lengths uniform in [T/2, T]): forward + both gradients through the
+    masked entry points, beside the same step on the full batch.  One JSON line.  `--masked` only."""
+    import numpy as np
+    import torch
+    from paper_1909_09577_amd import binding as nm
+    from paper_1909_09577_amd import inputs as syn
+    c = syn.HEADLINE
+    kw = dict(stride=c.stride, dilation=c.dilation, pad=c.pad)
+    x = torch.randn(c.B, c.Cin, c.T, device="cuda").bfloat16()
+    w = (torch.randn(c.Cout, c.Cin, c.K, device="cuda") / (c.Cin * c.K) ** 0.5).bfloat16()
+    res = torch.randn(c.B, c.Cout, c.T_out, device="cuda").bfloat16()
+    dy = torch.randn(c.B, c.Cout, c.T_out, device="cuda").bfloat16()
+    scale, shift = torch.rand(c.Cout, device="cuda") + 0.5, torch.randn(c.Cout, device="cuda") * 0.1
+    lens_host = np.random.default_rng(3).integers(c.T // 2, c.T + 1, c.B).astype(np.int32)
+    lens_host[0] = c.T
+    lens = torch.from_numpy(lens_host).cuda()
+    y, dx, dres = torch.empty_like(res), torch.empty_like(x), torch.empty_like(res)
+    dw = torch.empty(c.Cout, c.Cin, c.K, device="cuda")
+    ws = torch.empty(max(nm.nm_conv1d_workspace_bytes(op, *c.dims(), nm.NM_BF16, nm.NM_RELU) for op in (0, 1, 2, 3)),
+                     dtype=torch.uint8, device="cuda")
+
+    def step(lengths):
+        nm.nm_conv1d_block_fwd(x, w, scale, shift, res, y=y, relu=True, workspace=ws, lengths=lengths, **kw)
+        nm.nm_conv1d_bwd(x, dy, w, y=y, scale=scale, dx=dx, dres=dres, dw=dw, relu=True, workspace=ws, lengths=lengths, **kw)
+
+    def timed(lengths):
+        for _ in range(max(warmup, 1) + 100):
+            step(lengths)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step(lengths)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms_full, ms_ragged = timed(None), timed(lens)
+    flop = 3 * c.flops_per_pass
+    print(json.dumps({"metric": "conv1d fwd+dgrad+wgrad on a ragged batch (masked entry points), C=512 K=17 T=800",
+                      "ms_per_step": round(ms_ragged, 4), "ms_per_step_full_batch": round(ms_full, 4), "steps": steps,
+                      "valid_fraction": round(float(lens_host.sum()) / (c.B * c.T), 4),
+                      "value": round(flop / ms_ragged / 1e9, 1), "unit": "TFLOP/s (nominal flops of the padded batch)",
+                      "config": {"workload": describe(c) + ", lengths uniform in [T/2, T]"}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -388,6 +435,8 @@ def main():
                     help="instead of the headline: the same block with training-mode BatchNorm (batch statistics)")
     ap.add_argument("--decoder", action="store_true",
                     help="instead of the headline: the decoder tail (1x1 conv + log-softmax), an HBM-bound step")
+    ap.add_argument("--masked", action="store_true",
+                    help="instead of the headline: the same block on a ragged batch through the masked entry points")
     ap.add_argument("--fp8", choices=("512", "640", "768"), default=None,
                     help="instead of the headline: the block forward on E4M3 operands at this channel count")
     ap.add_argument("--workload", default="b3", choices=sorted(WORKLOADS),
@@ -416,6 +465,9 @@ def main():
         return
     if args.decoder:
         decoder_report(args.steps, args.warmup, not args.no_cpu_baseline)
+        return
+    if args.masked:
+        masked_report(args.steps, args.warmup)
         return
     if args.fp8:
         fp8_report(args.steps, args.warmup, args.fp8, not args.no_cpu_baseline)

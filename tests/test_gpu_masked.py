@@ -37,8 +37,22 @@ CASES = [
 @pytest.mark.parametrize("force_direct", [False, True], ids=["auto", "direct"])
 @pytest.mark.parametrize("case", CASES, ids=lambda c: c[0].name)
 def test_masked_passes(case, force_direct):
+    check_case(case[0], case[1], force_direct)
+
+
+def test_masked_passes_full_size_full_tensor():
+    """The headline block (B=32, 512 -> 512, K=17, T=800) on a ragged batch: lengths drawn uniformly from
+    [T/2, T] with one full-length item, every output element of all three passes compared."""
+    cfg = syn.shrink(syn.HEADLINE, B=syn.HEADLINE.B)
+    rng = np.random.default_rng(77)
+    lengths = rng.integers(cfg.T // 2, cfg.T + 1, cfg.B)
+    lengths[5] = cfg.T
+    lengths[11] = 437          # not a multiple of 8
+    check_case(cfg, [int(n) for n in lengths], False)
+
+
+def check_case(cfg, lengths, force_direct):
     import torch
-    cfg, lengths = case
     dtype = "bf16"
     inp = syn.make_inputs(cfg, dtype)
     lens = np.asarray(lengths, dtype=np.int32)
