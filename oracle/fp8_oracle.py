@@ -100,3 +100,40 @@ def block_fwd_fp8(conv_block_fwd, xq, sx, wq, sw, scale, shift, residual, relu, 
     if scale is not None:
         eff = eff * np.asarray(scale, dtype=np.float64)
     return conv_block_fwd(x, w, eff, shift, residual, relu, **geom)
+
+
+# ---- input gradient on E4M3 operands ------------------------------------------------------------
+# dx[b,ci,s] = sum over (co,t,k) with tau(t,k) = s of (w[co,ci,k]*scale[co]) * g[b,co,t],  g = dy*[y>0].
+# The contraction runs over co and k, so the weight operand is quantised per INPUT channel ci (the row of
+# the contraction's left operand): the affine factor is multiplied in first (one float32 multiplication),
+# then the slice {w[co,ci,k]*scale[co] : co, k} gets its scale amax/448 and is quantised like any other
+# slice.  g is exact in bfloat16 (a value of dy or zero) and is quantised with one scale for the tensor.
+def dgrad_weights(w, scale):
+    """float32 [Cin][Cout][K]: w[co,ci,k]*scale[co] (one float32 multiplication), input channel first."""
+    w32 = np.asarray(w, dtype=np.float32)
+    if scale is not None:
+        w32 = (w32 * np.asarray(scale, dtype=np.float32)[:, None, None]).astype(np.float32)
+    return np.ascontiguousarray(np.transpose(w32, (1, 0, 2)))
+
+
+def dgrad_weight_scales(w, scale) -> np.ndarray:
+    """float32 [Cin]: scale of each input channel's slice of the scaled weights."""
+    wt = dgrad_weights(w, scale)
+    return row_scales(wt, wt.shape[0])
+
+
+def masked_gradient(dy, y_saved, relu):
+    """g = dy*[y>0] (dy without a ReLU), float32, exact for bfloat16 inputs."""
+    dy32 = np.asarray(dy, dtype=np.float32)
+    if not relu:
+        return dy32
+    return np.where(np.asarray(y_saved, dtype=np.float64) > 0, dy32, np.float32(0.0)).astype(np.float32)
+
+
+def bwd_data_fp8(conv_bwd_data, gq, sg, wtq, swt, T, **geom) -> np.ndarray:
+    """dx of the block on the values the codes stand for.  `conv_bwd_data` is conv1d_oracle.bwd_data;
+    gq [B][Cout][T_out] codes of g with scale sg; wtq [Cin][Cout][K] codes of the scaled weights with the
+    per-input-channel scales swt."""
+    dz = e4m3_decode(gq) * float(np.float64(np.float32(sg)))
+    w_eff = e4m3_decode(wtq) * np.asarray(swt, dtype=np.float64)[:, None, None]   # [ci][co][k]
+    return conv_bwd_data(dz, np.ascontiguousarray(np.transpose(w_eff, (1, 0, 2))), T, **geom)

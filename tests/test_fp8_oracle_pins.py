@@ -122,3 +122,35 @@ def test_block_is_the_plain_block_on_the_decoded_values():
     # and it approximates the unquantised block to the accuracy of two 3-bit mantissas
     exact = orc.block_fwd(x.astype(np.float64), w.astype(np.float64), scale, shift, None, True, stride=1, dilation=1, pad=0)
     assert np.sqrt(np.mean((y - exact) ** 2)) / np.sqrt(np.mean(exact ** 2)) < 0.08
+
+
+def test_input_gradient_on_codes_is_the_textbook_product_for_k1_and_the_adjoint_of_the_forward():
+    rng = np.random.default_rng(5)
+    B, Cin, Cout, T, K = 2, 12, 8, 20, 1
+    w = rng.normal(0, 0.3, (Cout, Cin, K)).astype(np.float32)
+    scale = rng.uniform(0.5, 1.5, Cout).astype(np.float32)
+    dy = rng.normal(0, 1, (B, Cout, T)).astype(np.float32)
+    y = rng.normal(0, 1, (B, Cout, T))
+    g = f8.masked_gradient(dy, y, True)
+    assert np.array_equal(g, dy * (y > 0))
+    sg = f8.row_scales(g, 1)
+    gq = f8.quantize_rows(g, sg)
+    wt = f8.dgrad_weights(w, scale)
+    assert wt.shape == (Cin, Cout, K) and np.array_equal(wt[3, 5, 0], np.float32(w[5, 3, 0] * scale[5]))
+    swt = f8.dgrad_weight_scales(w, scale)
+    assert np.array_equal(swt, np.abs(wt).reshape(Cin, -1).max(axis=1) / np.float32(448))
+    wtq = f8.quantize_rows(wt, swt)
+    dx = f8.bwd_data_fp8(orc.bwd_data, gq, sg[0], wtq, swt, T, stride=1, dilation=1, pad=0)
+    gd = f8.e4m3_decode(gq) * float(sg[0])
+    wd = f8.e4m3_decode(wtq)[:, :, 0] * swt.astype(np.float64)[:, None]          # [ci][co]
+    np.testing.assert_allclose(dx, np.einsum("io,bot->bit", wd, gd), rtol=1e-12, atol=1e-12)
+    # K > 1: <conv(x, W), dz> == <x, dgrad(dz, W)> for the weights the codes stand for
+    K, pad = 5, 2
+    w = rng.normal(0, 0.3, (Cout, Cin, K)).astype(np.float32)
+    swt = f8.dgrad_weight_scales(w, None)
+    wtq = f8.quantize_rows(f8.dgrad_weights(w, None), swt)
+    w_eff = np.transpose(f8.e4m3_decode(wtq) * swt.astype(np.float64)[:, None, None], (1, 0, 2))
+    x = rng.normal(0, 1, (B, Cin, T))
+    z = orc.block_fwd(x, w_eff, None, None, None, False, stride=1, dilation=1, pad=pad)
+    dx = f8.bwd_data_fp8(orc.bwd_data, gq, sg[0], wtq, swt, T, stride=1, dilation=1, pad=pad)
+    np.testing.assert_allclose(np.sum(z * gd), np.sum(x * dx), rtol=1e-10)
