@@ -1,5 +1,6 @@
 /*
- * nm_conv1d_fp8.h -- C ABI of the 8-bit floating-point variant of the conv1d block forward (gfx950).
+ * nm_conv1d_fp8.h -- C ABI of the 8-bit floating-point variant of the conv1d block: forward and input
+ * gradient (gfx950).
  *
  * The paper's mixed-precision contract (Section 3.3) runs the convolutions on low-precision operands
  * and keeps sums in float32; it names float16.  This variant applies the same contract with the E4M3
@@ -65,6 +66,32 @@ int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, int stride, 
                             const void *x, const float *x_scale, const void *w, const float *w_scales,
                             const float *scale, const float *shift, const void *residual, void *y,
                             unsigned flags, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Input gradient of the block on E4M3 operands (paper Section 3: a trainable module computes its gradient flows;
+ * Section 3.3: in low precision with float32 sums).
+ *   g = dy*[y>0] (dy without NM_RELU), exact in bfloat16;  dres = g;
+ *   gq = E4M3(g * (1/g_scale)), one scale for the tensor;
+ *   the weight operand is w[co,ci,k]*scale[co] (one float32 multiplication), quantised per INPUT channel:
+ *   wq[ci,co,k] = E4M3( (w[co,ci,k]*scale[co]) * (1/wt_scales[ci]) );
+ *   dx[b,ci,s] = g_scale*wt_scales[ci] * sum over (co,t,k) with tau(t,k)==s of decode(wq[ci,co,k])*decode(gq[b,co,t]),
+ *   float32 sums, rounded to bfloat16.
+ *   dy, y     [B][Cout][T_out]  bfloat16, in (y required iff NM_RELU)
+ *   g_scale   [1] float         device, in (e.g. nm_fp8_row_scales of dy: |g| <= |dy|)
+ *   w         [Cout][Cin][K]    bfloat16, in;  scale [Cout] float, in, NULL means 1
+ *   wt_scales [Cin] float       device, in (nm_fp8_dgrad_weight_scales)
+ *   dx        [B][Cin][T]       bfloat16, out;  dres [B][Cout][T_out] bfloat16, out, or NULL
+ * Served geometries: those of nm_conv1d_fp8_supported.  Workspace: nm_conv1d_fp8_bwd_data_workspace_bytes(...). */
+int nm_conv1d_bwd_data_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                           const void *dy, const void *y, const float *g_scale, const void *w, const float *scale,
+                           const float *wt_scales, void *dx, void *dres, unsigned flags, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+size_t nm_conv1d_fp8_bwd_data_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
+
+/* scales[ci] = max over (co,k) of |w[co,ci,k]*scale[co]| / 448 (1 if that maximum is 0): the per-input-channel
+ * scales of the input gradient's weight operand.  w [Cout][Cin][K] bfloat16; scale [Cout] float or NULL;
+ * scales [Cin] float, device, out. */
+int nm_fp8_dgrad_weight_scales(int Cin, int Cout, int K, const void *w, const float *scale, float *scales,
+                               void *hip_stream);
 
 #ifdef __cplusplus
 }

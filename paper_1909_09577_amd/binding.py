@@ -25,7 +25,8 @@ EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_
            "nm_conv1d_bwd_data", "nm_conv1d_bwd_weight", "nm_conv1d_bwd", "nm_conv1d_block_fwd_masked", "nm_conv1d_bwd_data_masked",
            "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_bwd_masked", "nm_conv1d_time_next_main_kernel",
            "nm_fp8_row_scales", "nm_fp8_quantize_rows", "nm_conv1d_fp8_supported", "nm_conv1d_fp8_workspace_bytes",
-           "nm_conv1d_block_fwd_fp8")
+           "nm_conv1d_block_fwd_fp8", "nm_conv1d_bwd_data_fp8", "nm_conv1d_fp8_bwd_data_workspace_bytes",
+           "nm_fp8_dgrad_weight_scales")
 
 _lib = None
 
@@ -89,6 +90,12 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_fp8_workspace_bytes.restype = sz
         L.nm_conv1d_block_fwd_fp8.argtypes = [i] * 8 + [vp] * 8 + [u, vp, sz, vp]
         L.nm_conv1d_block_fwd_fp8.restype = i
+        L.nm_conv1d_bwd_data_fp8.argtypes = [i] * 8 + [vp] * 8 + [u, vp, sz, vp]
+        L.nm_conv1d_bwd_data_fp8.restype = i
+        L.nm_conv1d_fp8_bwd_data_workspace_bytes.argtypes = [i] * 8
+        L.nm_conv1d_fp8_bwd_data_workspace_bytes.restype = sz
+        L.nm_fp8_dgrad_weight_scales.argtypes = [i] * 3 + [vp] * 4
+        L.nm_fp8_dgrad_weight_scales.restype = i
         _lib = L
     return _lib
 
@@ -444,3 +451,43 @@ def nm_conv1d_block_fwd_fp8(x, x_scale, w, w_scales, scale=None, shift=None, res
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_block_fwd_fp8")
     return y
+
+
+def nm_fp8_dgrad_weight_scales(w, scale=None, *, stream=None):
+    """float32 [Cin]: per-input-channel scales of the input gradient's weight operand w[co,ci,k]*scale[co]."""
+    torch = _torch()
+    Cout, Cin, K = w.shape
+    out = torch.empty(Cin, dtype=torch.float32, device=w.device)
+    st = lib().nm_fp8_dgrad_weight_scales(Cin, Cout, K, _ptr(w, torch.bfloat16, name="w"),
+                                          _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(out), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_fp8_dgrad_weight_scales")
+    return out
+
+
+def nm_conv1d_fp8_bwd_data_workspace_bytes(B, Cin, Cout, T, K, stride=1, dilation=1, pad=0) -> int:
+    return int(lib().nm_conv1d_fp8_bwd_data_workspace_bytes(B, Cin, Cout, T, K, stride, dilation, pad))
+
+
+def nm_conv1d_bwd_data_fp8(dy, g_scale, w, wt_scales, T, y=None, scale=None, dx=None, dres=None, *, stride=1, dilation=1,
+                           pad=0, relu=False, want_dres=False, workspace=None, stream=None):
+    """Input gradient on E4M3 operands; returns (dx, dres)."""
+    torch = _torch()
+    B, Cout, To = dy.shape
+    _, Cin, K = w.shape
+    if dx is None:
+        dx = torch.empty((B, Cin, T), dtype=torch.bfloat16, device=dy.device)
+    if dres is None and want_dres:
+        dres = torch.empty_like(dy)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    if workspace is None:
+        workspace = torch.empty(max(nm_conv1d_fp8_bwd_data_workspace_bytes(*dims), 256), dtype=torch.uint8, device=dy.device)
+    st = lib().nm_conv1d_bwd_data_fp8(
+        *dims, _ptr(dy, torch.bfloat16, name="dy"), _ptr(y, torch.bfloat16, (B, Cout, To), "y"),
+        _ptr(g_scale, torch.float32, (1,), "g_scale"), _ptr(w, torch.bfloat16, (Cout, Cin, K), "w"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(wt_scales, torch.float32, (Cin,), "wt_scales"),
+        _ptr(dx, torch.bfloat16, (B, Cin, T), "dx"), _ptr(dres, torch.bfloat16, (B, Cout, To), "dres"),
+        NM_RELU if relu else 0, ctypes.c_void_p(workspace.data_ptr()), workspace.numel(), _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bwd_data_fp8")
+    return dx, dres

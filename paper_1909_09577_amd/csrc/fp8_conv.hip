@@ -232,6 +232,162 @@ __global__ __launch_bounds__(kPackThreads) void pack_w_kernel(const bf16_t *__re
     }
 }
 
+// ---- operands of the input gradient ------------------------------------------------------------
+// out[ci] = max over (co, k) of |w[co,ci,k]*scale[co]| / 448 (1 if that maximum is 0); one block per input channel
+__global__ __launch_bounds__(256) void dgrad_wscale_kernel(const bf16_t *__restrict__ w, const float *__restrict__ scale,
+                                                           float *__restrict__ out, int Cin, int Cout, int K)
+{
+    __shared__ float part[4];
+    const int ci = blockIdx.x;
+    float m = 0.f;
+    for (int co = threadIdx.x; co < Cout; co += 256) {
+        const float f = scale ? scale[co] : 1.f;
+        const bf16_t *row = w + ((size_t)co * Cin + ci) * K;
+        for (int k = 0; k < K; ++k) m = fmaxf(m, fabsf(bf16_to_f32(row[k]) * f));
+    }
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float a = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        out[ci] = a == 0.f ? 1.f : a / kE4M3Max;
+    }
+}
+
+// g = dy*[y>0] -> codes in the time-major layout of the activations (row r stands for time r - pad), and g itself
+// to dres when that is wanted.  Same structure as quant_x_vec_kernel; T % 8 == 0 and 16-byte aligned tensors.
+__global__ __launch_bounds__(256) void quant_g_vec_kernel(const bf16_t *__restrict__ dy, const bf16_t *__restrict__ y,
+                                                          const float *__restrict__ gs, unsigned char *__restrict__ gq,
+                                                          bf16_t *__restrict__ dres, int C, int T, int Tp, int pad)
+{
+    __shared__ __align__(16) unsigned char tile[kQxT * kRowBytes];
+    const int c = blockIdx.y, b = blockIdx.z, nck = gridDim.y;
+    const int t0 = blockIdx.x * kQxT;
+    const int g4 = threadIdx.x & 15, tv = threadIdx.x >> 4;
+    const float inv = 1.0f / gs[0];
+    const int t = t0 + tv * 8;
+    if (t < T) {
+        const size_t off = ((size_t)b * C + c * 64 + g4 * 4) * T + t;
+        u32x4 raw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4 *>(dy + off + (size_t)j * T);
+        if (y) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = masked_grad8(raw[j], *reinterpret_cast<const u32x4 *>(y + off + (size_t)j * T));
+        }
+        if (dres) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(dres + off + (size_t)j * T) = raw[j];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = bf16_to_f32((bf16_t)((raw[j][e >> 1] >> (16 * (e & 1))) & 0xffffu)) * inv;
+            *reinterpret_cast<uint32_t *>(tile + (tv * 8 + e) * kRowBytes + g4 * 4) = e4m3_pack4(v[0], v[1], v[2], v[3]);
+        }
+    }
+    __syncthreads();
+    unsigned char *const slab = gq + ((size_t)b * nck + c) * Tp * 64;
+    const int rows = min(kQxT, T - t0);
+    for (int i = threadIdx.x; i < rows * 4; i += 256) {
+        const int row = i >> 2, q = i & 3;
+        *reinterpret_cast<u32x4 *>(slab + (size_t)(t0 + row + pad) * 64 + q * 16) =
+            *reinterpret_cast<const u32x4 *>(tile + row * kRowBytes + q * 16);
+    }
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < pad * 4; i += 256) *reinterpret_cast<u32x4 *>(slab + (size_t)i * 16) = zero;
+    if (blockIdx.x == gridDim.x - 1)
+        for (int i = threadIdx.x; i < (Tp - T - pad) * 4; i += 256)
+            *reinterpret_cast<u32x4 *>(slab + (size_t)(T + pad) * 64 + (size_t)i * 16) = zero;
+}
+
+// The same element by element (any T and alignment); grid (ceil(Tp/64), C/64, B) as quant_x_kernel.
+__global__ __launch_bounds__(256) void quant_g_kernel(const bf16_t *__restrict__ dy, const bf16_t *__restrict__ y,
+                                                      const float *__restrict__ gs, unsigned char *__restrict__ gq,
+                                                      bf16_t *__restrict__ dres, int C, int T, int Tp, int pad)
+{
+    const int tl = threadIdx.x & 63, cg = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + tl;
+    if (r >= Tp) return;
+    const int c = blockIdx.y, b = blockIdx.z;
+    const int t = r - pad;
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (t >= 0 && t < T) {
+        const float inv = 1.0f / gs[0];
+        const size_t off = ((size_t)b * C + c * 64 + cg * 16) * T + t;
+        float v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            bf16_t gb = dy[off + (size_t)j * T];
+            if (y && !((uint32_t)y[off + (size_t)j * T] - 1u < 0x7f80u)) gb = 0;
+            if (dres) dres[off + (size_t)j * T] = gb;
+            v[j] = bf16_to_f32(gb) * inv;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = e4m3_pack4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+    }
+    *reinterpret_cast<u32x4 *>(gq + (((size_t)b * gridDim.y + c) * Tp + r) * 64 + cg * 16) = out;
+}
+
+// Weight operand of the input gradient: W'[ci][co][k'] = w[co][ci][K-1-k'] * scale[co], quantised with the scale of
+// its row ci, in fragment order wtq[Cin/64][Cout/64][K][2][64][32].  One block per (input-channel tile, chunk of 64
+// output channels, row half): for every output channel of the chunk the 32*K weights of the block's 32 input
+// channels are one contiguous piece of memory; they go through LDS as codes [co][ci*K + k].
+__global__ __launch_bounds__(kPackThreads) void pack_wt_kernel(const bf16_t *__restrict__ w, const float *__restrict__ scale,
+                                                               const float *__restrict__ wts, unsigned char *__restrict__ wtq,
+                                                               int Cin, int K)
+{
+    extern __shared__ __align__(16) unsigned char codes[];  // [64][pitch]
+    const int mi = blockIdx.x & 1, c = blockIdx.y, cit = blockIdx.z;
+    const int nck = gridDim.y;
+    const int rowlen = 32 * K;       // codes per output channel
+    const int pitch = rowlen + 8;
+    const int vec_per_row = rowlen / 8;
+    const int nvec = 64 * vec_per_row;
+    const int ci0 = cit * 64 + mi * 32;
+    for (int base = 0; base < nvec; base += 4 * kPackThreads) {
+        u32x4 raw[4];
+        int row[4], col[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int v = base + u * kPackThreads + threadIdx.x;
+            row[u] = v / vec_per_row;
+            col[u] = v - row[u] * vec_per_row;
+            if (v < nvec) raw[u] = *reinterpret_cast<const u32x4 *>(w + ((size_t)(c * 64 + row[u]) * Cin + ci0) * K + col[u] * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (base + u * kPackThreads + (int)threadIdx.x >= nvec) continue;
+            const float f = scale ? scale[c * 64 + row[u]] : 1.f;
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int e = col[u] * 8 + j;  // element (ci_l, k) = (e / K, e % K) of this output channel's piece
+                const float inv = 1.0f / wts[ci0 + e / K];
+                v[j] = (bf16_to_f32((bf16_t)((raw[u][j >> 1] >> (16 * (j & 1))) & 0xffffu)) * f) * inv;
+            }
+            const u32x2 o = {e4m3_pack4(v[0], v[1], v[2], v[3]), e4m3_pack4(v[4], v[5], v[6], v[7])};
+            *reinterpret_cast<u32x2 *>(codes + row[u] * pitch + col[u] * 8) = o;
+        }
+    }
+    __syncthreads();
+    for (int it = threadIdx.x; it < K * 64; it += kPackThreads) {
+        const int k = it >> 6, lane = it & 63;  // fragment of tap k' = k: row ci_l = lane % 32, output channels 32*(lane/32) .. +31
+        const unsigned char *src = codes + (32 * (lane >> 5)) * pitch + (lane & 31) * K + (K - 1 - k);
+        u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            lo[j >> 2] |= (uint32_t)src[j * pitch] << (8 * (j & 3));
+            hi[j >> 2] |= (uint32_t)src[(16 + j) * pitch] << (8 * (j & 3));
+        }
+        u32x4 *dst = reinterpret_cast<u32x4 *>(wtq + ((((size_t)(cit * nck + c) * K + k) * 2 + mi) * 64 + lane) * 32);
+        dst[0] = lo;
+        dst[1] = hi;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 struct Fp8Params {
     int B, Cin, Cout, To, K;
@@ -827,6 +983,96 @@ extern "C" int nm_conv1d_block_fwd_fp8(int B, int Cin, int Cout, int T, int K, i
     p.xs = x_scale; p.ws = w_scales; p.scale = scale; p.shift = shift;
     p.res = (const bf16_t *)residual;
     p.y = (bf16_t *)y;
+    hipError_t e;
+    if (dilation == 2) e = launch_fp8_conv<29, 2>(p, s);
+    else if (K == 17) e = launch_fp8_conv<17, 1>(p, s);
+    else if (K == 21) e = launch_fp8_conv<21, 1>(p, s);
+    else e = launch_fp8_conv<25, 1>(p, s);
+    return e == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+}
+
+// ---- input gradient ---------------------------------------------------------------------------------
+namespace {
+// the input gradient is the forward engine with the channel roles swapped, the taps flipped and the left padding
+// dil*(K-1) - pad: checks and layout in those terms
+int fp8_dgrad_check(int B, int Cin, int Cout, int T, int K, int stride, int dil, int pad, int *To)
+{
+    return fp8_check(B, Cin, Cout, T, K, stride, dil, pad, To);
+}
+Fp8Layout fp8_dgrad_layout(int B, int Cin, int Cout, int T, int K, int dil)
+{
+    return fp8_layout(B, /*reduction channels*/ Cout, /*output channels*/ Cin, /*output length*/ T, K, dil);
+}
+}  // namespace
+
+extern "C" int nm_fp8_dgrad_weight_scales(int Cin, int Cout, int K, const void *w, const float *scale, float *scales,
+                                          void *hip_stream)
+{
+    if (!w || !scales || Cin <= 0 || Cout <= 0 || K <= 0) return NM_ERR_BAD_ARG;
+    if ((long long)Cin * Cout * K > (1LL << 31) - 1) return NM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(dgrad_wscale_kernel, dim3(Cin), dim3(256), 0, (hipStream_t)hip_stream, (const bf16_t *)w, scale, scales,
+                       Cin, Cout, K);
+    return hipGetLastError() == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+}
+
+extern "C" size_t nm_conv1d_fp8_bwd_data_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation,
+                                                         int pad)
+{
+    int To = 0;
+    if (fp8_dgrad_check(B, Cin, Cout, T, K, stride, dilation, pad, &To) != NM_OK) return 0;
+    return fp8_dgrad_layout(B, Cin, Cout, T, K, dilation).total;
+}
+
+extern "C" int nm_conv1d_bwd_data_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad,
+                                      const void *dy, const void *y, const float *g_scale, const void *w, const float *scale,
+                                      const float *wt_scales, void *dx, void *dres, unsigned flags, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    int To = 0;
+    const int st = fp8_dgrad_check(B, Cin, Cout, T, K, stride, dilation, pad, &To);
+    if (st != NM_OK) return st;
+    if (!dy || !g_scale || !w || !wt_scales || !dx) return NM_ERR_BAD_ARG;
+    if (flags & ~(unsigned)NM_RELU) return NM_ERR_BAD_ARG;
+    const bool relu = (flags & NM_RELU) != 0;
+    if (relu && !y) return NM_ERR_BAD_ARG;
+    const Fp8Layout l = fp8_dgrad_layout(B, Cin, Cout, T, K, dilation);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < l.total) return NM_ERR_WORKSPACE;
+    const size_t nx = (size_t)B * Cin * T * 2, ny = (size_t)B * Cout * To * 2, nw = (size_t)Cout * Cin * K * 2;
+    if (((uintptr_t)w & 15) || ((uintptr_t)dy & 1) || ((uintptr_t)y & 1) || ((uintptr_t)dx & 1) || ((uintptr_t)dres & 1))
+        return NM_ERR_BAD_ARG;
+    if (overlap(dx, nx, dy, ny) || overlap(dx, nx, y, ny) || overlap(dx, nx, w, nw) || overlap(dx, nx, dres, ny) ||
+        overlap(dres, ny, dy, ny) || overlap(dres, ny, y, ny) || overlap(dres, ny, w, nw) || overlap(dx, nx, workspace, l.total) ||
+        overlap(dres, ny, workspace, l.total) || overlap(dy, ny, workspace, l.total) || overlap(y, ny, workspace, l.total) ||
+        overlap(w, nw, workspace, l.total))
+        return NM_ERR_BAD_ARG;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    unsigned char *gq = (unsigned char *)workspace;
+    unsigned char *wtq = gq + l.xq_bytes;
+    const int padL = dilation * (K - 1) - pad;
+    const bf16_t *ym = relu ? (const bf16_t *)y : nullptr;
+    const bool vec = To % 8 == 0 && !((uintptr_t)dy & 15) && !((uintptr_t)y & 15) && !((uintptr_t)dres & 15);
+    if (vec)
+        hipLaunchKernelGGL(quant_g_vec_kernel, dim3((To + kQxT - 1) / kQxT, l.nck, B), dim3(256), 0, s, (const bf16_t *)dy, ym,
+                           g_scale, gq, (bf16_t *)dres, Cout, To, l.Tp, padL);
+    else
+        hipLaunchKernelGGL(quant_g_kernel, dim3((l.Tp + 63) / 64, l.nck, B), dim3(256), 0, s, (const bf16_t *)dy, ym, g_scale, gq,
+                           (bf16_t *)dres, Cout, To, l.Tp, padL);
+    hipLaunchKernelGGL(pack_wt_kernel, dim3(2, l.nck, l.ncot), dim3(kPackThreads), (size_t)64 * (32 * K + 8), s,
+                       (const bf16_t *)w, scale, wt_scales, wtq, Cin, K);
+    if (hipGetLastError() != hipSuccess) return NM_ERR_DEVICE;
+
+    Fp8Params p;
+    p.B = B; p.Cin = Cout; p.Cout = Cin; p.To = T; p.K = K;
+    p.ncot = l.ncot; p.nck = l.nck; p.ntt = l.ntt; p.Tp = l.Tp;
+    p.nbt = B * l.ntt;
+    p.ntiles = l.ncot * 4 * ((p.nbt + 3) / 4);
+    p.relu = 0;
+    p.vec_io = (T % 8 == 0 && !((uintptr_t)dx & 15)) ? 1 : 0;
+    p.xq = gq; p.wq = wtq;
+    p.xs = g_scale; p.ws = wt_scales; p.scale = nullptr; p.shift = nullptr;
+    p.res = nullptr;
+    p.y = (bf16_t *)dx;
     hipError_t e;
     if (dilation == 2) e = launch_fp8_conv<29, 2>(p, s);
     else if (K == 17) e = launch_fp8_conv<17, 1>(p, s);

@@ -261,3 +261,28 @@ def test_fp8_entry_points_report_argument_errors_before_any_device_call():
     assert L.nm_fp8_row_scales(FAKE2, 1 << 20, 1 << 20, FAKE, None) == nm.NM_ERR_UNSUPPORTED
     assert L.nm_fp8_quantize_rows(FAKE2, 1, 0, FAKE, FAKE3, None) == nm.NM_ERR_BAD_ARG
     assert L.nm_fp8_quantize_rows(FAKE2, 2, 8, FAKE, FAKE2, None) == nm.NM_ERR_BAD_ARG       # codes alias x
+
+
+def test_fp8_input_gradient_reports_argument_errors_before_any_device_call():
+    L = nm.lib()
+    ok = dict(B=2, Cin=64, Cout=128, T=200, K=17, stride=1, dilation=1, pad=8)
+    need = nm.nm_conv1d_fp8_bwd_data_workspace_bytes(**ok)
+    # codes of g: 2 items x 2 chunks x (2*160 + 16) rows x 64 B; of the weights: 1 tile x 2 chunks x 17 taps x 4 KiB
+    assert need >= 2 * 2 * 336 * 64 + 2 * 17 * 4096 and need % 256 == 0
+    assert nm.nm_conv1d_fp8_bwd_data_workspace_bytes(**dict(ok, K=5, pad=2)) == 0
+
+    def call(dy=FAKE2, yv=None, gs=FAKE, w=FAKE3, wts=FAKE, dx=FAKE4, dres=None, flags=0, wsp=FAKE5, wsb=None, **kw):
+        d = dict(ok, **kw)
+        return L.nm_conv1d_bwd_data_fp8(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"],
+                                        dy, yv, gs, w, None, wts, dx, dres, flags, wsp, need if wsb is None else wsb, None)
+
+    assert call(K=11, pad=5) == nm.NM_ERR_UNSUPPORTED and call(Cout=100) == nm.NM_ERR_UNSUPPORTED
+    assert call(T=0) == nm.NM_ERR_BAD_ARG
+    for missing in ("dy", "gs", "w", "wts", "dx"):
+        assert call(**{missing: None}) == nm.NM_ERR_BAD_ARG, missing
+    assert call(flags=nm.NM_RELU) == nm.NM_ERR_BAD_ARG                                  # the mask needs y
+    assert call(flags=nm.NM_ACCUM_DX) == nm.NM_ERR_BAD_ARG
+    assert call(wsp=None) == nm.NM_ERR_WORKSPACE and call(wsb=need - 1) == nm.NM_ERR_WORKSPACE
+    assert call(dx=FAKE2) == nm.NM_ERR_BAD_ARG and call(dres=FAKE2) == nm.NM_ERR_BAD_ARG   # dx / dres alias dy
+    assert L.nm_fp8_dgrad_weight_scales(64, 64, 17, None, None, FAKE, None) == nm.NM_ERR_BAD_ARG
+    assert L.nm_fp8_dgrad_weight_scales(0, 64, 17, FAKE2, None, FAKE, None) == nm.NM_ERR_BAD_ARG

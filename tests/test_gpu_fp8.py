@@ -157,3 +157,55 @@ def test_impulse_recovers_the_quantised_weights():
         got = y[0]
         assert np.array_equal(got != 0, expect != 0), f"channel {ci}: support of the response"
         np.testing.assert_allclose(got, expect, rtol=2.0 ** -8, atol=0)
+
+
+# ---- input gradient on E4M3 operands ------------------------------------------------------------------
+DGRAD_CASES = [
+    L("f8d_two_tiles", 2, 64, 64, 200, 17, residual=True),
+    L("f8d_nine_pairs", 3, 192, 128, 333, 21, residual=True),             # odd length: element-wise passes
+    L("f8d_k25_no_relu", 2, 128, 192, 160, 25, relu=False, affine=False),
+    L("f8d_k29_d2", 2, 64, 128, 248, 29, dilation=2),
+    L("f8d_short_pad", 2, 128, 64, 180, 17, pad=3),                        # T_out < T: left padding of g is 13
+    L("f8d_long_pad", 2, 64, 64, 104, 17, pad=16),                         # T_out > T
+    L("f8d_shared", 2, 128, 256, 200, 17, residual=True),                 # reduction over 256 output channels: shared tiles
+    L("f8d_private_then_shared", 33, 256, 256, 1280, 17),                 # 1056 tiles = 1024 + 32
+]
+
+
+def run_dgrad_case(cfg):
+    import torch
+    inp = syn.make_inputs(cfg, DT)
+    kw = U.geom_kw(cfg)
+    scale = inp["scale"] if cfg.affine else None
+    y_saved = inp["y_saved"]
+    g = f8.masked_gradient(inp["dy"], y_saved, cfg.relu)
+    sg = f8.row_scales(inp["dy"], 1)                      # the scale of dy bounds g
+    gq = f8.quantize_rows(g, sg)
+    swt = f8.dgrad_weight_scales(inp["w"], scale)
+    wtq = f8.quantize_rows(f8.dgrad_weights(inp["w"], scale), swt)
+    dx_ref = f8.bwd_data_fp8(orc.bwd_data, gq, sg[0], wtq, swt, cfg.T, **kw)
+
+    dyd, wd = U.to_dev(inp, "dy", DT), U.to_dev(inp, "w", DT)
+    yd = U.to_dev(inp, "y_saved", DT) if cfg.relu else None
+    scd = U.to_dev(inp, "scale", DT) if cfg.affine else None
+    sgd = nm.nm_fp8_row_scales(dyd, 1)
+    swtd = nm.nm_fp8_dgrad_weight_scales(wd, scd)
+    assert np.array_equal(sgd.cpu().numpy(), sg)
+    assert np.array_equal(swtd.cpu().numpy().view(np.uint32), swt.view(np.uint32)), "per-input-channel weight scales"
+    dx, dres = nm.nm_conv1d_bwd_data_fp8(dyd, sgd, wd, swtd, cfg.T, y=yd, scale=scd, relu=cfg.relu, want_dres=True, **kw)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(U.to_host_f64(dres), g.astype(np.float64))   # dres = g, bit for bit
+    return U.to_host_f64(dx), dx_ref
+
+
+@pytest.mark.parametrize("cfg", DGRAD_CASES, ids=lambda c: c.name)
+def test_bwd_data_fp8(cfg):
+    got, ref = run_dgrad_case(cfg)
+    assert got.shape == (cfg.B, cfg.Cin, cfg.T)
+    U.assert_close(got, ref, DT, f"{cfg.name} dx")
+
+
+def test_bwd_data_fp8_full_size_full_tensor():
+    cfg = L("f8d_b3_512_k17", 32, 512, 512, 800, 17, residual=True, seed=2)
+    got, ref = run_dgrad_case(cfg)
+    U.assert_close(got, ref, DT, f"{cfg.name} dx")
