@@ -319,6 +319,15 @@ def fp8_report(steps, warmup, shape, with_cpu):
     def step():
         nm.nm_conv1d_block_fwd_fp8(x, sx, w, sw, scale, shift, res, y, relu=True, workspace=ws, **kw)
 
+    # the input gradient on E4M3 operands, timed beside the forward (reported as "bwd_data")
+    dy = torch.randn(B, C, T, device="cuda", generator=g).bfloat16()
+    dx, dres = torch.empty_like(x), torch.empty_like(res)
+    sg, swt = nm.nm_fp8_row_scales(dy, 1), nm.nm_fp8_dgrad_weight_scales(w, scale)
+    wsb = torch.empty(nm.nm_conv1d_fp8_bwd_data_workspace_bytes(B, C, C, T, K, 1, 1, pad), dtype=torch.uint8, device="cuda")
+
+    def step_bwd():
+        nm.nm_conv1d_bwd_data_fp8(dy, sg, w, swt, T, y=y, scale=scale, dx=dx, dres=dres, relu=True, workspace=wsb, **kw)
+
     for _ in range(max(warmup, 1) + 100):
         step()
     torch.cuda.synchronize()
@@ -353,6 +362,25 @@ def fp8_report(steps, warmup, shape, with_cpu):
                         "frac": round(flop / kms / 1e9 / PEAK_FP8_TFLOPS, 4), "traffic": None,
                         "kernel": f"fp8_conv_kernel<{K}, 1>", "flops_per_launch": flop, "algorithmic_bytes_per_launch": alg,
                         "avg_launch_ms": round(kms, 4), "timed_launches": len(pairs)}}
+    for _ in range(50):
+        step_bwd()
+    torch.cuda.synchronize()
+    b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kb0, kb1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kb0.record()
+    kb1.record()
+    b0.record()
+    for _ in range(steps):
+        step_bwd()
+    b1.record()
+    nm.nm_conv1d_time_next_main_kernel(kb0, kb1)
+    step_bwd()
+    torch.cuda.synchronize()
+    ms_b = b0.elapsed_time(b1) / steps
+    out["bwd_data"] = {"ms_per_call": round(ms_b, 4), "value": round(flop / ms_b / 1e9, 1), "unit": "TFLOP/s",
+                       "frac_of_fp8_mfma_peak": round(flop / ms_b / 1e9 / PEAK_FP8_TFLOPS, 4),
+                       "main_kernel_ms": round(kb0.elapsed_time(kb1), 4),
+                       "step": "nm_conv1d_bwd_data_fp8 (mask + quantise g + dres, quantise+pack flipped weights, matrix-core kernel)"}
     if with_cpu:
         from oracle import conv1d_oracle as orc
         from oracle import fp8_oracle as f8
