@@ -137,3 +137,16 @@ def bwd_data_fp8(conv_bwd_data, gq, sg, wtq, swt, T, **geom) -> np.ndarray:
     dz = e4m3_decode(gq) * float(np.float64(np.float32(sg)))
     w_eff = e4m3_decode(wtq) * np.asarray(swt, dtype=np.float64)[:, None, None]   # [ci][co][k]
     return conv_bwd_data(dz, np.ascontiguousarray(np.transpose(w_eff, (1, 0, 2))), T, **geom)
+
+
+# ---- weight gradient on E4M3 operands -----------------------------------------------------------
+# dw[co,ci,k] = scale[co] * sum_b sum_t g[b,co,t] * x[b,ci,tau(t,k)] on the values the codes of g and x stand
+# for (one scale per tensor each); the affine factor multiplies the sums, as in the bfloat16 path.
+def bwd_weight_fp8(conv_bwd_weight, xq, sx, gq, sg, scale, K, **geom) -> np.ndarray:
+    """dw [Cout][Cin][K] float64.  `conv_bwd_weight` is conv1d_oracle.bwd_weight; xq [B][Cin][T] codes with
+    scale sx, gq [B][Cout][T_out] codes with scale sg, scale [Cout] or None."""
+    x = e4m3_decode(xq) * float(np.float64(np.float32(sx)))
+    dz = e4m3_decode(gq) * float(np.float64(np.float32(sg)))
+    if scale is not None:
+        dz = dz * np.asarray(scale, dtype=np.float64)[None, :, None]
+    return conv_bwd_weight(x, dz, K, **geom)

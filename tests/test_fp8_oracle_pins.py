@@ -154,3 +154,28 @@ def test_input_gradient_on_codes_is_the_textbook_product_for_k1_and_the_adjoint_
     z = orc.block_fwd(x, w_eff, None, None, None, False, stride=1, dilation=1, pad=pad)
     dx = f8.bwd_data_fp8(orc.bwd_data, gq, sg[0], wtq, swt, T, stride=1, dilation=1, pad=pad)
     np.testing.assert_allclose(np.sum(z * gd), np.sum(x * dx), rtol=1e-10)
+
+
+def test_weight_gradient_on_codes_is_the_textbook_product_for_k1_and_matches_finite_differences():
+    rng = np.random.default_rng(6)
+    B, Cin, Cout, T = 2, 10, 6, 24
+    x = rng.normal(0, 1, (B, Cin, T)).astype(np.float32)
+    g = rng.normal(0, 1, (B, Cout, T)).astype(np.float32)
+    scale = rng.uniform(0.5, 1.5, Cout).astype(np.float32)
+    sx, sg = f8.row_scales(x, 1), f8.row_scales(g, 1)
+    xq, gq = f8.quantize_rows(x, sx), f8.quantize_rows(g, sg)
+    dw = f8.bwd_weight_fp8(orc.bwd_weight, xq, sx[0], gq, sg[0], scale, 1, stride=1, dilation=1, pad=0)
+    xd, gd = f8.e4m3_decode(xq) * float(sx[0]), f8.e4m3_decode(gq) * float(sg[0])
+    ref = np.einsum("bot,bit->oi", gd, xd) * scale.astype(np.float64)[:, None]
+    np.testing.assert_allclose(dw[:, :, 0], ref, rtol=1e-12, atol=1e-12)
+    # K = 5: dw is the derivative of <conv(xd, w) * scale, gd> with respect to w (linear in w: one difference is exact)
+    K, pad = 5, 2
+    dw = f8.bwd_weight_fp8(orc.bwd_weight, xq, sx[0], gq, sg[0], scale, K, stride=1, dilation=1, pad=pad)
+    w0 = rng.normal(0, 1, (Cout, Cin, K))
+
+    def loss(w):
+        return np.sum(orc.block_fwd(xd, w, scale, None, None, False, stride=1, dilation=1, pad=pad) * gd)
+    for (co, ci, k) in [(0, 0, 0), (5, 9, 4), (2, 3, 2)]:
+        e = np.zeros_like(w0)
+        e[co, ci, k] = 1.0
+        np.testing.assert_allclose(loss(w0 + e) - loss(w0), dw[co, ci, k], rtol=1e-9, atol=1e-9)
