@@ -1,6 +1,6 @@
 /*
- * nm_conv1d_fp8.h -- C ABI of the 8-bit floating-point variant of the conv1d block: forward and input
- * gradient (gfx950).
+ * nm_conv1d_fp8.h -- C ABI of the 8-bit floating-point variant of the conv1d block: forward, input gradient
+ * and weight gradient (gfx950).
  *
  * The paper's mixed-precision contract (Section 3.3) runs the convolutions on low-precision operands
  * and keeps sums in float32; it names float16.  This variant applies the same contract with the E4M3
@@ -92,6 +92,21 @@ size_t nm_conv1d_fp8_bwd_data_workspace_bytes(int B, int Cin, int Cout, int T, i
  * scales [Cin] float, device, out. */
 int nm_fp8_dgrad_weight_scales(int Cin, int Cout, int K, const void *w, const float *scale, float *scales,
                                void *hip_stream);
+
+/* Weight gradient of the block on E4M3 operands (same passages as the input gradient).
+ *   g = dy*[y>0] quantised with g_scale, x quantised with x_scale (one scale per tensor each, as in the forward);
+ *   dw[co,ci,k] = scale[co]*g_scale*x_scale * sum_b sum_t decode(gq[b,co,t])*decode(xq[b,ci,tau(t,k)]),
+ *   float32 sums; the factor multiplies the sums in the final deterministic reduction.
+ *   x   [B][Cin][T] bfloat16, in;  dy, y [B][Cout][T_out] bfloat16, in (y required iff NM_RELU)
+ *   x_scale, g_scale [1] float, device, in;  scale [Cout] float, in, NULL means 1
+ *   dw  [Cout][Cin][K] float, out (in/out with NM_ACCUM_DW)
+ * flags: NM_RELU, NM_ACCUM_DW.  Served geometries: those of nm_conv1d_fp8_supported.
+ * Workspace: nm_conv1d_fp8_bwd_weight_workspace_bytes(...). */
+int nm_conv1d_bwd_weight_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                             const float *x_scale, const void *dy, const void *y, const float *g_scale,
+                             const float *scale, float *dw, unsigned flags, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+size_t nm_conv1d_fp8_bwd_weight_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
 
 #ifdef __cplusplus
 }

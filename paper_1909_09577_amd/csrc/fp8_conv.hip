@@ -899,6 +899,37 @@ bool overlap(const void *a, size_t na, const void *b, size_t nb)
 }
 
 }  // namespace
+
+// ---- quantisation passes shared with the weight-gradient kernel (fp8_wgrad.hip) ------------------
+bool fp8_taps_supported(int K, int dil) { return taps_supported(K, dil); }
+
+// x [B][C][T] -> codes [B][C/64][Tp][64], row r standing for time r - pad, zero rows elsewhere
+hipError_t fp8_launch_quant_x(const void *x, const float *xs, unsigned char *xq, int B, int C, int T, int Tp, int pad,
+                              hipStream_t s)
+{
+    if (T % 8 == 0 && !((uintptr_t)x & 15))
+        hipLaunchKernelGGL(quant_x_vec_kernel, dim3((T + kQxT - 1) / kQxT, C / 64, B), dim3(256), 0, s, (const bf16_t *)x, xs, xq,
+                           C, T, Tp, pad);
+    else
+        hipLaunchKernelGGL(quant_x_kernel, dim3((Tp + 63) / 64, C / 64, B), dim3(256), 0, s, (const bf16_t *)x, xs, xq, C, T, Tp,
+                           pad);
+    return hipGetLastError();
+}
+
+// g = dy*[y>0] (y NULL: dy) -> codes in the same layout; g itself to dres when that is given
+hipError_t fp8_launch_quant_g(const void *dy, const void *y, const float *gs, unsigned char *gq, void *dres, int B, int C,
+                              int T, int Tp, int pad, hipStream_t s)
+{
+    const bool vec = T % 8 == 0 && !((uintptr_t)dy & 15) && !((uintptr_t)y & 15) && !((uintptr_t)dres & 15);
+    if (vec)
+        hipLaunchKernelGGL(quant_g_vec_kernel, dim3((T + kQxT - 1) / kQxT, C / 64, B), dim3(256), 0, s, (const bf16_t *)dy,
+                           (const bf16_t *)y, gs, gq, (bf16_t *)dres, C, T, Tp, pad);
+    else
+        hipLaunchKernelGGL(quant_g_kernel, dim3((Tp + 63) / 64, C / 64, B), dim3(256), 0, s, (const bf16_t *)dy, (const bf16_t *)y,
+                           gs, gq, (bf16_t *)dres, C, T, Tp, pad);
+    return hipGetLastError();
+}
+
 }  // namespace nm
 
 using namespace nm;

@@ -209,3 +209,59 @@ def test_bwd_data_fp8_full_size_full_tensor():
     cfg = L("f8d_b3_512_k17", 32, 512, 512, 800, 17, residual=True, seed=2)
     got, ref = run_dgrad_case(cfg)
     U.assert_close(got, ref, DT, f"{cfg.name} dx")
+
+
+# ---- weight gradient on E4M3 operands -----------------------------------------------------------------
+# The products of two E4M3 values are exact, but the matrix core does not add the 64 products of one instruction as
+# 64 float32 additions: it sums them in a wider fixed-point tree aligned to the largest product and rounds once into
+# the float32 accumulator, dropping low bits of much smaller products.  Observed against the fp64 oracle: relative rms
+# 1e-5, largest scaled error 2.3e-4 (elements whose sum nearly cancels).  Gates an order of magnitude below the bf16
+# gate and far below the 3-bit mantissa of the operands themselves.
+WGRAD_TOL = 1e-3
+WGRAD_RMS = 1e-4
+
+
+def run_wgrad_case(cfg, accumulate=False):
+    import torch
+    inp = syn.make_inputs(cfg, DT)
+    kw = U.geom_kw(cfg)
+    scale = inp["scale"] if cfg.affine else None
+    g = f8.masked_gradient(inp["dy"], inp["y_saved"], cfg.relu)
+    sg, sx = f8.row_scales(inp["dy"], 1), f8.row_scales(inp["x"], 1)
+    gq, xq = f8.quantize_rows(g, sg), f8.quantize_rows(inp["x"], sx)
+    dw_ref = f8.bwd_weight_fp8(orc.bwd_weight, xq, sx[0], gq, sg[0], scale, cfg.K, **kw)
+    xd, dyd = U.to_dev(inp, "x", DT), U.to_dev(inp, "dy", DT)
+    yd = U.to_dev(inp, "y_saved", DT) if cfg.relu else None
+    scd = U.to_dev(inp, "scale", DT) if cfg.affine else None
+    sxd, sgd = nm.nm_fp8_row_scales(xd, 1), nm.nm_fp8_row_scales(dyd, 1)
+    dw = nm.nm_conv1d_bwd_weight_fp8(xd, sxd, dyd, sgd, cfg.K, y=yd, scale=scd, relu=cfg.relu, **kw)
+    if accumulate:
+        dw2 = nm.nm_conv1d_bwd_weight_fp8(xd, sxd, dyd, sgd, cfg.K, y=yd, scale=scd, dw=dw.clone(), relu=cfg.relu,
+                                          accumulate=True, **kw)
+        np.testing.assert_allclose(dw2.cpu().numpy(), 2 * dw.cpu().numpy(), rtol=1e-6)
+        again = nm.nm_conv1d_bwd_weight_fp8(xd, sxd, dyd, sgd, cfg.K, y=yd, scale=scd, relu=cfg.relu, **kw)
+        assert torch.equal(again, dw), "the weight gradient must be deterministic"
+    return dw.cpu().numpy().astype(np.float64), dw_ref
+
+
+@pytest.mark.parametrize("cfg", [
+    L("f8w_one_unit", 1, 64, 64, 64, 17),
+    L("f8w_ragged_units", 3, 128, 64, 200, 17, residual=True),            # 200 = 3 units + 8 steps; several batch items
+    L("f8w_odd_length", 2, 64, 128, 333, 21, relu=False),                 # element-wise quantisation passes
+    L("f8w_k25", 2, 192, 128, 160, 25),
+    L("f8w_k29_d2", 2, 128, 64, 248, 29, dilation=2),
+    L("f8w_short_pad", 2, 64, 64, 180, 17, pad=3, affine=False),
+    L("f8w_long_pad", 2, 64, 64, 104, 17, pad=16),
+    L("f8w_many_tiles", 4, 512, 256, 320, 17),                            # 64 tiles, four workgroups per tile
+], ids=lambda c: c.name)
+def test_bwd_weight_fp8(cfg):
+    got, ref = run_wgrad_case(cfg, accumulate=cfg.name == "f8w_ragged_units")
+    mx, rr = U.err_metrics(got, ref)
+    assert mx <= WGRAD_TOL and rr <= WGRAD_RMS, f"{cfg.name} dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
+
+
+def test_bwd_weight_fp8_full_size_full_tensor():
+    cfg = L("f8w_b3_512_k17", 32, 512, 512, 800, 17, residual=True, seed=2)
+    got, ref = run_wgrad_case(cfg)
+    mx, rr = U.err_metrics(got, ref)
+    assert mx <= WGRAD_TOL and rr <= WGRAD_RMS, f"{cfg.name} dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
