@@ -381,6 +381,42 @@ def fp8_report(steps, warmup, shape, with_cpu):
                        "frac_of_fp8_mfma_peak": round(flop / ms_b / 1e9 / PEAK_FP8_TFLOPS, 4),
                        "main_kernel_ms": round(kb0.elapsed_time(kb1), 4),
                        "step": "nm_conv1d_bwd_data_fp8 (mask + quantise g + dres, quantise+pack flipped weights, matrix-core kernel)"}
+    # the weight gradient on E4M3 operands, and the three calls as one training step
+    dw = torch.empty(C, C, K, device="cuda")
+    wsw = torch.empty(nm.nm_conv1d_fp8_bwd_weight_workspace_bytes(B, C, C, T, K, 1, 1, pad), dtype=torch.uint8, device="cuda")
+
+    def step_wgrad():
+        nm.nm_conv1d_bwd_weight_fp8(x, sx, dy, sg, K, y=y, scale=scale, dw=dw, relu=True, workspace=wsw, **kw)
+
+    for _ in range(50):
+        step_wgrad()
+    torch.cuda.synchronize()
+    kw0, kw1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kw0.record()
+    kw1.record()
+    b0.record()
+    for _ in range(steps):
+        step_wgrad()
+    b1.record()
+    nm.nm_conv1d_time_next_main_kernel(kw0, kw1)
+    step_wgrad()
+    torch.cuda.synchronize()
+    ms_w = b0.elapsed_time(b1) / steps
+    out["bwd_weight"] = {"ms_per_call": round(ms_w, 4), "value": round(flop / ms_w / 1e9, 1), "unit": "TFLOP/s",
+                         "frac_of_fp8_mfma_peak": round(flop / ms_w / 1e9 / PEAK_FP8_TFLOPS, 4),
+                         "main_kernel_ms": round(kw0.elapsed_time(kw1), 4),
+                         "step": "nm_conv1d_bwd_weight_fp8 (quantise g and x, matrix-core kernel, split reduction)"}
+    b0.record()
+    for _ in range(steps):
+        step()
+        step_bwd()
+        step_wgrad()
+    b1.record()
+    torch.cuda.synchronize()
+    ms_all = b0.elapsed_time(b1) / steps
+    out["training_step"] = {"ms_per_step": round(ms_all, 4), "value": round(3 * flop / ms_all / 1e9, 1), "unit": "TFLOP/s",
+                            "frac_of_fp8_mfma_peak": round(3 * flop / ms_all / 1e9 / PEAK_FP8_TFLOPS, 4),
+                            "step": "forward + input gradient + weight gradient, all on E4M3 operands"}
     if with_cpu:
         from oracle import conv1d_oracle as orc
         from oracle import fp8_oracle as f8

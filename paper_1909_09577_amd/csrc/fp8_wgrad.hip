@@ -70,15 +70,20 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
 }
 
+// One transposing read: rows row0 + 32*(lane/32) .. +7 of channel col0 + lane%32 (8 reduction indices per lane)
+__device__ __forceinline__ i32x2 read_block(const unsigned char *win, int pitch, int row0, int col0, int lane)
+{
+    const int gi = lane >> 4, j = lane & 15;
+    const unsigned char *a = win + (row0 + 32 * (gi >> 1) + (j >> 1)) * pitch + col0 + 16 * (gi & 1) + 8 * (j & 1);
+    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)a);
+}
 // 32 reduction indices (rows row0 + 32*(lane/32) .. +31) of channel col0 + lane%32 from a time-major LDS window
 __device__ __forceinline__ i32x8 read_operand(const unsigned char *win, int pitch, int row0, int col0, int lane)
 {
-    const int gi = lane >> 4, j = lane & 15;
-    const unsigned char *base = win + (row0 + 32 * (gi >> 1) + (j >> 1)) * pitch + col0 + 16 * (gi & 1) + 8 * (j & 1);
     i32x8 r;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const i32x2 v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)(base + 8 * q * pitch));
+        const i32x2 v = read_block(win, pitch, row0 + 8 * q, col0, lane);
         r[2 * q] = v[0];
         r[2 * q + 1] = v[1];
     }
@@ -90,6 +95,12 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
 {
     constexpr int XROWS = kUnitT + (KT - 1) * DIL;
     constexpr int NTW = (KT - W + 3) / 4;  // taps W, W+4, ... of this wavefront
+    // The operand of tap W+4i is the four 8-row blocks at rows (W+4i)*DIL + 8q.  All those rows lie on the grid
+    // W*DIL + STEP*j, so every block is read once per unit and the taps pick their four from the registers.
+    constexpr int STEP = DIL == 1 ? 4 : 8;
+    static_assert((4 * DIL) % STEP == 0 && 8 % STEP == 0, "block grid");
+    constexpr int PER_TAP = 4 * DIL / STEP, PER_Q = 8 / STEP;
+    constexpr int NB = PER_TAP * (NTW - 1) + PER_Q * 3 + 1;
     const int tid = threadIdx.x, lane = tid & 63;
     f32x16 acc[NTW][2];
 #pragma unroll
@@ -134,9 +145,15 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
         const unsigned char *gw = gbuf + cur * GBUF, *xw = xbuf + cur * XBUF;
         const i32x8 a0 = read_operand(gw, kGPitch, 0, 0, lane);
         const i32x8 a1 = read_operand(gw, kGPitch, 0, 32, lane);
+        i32x2 blk[NB];
+        static_for<NB>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            blk[j] = read_block(xw, kXPitch, W * DIL + STEP * j, 0, lane);
+        });
         static_for<NTW>([&](auto ic) {
-            constexpr int i = decltype(ic)::value, k = W + 4 * i;
-            const i32x8 bk = read_operand(xw, kXPitch, k * DIL, 0, lane);
+            constexpr int i = decltype(ic)::value, j0 = PER_TAP * i;
+            const i32x8 bk = {blk[j0][0], blk[j0][1], blk[j0 + PER_Q][0], blk[j0 + PER_Q][1],
+                              blk[j0 + 2 * PER_Q][0], blk[j0 + 2 * PER_Q][1], blk[j0 + 3 * PER_Q][0], blk[j0 + 3 * PER_Q][1]};
             acc[i][0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, bk, acc[i][0], 0, 0, 0, 0, 0, 0);
             acc[i][1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, bk, acc[i][1], 0, 0, 0, 0, 0, 0);
         });
@@ -200,7 +217,8 @@ WgLayout wg_layout(int B, int Cin, int Cout, int To, int K, int dil)
     l.Tpx = l.nu * kUnitT + (K - 1) * dil;
     l.ntiles = (Cout / kTileCo) * (Cin / kTileCi);
     const int cus = current_device_info().cus;
-    l.S = std::max(1, std::min(8, cus / l.ntiles));
+    const int slots = (K == 17 ? 2 : 1) * cus;  // K = 17 fits two workgroups per CU (registers), which hides the load latency
+    l.S = std::max(1, std::min(8, slots / l.ntiles));
     l.S = std::min(l.S, std::max(1, B * l.nu));
     l.gq_bytes = align_up((size_t)B * (Cout / 64) * l.Tpg * 64 + kSlack, 256);
     l.xq_bytes = align_up((size_t)B * (Cin / 64) * l.Tpx * 64 + kSlack, 256);
