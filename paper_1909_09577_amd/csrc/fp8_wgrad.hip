@@ -90,21 +90,28 @@ __device__ __forceinline__ i32x8 read_operand(const unsigned char *win, int pitc
     return r;
 }
 
-template <int KT, int DIL, int W>
+// TG workgroups share the taps of a tile (workgroup G of them takes the taps G, G+TG, ...); inside a workgroup
+// wavefront W takes every fourth of those: taps K0 + KS*i with K0 = G + TG*W, KS = 4*TG.
+template <int KT, int DIL, int TG, int G, int W>
 __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gbuf, unsigned char *xbuf, int sp, int cot, int cit)
 {
     constexpr int XROWS = kUnitT + (KT - 1) * DIL;
-    constexpr int NTW = (KT - W + 3) / 4;  // taps W, W+4, ... of this wavefront
-    // The operand of tap W+4i is the four 8-row blocks at rows (W+4i)*DIL + 8q.  All those rows lie on the grid
-    // W*DIL + STEP*j, so every block is read once per unit and the taps pick their four from the registers.
-    constexpr int STEP = DIL == 1 ? 4 : 8;
-    static_assert((4 * DIL) % STEP == 0 && 8 % STEP == 0, "block grid");
-    constexpr int PER_TAP = 4 * DIL / STEP, PER_Q = 8 / STEP;
-    constexpr int NB = PER_TAP * (NTW - 1) + PER_Q * 3 + 1;
+    constexpr int K0 = G + TG * W, KS = 4 * TG;
+    constexpr int NTW = K0 < KT ? (KT - K0 + KS - 1) / KS : 0;  // taps of this wavefront
+    if constexpr (NTW == 0) {
+        // no tap for this wavefront: it still takes part in the staging and the barriers below
+    }
+    // The operand of tap K0+KS*i is the four 8-row blocks at rows (K0+KS*i)*DIL + 8q.  All those rows lie on the grid
+    // K0*DIL + STEP*j, so every block is read once per unit and the taps pick their four from the registers.
+    constexpr int STEP = (KS * DIL) % 8 == 0 ? 8 : 4;
+    static_assert((KS * DIL) % STEP == 0 && 8 % STEP == 0, "block grid");
+    constexpr int PER_TAP = KS * DIL / STEP, PER_Q = 8 / STEP;
+    constexpr int NB = NTW > 0 ? PER_TAP * (NTW - 1) + PER_Q * 3 + 1 : 1;
+    constexpr int NACC = NTW > 0 ? NTW : 1;
     const int tid = threadIdx.x, lane = tid & 63;
-    f32x16 acc[NTW][2];
+    f32x16 acc[NACC][2];
 #pragma unroll
-    for (int i = 0; i < NTW; ++i)
+    for (int i = 0; i < NACC; ++i)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -148,7 +155,7 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
         i32x2 blk[NB];
         static_for<NB>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            blk[j] = read_block(xw, kXPitch, W * DIL + STEP * j, 0, lane);
+            if constexpr (NTW > 0) blk[j] = read_block(xw, kXPitch, K0 * DIL + STEP * j, 0, lane);
         });
         static_for<NTW>([&](auto ic) {
             constexpr int i = decltype(ic)::value, j0 = PER_TAP * i;
@@ -169,7 +176,7 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
     const int ci = cit * kTileCi + (lane & 31);
 #pragma unroll
     for (int i = 0; i < NTW; ++i) {
-        const int k = W + 4 * i;
+        const int k = K0 + KS * i;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -180,21 +187,35 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
     }
 }
 
-template <int KT, int DIL>
+template <int KT, int DIL, int TG>
 __global__ __launch_bounds__(kThreads) void fp8_wgrad_kernel(const WgParams p)
 {
     constexpr int XROWS = kUnitT + (KT - 1) * DIL;
     static_assert(2 * XROWS <= kThreads, "one 16-byte piece of the x window per thread");
+    static_assert(TG == 1 || TG == 2, "tap groups");
     __shared__ __align__(16) unsigned char gbuf[2 * kUnitT * kGPitch];
     __shared__ __align__(16) unsigned char xbuf[2 * XROWS * kXPitch];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int sp = blockIdx.x % p.S, tile = blockIdx.x / p.S;
+    int id = blockIdx.x;
+    const int grp = id % TG;
+    id /= TG;
+    const int sp = id % p.S, tile = id / p.S;
     const int cit = tile % p.ncit, cot = tile / p.ncit;
-    switch (wave) {  // one copy per wavefront number: the tap lists are static
-    case 0: wgrad_units<KT, DIL, 0>(p, gbuf, xbuf, sp, cot, cit); break;
-    case 1: wgrad_units<KT, DIL, 1>(p, gbuf, xbuf, sp, cot, cit); break;
-    case 2: wgrad_units<KT, DIL, 2>(p, gbuf, xbuf, sp, cot, cit); break;
-    default: wgrad_units<KT, DIL, 3>(p, gbuf, xbuf, sp, cot, cit); break;
+    // one copy per (tap group, wavefront number): the tap lists are static
+    if (TG == 1 || grp == 0) {
+        switch (wave) {
+        case 0: wgrad_units<KT, DIL, TG, 0, 0>(p, gbuf, xbuf, sp, cot, cit); break;
+        case 1: wgrad_units<KT, DIL, TG, 0, 1>(p, gbuf, xbuf, sp, cot, cit); break;
+        case 2: wgrad_units<KT, DIL, TG, 0, 2>(p, gbuf, xbuf, sp, cot, cit); break;
+        default: wgrad_units<KT, DIL, TG, 0, 3>(p, gbuf, xbuf, sp, cot, cit); break;
+        }
+    } else {
+        switch (wave) {
+        case 0: wgrad_units<KT, DIL, TG, TG - 1, 0>(p, gbuf, xbuf, sp, cot, cit); break;
+        case 1: wgrad_units<KT, DIL, TG, TG - 1, 1>(p, gbuf, xbuf, sp, cot, cit); break;
+        case 2: wgrad_units<KT, DIL, TG, TG - 1, 2>(p, gbuf, xbuf, sp, cot, cit); break;
+        default: wgrad_units<KT, DIL, TG, TG - 1, 3>(p, gbuf, xbuf, sp, cot, cit); break;
+        }
     }
 }
 
@@ -206,7 +227,7 @@ __global__ __launch_bounds__(256) void wgrad_factor_kernel(const float *scale, c
 }
 
 struct WgLayout {
-    int nu, Tpg, Tpx, S, ntiles;
+    int nu, Tpg, Tpx, S, TG, ntiles;
     size_t gq_bytes, xq_bytes, part_bytes, eff_bytes, total;
 };
 WgLayout wg_layout(int B, int Cin, int Cout, int To, int K, int dil)
@@ -217,8 +238,10 @@ WgLayout wg_layout(int B, int Cin, int Cout, int To, int K, int dil)
     l.Tpx = l.nu * kUnitT + (K - 1) * dil;
     l.ntiles = (Cout / kTileCo) * (Cin / kTileCi);
     const int cus = current_device_info().cus;
-    const int slots = (K == 17 ? 2 : 1) * cus;  // K = 17 fits two workgroups per CU (registers), which hides the load latency
-    l.S = std::max(1, std::min(8, slots / l.ntiles));
+    // Two workgroups fit a CU when a wavefront holds at most five taps (registers), which hides the load latency:
+    // K = 17 as it is, longer filters with their taps dealt to two workgroups per tile.
+    l.TG = K > 20 ? 2 : 1;
+    l.S = std::max(1, std::min(8, 2 * cus / (l.ntiles * l.TG)));
     l.S = std::min(l.S, std::max(1, B * l.nu));
     l.gq_bytes = align_up((size_t)B * (Cout / 64) * l.Tpg * 64 + kSlack, 256);
     l.xq_bytes = align_up((size_t)B * (Cin / 64) * l.Tpx * 64 + kSlack, 256);
@@ -250,11 +273,11 @@ bool overlap(const void *a, size_t na, const void *b, size_t nb)
     return pa < pb + nb && pb < pa + na;
 }
 
-template <int KT, int DIL>
+template <int KT, int DIL, int TG>
 hipError_t launch_wgrad(const WgParams &p, int grid, hipStream_t s)
 {
     MainKernelTimer timer(s);
-    hipLaunchKernelGGL((fp8_wgrad_kernel<KT, DIL>), dim3(grid), dim3(kThreads), 0, s, p);
+    hipLaunchKernelGGL((fp8_wgrad_kernel<KT, DIL, TG>), dim3(grid), dim3(kThreads), 0, s, p);
     return hipGetLastError();
 }
 
@@ -306,12 +329,12 @@ extern "C" int nm_conv1d_bwd_weight_fp8(int B, int Cin, int Cout, int T, int K, 
     p.nu = l.nu; p.units = B * l.nu;
     p.Tpg = l.Tpg; p.Tpx = l.Tpx;
     p.gq = gq; p.xq = xq; p.part = part;
-    const int grid = l.ntiles * l.S;
+    const int grid = l.ntiles * l.S * l.TG;
     hipError_t e;
-    if (dilation == 2) e = launch_wgrad<29, 2>(p, grid, s);
-    else if (K == 17) e = launch_wgrad<17, 1>(p, grid, s);
-    else if (K == 21) e = launch_wgrad<21, 1>(p, grid, s);
-    else e = launch_wgrad<25, 1>(p, grid, s);
+    if (dilation == 2) e = launch_wgrad<29, 2, 2>(p, grid, s);
+    else if (K == 17) e = launch_wgrad<17, 1, 1>(p, grid, s);
+    else if (K == 21) e = launch_wgrad<21, 1, 2>(p, grid, s);
+    else e = launch_wgrad<25, 1, 2>(p, grid, s);
     if (e != hipSuccess) return NM_ERR_DEVICE;
     Geom g;
     g.B = B; g.Cin = Cin; g.Cout = Cout; g.T = T; g.K = K; g.stride = 1; g.dil = dilation; g.pad = pad; g.To = To;
