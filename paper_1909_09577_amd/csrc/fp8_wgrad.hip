@@ -241,7 +241,18 @@ WgLayout wg_layout(int B, int Cin, int Cout, int To, int K, int dil)
     // Two workgroups fit a CU when a wavefront holds at most five taps (registers), which hides the load latency:
     // K = 17 as it is, longer filters with their taps dealt to two workgroups per tile.
     l.TG = K > 20 ? 2 : 1;
-    l.S = std::max(1, std::min(8, 2 * cus / (l.ntiles * l.TG)));
+    // Workgroups per (tile, tap group): the count that minimises the number of rounds over the 2*cus slots, per
+    // split, with a charge for the float32 partial tiles every split writes and the reduction reads again.
+    const int items = l.ntiles * l.TG, slots = 2 * cus;
+    double best = 1e30;
+    l.S = 1;
+    for (int sc = 1; sc <= 8; ++sc) {
+        const double cost = (double)((items * sc + slots - 1) / slots) / sc + 0.05 * sc;
+        if (cost < best - 1e-9) {
+            best = cost;
+            l.S = sc;
+        }
+    }
     l.S = std::min(l.S, std::max(1, B * l.nu));
     l.gq_bytes = align_up((size_t)B * (Cout / 64) * l.Tpg * 64 + kSlack, 256);
     l.xq_bytes = align_up((size_t)B * (Cin / 64) * l.Tpx * 64 + kSlack, 256);
