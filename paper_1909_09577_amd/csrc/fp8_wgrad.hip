@@ -11,13 +11,17 @@
 // Four such reads fill a 32-byte operand; A and B use the same (lane half, byte) -> time step assignment, which is
 // all the contraction needs.
 //
-// Work decomposition: an output tile is 64 output channels x 32 input channels x all K taps, one workgroup (four
-// wavefronts) per tile and split; wavefront w owns the taps w, w+4, ... (two 32x32 accumulators per tap).  The
-// reduction is cut into units of one batch item x 64 time steps; the S workgroups that share a tile take every S-th
-// unit.  Per unit the workgroup stages the 64 x 64 window of g and the (64 + (K-1)*dil) x 32 window of x in LDS (one
-// 16-byte load per thread and window, requested a unit ahead, double buffered, one barrier per unit).  Every
-// workgroup writes its float32 partial tile to [S][K][Cout][Cin]; the reduction kernel of the bfloat16 path adds
-// the S partials in a fixed order, applies the per-channel factor and writes dw[co][ci][k]: deterministic.
+// Work decomposition: an output tile is 64 output channels x 32 input channels x all K taps.  A workgroup (four
+// wavefronts) takes the tile's taps -- for K > 20 every second of them, two workgroups sharing the tile -- and
+// wavefront w every fourth of those (two 32x32 accumulators per tap), so that no wavefront holds more than five taps
+// and two workgroups fit a CU: the second one's MFMAs cover the first one's waits.  The taps of a wavefront are
+// 4 or 8 rows apart, so the 8-row blocks their operands are made of lie on one grid: each block is read once per
+// unit and every tap picks its four from the registers.  The reduction is cut into units of one batch item x 64
+// time steps; the S workgroups that share a (tile, tap group) take every S-th unit.  Per unit the workgroup stages
+// the 64 x 64 window of g and the (64 + (K-1)*dil) x 32 window of x in LDS (one 16-byte load per thread and window,
+// requested a unit ahead, double buffered, one barrier per unit).  Every workgroup writes its float32 partial tile
+// to [S][K][Cout][Cin]; the reduction kernel of the bfloat16 path adds the S partials in a fixed order, applies the
+// per-channel factor and writes dw[co][ci][k]: deterministic.
 #include "../../include/nm_conv1d.h"
 #include "../../include/nm_conv1d_fp8.h"
 #include "nm_common.h"

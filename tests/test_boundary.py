@@ -286,3 +286,25 @@ def test_fp8_input_gradient_reports_argument_errors_before_any_device_call():
     assert call(dx=FAKE2) == nm.NM_ERR_BAD_ARG and call(dres=FAKE2) == nm.NM_ERR_BAD_ARG   # dx / dres alias dy
     assert L.nm_fp8_dgrad_weight_scales(64, 64, 17, None, None, FAKE, None) == nm.NM_ERR_BAD_ARG
     assert L.nm_fp8_dgrad_weight_scales(0, 64, 17, FAKE2, None, FAKE, None) == nm.NM_ERR_BAD_ARG
+
+
+def test_fp8_weight_gradient_reports_argument_errors_before_any_device_call():
+    L = nm.lib()
+    ok = dict(B=2, Cin=64, Cout=128, T=200, K=17, stride=1, dilation=1, pad=8)
+    need = nm.nm_conv1d_fp8_bwd_weight_workspace_bytes(**ok)
+    assert need > 0 and need % 256 == 0
+    assert nm.nm_conv1d_fp8_bwd_weight_workspace_bytes(**dict(ok, stride=2)) == 0
+
+    def call(x=FAKE2, xs=FAKE, dy=FAKE3, yv=None, gs=FAKE, dw=FAKE4, flags=0, wsp=FAKE5, wsb=None, **kw):
+        d = dict(ok, **kw)
+        return L.nm_conv1d_bwd_weight_fp8(d["B"], d["Cin"], d["Cout"], d["T"], d["K"], d["stride"], d["dilation"], d["pad"],
+                                          x, xs, dy, yv, gs, None, dw, flags, wsp, need if wsb is None else wsb, None)
+
+    assert call(K=13, pad=6) == nm.NM_ERR_UNSUPPORTED and call(Cin=32) == nm.NM_ERR_UNSUPPORTED
+    assert call(K=0) == nm.NM_ERR_BAD_ARG
+    for missing in ("x", "xs", "dy", "gs", "dw"):
+        assert call(**{missing: None}) == nm.NM_ERR_BAD_ARG, missing
+    assert call(flags=nm.NM_RELU) == nm.NM_ERR_BAD_ARG                # the mask needs y
+    assert call(flags=nm.NM_ACCUM_DX) == nm.NM_ERR_BAD_ARG
+    assert call(wsp=None) == nm.NM_ERR_WORKSPACE and call(wsb=need - 1) == nm.NM_ERR_WORKSPACE
+    assert call(dw=FAKE2) == nm.NM_ERR_BAD_ARG                          # dw aliases x
