@@ -265,3 +265,29 @@ def test_bwd_weight_fp8_full_size_full_tensor():
     got, ref = run_wgrad_case(cfg)
     mx, rr = U.err_metrics(got, ref)
     assert mx <= WGRAD_TOL and rr <= WGRAD_RMS, f"{cfg.name} dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
+
+
+def random_fp8_layers(n, seed):
+    """Seeded random geometries inside the served set (stride 1, channels in multiples of 64, the encoder's taps)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        K, dil = [(17, 1), (21, 1), (25, 1), (29, 2)][int(rng.integers(0, 4))]
+        Cin, Cout = 64 * int(rng.integers(1, 6)), 64 * int(rng.integers(1, 5))
+        B, T = int(rng.integers(1, 5)), int(rng.integers((K - 1) * dil + 1, 420))
+        pad = int(rng.integers(0, (K - 1) * dil + 1))
+        out.append(L(f"f8r{i}_b{B}_{Cin}to{Cout}_t{T}_k{K}d{dil}p{pad}", B, Cin, Cout, T, K, dilation=dil, pad=pad,
+                     affine=bool(rng.integers(0, 2)), relu=bool(rng.integers(0, 2)), residual=bool(rng.integers(0, 2)),
+                     seed=100 + i))
+    return out
+
+
+@pytest.mark.parametrize("cfg", random_fp8_layers(12, 2024), ids=lambda c: c.name)
+def test_random_geometries_all_three_passes(cfg):
+    got, ref, _ = run_case(cfg)
+    U.assert_close(got, ref, DT, f"{cfg.name} y")
+    got, ref = run_dgrad_case(cfg)
+    U.assert_close(got, ref, DT, f"{cfg.name} dx")
+    got, ref = run_wgrad_case(cfg)
+    mx, rr = U.err_metrics(got, ref)
+    assert mx <= WGRAD_TOL and rr <= WGRAD_RMS, f"{cfg.name} dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
