@@ -108,6 +108,16 @@ int nm_conv1d_bwd_weight_fp8(int B, int Cin, int Cout, int T, int K, int stride,
                              void *hip_stream);
 size_t nm_conv1d_fp8_bwd_weight_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
 
+/* Both gradients on E4M3 operands in one call: the results of nm_conv1d_bwd_data_fp8 and nm_conv1d_bwd_weight_fp8
+ * on the same arguments, bit for bit; the pass over dy and y that masks and quantises g runs once and feeds both.
+ * Arguments as for those two calls (dres may be NULL); flags: NM_RELU, NM_ACCUM_DW.
+ * Workspace: nm_conv1d_fp8_bwd_workspace_bytes(...). */
+int nm_conv1d_bwd_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                      const float *x_scale, const void *dy, const void *y, const float *g_scale, const void *w,
+                      const float *scale, const float *wt_scales, void *dx, void *dres, float *dw, unsigned flags,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t nm_conv1d_fp8_bwd_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,8 @@ EXPORTS = ("nm_conv1d_out_len", "nm_conv1d_workspace_bytes", "nm_strerror", "nm_
            "nm_conv1d_bwd_weight_masked", "nm_decoder_logsoftmax_fwd", "nm_conv1d_block_fwd_static", "nm_conv1d_time_next_kernel_of", "nm_conv1d_bn_fwd", "nm_conv1d_bn_bwd", "nm_conv1d_bwd_masked", "nm_conv1d_time_next_main_kernel",
            "nm_fp8_row_scales", "nm_fp8_quantize_rows", "nm_conv1d_fp8_supported", "nm_conv1d_fp8_workspace_bytes",
            "nm_conv1d_block_fwd_fp8", "nm_conv1d_bwd_data_fp8", "nm_conv1d_fp8_bwd_data_workspace_bytes",
-           "nm_fp8_dgrad_weight_scales", "nm_conv1d_bwd_weight_fp8", "nm_conv1d_fp8_bwd_weight_workspace_bytes")
+           "nm_fp8_dgrad_weight_scales", "nm_conv1d_bwd_weight_fp8", "nm_conv1d_fp8_bwd_weight_workspace_bytes",
+           "nm_conv1d_bwd_fp8", "nm_conv1d_fp8_bwd_workspace_bytes")
 
 _lib = None
 
@@ -100,6 +101,10 @@ def lib() -> ctypes.CDLL:
         L.nm_conv1d_bwd_weight_fp8.restype = i
         L.nm_conv1d_fp8_bwd_weight_workspace_bytes.argtypes = [i] * 8
         L.nm_conv1d_fp8_bwd_weight_workspace_bytes.restype = sz
+        L.nm_conv1d_bwd_fp8.argtypes = [i] * 8 + [vp] * 11 + [u, vp, sz, vp]
+        L.nm_conv1d_bwd_fp8.restype = i
+        L.nm_conv1d_fp8_bwd_workspace_bytes.argtypes = [i] * 8
+        L.nm_conv1d_fp8_bwd_workspace_bytes.restype = sz
         _lib = L
     return _lib
 
@@ -524,3 +529,39 @@ def nm_conv1d_bwd_weight_fp8(x, x_scale, dy, g_scale, K, y=None, scale=None, dw=
     if st != NM_OK:
         raise NmError(st, "nm_conv1d_bwd_weight_fp8")
     return dw
+
+
+def nm_conv1d_fp8_bwd_workspace_bytes(B, Cin, Cout, T, K, stride=1, dilation=1, pad=0) -> int:
+    return int(lib().nm_conv1d_fp8_bwd_workspace_bytes(B, Cin, Cout, T, K, stride, dilation, pad))
+
+
+def nm_conv1d_bwd_fp8(x, x_scale, dy, g_scale, w, wt_scales, y=None, scale=None, dx=None, dres=None, dw=None, *, stride=1,
+                      dilation=1, pad=0, relu=False, want_dres=False, accumulate=False, workspace=None, stream=None):
+    """Both gradients on E4M3 operands from one call; returns (dx, dres, dw)."""
+    torch = _torch()
+    B, Cin, T = x.shape
+    _, Cout, To = dy.shape
+    K = w.shape[2]
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dres is None and want_dres:
+        dres = torch.empty_like(dy)
+    if dw is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dw")
+        dw = torch.empty((Cout, Cin, K), dtype=torch.float32, device=x.device)
+    dims = (B, Cin, Cout, T, K, stride, dilation, pad)
+    if workspace is None:
+        workspace = torch.empty(max(nm_conv1d_fp8_bwd_workspace_bytes(*dims), 256), dtype=torch.uint8, device=x.device)
+    flags = (NM_RELU if relu else 0) | (NM_ACCUM_DW if accumulate else 0)
+    st = lib().nm_conv1d_bwd_fp8(
+        *dims, _ptr(x, torch.bfloat16, name="x"), _ptr(x_scale, torch.float32, (1,), "x_scale"),
+        _ptr(dy, torch.bfloat16, name="dy"), _ptr(y, torch.bfloat16, (B, Cout, To), "y"),
+        _ptr(g_scale, torch.float32, (1,), "g_scale"), _ptr(w, torch.bfloat16, (Cout, Cin, K), "w"),
+        _ptr(scale, torch.float32, (Cout,), "scale"), _ptr(wt_scales, torch.float32, (Cin,), "wt_scales"),
+        _ptr(dx, torch.bfloat16, (B, Cin, T), "dx"), _ptr(dres, torch.bfloat16, (B, Cout, To), "dres"),
+        _ptr(dw, torch.float32, (Cout, Cin, K), "dw"), flags, ctypes.c_void_p(workspace.data_ptr()), workspace.numel(),
+        _stream(stream))
+    if st != NM_OK:
+        raise NmError(st, "nm_conv1d_bwd_fp8")
+    return dx, dres, dw

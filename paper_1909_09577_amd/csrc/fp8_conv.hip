@@ -930,6 +930,39 @@ hipError_t fp8_launch_quant_g(const void *dy, const void *y, const float *gs, un
     return hipGetLastError();
 }
 
+// Input gradient behind the quantisation of g: packs the flipped, scale-folded weights (quantised per input
+// channel) into wtq and runs the matrix-core kernel on the codes gq (time-major, Tp rows per batch item and
+// 64-channel group, row r standing for output time r - (dil*(K-1) - pad)).
+hipError_t fp8_dgrad_run(int B, int Cin, int Cout, int T, int K, int dil, const unsigned char *gq, int Tp, const float *g_scale,
+                         const void *w, const float *scale, const float *wt_scales, void *dx, unsigned char *wtq, hipStream_t s)
+{
+    const int ncit = Cin / kTileCo, nck = Cout / kChunk, ntt = (T + kTileT - 1) / kTileT;
+    hipLaunchKernelGGL(pack_wt_kernel, dim3(2, nck, ncit), dim3(kPackThreads), (size_t)64 * (32 * K + 8), s, (const bf16_t *)w,
+                       scale, wt_scales, wtq, Cin, K);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    Fp8Params p;
+    p.B = B; p.Cin = Cout; p.Cout = Cin; p.To = T; p.K = K;
+    p.ncot = ncit; p.nck = nck; p.ntt = ntt; p.Tp = Tp;
+    p.nbt = B * ntt;
+    p.ntiles = ncit * 4 * ((p.nbt + 3) / 4);
+    p.relu = 0;
+    p.vec_io = (T % 8 == 0 && !((uintptr_t)dx & 15)) ? 1 : 0;
+    p.xq = gq; p.wq = wtq;
+    p.xs = g_scale; p.ws = wt_scales; p.scale = nullptr; p.shift = nullptr;
+    p.res = nullptr;
+    p.y = (bf16_t *)dx;
+    if (dil == 2) return launch_fp8_conv<29, 2>(p, s);
+    if (K == 17) return launch_fp8_conv<17, 1>(p, s);
+    if (K == 21) return launch_fp8_conv<21, 1>(p, s);
+    return launch_fp8_conv<25, 1>(p, s);
+}
+// bytes of the packed weight operand (either direction) including the slack prefetches may read
+size_t fp8_packed_weight_bytes(int Cin, int Cout, int K)
+{
+    return align_up((size_t)(Cout / kTileCo) * (Cin / kChunk) * K * kTapBytes + kSlack, 256);
+}
+
 }  // namespace nm
 
 using namespace nm;
@@ -1089,25 +1122,8 @@ extern "C" int nm_conv1d_bwd_data_fp8(int B, int Cin, int Cout, int T, int K, in
     else
         hipLaunchKernelGGL(quant_g_kernel, dim3((l.Tp + 63) / 64, l.nck, B), dim3(256), 0, s, (const bf16_t *)dy, ym, g_scale, gq,
                            (bf16_t *)dres, Cout, To, l.Tp, padL);
-    hipLaunchKernelGGL(pack_wt_kernel, dim3(2, l.nck, l.ncot), dim3(kPackThreads), (size_t)64 * (32 * K + 8), s,
-                       (const bf16_t *)w, scale, wt_scales, wtq, Cin, K);
     if (hipGetLastError() != hipSuccess) return NM_ERR_DEVICE;
-
-    Fp8Params p;
-    p.B = B; p.Cin = Cout; p.Cout = Cin; p.To = T; p.K = K;
-    p.ncot = l.ncot; p.nck = l.nck; p.ntt = l.ntt; p.Tp = l.Tp;
-    p.nbt = B * l.ntt;
-    p.ntiles = l.ncot * 4 * ((p.nbt + 3) / 4);
-    p.relu = 0;
-    p.vec_io = (T % 8 == 0 && !((uintptr_t)dx & 15)) ? 1 : 0;
-    p.xq = gq; p.wq = wtq;
-    p.xs = g_scale; p.ws = wt_scales; p.scale = nullptr; p.shift = nullptr;
-    p.res = nullptr;
-    p.y = (bf16_t *)dx;
-    hipError_t e;
-    if (dilation == 2) e = launch_fp8_conv<29, 2>(p, s);
-    else if (K == 17) e = launch_fp8_conv<17, 1>(p, s);
-    else if (K == 21) e = launch_fp8_conv<21, 1>(p, s);
-    else e = launch_fp8_conv<25, 1>(p, s);
-    return e == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+    return fp8_dgrad_run(B, Cin, Cout, T, K, dilation, gq, l.Tp, g_scale, w, scale, wt_scales, dx, wtq, s) == hipSuccess
+               ? NM_OK
+               : NM_ERR_DEVICE;
 }

@@ -36,6 +36,9 @@ hipError_t fp8_launch_quant_x(const void *x, const float *xs, unsigned char *xq,
 hipError_t fp8_launch_quant_g(const void *dy, const void *y, const float *gs, unsigned char *gq, void *dres, int B, int C,
                               int T, int Tp, int pad, hipStream_t s);
 bool fp8_taps_supported(int K, int dil);
+hipError_t fp8_dgrad_run(int B, int Cin, int Cout, int T, int K, int dil, const unsigned char *gq, int Tp, const float *g_scale,
+                         const void *w, const float *scale, const float *wt_scales, void *dx, unsigned char *wtq, hipStream_t s);
+size_t fp8_packed_weight_bytes(int Cin, int Cout, int K);
 
 namespace {
 
@@ -58,6 +61,7 @@ struct WgParams {
     int ncit, S;         // input-channel tiles (of 32); workgroups per output tile
     int nu, units;       // units per batch item; B * nu
     int Tpg, Tpx;        // rows per (batch item, 64-channel group) of gq / xq
+    int g_row0;          // row of gq that stands for output time 0
     const unsigned char *gq;  // [B][Cout/64][Tpg][64]
     const unsigned char *xq;  // [B][Cin/64][Tpx][64]
     float *part;              // [S][K][Cout][Cin]
@@ -126,7 +130,7 @@ __device__ __forceinline__ void wgrad_units(const WgParams &p, unsigned char *gb
     const bool has_x = tid < 2 * XROWS;
     auto g_src = [&](int u) {
         const int b = u / p.nu, tu = u - b * p.nu;
-        return p.gq + (((size_t)b * nckg + cot) * p.Tpg + (size_t)tu * kUnitT) * 64 + tid * 16;
+        return p.gq + (((size_t)b * nckg + cot) * p.Tpg + (size_t)tu * kUnitT + p.g_row0) * 64 + tid * 16;
     };
     auto x_src = [&](int u) {
         const int b = u / p.nu, tu = u - b * p.nu;
@@ -296,6 +300,37 @@ hipError_t launch_wgrad(const WgParams &p, int grid, hipStream_t s)
     return hipGetLastError();
 }
 
+// The weight gradient behind the quantisation of g: quantises x into `rest`, runs the matrix-core kernel on the
+// codes gq (Tpg rows per batch item and channel group, row g_row0 standing for output time 0) and reduces the
+// partial tiles into dw.  `rest`: xq, partial tiles, per-channel factors (sizes of `l`).
+hipError_t wgrad_run(int B, int Cin, int Cout, int T, int To, int K, int dil, int pad, const WgLayout &l, const unsigned char *gq,
+                     int Tpg, int g_row0, const void *x, const float *x_scale, const float *g_scale, const float *scale, float *dw,
+                     bool accumulate, unsigned char *rest, hipStream_t s)
+{
+    unsigned char *xq = rest;
+    float *part = reinterpret_cast<float *>(xq + l.xq_bytes);
+    float *eff = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(part) + l.part_bytes);
+    hipError_t e = fp8_launch_quant_x(x, x_scale, xq, B, Cin, T, l.Tpx, pad, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(wgrad_factor_kernel, dim3((Cout + 255) / 256), dim3(256), 0, s, scale, g_scale, x_scale, eff, Cout);
+    WgParams p;
+    p.B = B; p.Cin = Cin; p.Cout = Cout; p.K = K;
+    p.ncit = Cin / kTileCi; p.S = l.S;
+    p.nu = l.nu; p.units = B * l.nu;
+    p.Tpg = Tpg; p.Tpx = l.Tpx; p.g_row0 = g_row0;
+    p.gq = gq; p.xq = xq; p.part = part;
+    const int grid = l.ntiles * l.S * l.TG;
+    if (dil == 2) e = launch_wgrad<29, 2, 2>(p, grid, s);
+    else if (K == 17) e = launch_wgrad<17, 1, 1>(p, grid, s);
+    else if (K == 21) e = launch_wgrad<21, 1, 2>(p, grid, s);
+    else e = launch_wgrad<25, 1, 2>(p, grid, s);
+    if (e != hipSuccess) return e;
+    Geom g;
+    g.B = B; g.Cin = Cin; g.Cout = Cout; g.T = T; g.K = K; g.stride = 1; g.dil = dil; g.pad = pad; g.To = To;
+    g.len = nullptr;
+    return launch_wgrad_reduce(g, part, dw, eff, l.S, accumulate, s);
+}
+
 }  // namespace
 }  // namespace nm
 
@@ -331,29 +366,84 @@ extern "C" int nm_conv1d_bwd_weight_fp8(int B, int Cin, int Cout, int T, int K, 
 
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char *gq = (unsigned char *)workspace;
-    unsigned char *xq = gq + l.gq_bytes;
-    float *part = reinterpret_cast<float *>(xq + l.xq_bytes);
-    float *eff = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(part) + l.part_bytes);
+    unsigned char *rest = gq + l.gq_bytes;
     if (fp8_launch_quant_g(dy, relu ? y : nullptr, g_scale, gq, nullptr, B, Cout, To, l.Tpg, 0, s) != hipSuccess) return NM_ERR_DEVICE;
-    if (fp8_launch_quant_x(x, x_scale, xq, B, Cin, T, l.Tpx, pad, s) != hipSuccess) return NM_ERR_DEVICE;
-    hipLaunchKernelGGL(wgrad_factor_kernel, dim3((Cout + 255) / 256), dim3(256), 0, s, scale, g_scale, x_scale, eff, Cout);
+    return wgrad_run(B, Cin, Cout, T, To, K, dilation, pad, l, gq, l.Tpg, 0, x, x_scale, g_scale, scale, dw,
+                     (flags & NM_ACCUM_DW) != 0, rest, s) == hipSuccess
+               ? NM_OK
+               : NM_ERR_DEVICE;
+}
 
-    WgParams p;
-    p.B = B; p.Cin = Cin; p.Cout = Cout; p.K = K;
-    p.ncit = Cin / kTileCi; p.S = l.S;
-    p.nu = l.nu; p.units = B * l.nu;
-    p.Tpg = l.Tpg; p.Tpx = l.Tpx;
-    p.gq = gq; p.xq = xq; p.part = part;
-    const int grid = l.ntiles * l.S * l.TG;
-    hipError_t e;
-    if (dilation == 2) e = launch_wgrad<29, 2, 2>(p, grid, s);
-    else if (K == 17) e = launch_wgrad<17, 1, 1>(p, grid, s);
-    else if (K == 21) e = launch_wgrad<21, 1, 2>(p, grid, s);
-    else e = launch_wgrad<25, 1, 2>(p, grid, s);
-    if (e != hipSuccess) return NM_ERR_DEVICE;
-    Geom g;
-    g.B = B; g.Cin = Cin; g.Cout = Cout; g.T = T; g.K = K; g.stride = 1; g.dil = dilation; g.pad = pad; g.To = To;
-    g.len = nullptr;
-    e = launch_wgrad_reduce(g, part, dw, eff, l.S, (flags & NM_ACCUM_DW) != 0, s);
-    return e == hipSuccess ? NM_OK : NM_ERR_DEVICE;
+// ---- both gradients in one call: g is masked and quantised once ------------------------------------------
+namespace {
+struct BwdLayout {
+    WgLayout wg;
+    int Tp;  // rows of the shared codes of g: the input gradient's window rows and the weight gradient's units behind padL
+    size_t gq_bytes, wtq_bytes, total;
+};
+BwdLayout bwd_layout(int B, int Cin, int Cout, int T, int To, int K, int dil, int pad)
+{
+    BwdLayout l;
+    l.wg = wg_layout(B, Cin, Cout, To, K, dil);
+    const int padL = dil * (K - 1) - pad;
+    l.Tp = std::max((T + 159) / 160 * 160 + (K - 1) * dil, l.wg.nu * kUnitT + padL);
+    l.gq_bytes = align_up((size_t)B * (Cout / 64) * l.Tp * 64 + kSlack, 256);
+    l.wtq_bytes = fp8_packed_weight_bytes(Cout, Cin, K);
+    l.total = l.gq_bytes + l.wtq_bytes + l.wg.xq_bytes + l.wg.part_bytes + l.wg.eff_bytes;
+    return l;
+}
+}  // namespace
+
+extern "C" size_t nm_conv1d_fp8_bwd_workspace_bytes(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad)
+{
+    int To = 0;
+    if (wg_check(B, Cin, Cout, T, K, stride, dilation, pad, &To) != NM_OK) return 0;
+    return bwd_layout(B, Cin, Cout, T, To, K, dilation, pad).total;
+}
+
+extern "C" int nm_conv1d_bwd_fp8(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,
+                                 const float *x_scale, const void *dy, const void *y, const float *g_scale, const void *w,
+                                 const float *scale, const float *wt_scales, void *dx, void *dres, float *dw, unsigned flags,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int To = 0;
+    const int st = wg_check(B, Cin, Cout, T, K, stride, dilation, pad, &To);
+    if (st != NM_OK) return st;
+    if (!x || !x_scale || !dy || !g_scale || !w || !wt_scales || !dx || !dw) return NM_ERR_BAD_ARG;
+    if (flags & ~(unsigned)(NM_RELU | NM_ACCUM_DW)) return NM_ERR_BAD_ARG;
+    const bool relu = (flags & NM_RELU) != 0;
+    if (relu && !y) return NM_ERR_BAD_ARG;
+    if (((uintptr_t)w & 15) || ((uintptr_t)x & 1) || ((uintptr_t)dy & 1) || ((uintptr_t)y & 1) || ((uintptr_t)dx & 1) ||
+        ((uintptr_t)dres & 1) || ((uintptr_t)dw & 3))
+        return NM_ERR_BAD_ARG;
+    const BwdLayout l = bwd_layout(B, Cin, Cout, T, To, K, dilation, pad);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < l.total) return NM_ERR_WORKSPACE;
+    const size_t nx = (size_t)B * Cin * T * 2, ny = (size_t)B * Cout * To * 2, nw = (size_t)Cout * Cin * K * 2, ndw = nw * 2;
+    const void *ins[] = {x, dy, y, w};
+    const size_t in_bytes[] = {nx, ny, ny, nw};
+    void *outs[] = {dx, dres, dw};
+    const size_t out_bytes[] = {nx, ny, ndw};
+    for (int o = 0; o < 3; ++o) {
+        if (overlap(outs[o], out_bytes[o], workspace, l.total)) return NM_ERR_BAD_ARG;
+        for (int i = 0; i < 4; ++i)
+            if (overlap(outs[o], out_bytes[o], ins[i], in_bytes[i])) return NM_ERR_BAD_ARG;
+        for (int o2 = o + 1; o2 < 3; ++o2)
+            if (overlap(outs[o], out_bytes[o], outs[o2], out_bytes[o2])) return NM_ERR_BAD_ARG;
+    }
+    for (int i = 0; i < 4; ++i)
+        if (overlap(ins[i], in_bytes[i], workspace, l.total)) return NM_ERR_BAD_ARG;
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    unsigned char *gq = (unsigned char *)workspace;
+    unsigned char *wtq = gq + l.gq_bytes;
+    unsigned char *rest = wtq + l.wtq_bytes;
+    const int padL = dilation * (K - 1) - pad;
+    // one pass over dy and y: dres and the codes of g, laid out for the input gradient (row = time + padL)
+    if (fp8_launch_quant_g(dy, relu ? y : nullptr, g_scale, gq, dres, B, Cout, To, l.Tp, padL, s) != hipSuccess) return NM_ERR_DEVICE;
+    if (fp8_dgrad_run(B, Cin, Cout, T, K, dilation, gq, l.Tp, g_scale, w, scale, wt_scales, dx, wtq, s) != hipSuccess)
+        return NM_ERR_DEVICE;
+    return wgrad_run(B, Cin, Cout, T, To, K, dilation, pad, l.wg, gq, l.Tp, padL, x, x_scale, g_scale, scale, dw,
+                     (flags & NM_ACCUM_DW) != 0, rest, s) == hipSuccess
+               ? NM_OK
+               : NM_ERR_DEVICE;
 }

@@ -291,3 +291,29 @@ def test_random_geometries_all_three_passes(cfg):
     got, ref = run_wgrad_case(cfg)
     mx, rr = U.err_metrics(got, ref)
     assert mx <= WGRAD_TOL and rr <= WGRAD_RMS, f"{cfg.name} dw: max scaled error {mx:.3e}, rel rms {rr:.3e}"
+
+
+@pytest.mark.parametrize("cfg", [
+    L("f8b_ragged", 3, 128, 64, 200, 17, residual=True),
+    L("f8b_odd_length", 2, 64, 128, 333, 21),
+    L("f8b_k25_no_relu", 2, 192, 128, 160, 25, relu=False, affine=False),
+    L("f8b_k29_d2", 2, 128, 64, 248, 29, dilation=2),
+    L("f8b_short_pad", 2, 64, 64, 180, 17, pad=3),
+    L("f8b_long_pad", 2, 64, 64, 104, 17, pad=16),
+    L("f8b_b3_512_k17", 32, 512, 512, 800, 17, residual=True, seed=2),
+], ids=lambda c: c.name)
+def test_fused_backward_fp8_is_bit_identical_to_the_two_calls(cfg):
+    import torch
+    inp = syn.make_inputs(cfg, DT)
+    kw = U.geom_kw(cfg)
+    xd, dyd, wd = U.to_dev(inp, "x", DT), U.to_dev(inp, "dy", DT), U.to_dev(inp, "w", DT)
+    yd = U.to_dev(inp, "y_saved", DT) if cfg.relu else None
+    scd = U.to_dev(inp, "scale", DT) if cfg.affine else None
+    sxd, sgd = nm.nm_fp8_row_scales(xd, 1), nm.nm_fp8_row_scales(dyd, 1)
+    swtd = nm.nm_fp8_dgrad_weight_scales(wd, scd)
+    dx, dres = nm.nm_conv1d_bwd_data_fp8(dyd, sgd, wd, swtd, cfg.T, y=yd, scale=scd, relu=cfg.relu, want_dres=True, **kw)
+    dw = nm.nm_conv1d_bwd_weight_fp8(xd, sxd, dyd, sgd, cfg.K, y=yd, scale=scd, relu=cfg.relu, **kw)
+    dx1, dres1, dw1 = nm.nm_conv1d_bwd_fp8(xd, sxd, dyd, sgd, wd, swtd, y=yd, scale=scd, relu=cfg.relu, want_dres=True, **kw)
+    assert torch.equal(dx1, dx) and torch.equal(dres1, dres) and torch.equal(dw1, dw)
+    dx2, dres2, dw2 = nm.nm_conv1d_bwd_fp8(xd, sxd, dyd, sgd, wd, swtd, y=yd, scale=scd, relu=cfg.relu, **kw)
+    assert dres2 is None and torch.equal(dx2, dx) and torch.equal(dw2, dw)
