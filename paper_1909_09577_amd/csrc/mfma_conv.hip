@@ -244,7 +244,8 @@ struct TileCoords {
 
 // KT > 0: the number of taps is a compile-time constant and a chunk is one straight-line block
 // (see the unrolled main loop below); KT == 0: any K, tap pairs in a loop.
-template <int NT, int STRIDE, int KT>
+// LEN: the instance for calls with per-sample lengths; it alone carries the test for tiles in the padding.
+template <int NT, int STRIDE, int KT, bool LEN = false>
 __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -485,7 +486,18 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
         if (!p.overlap && nmy > 0) stage_chunk_now(tc.b, wave, tc.ws_al, buf_ptr(cc));
 
         if constexpr (KT > 0) {
-            const int n_ch = priv ? p.nch : nmy;  // chunks of this item for this wavefront
+            // A tile that lies wholly in the padding of its batch item -- every input sample its window covers is at or
+            // beyond the valid length (forward), or every output position is at or beyond the output limit (input
+            // gradient) -- needs no arithmetic: its accumulators stay zero (the staged window is zero) or its outputs are
+            // written as zeros.  It still runs ONE chunk, which keeps the pipeline (staging of the next item's first
+            // chunk, weight sets) exactly as it is for a live tile.
+            bool dead = false;
+            if constexpr (LEN) {
+                if (p.len_in) dead = tc.t0 * STRIDE - p.padL >= clipped_len(p.len_in, tc.b, p.Tin);
+                if (p.len_out) dead = dead || tc.t0 >= epi.out_limit(tc.b);
+            }
+            const int n_full = priv ? p.nch : nmy;  // chunks of this item for this wavefront
+            const int n_ch = dead ? min(n_full, 1) : n_full;
             auto chunk_of = [&](int i) { return priv ? i : wave + kWaves * i; };
             if (n_ch > 0) {
                 // ---- unrolled main loop: one chunk (KT taps, 4*NT*KT MFMAs) is a single straight-line
@@ -1216,10 +1228,10 @@ size_t packed_bytes(int M, int R, int K)
 constexpr size_t kMaxPacked = (size_t)1 << 31;  // the kernel addresses packed weights with 32-bit offsets
 constexpr size_t kMaxInput = (size_t)1 << 30;   // and the activation tensors through buffer descriptors
 
-template <int NT, int STRIDE, int KT>
+template <int NT, int STRIDE, int KT, bool LEN = false>
 hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 {
-    auto kern = conv_gemm_kernel<NT, STRIDE, KT>;
+    auto kern = conv_gemm_kernel<NT, STRIDE, KT, LEN>;
     static LdsOptIn opt_in;
     hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), kMaxLds);
     if (e != hipSuccess) return e;
@@ -1253,6 +1265,17 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
     // one tap, no padding, wide tiles: the GEMM kernel whose wavefronts share the staged activations
     // (worth it from two 64-channel row tiles on: a single one would leave three wavefronts idle)
     if (p.K == 1 && p.nmt >= 2 && pl.nt == 5 && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout) return launch_pointwise(p, s);
+    if (pl.unrolled && (p.len_in || p.len_out)) {
+        switch (p.K) {
+        case 11: return launch_t<5, 1, 11, true>(p, pl.lds, s);
+        case 13: return launch_t<5, 1, 13, true>(p, pl.lds, s);
+        case 21: return launch_t<5, 1, 21, true>(p, pl.lds, s);
+        case 25: return launch_t<5, 1, 25, true>(p, pl.lds, s);
+        case 29: return launch_t<5, 1, 29, true>(p, pl.lds, s);
+        case 17: return launch_t<5, 1, 17, true>(p, pl.lds, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     if (pl.unrolled) {
         switch (p.K) {
         case 11: return launch_t<5, 1, 11>(p, pl.lds, s);
