@@ -703,7 +703,9 @@ constexpr TapPlan make_tap_plan()
     return q;
 }
 
-template <int KG, int DIL, int W>
+// LEN: the launch carries valid lengths; the units of an item whose x window lies wholly in the padding
+// multiply zeros and are left out of the enumeration (every workgroup walks the same shortened list).
+template <int KG, int DIL, int W, bool LEN>
 __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char *smem, int sp, int k0, int kt, int co0,
                                              int ci0)
 {
@@ -741,13 +743,36 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     struct UnitPos {
         int b, c;
     };
-    auto unit_pos = [&](int u) { return UnitPos{u / p.nchunk, u % p.nchunk}; };
+    // with lengths: chunks of item b that reach below its valid length (chunk c reads x from c*80 - pad on)
+    auto live_chunks_of = [&](int tl) { return tl > 0 ? min(p.nchunk, (tl + p.pad + kFastTCH - 1) / kFastTCH) : 0; };
+    auto carry_over = [&](UnitPos &q) {  // c counts live chunks from the start of item b onwards
+        while (q.b < p.B) {
+            const int n = live_chunks_of(__builtin_amdgcn_readfirstlane(clipped_len(p.len, q.b, p.T)));
+            if (q.c < n) break;
+            q.c -= n;
+            ++q.b;
+        }
+    };
+    auto unit_pos = [&](int u) {
+        if constexpr (LEN) {
+            UnitPos q{0, u};
+            carry_over(q);
+            return q;
+        } else {
+            return UnitPos{u / p.nchunk, u % p.nchunk};
+        }
+    };
     auto advance = [&](UnitPos &q) {
-        q.b += step_b;
-        q.c += step_c;
-        const bool carry = q.c >= p.nchunk;
-        q.c -= carry ? p.nchunk : 0;
-        q.b += carry ? 1 : 0;
+        if constexpr (LEN) {
+            q.c += S;
+            carry_over(q);
+        } else {
+            q.b += step_b;
+            q.c += step_c;
+            const bool carry = q.c >= p.nchunk;
+            q.c -= carry ? p.nchunk : 0;
+            q.b += carry ? 1 : 0;
+        }
     };
     auto unit_addr = [&](const UnitPos &q) {
         UnitAddr a;
@@ -810,19 +835,31 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
-    const int my_units = sp < p.units ? (p.units - sp + S - 1) / S : 0;  // the same for all four wavefronts
+    int units = p.units;
+    if constexpr (LEN) {  // live units of the whole batch: one item per lane, summed over the wavefront
+        units = 0;
+        for (int b0 = 0; b0 < p.B; b0 += 64) {
+            int n = b0 + lane < p.B ? live_chunks_of(clipped_len(p.len, b0 + lane, p.T)) : 0;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) n += __shfl_xor(n, m, 64);
+            units += __builtin_amdgcn_readfirstlane(n);
+        }
+    }
+    const int my_units = sp < units ? (units - sp + S - 1) / S : 0;  // the same for all four wavefronts
     // x items in flight: two register sets; set X(u mod 2) is written to LDS during unit u (it holds this
     // wavefront's item of window u+2), set X((u+1) mod 2) is requested during unit u (window u+3)
     u32x4 xa0, xb0r, xa1, xb1r;
     int tlen0 = 0, tbase0 = 0, tlen1 = 0, tbase1 = 0;  // of the windows waiting in the two sets
     s16x4 rd[2][NROW];                                  // rows of the current / the next step
     UnitPos ahead = unit_pos(sp);                       // the unit whose window is requested next
+    UnitPos behind = ahead;                             // with lengths: the unit before `ahead`
     {
         const UnitAddr a0 = unit_addr(ahead);
         advance(ahead);
         const UnitAddr a1 = unit_addr(ahead);
         advance(ahead);
         const UnitAddr a2 = unit_addr(ahead);
+        behind = ahead;
         advance(ahead);
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
@@ -851,11 +888,16 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
         constexpr int PAR = decltype(par_c)::value;
         // the dz fragments requested in this unit are those of the unit after the next; the x item is one further
         UnitPos two = ahead;  // `ahead` is three units on
-        two.b -= step_b;
-        two.c -= step_c;
-        if (two.c < 0) {
-            two.c += p.nchunk;
-            two.b -= 1;
+        if constexpr (LEN) {
+            two = behind;  // the shortened list has no fixed step to take back
+            behind = ahead;
+        } else {
+            two.b -= step_b;
+            two.c -= step_c;
+            if (two.c < 0) {
+                two.c += p.nchunk;
+                two.b -= 1;
+            }
         }
         const UnitAddr an2 = unit_addr(two);
         const UnitAddr an3 = unit_addr(ahead);
@@ -935,7 +977,7 @@ __device__ __forceinline__ void shared_units(const WgradParams &p, unsigned char
     }
 }
 
-template <int KG, int DIL>
+template <int KG, int DIL, bool LEN = false>
 __global__ __launch_bounds__(kThreads) void wgrad_shared_kernel(const WgradParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -946,10 +988,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_shared_kernel(const WgradParam
     const int kt = min(p.KTg, p.K - k0);
     const int co0 = tcd.cot * kTileCo, ci0 = tcd.cit * kTileCi;
     switch (wave) {  // one copy per wavefront number: the block lists are static
-    case 0: shared_units<KG, DIL, 0>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
-    case 1: shared_units<KG, DIL, 1>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
-    case 2: shared_units<KG, DIL, 2>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
-    default: shared_units<KG, DIL, 3>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    case 0: shared_units<KG, DIL, 0, LEN>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    case 1: shared_units<KG, DIL, 1, LEN>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    case 2: shared_units<KG, DIL, 2, LEN>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
+    default: shared_units<KG, DIL, 3, LEN>(p, smem, tcd.sp, k0, kt, co0, ci0); break;
     }
 }
 
@@ -1157,9 +1199,11 @@ hipError_t launch_fast_kt(const WgradParams &p, size_t lds, int grid, hipStream_
 template <int KG, int DIL>
 hipError_t launch_shared(const WgradParams &p, size_t lds, int grid, hipStream_t s)
 {
-    auto kern = wgrad_shared_kernel<KG, DIL>;
     MainKernelTimer timer(s);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, s, p);
+    if (p.len)
+        hipLaunchKernelGGL((wgrad_shared_kernel<KG, DIL, true>), dim3(grid), dim3(kThreads), lds, s, p);
+    else
+        hipLaunchKernelGGL((wgrad_shared_kernel<KG, DIL>), dim3(grid), dim3(kThreads), lds, s, p);
     return hipGetLastError();
 }
 
