@@ -762,25 +762,42 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 // workgroup barrier per stage.  Stages form one stream across the tiles of a workgroup: stage n is
 // requested during stage n-2 (two register sets), written to LDS buffer n&1 during stage n-1, and
 // each wavefront reloads a weight fragment right after its use with the next stage's.  Every
-// wavefront finishes its own 64 rows (no exchange); the LDS tile of that epilogue lies in the buffer
+// wavefront finishes its own rows (no exchange); the LDS tile of that epilogue lies in the buffer
 // the tile's last stage has just used.  Packed weights: the layout of prepack_kernel (Kp = 2, tap 0).
-constexpr int kPwStageCh = 128;
-constexpr int kPwChunks = kPwStageCh / kChunk;      // 4 chunks of 32 channels per stage
-constexpr int kPwRowBytes = kPwStageCh * 2 + 16;    // 272: any 16 consecutive rows cover all banks with 16-byte reads
-constexpr int kPwRows = 160;                        // time steps per tile (NT = 5)
-constexpr int kPwBufBytes = kPwRows * kPwRowBytes;  // 43520
-constexpr int kPwItems = kPwRows / 8 * (kPwStageCh / 2) / kThreads;  // 5 staging items per lane and stage
-static_assert(kPwItems * kWaves == 20, "20 blocks of 16 channel pairs x 4 time groups");
-constexpr size_t kPwLds = 2 * (size_t)kPwBufBytes;
+// (The figures above are those of the shape (2, 5, 128); PwShape lists the shapes.)
+// The shape of a workgroup tile: every wavefront owns MI row blocks (32 channels each) x NT time blocks and the
+// reduction runs in stages of SC channels.  (2, 5, 128): 256 channels x 160 steps, 512 LDS bytes read per MFMA;
+// (4, 4, 64): 512 channels x 128 steps, all 256 accumulation registers in use, 256 LDS bytes read and half the
+// staging work per MFMA -- the faster one wherever its tiles fit the tensor.
+template <int MI, int NT, int SC>
+struct PwShape {
+    static_assert(MI % 2 == 0 && SC % kChunk == 0, "whole 64-row tiles, whole chunks");
+    static constexpr int kRowTiles = MI / 2;                 // 64-row tiles of the packed weights per wavefront
+    static constexpr int kChunks = SC / kChunk;              // chunks of 32 channels per stage
+    static constexpr int kRowBytes = SC * 2 + 16;            // 272 / 144: any 16 consecutive rows cover all banks with 16-byte reads
+    static constexpr int kRows = NT * 32;                    // time steps per tile
+    static constexpr int kBufBytes = kRows * kRowBytes;
+    static constexpr int kPairBlocks = SC / 32;              // blocks of 16 channel pairs
+    static constexpr int kItems = NT * kPairBlocks / kWaves; // staging items per lane and stage (blocks of 16 pairs x 4 time groups)
+    static_assert(kItems * kWaves == NT * kPairBlocks && kItems <= 2 * kChunks, "one staging item per k-step");
+    static constexpr int kEpiBytes = kWaves * 16 * kRows * (int)sizeof(float);  // the four epilogue tiles
+    static constexpr bool kEpiInBuf = kEpiBytes <= kBufBytes;  // they fit the buffer the tile's last stage has used
+    static constexpr size_t kLds = 2 * (size_t)kBufBytes + (kEpiInBuf ? 0 : kEpiBytes);
+};
 
-__global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemmParams p)
+// LEN: the launch carries input lengths (a staged group may straddle the valid length of its item).
+template <bool LEN, int MI, int NT, int SC>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void pointwise_gemm_kernel(const ConvGemmParams p)
 {
-    constexpr int NT = 5, TN = NT * 32;
+    using Sh = PwShape<MI, NT, SC>;
+    constexpr int TN = NT * 32, RT = Sh::kRowTiles;
+    constexpr int kPwStageCh = SC, kPwChunks = Sh::kChunks, kPwRowBytes = Sh::kRowBytes, kPwBufBytes = Sh::kBufBytes;
+    constexpr int kPwItems = Sh::kItems, kPB = Sh::kPairBlocks;
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int T = p.Tout;                                  // == p.Tin
-    const int nmt4 = (p.nmt + kWaves - 1) / kWaves;        // workgroup row tiles
+    const int nmt4 = (p.nmt + kWaves * RT - 1) / (kWaves * RT);  // workgroup row tiles
     const int nst = (p.R + kPwStageCh - 1) / kPwStageCh;   // stages per tile
     const int ncols = p.ntt * p.B;                         // time tiles of all batch items
     const int ntiles = nmt4 * ncols;
@@ -835,8 +852,8 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
             decode(q);
         }
     };
-    // ---- activations: the stage is 64 channel pairs x 20 time groups (8 steps each), cut into 20 blocks
-    // of 16 pairs x 4 groups; block 5*wave + it is item `it` of this wavefront: lane = (group, pair), so
+    // ---- activations: the stage is SC/2 channel pairs x 4*NT time groups (8 steps each), cut into blocks
+    // of 16 pairs x 4 groups; block kItems*wave + it is item `it` of this wavefront: lane = (group, pair), so
     // a load instruction reads 16 rows x 64 contiguous bytes and a write instruction 16 consecutive
     // dwords in each of 4 rows
     u32x4 xa0[kPwItems], xb0[kPwItems], xa1[kPwItems], xb1[kPwItems];
@@ -844,7 +861,7 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         const uint32_t soff = (uint32_t)(q.b * p.R + q.s * kPwStageCh) * (uint32_t)(T * 2);  // < 2^30: checked by the host
         const int rem = p.R - q.s * kPwStageCh;  // channels left from this stage on
         const int blk = wave * kPwItems + it;
-        const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
+        const int pair = (blk % kPB) * 16 + (lane & 15), tg = (blk / kPB) * 4 + (lane >> 4);
         const int t = q.t0 + 8 * tg;
         const bool ok = q.valid && t < q.tlen;  // groups that start inside the valid length (T % 8 == 0: they end inside the row)
         const uint32_t off = (uint32_t)(((2 * pair) * T + t) * 2);
@@ -858,21 +875,26 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
     // (time steps at or beyond the valid length of the stage's batch item are written as zeros)
     auto x_write_item = [&](unsigned char *buf, const Pos &q, int it, const u32x4 &xa, const u32x4 &xb) {
         const int blk = wave * kPwItems + it;
-        const int pair = (blk & 3) * 16 + (lane & 15), tg = (blk >> 2) * 4 + (lane >> 4);
+        const int pair = (blk % kPB) * 16 + (lane & 15), tg = (blk / kPB) * 4 + (lane >> 4);
         uint32_t *dst = reinterpret_cast<uint32_t *>(buf + (8 * tg) * kPwRowBytes + pair * 4);
         const int nvalid = q.tlen - (q.t0 + 8 * tg);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            dst[(2 * j) * (kPwRowBytes / 4)] = nvalid > 2 * j ? zip_lo16(xa[j], xb[j]) : 0u;
-            dst[(2 * j + 1) * (kPwRowBytes / 4)] = nvalid > 2 * j + 1 ? zip_hi16(xa[j], xb[j]) : 0u;
+            if constexpr (LEN) {
+                dst[(2 * j) * (kPwRowBytes / 4)] = nvalid > 2 * j ? zip_lo16(xa[j], xb[j]) : 0u;
+                dst[(2 * j + 1) * (kPwRowBytes / 4)] = nvalid > 2 * j + 1 ? zip_hi16(xa[j], xb[j]) : 0u;
+            } else {  // T % 8 == 0: a group lies wholly inside the row or was loaded as zeros
+                dst[(2 * j) * (kPwRowBytes / 4)] = zip_lo16(xa[j], xb[j]);
+                dst[(2 * j + 1) * (kPwRowBytes / 4)] = zip_hi16(xa[j], xb[j]);
+            }
         }
     };
-    // ---- weights of this wavefront's 64 rows: [chunk of the stage][ks][mi], reloaded in place
-    bf16x8 wf[kPwChunks][2][2];
+    // ---- weights of this wavefront's 32*MI rows: [chunk of the stage][ks][mi], reloaded in place
+    bf16x8 wf[kPwChunks][2][MI];
     const uint32_t w_lane = (uint32_t)lane * 16;
     const uint32_t chunk_bytes = (uint32_t)p.Kp * 4 * 64 * 16;
-    auto w_off = [&](const Pos &q, int j) {  // byte offset of chunk j of the stage for this wavefront, or out of range
-        const int mt = q.mt4 * kWaves + wave, c = q.s * kPwChunks + j;
+    auto w_off = [&](const Pos &q, int j, int rt) {  // byte offset of chunk j of the stage for row tile rt of this wavefront, or out of range
+        const int mt = (q.mt4 * kWaves + wave) * RT + rt, c = q.s * kPwChunks + j;
         return (q.valid && mt < p.nmt && c < p.nch) ? (uint32_t)(mt * p.nch + c) * chunk_bytes : kOutOfRange;
     };
     auto w_load = [&](uint32_t off, int f) {
@@ -881,14 +903,24 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
                                                                                 off == kOutOfRange ? 0u : off, 0));
     };
 
-    f32x16 acc[2][NT];
+    f32x16 acc[RT][2][NT];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[mi >> 1][mi & 1][ni][r] = 0.f;
 
+    // The accumulators stay in accumulation registers across stages: without these empty statements at
+    // every place where the loop-carried value is defined, the allocator moves all of them to vector
+    // registers and back at every loop header.
+    auto pin_acc = [&]() {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni) asm volatile("" : "+a"(acc[mi >> 1][mi & 1][ni]));
+    };
+    pin_acc();
     // ---- prologue: stage 0 into buffer 0, stage 1 into the second register set, weights of stage 0
     Pos q0, q1, q2;  // this stage, the next, the one after
     q0.tile = 0;  // turn number
@@ -900,11 +932,13 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
     advance(q2);
     {
 #pragma unroll
-        for (int j = 0; j < kPwChunks; ++j) {
-            const uint32_t o = w_off(q0, j);
+        for (int j = 0; j < kPwChunks; ++j)
 #pragma unroll
-            for (int f = 0; f < 4; ++f) wf[j][f >> 1][f & 1] = w_load(o, f);
-        }
+            for (int rt = 0; rt < RT; ++rt) {
+                const uint32_t o = w_off(q0, j, rt);
+#pragma unroll
+                for (int f = 0; f < 4; ++f) wf[j][f >> 1][2 * rt + (f & 1)] = w_load(o, f);
+            }
         x_load(q0, xa0, xb0);
         x_load(q1, xa1, xb1);
 #pragma unroll
@@ -919,22 +953,23 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         const Pos q = q0;
         const unsigned char *bbase = cur + lane_off;
         bf16x8 b0[NT], b1[NT];
+        pin_acc();
         auto read_b = [&](bf16x8(&dst)[NT], int j, int ks) {
 #pragma unroll
             for (int ni = 0; ni < NT; ++ni)
                 dst[ni] = *reinterpret_cast<const bf16x8 *>(bbase + ni * 32 * kPwRowBytes + j * 64 + ks * 32);
         };
         read_b(b0, 0, 0);
-        // one k-step: 2*NT MFMAs from fragments (j, ks), which are then reloaded with the next stage's
-        auto kstep = [&](int j, int ks, const bf16x8(&bc)[NT], uint32_t o) {
+        // one k-step: MI*NT MFMAs from fragments (j, ks), which are then reloaded with the next stage's
+        auto kstep = [&](int j, int ks, const bf16x8(&bc)[NT], const uint32_t(&o)[RT]) {
 #pragma unroll
-            for (int ni = 0; ni < NT; ++ni)
-                acc[0][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][ks][0], bc[ni], acc[0][ni], 0, 0, 0);
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NT; ++ni)
-                acc[1][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][ks][1], bc[ni], acc[1][ni], 0, 0, 0);
-            wf[j][ks][0] = w_load(o, ks * 2);
-            wf[j][ks][1] = w_load(o, ks * 2 + 1);
+                for (int ni = 0; ni < NT; ++ni)
+                    acc[mi >> 1][mi & 1][ni] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][ks][mi], bc[ni], acc[mi >> 1][mi & 1][ni], 0, 0, 0);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) wf[j][ks][mi] = w_load(o[mi >> 1], ks * 2 + (mi & 1));
             // the writes of the next stage ride on the last k-steps (its loads are two stages old)
             constexpr int first = 2 * kPwChunks - kPwItems;
             const int step = 2 * j + ks;
@@ -944,7 +979,9 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         };
 #pragma unroll
         for (int j = 0; j < kPwChunks; ++j) {
-            const uint32_t o = w_off(q1, j);
+            uint32_t o[RT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) o[rt] = w_off(q1, j, rt);
             read_b(b1, j, 1);
             kstep(j, 0, b0, o);
             if (j + 1 < kPwChunks) read_b(b0, j + 1, 0);
@@ -952,24 +989,27 @@ __global__ __launch_bounds__(kThreads) void pointwise_gemm_kernel(const ConvGemm
         }
         __syncthreads();  // stage k+1 is complete in LDS; buffer `cur` may be overwritten
         if (q.valid && q.s == nst - 1) {
-            // the tile is finished: this wavefront's 64 rows leave through its slice of `cur`
+            // the tile is finished: this wavefront's rows leave through its slice of `cur` (or of the
+            // region behind the two buffers where the four slices do not fit one buffer)
             const int el = fresh_lane();
-            float *tp = reinterpret_cast<float *>(cur + (size_t)wave * 16 * TN * sizeof(float));
-            epi.store_private_tile(acc, tp, el, q.b, q.t0, (q.mt4 * kWaves + wave) * kTileM);
+            unsigned char *ebase = Sh::kEpiInBuf ? cur : smem + 2 * kPwBufBytes;
+            float *tp = reinterpret_cast<float *>(ebase + (size_t)wave * 16 * TN * sizeof(float));
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int rt = 0; rt < RT; ++rt)
+                epi.store_private_tile(acc[rt], tp, el, q.b, q.t0, ((q.mt4 * kWaves + wave) * RT + rt) * kTileM);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-            __syncthreads();  // before the next stage writes into `cur`
+                    for (int r = 0; r < 16; ++r) acc[mi >> 1][mi & 1][ni][r] = 0.f;
+            if (Sh::kEpiInBuf) __syncthreads();  // before the next stage writes into `cur`
         }
+        pin_acc();
         q0 = q1;
         q1 = q2;
         advance(q2);
     };
-    static_assert(kPwItems <= 2 * kPwChunks, "one staging item per k-step");
-    static_assert((size_t)kWaves * 16 * TN * sizeof(float) <= (size_t)kPwBufBytes, "the epilogue tiles fit one buffer");
     for (int k = 0; k < total; k += 2) {
         stage(smem, smem + kPwBufBytes, xa0, xb0, xa1, xb1);
         stage(smem + kPwBufBytes, smem, xa1, xb1, xa0, xb0);
@@ -1248,16 +1288,46 @@ hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
     return hipGetLastError();
 }
 
+template <bool LEN, int MI, int NT, int SC>
+hipError_t launch_pointwise_shape(const ConvGemmParams &p, hipStream_t s)
+{
+    using Sh = PwShape<MI, NT, SC>;
+    auto kern = pointwise_gemm_kernel<LEN, MI, NT, SC>;
+    static LdsOptIn opt_in;
+    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), (int)Sh::kLds);
+    if (e != hipSuccess) return e;
+    ConvGemmParams q = p;
+    q.ntt = (p.Tout + NT * 32 - 1) / (NT * 32);
+    const int cus = current_device_info().cus;
+    const int ntiles = (p.nmt + kWaves * Sh::kRowTiles - 1) / (kWaves * Sh::kRowTiles) * q.ntt * p.B;
+    MainKernelTimer timer(s);
+    hipLaunchKernelGGL(kern, dim3(ntiles < cus ? ntiles : cus), dim3(kThreads), Sh::kLds, s, q);
+    return hipGetLastError();
+}
+
+// Padded work of a shape: MFMAs of all its tiles over the MFMAs of the contraction, times the rounds the
+// workgroups need over the rounds a perfectly divisible launch would need.
+template <int MI, int NT>
+double pointwise_waste(const ConvGemmParams &p, int cus)
+{
+    const int rows = kWaves * MI * 32, cols = NT * 32;
+    const long tr = (p.M + rows - 1) / rows, tc = (p.Tout + cols - 1) / cols;
+    const long tiles = tr * tc * p.B;
+    const double pad = (double)(tr * rows) * (double)(tc * cols) / ((double)p.M * p.Tout);
+    const double rounds = (double)((tiles + cus - 1) / cus) * cus / (double)tiles;
+    return pad * rounds;
+}
+
 hipError_t launch_pointwise(const ConvGemmParams &p, hipStream_t s)
 {
-    static LdsOptIn opt_in;
-    hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(pointwise_gemm_kernel), (int)kPwLds);
-    if (e != hipSuccess) return e;
+    // the 512 x 128 tile does half the LDS and staging work per MFMA and has half as many epilogue rounds per
+    // output (measured 1.1 to 1.2 times faster per MFMA issued at 896 <-> 1024 channels); it is taken unless
+    // its padding and last-round losses outweigh that
     const int cus = current_device_info().cus;
-    const int ntiles = (p.nmt + kWaves - 1) / kWaves * p.ntt * p.B;
-    MainKernelTimer timer(s);
-    hipLaunchKernelGGL(pointwise_gemm_kernel, dim3(ntiles < cus ? ntiles : cus), dim3(kThreads), kPwLds, s, p);
-    return hipGetLastError();
+    const bool big = pointwise_waste<4, 4>(p, cus) <= 1.12 * pointwise_waste<2, 5>(p, cus);
+    if (p.len_in)
+        return big ? launch_pointwise_shape<true, 4, 4, 64>(p, s) : launch_pointwise_shape<true, 2, 5, 128>(p, s);
+    return big ? launch_pointwise_shape<false, 4, 4, 64>(p, s) : launch_pointwise_shape<false, 2, 5, 128>(p, s);
 }
 
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)

@@ -24,6 +24,8 @@ CASES = [
     (L("k_ragged", 3, 72, 100, 336, 11, pad=5, residual=True), [336, 200, 37]),
     (L("k_two_tiles", 2, 128, 192, 320, 17, pad=8), [163, 320]),
     (L("k_k1", 2, 256, 160, 400, 1, affine=False, relu=False), [400, 123]),
+    (L("k_k1_bigtile", 2, 136, 1000, 200, 1, residual=True), [200, 77]),   # K=1 kernel, 512 x 128 tile (forward)
+    (L("k_k1_bigtile_t", 2, 1000, 136, 200, 1), [131, 200]),               # the same tile in the input gradient
     (L("k_stride2", 2, 64, 96, 400, 11, stride=2, pad=5), [399, 201]),
     (L("k_dil2", 2, 96, 80, 248, 9, dilation=2, pad=8), [248, 100]),
     (L("k_zero_len", 2, 16, 16, 64, 5, pad=2), [0, 64]),

@@ -83,6 +83,10 @@ MEDIUM = [
     L("m_k1_ragged", 3, 136, 200, 336, 1, residual=True),
     L("m_k1_proj", 5, 320, 264, 88, 1, relu=False),
     L("m_k1_tiles", 2, 384, 520, 400, 1),
+    # the 512-channel x 128-step tile of the K=1 kernel: forward (1000 rows) resp. input gradient (1000 rows), ragged
+    # in rows, time (200 = 128 + 72) and reduction length (136 = 2 stages of 64 + 8)
+    L("m_k1_bigtile", 2, 136, 1000, 200, 1, residual=True),
+    L("m_k1_bigtile_t", 2, 1000, 136, 200, 1),
     # pointwise layers with at most 32 output channels: the forward pass streams x once (decoder-style kernel)
     L("m_k1_skinny", 3, 96, 29, 328, 1, residual=True),
     L("m_k1_skinny32", 2, 160, 32, 136, 1, relu=False),
