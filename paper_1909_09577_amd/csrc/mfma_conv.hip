@@ -1016,6 +1016,113 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
 }
 
+// ---- K = 1 with at most 32 reduction channels and no epilogue (the input gradient of a projection onto a few
+// channels, 1024 -> 29 in front of the decoder): out[b][m][t] = sum_{r < R} W'[m][r] * in[b][r][t] ------------
+// The arithmetic is nothing; the pass is bound by writing `out` once.  A workgroup owns 64 time steps of one
+// batch item: the R x 64 strip of `in` is copied to LDS as it lies in memory (one 16-byte load per lane) and
+// comes back through the transposing LDS read as the A operand (row = time step, k = reduction channel), the
+// packed weights are the B operand straight from L2 (column = output channel), so an accumulator register
+// holds four consecutive time steps of one output channel and a block is transposed for the stores with 8-byte
+// LDS writes.  The wavefronts of the workgroups of a grid column share out the output channels in blocks of 32.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+constexpr int kFewStrip = 64;  // time steps per workgroup
+constexpr int kFewRowBytes = kFewStrip * 2 + 16;  // 144: 16-byte aligned rows; 16 consecutive lanes write 16 different bank pairs
+constexpr int kFewTileBytes = 32 * kFewRowBytes;  // 32 channel rows
+
+__global__ __launch_bounds__(kThreads) void few_channels_gemm_kernel(const ConvGemmParams p)
+{
+    __shared__ __align__(16) unsigned char strip[4 * 1024];  // block (step s of 16 channels, 32-step half mb): 16 rows x 64 bytes
+    __shared__ __align__(16) unsigned char otile[kWaves * 2 * kFewTileBytes];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int T = p.Tout;  // == p.Tin
+    const int nstrips = (T + kFewStrip - 1) / kFewStrip;
+    const int b = (int)blockIdx.x / nstrips, t0 = ((int)blockIdx.x - b * nstrips) * kFewStrip;
+    const __amdgpu_buffer_rsrc_t rs_in =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.in, 0, (int)((size_t)p.B * p.R * T * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.wp, 0, (int)p.wp_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_out =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.out, 0, (int)((size_t)p.B * p.M * T * 2), 0x00020000);
+    {   // wavefront w copies block w: lane = (channel row lane/4, time steps 8*(lane%4) .. +7)
+        const int s = wave >> 1, mb = wave & 1;
+        const int r = s * 16 + (lane >> 2), t = t0 + mb * 32 + 8 * (lane & 3);
+        const bool ok = r < p.R && t < T;  // T % 8 == 0: a group lies inside the row or outside
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs_in, ok ? (uint32_t)(((b * p.R + r) * T + t) * 2) : kOutOfRange, 0, 0);
+        *reinterpret_cast<u32x4 *>(strip + wave * 1024 + lane * 16) = v;
+    }
+    __syncthreads();
+    // transposing read of a block: the lane receives time step lane%32, channels 8*(lane/32) .. +7 of the step
+    const int g4 = lane >> 4, i16 = lane & 15;
+    const uint32_t tr_off = (uint32_t)((8 * (g4 >> 1) + (i16 >> 2)) * 64 + (16 * (g4 & 1) + 4 * (i16 & 3)) * 2);
+    bf16x8 a[2][2];  // [mb][ks]
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            union {
+                s16x4 h[2];
+                bf16x8 v;
+            } cvt;
+            const unsigned char *q = strip + (ks * 2 + mb) * 1024 + tr_off;
+            cvt.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(q));
+            cvt.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(q + 4 * 64));
+            a[mb][ks] = cvt.v;
+        }
+    // blocks of 32 output channels of this wavefront
+    const int nblocks = (p.M + 31) >> 5, nshare = kWaves * (int)gridDim.y, per = (nblocks + nshare - 1) / nshare;
+    const int nb0 = ((int)blockIdx.y * kWaves + wave) * per, nb1 = min(nblocks, nb0 + per);
+    const uint32_t chunk_bytes = (uint32_t)p.Kp * 4 * 64 * 16;  // one 64-row tile of the packed weights (R <= 32: one chunk)
+    auto load_w = [&](int nb, int ks) {  // fragment (ks, mi = nb % 2) of tap 0 of row tile nb / 2; beyond the range: zeros
+        const uint32_t off = (uint32_t)(nb >> 1) * chunk_bytes + (uint32_t)(ks * 2 + (nb & 1)) * 1024u;
+        return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs_w, nb < nb1 ? (uint32_t)lane * 16 : kOutOfRange,
+                                                                                nb < nb1 ? off : 0u, 0));
+    };
+    // The result block (32 output channels x 64 time steps) goes through a wave-private LDS tile, [channel][time]
+    // in bf16 with rows of 144 bytes, so that it leaves in 16-byte stores whose lanes run along the row: a request to L2 per 64 bytes instead of one per
+    // 8 (at one request per lane the pass was bound by the request rate, not by the bytes).  Two tiles in turn.
+    unsigned char *tiles = otile + wave * 2 * kFewTileBytes;
+    const int h = lane >> 5;
+    auto block = [&](int nb, const bf16x8(&w)[2], int par) {
+        if (nb >= nb1) return;
+        unsigned char *tile = tiles + par * kFewTileBytes;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][0], w[0], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb][1], w[1], acc, 0, 0, 0);
+            // registers 4j .. 4j+3: time steps 32*mb + 8*j + 4*h .. +3 of output channel lane % 32
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x2 o = {pack_bf16x2(acc[4 * j], acc[4 * j + 1]), pack_bf16x2(acc[4 * j + 2], acc[4 * j + 3])};
+                *reinterpret_cast<u32x2 *>(tile + (lane & 31) * kFewRowBytes + (32 * mb + 8 * j + 4 * h) * 2) = o;
+            }
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // item: (channel row, 8 time steps)
+            const int idx = lane + 64 * i, row = idx >> 3, piece = idx & 7;
+            const int m = nb * 32 + row, t = t0 + 8 * piece;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(tile + row * kFewRowBytes + piece * 16);
+            const bool ok = m < p.M && t < T;  // T % 8 == 0
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs_out, ok ? (uint32_t)(((b * p.M + m) * T + t) * 2) : kOutOfRange, 0, 0);
+        }
+    };
+    bf16x8 w0[2] = {load_w(nb0, 0), load_w(nb0, 1)}, w1[2] = {load_w(nb0 + 1, 0), load_w(nb0 + 1, 1)};
+    for (int nb = nb0; nb < nb1; nb += 2) {
+        block(nb, w0, 0);
+        w0[0] = load_w(nb + 2, 0);
+        w0[1] = load_w(nb + 2, 1);
+        block(nb + 1, w1, 1);
+        w1[0] = load_w(nb + 3, 0);
+        w1[1] = load_w(nb + 3, 1);
+        wave_lds_fence();  // the reads of both tiles are done before the next pair of blocks writes them
+    }
+}
+
 // Packed weights: [mt][chunk][tap < Kp][ks][mi][lane][8] (Kp = K rounded up to even, the extra
 // tap is zero); element (lane, j) of fragment (ks, mi) is
 // W'[m = mt*64 + mi*32 + lane%32][r = chunk*32 + ks*16 + 8*(lane/32) + j][tap], zero outside,
@@ -1330,8 +1437,26 @@ hipError_t launch_pointwise(const ConvGemmParams &p, hipStream_t s)
     return big ? launch_pointwise_shape<false, 4, 4, 64>(p, s) : launch_pointwise_shape<false, 2, 5, 128>(p, s);
 }
 
+hipError_t launch_few_channels(const ConvGemmParams &p, hipStream_t s)
+{
+    const int nstrips = (p.Tout + kFewStrip - 1) / kFewStrip;
+    MainKernelTimer timer(s);
+    // the output channels of a strip are shared out among the workgroups of a column of the grid: enough
+    // workgroups to give every SIMD several wavefronts (the stores are the work)
+    const int cus = current_device_info().cus;
+    const int nblocks = (p.M + 31) / 32;
+    int split = 1;
+    while (split < 8 && p.B * nstrips * split < 4 * cus && nblocks >= 2 * kWaves * split) split *= 2;
+    hipLaunchKernelGGL(few_channels_gemm_kernel, dim3(p.B * nstrips, split), dim3(kThreads), 0, s, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
 {
+    // one tap, at most one chunk of reduction channels, nothing to do after the sums: the store-bound kernel
+    if (p.K == 1 && p.R <= kChunk && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout && p.Tout % 8 == 0 && !p.res &&
+        !p.scale && !p.shift && !p.relu && !p.len_in && !p.len_out)
+        return launch_few_channels(p, s);
     // one tap, no padding, wide tiles: the GEMM kernel whose wavefronts share the staged activations
     // (worth it from two 64-channel row tiles on: a single one would leave three wavefronts idle)
     if (p.K == 1 && p.nmt >= 2 && pl.nt == 5 && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout) return launch_pointwise(p, s);
