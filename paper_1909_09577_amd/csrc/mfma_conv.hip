@@ -1714,8 +1714,9 @@ void fill_dgrad(ConvGemmParams &p, const Plan &pl, const Geom &g, const void *gi
 
 // accumulate (stride 1 only): dx = bf16(dx + gradient), one rounding.
 hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale, const void *w,
-                             void *dx, void *dres, bool relu, bool accumulate, void *ws, hipStream_t s)
+                             void *dx, void *dres, bool relu, bool accumulate, void *ws, hipStream_t s, const void **g_used)
 {
+    if (g_used) *g_used = nullptr;
     if (g.stride == 2) {
         if (accumulate) return hipErrorInvalidValue;
         return launch_mfma_dgrad_stride2(g, dy, y, scale, w, dx, dres, relu, ws, s);
@@ -1748,6 +1749,7 @@ hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const
         e = mask_pass(g, dy, y, relu, gbuf, dres, &gin, s);
         if (e != hipSuccess) return e;
     }
+    if (g_used) *g_used = gin;
     ConvGemmParams p = {};
     fill_dgrad(p, pl, g, gin, ws, dx, accumulate);
     return launch_plan(pl, p, s);

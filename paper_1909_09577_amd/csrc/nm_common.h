@@ -203,9 +203,11 @@ hipError_t launch_skinny_fwd(const Geom &g, const void *x, const void *w, const 
 
 bool mfma_dgrad_supported(const Geom &g);
 size_t mfma_dgrad_workspace(const Geom &g);
+// g_used (optional, stride 1): receives the tensor the kernel contracted, g = dy*[y>0] -- dy itself without
+// ReLU, else dres or a buffer inside ws -- so that a weight gradient launched next need not form it again
 hipError_t launch_mfma_dgrad(const Geom &g, const void *dy, const void *y, const float *scale,
                              const void *w, void *dx, void *dres, bool relu, bool accumulate, void *ws,
-                             hipStream_t s);
+                             hipStream_t s, const void **g_used = nullptr);
 
 bool mfma_wgrad_supported(const Geom &g);
 size_t mfma_wgrad_workspace(const Geom &g, bool need_dz);

@@ -462,6 +462,29 @@ static int bwd_impl(int B, int Cin, int Cout, int T, int K, int stride, int dila
                        g.stride == 1 && mfma_wgrad_fast_supported(g) && !wgrad_k1_supported(g) && aligned16(x) && aligned16(dy) &&
                        aligned16(dx) && (!relu || aligned16(y)) && (!dres || aligned16(dres));
     const size_t ws_data = mfma_dgrad_workspace(g);  // only meaningful when fused
+    // pointwise layers: the input gradient's masked g = dy*[y>0] also feeds the K=1 weight-gradient GEMM
+    const bool fused_k1 = !lengths && g.stride == 1 && use_mfma(NM_OP_BWD_DATA, g, dtype, flags) &&
+                          use_mfma(NM_OP_BWD_WEIGHT, g, dtype, flags) && wgrad_k1_supported(g) && aligned16(x) &&
+                          aligned16(dy) && aligned16(dx) && (!relu || aligned16(y));
+    if (fused_k1) {
+        DisarmOnExit disarm;
+        const size_t e = elt(dtype);
+        const size_t ndy = (size_t)g.B * g.Cout * g.To * e, nx = (size_t)g.B * g.Cin * g.T * e;
+        const size_t nw = (size_t)g.Cout * g.Cin * g.K * e, ndw = (size_t)g.Cout * g.Cin * g.K * sizeof(float);
+        if (overlap(dx, nx, dy, ndy) || overlap(dx, nx, y, ndy) || overlap(dx, nx, w, nw) || overlap(dx, nx, x, nx) ||
+            overlap(dres, ndy, dy, ndy) || overlap(dres, ndy, y, ndy) || overlap(dres, ndy, dx, nx) ||
+            overlap(dw, ndw, dy, ndy) || overlap(dw, ndw, y, ndy) || overlap(dw, ndw, x, nx) || overlap(dw, ndw, dx, nx) ||
+            overlap(dw, ndw, dres, ndy) || overlap(dx, nx, workspace, need) || overlap(dres, ndy, workspace, need) ||
+            overlap(dw, ndw, workspace, need))
+            return NM_ERR_BAD_ARG;
+        hipStream_t s = (hipStream_t)hip_stream;
+        const void *g_plain = nullptr;
+        t_current_op = NM_OP_BWD_DATA;
+        hipError_t err = launch_mfma_dgrad(g, dy, y, scale, w, dx, dres, relu, (flags & NM_ACCUM_DX) != 0, workspace, s, &g_plain);
+        if (err != hipSuccess || !g_plain) return NM_ERR_DEVICE;
+        t_current_op = NM_OP_BWD_WEIGHT;
+        return dev(launch_wgrad_k1(g, x, g_plain, scale, dw, (flags & NM_ACCUM_DW) != 0, (unsigned char *)workspace + ws_data, s));
+    }
     if (!fused) {
         // two calls sharing the workspace one after the other (their own argument checks apply)
         const size_t w1 = nm_conv1d_workspace_bytes(NM_OP_BWD_DATA, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);

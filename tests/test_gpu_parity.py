@@ -428,6 +428,8 @@ FUSED = [
     L("f_no_epilogue", 2, 64, 64, 176, 5, pad=6, affine=False, relu=False),  # dz = dy: two calls inside
     L("f_odd_len", 2, 40, 48, 333, 7, pad=3, residual=True),         # plain kernels: two calls inside
     L("f_stride2", 2, 64, 96, 400, 11, stride=2, pad=5),
+    L("f_k1", 3, 136, 200, 336, 1, residual=True),                   # K=1: the input gradient's g feeds the weight-gradient GEMM
+    L("f_k1_no_relu", 2, 320, 264, 88, 1, relu=False),               # K=1 without a mask pass: g is dy
 ]
 
 
