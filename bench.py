@@ -60,11 +60,22 @@ def describe(cfg):
 def kernel_names_for(cfg):
     """Names of the three main kernels as a profiler lists them (for matching against profiles/)."""
     if cfg.K == 1:
+        def pointwise(rows):
+            # the launcher's choice between the 512 x 128 and the 256 x 160 tile: padded work times last-round loss
+            def waste(tile_rows, tile_cols):
+                tr, tc = -(-rows // tile_rows), -(-cfg.T // tile_cols)
+                tiles = tr * tc * cfg.B
+                return (tr * tile_rows) * (tc * tile_cols) / (rows * cfg.T) * (-(-tiles // 256) * 256 / tiles)
+            return ("pointwise_gemm_kernel<false, 4, 4, 64>" if waste(512, 128) <= 1.12 * waste(256, 160)
+                    else "pointwise_gemm_kernel<false, 2, 5, 128>")
         if cfg.Cout <= 32 and cfg.Cin % 16 == 0 and cfg.T % 8 == 0:
             conv = "decoder_mfma_kernel<true>"
         else:
-            conv = "pointwise_gemm_kernel" if cfg.Cout > 64 else "conv_gemm_kernel<5, 1, 0, false>"
-        conv_d = "pointwise_gemm_kernel" if cfg.Cin > 64 else "conv_gemm_kernel<5, 1, 0, false>"
+            conv = pointwise(cfg.Cout) if cfg.Cout > 64 else "conv_gemm_kernel<5, 1, 0, false>"
+        if cfg.Cout <= 32 and cfg.T % 8 == 0:
+            conv_d = "few_channels_gemm_kernel"
+        else:
+            conv_d = pointwise(cfg.Cin) if cfg.Cin > 64 else "conv_gemm_kernel<5, 1, 0, false>"
         wg = "wgrad_k1_kernel" if min(cfg.Cin, cfg.Cout) >= 64 and cfg.T % 8 == 0 else "wgrad_fast_kernel<1, 1>"
         return {"fwd": conv + " (forward)", "dgrad": conv_d + " (input gradient)", "wgrad": wg}
     conv = f"conv_gemm_kernel<5, 1, {cfg.K}, false>"
