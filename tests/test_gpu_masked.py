@@ -33,6 +33,11 @@ CASES = [
     # the weight-gradient kernel with shared staging (8 x 32 = 256 output tiles) and the K=1 kernel at full width
     (L("k_shared_wgrad", 2, 1024, 512, 160, 17, pad=8, affine=False, relu=False), [160, 77]),
     (L("k_shared_wgrad_k13", 3, 1024, 512, 240, 13, pad=6, affine=False, relu=False), [1, 239, 100]),
+    # the same kernel walks only the units that reach below the valid length: empty items at both ends, fewer live
+    # units than workgroups per tile, a batch with nothing in it (dw = 0, dx = 0)
+    (L("k_shared_wgrad_gaps", 4, 1024, 512, 160, 17, pad=8, affine=False, relu=False), [0, 160, 0, 9]),
+    (L("k_shared_wgrad_one_unit", 3, 1024, 512, 240, 13, pad=6, residual=True), [0, 0, 50]),
+    (L("k_shared_wgrad_empty", 2, 1024, 512, 160, 17, pad=8, affine=False, relu=False), [0, 0]),
 ]
 
 
@@ -92,8 +97,11 @@ def check_case(cfg, lengths, force_direct):
     # the gate is applied to the valid part: the exact zeros of the padding would only shrink rms(o)
     valid = np.concatenate([dxh[b, :, :n].reshape(-1) for b, n in enumerate(lens)])
     valid_ref = np.concatenate([dx_ref[b, :, :n].reshape(-1) for b, n in enumerate(lens)])
-    U.assert_close(valid, valid_ref, dtype, f"{cfg.name} dx")
-    U.assert_close(U.to_host_f64(dw), dw_ref, dtype, f"{cfg.name} dw", rms_bound=U.RMS_DW_BF16)
+    if valid.size:
+        U.assert_close(valid, valid_ref, dtype, f"{cfg.name} dx")
+        U.assert_close(U.to_host_f64(dw), dw_ref, dtype, f"{cfg.name} dw", rms_bound=U.RMS_DW_BF16)
+    else:  # a batch with nothing in it: every x reads as zero, so the weight gradient is exactly zero
+        assert not np.any(dw_ref) and not np.any(U.to_host_f64(dw)), f"{cfg.name}: dw of an empty batch"
     # both gradients from one call: bit-identical to the two calls
     dx1, dres1, dw1 = nm.nm_conv1d_bwd(xd, dyd, wd, y=ysv, scale=sc, relu=cfg.relu, want_dres=True, force_direct=force_direct,
                                        lengths=ld, **kw)
