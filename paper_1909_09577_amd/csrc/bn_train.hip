@@ -102,23 +102,31 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(const TS *__restrict
     }
 }
 
-// One thread per channel: merge the G block results in order; mean, invstd, and the affine they imply.
-__global__ void bn_finalize_kernel(const double *__restrict__ part, int G, int C, const float *__restrict__ gamma,
-                                   const float *__restrict__ beta, float eps, float *__restrict__ mean,
-                                   float *__restrict__ invstd, float *__restrict__ scale, float *__restrict__ shift)
+// One wavefront per channel: lane l merges parts l, l+64, ... in order (Chan's update), then the lanes merge in a
+// fixed tree; mean, invstd, and the affine they imply.
+__global__ __launch_bounds__(64) void bn_finalize_kernel(const double *__restrict__ part, int G, int C,
+                                                         const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                         float eps, float *__restrict__ mean, float *__restrict__ invstd,
+                                                         float *__restrict__ scale, float *__restrict__ shift)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
+    const int c = blockIdx.x, lane = threadIdx.x;
     double n = 0.0, mu = 0.0, m2 = 0.0;
-    for (int g = 0; g < G; ++g) {
-        const double *p = part + ((size_t)g * C + c) * 3;
-        const double nb = p[0];
-        if (nb <= 0.0) continue;
-        const double delta = p[1] - mu, tot = n + nb;
+    auto merge = [&](double nb, double mb, double qb) {
+        if (nb <= 0.0) return;
+        const double delta = mb - mu, tot = n + nb;
         mu += delta * nb / tot;
-        m2 += p[2] + delta * delta * n * nb / tot;
+        m2 += qb + delta * delta * n * nb / tot;
         n = tot;
+    };
+    for (int g = lane; g < G; g += 64) {
+        const double *p = part + ((size_t)g * C + c) * 3;
+        merge(p[0], p[1], p[2]);
     }
+    for (int off = 32; off > 0; off >>= 1) {
+        const double nb = __shfl_down(n, off, 64), mb = __shfl_down(mu, off, 64), qb = __shfl_down(m2, off, 64);
+        if (lane < off) merge(nb, mb, qb);
+    }
+    if (lane != 0) return;
     const double var = n > 0 ? (m2 > 0 ? m2 / n : 0.0) : 0.0;
     const double is = 1.0 / sqrt(var + (double)eps);
     const double ga = gamma ? (double)gamma[c] : 1.0, be = beta ? (double)beta[c] : 0.0;
@@ -252,9 +260,17 @@ bool vec8_ok(bool is_bf16, int T, std::initializer_list<const void *> ptrs)
 
 }  // namespace
 
-size_t bn_fwd_scratch_bytes(int B, int C)
+// parts of a channel's statistics: the groups of batch items of bn_stats_kernel, or one per (batch item, 160-step
+// time tile) when the convolution kernel writes them from its epilogue
+size_t bn_parts_cap(int B, int T)
 {
-    return align_up((size_t)batch_groups(B) * C * 3 * sizeof(double), 256) + 2 * align_up((size_t)C * sizeof(float), 256);
+    const size_t tiles = (size_t)B * ((T + 159) / 160);
+    return tiles > (size_t)batch_groups(B) ? tiles : (size_t)batch_groups(B);
+}
+
+size_t bn_fwd_scratch_bytes(int B, int C, int T)
+{
+    return align_up(bn_parts_cap(B, T) * C * 3 * sizeof(double), 256) + 2 * align_up((size_t)C * sizeof(float), 256);
 }
 
 size_t bn_bwd_scratch_bytes(int B, int C)
@@ -264,15 +280,19 @@ size_t bn_bwd_scratch_bytes(int B, int C)
 
 // Statistics of z [B][C][T], then y = relu?(gamma*zhat + beta + residual).  scratch: bn_fwd_scratch_bytes.
 hipError_t launch_bn_fwd(int B, int C, int T, bool is_bf16, const void *z, const float *gamma, const float *beta, float eps,
-                         const void *residual, bool relu, void *y, float *mean, float *invstd, void *scratch, hipStream_t s)
+                         const void *residual, bool relu, void *y, float *mean, float *invstd, void *scratch, hipStream_t s,
+                         int given_parts)
 {
-    const int G = batch_groups(B);
+    // given_parts > 0: the part array already holds that many parts per channel (written by the convolution kernel)
+    const int G = given_parts > 0 ? given_parts : batch_groups(B);
     double *part = (double *)scratch;
-    float *scale = (float *)((unsigned char *)scratch + align_up((size_t)G * C * 3 * sizeof(double), 256));
+    float *scale = (float *)((unsigned char *)scratch + align_up(bn_parts_cap(B, T) * C * 3 * sizeof(double), 256));
     float *shift = (float *)((unsigned char *)scale + align_up((size_t)C * sizeof(float), 256));
     const bool v8 = vec8_ok(is_bf16, T, {z, residual, y});
     const dim3 sgrid(C, G);
-    if (v8)
+    if (given_parts > 0)
+        ;
+    else if (v8)
         hipLaunchKernelGGL((bn_stats_kernel<bf16_t, 8>), sgrid, dim3(kThreads), 0, s, (const bf16_t *)z, B, C, T, G, part);
     else if (is_bf16)
         hipLaunchKernelGGL((bn_stats_kernel<bf16_t, 1>), sgrid, dim3(kThreads), 0, s, (const bf16_t *)z, B, C, T, G, part);
@@ -280,8 +300,7 @@ hipError_t launch_bn_fwd(int B, int C, int T, bool is_bf16, const void *z, const
         hipLaunchKernelGGL((bn_stats_kernel<float, 1>), sgrid, dim3(kThreads), 0, s, (const float *)z, B, C, T, G, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 127) / 128), dim3(128), 0, s, part, G, C, gamma, beta, eps, mean, invstd,
-                       scale, shift);
+    hipLaunchKernelGGL(bn_finalize_kernel, dim3(C), dim3(64), 0, s, part, G, C, gamma, beta, eps, mean, invstd, scale, shift);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int ng = v8 ? T / 8 : T;

@@ -41,6 +41,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
@@ -71,6 +72,8 @@ struct ConvGemmParams {
     const float *shift;     // epilogue (may be NULL)
     const bf16_t *res;      // epilogue (may be NULL)
     bf16_t *out;            // [B][M][Tout]
+    double *stats;          // optional [B*ntt][M][3]: count, mean and centred second moment of the stored outputs of
+                            // every (batch item, time tile, channel) -- the partial statistics of a BatchNorm over out
 };
 
 __device__ __forceinline__ void wave_lds_fence()
@@ -121,6 +124,9 @@ struct Epilogue {
     bool has_scale, relu;
     const int *len_out;  // optional [B]: outputs at t >= ceil((len_out[b] - sub) / div) are written as zero
     int len_sub, len_div;
+    double *stats;       // see ConvGemmParams::stats (used by the STATS instances only)
+    static constexpr int kStatsOffset = 16 * TN;  // float2 [16 rows][TN/8] behind the tile (in floats)
+    static constexpr int kTileBytesWithStats = 16 * TN * (int)sizeof(float) + 16 * (TN / 8) * 2 * (int)sizeof(float);
 
     struct RowLoads {
         u32x4 rvec[kItems];
@@ -137,8 +143,10 @@ struct Epilogue {
     }
 
     __device__ __forceinline__ void init(const bf16_t *out, const bf16_t *res, const float *scale, const float *shift, int B,
-                                         int M_, int Tout_, int relu_, const int *len_out_ = nullptr, int sub = 0, int div = 1)
+                                         int M_, int Tout_, int relu_, const int *len_out_ = nullptr, int sub = 0, int div = 1,
+                                         double *stats_ = nullptr)
     {
+        stats = stats_;
         len_out = len_out_;
         len_sub = sub;
         len_div = div < 1 ? 1 : div;
@@ -174,7 +182,8 @@ struct Epilogue {
         return ld;
     }
     // affine, residual, ReLU, rounding and the stores of the 16 rows that sit in the LDS tile tp
-    __device__ __forceinline__ void finish_rows(int el, const float *tp, const RowLoads &ld) const
+    template <bool STATS = false>
+    __device__ __forceinline__ void finish_rows(int el, float *tp, const RowLoads &ld) const
     {
 #pragma unroll
         for (int q = 0; q < kItems; ++q) {
@@ -201,13 +210,46 @@ struct Epilogue {
                 for (int e = 0; e < 4; ++e) o[e] &= nvalid >= 2 * e + 2 ? 0xffffffffu : (nvalid == 2 * e + 1 ? 0x0000ffffu : 0u);
             }
             __builtin_amdgcn_raw_buffer_store_b128(o, rs_out, ld.ooff[q], 0, 0);
+            if constexpr (STATS) {  // sums of the eight stored (rounded) values; an item outside the tensor adds nothing
+                float s1 = 0.f, s2 = 0.f;
+                if (ld.ooff[q] != kOutOfRange) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float v0 = __uint_as_float(o[e] << 16), v1 = __uint_as_float(o[e] & 0xffff0000u);
+                        s1 += v0 + v1;
+                        s2 = fmaf(v0, v0, fmaf(v1, v1, s2));
+                    }
+                }
+                reinterpret_cast<f32x2 *>(tp + kStatsOffset)[idx] = f32x2{s1, s2};
+            }
         }
+    }
+    // (STATS instances) after finish_rows<true> and a fence: lane r < 16 adds the TN/8 partial sums of tile row r in
+    // order and writes count, mean and centred second moment of that row's part of channel m_of_row
+    __device__ __forceinline__ void emit_row_stats(int el, const float *tp, int m_of_row, int part, int t0) const
+    {
+        if (el >= 16 || m_of_row >= M) return;
+        const f32x2 *sp = reinterpret_cast<const f32x2 *>(tp + kStatsOffset) + el * (TN / 8);
+        double a = 0.0, b2 = 0.0;
+#pragma unroll
+        for (int i = 0; i < TN / 8; ++i) {
+            const f32x2 v = sp[i];
+            a += (double)v[0];
+            b2 += (double)v[1];
+        }
+        const int left = Tout - t0;
+        const double n = (double)(left < TN ? (left > 0 ? left : 0) : TN);
+        double *o = stats + ((size_t)part * M + m_of_row) * 3;
+        o[0] = n;
+        o[1] = n > 0 ? a / n : 0.0;
+        o[2] = n > 0 ? b2 - a * a / n : 0.0;
     }
     // A whole 64-row tile held by one wavefront (rows m_first .. m_first+63): four rounds of 16 rows
     // (row of blocks mi, accumulator registers 8*gp .. 8*gp+7) through tp; the operands of a round
     // are requested two rounds ahead.
+    template <bool STATS = false>
     __device__ __forceinline__ void store_private_tile(const f32x16 (&acc)[2][NT], float *tp, int el, int b, int t0,
-                                                       int m_first) const
+                                                       int m_first, int part = 0) const
     {
         const int tcol = el & 31, thalf = el >> 5;
         RowLoads ld[2] = {request_rows(el, b, t0, m_first, false), request_rows(el, b, t0, m_first + 16, false)};
@@ -223,9 +265,10 @@ struct Epilogue {
                     for (int ni = 0; ni < NT; ++ni) tp[r * TN + ni * 32 + tcol] = acc[mi][ni][4 * (2 * gp + g) + j];
                 }
             wave_lds_fence();
-            finish_rows(el, tp, ld[rd & 1]);
+            finish_rows<STATS>(el, tp, ld[rd & 1]);
             if (rd + 2 < 4) ld[rd & 1] = request_rows(el, b, t0, m_first + (rd + 2) * 16, false);
             wave_lds_fence();
+            if constexpr (STATS) emit_row_stats(el, tp, m_first + rd * 16 + el, part, t0);
         }
     }
 };
@@ -245,7 +288,8 @@ struct TileCoords {
 // KT > 0: the number of taps is a compile-time constant and a chunk is one straight-line block
 // (see the unrolled main loop below); KT == 0: any K, tap pairs in a loop.
 // LEN: the instance for calls with per-sample lengths; it alone carries the test for tiles in the padding.
-template <int NT, int STRIDE, int KT, bool LEN = false>
+// STATS: the instance that also writes the per-tile statistics of its stored outputs (ConvGemmParams::stats).
+template <int NT, int STRIDE, int KT, bool LEN = false, bool STATS = false>
 __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -427,7 +471,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
     uint32_t w_cur = 0;
 
     Epilogue<NT> epi;
-    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu, p.len_out, p.len_out_sub, p.len_out_div);
+    epi.init(p.out, p.res, p.scale, p.shift, p.B, p.M, p.Tout, p.relu, p.len_out, p.len_out_sub, p.len_out_div, p.stats);
 
     int cc = 0;  // chunks this wavefront has consumed so far: chunk number cc uses buffer cc & 1
     // accumulators: zero here, and again in the epilogue as soon as a tile's values have been handed over
@@ -680,7 +724,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
 
         if (priv) {
             // A private tile: this wavefront holds all 64 rows.
-            epi.store_private_tile(acc, tp, el, tc.b, tc.t0, tc.mt * kTileM);
+            epi.template store_private_tile<STATS>(acc, tp, el, tc.b, tc.t0, tc.mt * kTileM, tc.b * p.ntt + tc.t0 / TN);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -746,8 +790,13 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(const ConvGemmParam
             default: exchange(std::integral_constant<int, 3>{}); break;
             }
             wave_lds_fence();
-            epi.finish_rows(el, tp, ld);
+            epi.template finish_rows<STATS>(el, tp, ld);
             wave_lds_fence();
+            if constexpr (STATS) {  // this wavefront's rows: channels 8*wave .. +7 of both row blocks of the tile
+                epi.emit_row_stats(el, tp, tc.mt * kTileM + 8 * wave + (el >> 3) * 32 + (el & 7), tc.b * p.ntt + tc.t0 / TN,
+                                   tc.t0);
+                wave_lds_fence();
+            }
         }
     }
 }
@@ -1375,10 +1424,10 @@ size_t packed_bytes(int M, int R, int K)
 constexpr size_t kMaxPacked = (size_t)1 << 31;  // the kernel addresses packed weights with 32-bit offsets
 constexpr size_t kMaxInput = (size_t)1 << 30;   // and the activation tensors through buffer descriptors
 
-template <int NT, int STRIDE, int KT, bool LEN = false>
+template <int NT, int STRIDE, int KT, bool LEN = false, bool STATS = false>
 hipError_t launch_t(const ConvGemmParams &p, size_t lds, hipStream_t s)
 {
-    auto kern = conv_gemm_kernel<NT, STRIDE, KT, LEN>;
+    auto kern = conv_gemm_kernel<NT, STRIDE, KT, LEN, STATS>;
     static LdsOptIn opt_in;
     hipError_t e = ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), kMaxLds);
     if (e != hipSuccess) return e;
@@ -1460,6 +1509,17 @@ hipError_t launch_plan(const Plan &pl, const ConvGemmParams &p, hipStream_t s)
     // one tap, no padding, wide tiles: the GEMM kernel whose wavefronts share the staged activations
     // (worth it from two 64-channel row tiles on: a single one would leave three wavefronts idle)
     if (p.K == 1 && p.nmt >= 2 && pl.nt == 5 && pl.stride == 1 && p.padL == 0 && p.Tin == p.Tout) return launch_pointwise(p, s);
+    if (p.stats) {  // (the caller has checked stats_on_engine)
+        switch (p.K) {
+        case 11: return launch_t<5, 1, 11, false, true>(p, pl.lds, s);
+        case 13: return launch_t<5, 1, 13, false, true>(p, pl.lds, s);
+        case 21: return launch_t<5, 1, 21, false, true>(p, pl.lds, s);
+        case 25: return launch_t<5, 1, 25, false, true>(p, pl.lds, s);
+        case 29: return launch_t<5, 1, 29, false, true>(p, pl.lds, s);
+        case 17: return launch_t<5, 1, 17, false, true>(p, pl.lds, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     if (pl.unrolled && (p.len_in || p.len_out)) {
         switch (p.K) {
         case 11: return launch_t<5, 1, 11, true>(p, pl.lds, s);
@@ -1559,11 +1619,22 @@ bool mfma_fwd_supported(const Geom &g)
 
 size_t mfma_fwd_workspace(const Geom &g) { return packed_bytes(g.Cout, g.Cin, g.K); }
 
+// Whether the forward pass of this geometry runs on a kernel instance that can also write the statistics of its
+// outputs, and into how many (batch item, time tile) parts: the unrolled engine, wide tile, no lengths.
+int mfma_fwd_stats_parts(const Geom &g)
+{
+    const Plan pl = make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil);
+    if (!pl.ok || !pl.unrolled || pl.nt != 5 || g.len || !mfma_fwd_supported(g)) return 0;
+    if (pl.buf_bytes < Epilogue<5>::kTileBytesWithStats) return 0;
+    return g.B * ((g.To + 159) / 160);
+}
+
 hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const float *scale, const float *shift,
-                           const void *res, void *y, bool relu, void *ws, hipStream_t s)
+                           const void *res, void *y, bool relu, void *ws, hipStream_t s, double *stats)
 {
     const Plan pl = make_plan(g.T, g.To, g.Cin, g.K, g.stride, g.dil);
     if (!pl.ok || !mfma_fwd_supported(g)) return hipErrorInvalidValue;
+    if (stats && mfma_fwd_stats_parts(g) == 0) return hipErrorInvalidValue;
     // a pointwise layer with a handful of output channels is a stream over x: no packing, no tiles
     if (skinny_fwd_supported(g) && ((uintptr_t)w % 16) == 0) return launch_skinny_fwd(g, x, w, scale, shift, res, y, relu, s);
     hipError_t e = run_prepack(w, ws, g.Cout, g.Cin, g.K, false, nullptr, s);
@@ -1576,6 +1647,7 @@ hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const fl
     p.wp = (const bf16x8 *)ws;
     p.scale = scale; p.shift = shift; p.res = (const bf16_t *)res;
     p.out = (bf16_t *)y;
+    p.stats = stats;
     return launch_plan(pl, p, s);
 }
 

@@ -192,9 +192,12 @@ hipError_t launch_direct_wgrad(const Geom &g, bool is_bf16, const void *x, const
 // *_workspace functions give its scratch need; launches return hipSuccess or the error.
 bool mfma_fwd_supported(const Geom &g);
 size_t mfma_fwd_workspace(const Geom &g);
+// stats (optional, only where mfma_fwd_stats_parts(g) > 0): [parts][Cout][3] doubles that receive count, mean and
+// centred second moment of the stored outputs of every (batch item, 160-step time tile) part and channel
 hipError_t launch_mfma_fwd(const Geom &g, const void *x, const void *w, const float *scale,
                            const float *shift, const void *res, void *y, bool relu, void *ws,
-                           hipStream_t s);
+                           hipStream_t s, double *stats = nullptr);
+int mfma_fwd_stats_parts(const Geom &g);
 
 // pointwise forward with at most 32 output channels: bound by reading x once (decoder_logsoftmax.hip)
 bool skinny_fwd_supported(const Geom &g);
@@ -250,10 +253,11 @@ hipError_t launch_mfma_dgrad_prepared(const Geom &g, const void *g_plain, void *
                                       hipStream_t s);
 
 // ---- training-mode BatchNorm passes (bn_train.hip) ---------------------------------------------
-size_t bn_fwd_scratch_bytes(int B, int C);
+size_t bn_fwd_scratch_bytes(int B, int C, int T);
 size_t bn_bwd_scratch_bytes(int B, int C);
 hipError_t launch_bn_fwd(int B, int C, int T, bool is_bf16, const void *z, const float *gamma, const float *beta, float eps,
-                         const void *residual, bool relu, void *y, float *mean, float *invstd, void *scratch, hipStream_t s);
+                         const void *residual, bool relu, void *y, float *mean, float *invstd, void *scratch, hipStream_t s,
+                         int given_parts = 0);
 hipError_t launch_bn_bwd(int B, int C, int T, bool is_bf16, const void *dy, const void *y, const void *z, const float *gamma,
                          const float *mean, const float *invstd, bool relu, void *dz, void *dres, float *dgamma,
                          float *dbeta, bool accumulate, void *scratch, hipStream_t s);

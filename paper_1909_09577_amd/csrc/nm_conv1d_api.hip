@@ -205,7 +205,7 @@ size_t nm_conv1d_workspace_bytes(int op, int B, int Cin, int Cout, int T, int K,
         return 0;
     // the BatchNorm calls keep their own scratch (and, backward, the dz tensor) in front of the inner call's workspace
     if (op == NM_OP_BN_FWD)
-        return bn_fwd_scratch_bytes(g.B, g.Cout) +
+        return bn_fwd_scratch_bytes(g.B, g.Cout, g.To) +
                nm_conv1d_workspace_bytes(NM_OP_FWD, B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags);
     if (op == NM_OP_BN_BWD)
         return bn_bwd_scratch_bytes(g.B, g.Cout) + align_up((size_t)g.B * g.Cout * g.To * elt(dtype), kWsAlign) +
@@ -254,9 +254,12 @@ const char *nm_strerror(int status)
 static int block_fwd_impl(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const int *lengths,
                           const void *x, const void *w, const float *scale, const float *shift,
                           const void *residual, void *y, unsigned flags, int dtype, void *workspace,
-                          size_t workspace_bytes, void *hip_stream)
+                          size_t workspace_bytes, void *hip_stream, double *stats = nullptr, int *stats_parts = nullptr)
 {
+    // stats / stats_parts (the BatchNorm entry point): where the kernel that runs can write the partial statistics of
+    // its outputs it does, and *stats_parts says into how many parts per channel (0: it did not)
     DisarmOnExit disarm;
+    if (stats_parts) *stats_parts = 0;
     Geom g;
     int st = check_geometry(B, Cin, Cout, T, K, stride, dilation, pad, dtype, flags,
                             NM_RELU | NM_FORCE_DIRECT, &g);
@@ -277,7 +280,12 @@ static int block_fwd_impl(int B, int Cin, int Cout, int T, int K, int stride, in
     hipStream_t s = (hipStream_t)hip_stream;
     const bool relu = (flags & NM_RELU) != 0;
     t_current_op = NM_OP_FWD;
-    if (mfma) return dev(launch_mfma_fwd(g, x, w, scale, shift, residual, y, relu, workspace, s));
+    if (mfma) {
+        const int parts = (stats && stats_parts) ? mfma_fwd_stats_parts(g) : 0;
+        const hipError_t err = launch_mfma_fwd(g, x, w, scale, shift, residual, y, relu, workspace, s, parts > 0 ? stats : nullptr);
+        if (err == hipSuccess && parts > 0) *stats_parts = parts;
+        return dev(err);
+    }
     MainKernelTimer timer(s);
     return dev(launch_direct_fwd(g, dtype == NM_BF16, x, w, scale, shift, residual, y, relu, s));
 }
@@ -564,13 +572,16 @@ int nm_conv1d_bn_fwd(int B, int Cin, int Cout, int T, int K, int stride, int dil
         DisarmOnExit disarm;
         return st;
     }
-    const size_t own = bn_fwd_scratch_bytes(g.B, g.Cout);
-    // the convolution itself: z = conv(x, w), no epilogue (its own argument checks apply once more)
-    st = nm_conv1d_block_fwd(B, Cin, Cout, T, K, stride, dilation, pad, x, w, nullptr, nullptr, nullptr, z,
-                             flags & NM_FORCE_DIRECT, dtype, (unsigned char *)workspace + own, workspace_bytes - own, hip_stream);
+    const size_t own = bn_fwd_scratch_bytes(g.B, g.Cout, g.To);
+    // the convolution itself: z = conv(x, w), no epilogue (its own argument checks apply once more); the unrolled
+    // matrix-core kernels write the partial statistics of z from their epilogue, for the others a pass over z follows
+    int parts = 0;
+    st = block_fwd_impl(B, Cin, Cout, T, K, stride, dilation, pad, nullptr, x, w, nullptr, nullptr, nullptr, z,
+                        flags & NM_FORCE_DIRECT, dtype, (unsigned char *)workspace + own, workspace_bytes - own, hip_stream,
+                        (double *)workspace, &parts);
     if (st != NM_OK) return st;
     return dev(launch_bn_fwd(g.B, g.Cout, g.To, dtype == NM_BF16, z, gamma, beta, eps, residual, (flags & NM_RELU) != 0, y, mean,
-                             invstd, workspace, (hipStream_t)hip_stream));
+                             invstd, workspace, (hipStream_t)hip_stream, parts));
 }
 
 int nm_conv1d_bn_bwd(int B, int Cin, int Cout, int T, int K, int stride, int dilation, int pad, const void *x,

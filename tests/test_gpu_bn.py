@@ -34,6 +34,9 @@ CASES = [
     L("bn_k1_proj", 2, 256, 384, 320, 1, relu=False),
     L("bn_stride2", 2, 64, 96, 400, 11, stride=2, pad=5),
     L("bn_b9", 9, 32, 64, 160, 7, pad=3, residual=True),            # more batch items than reduction groups
+    # statistics written by the convolution kernel's epilogue (unrolled engine): tiles ragged in rows and time
+    L("bn_k11_ragged_tiles", 3, 128, 200, 328, 11, pad=5, residual=True),
+    L("bn_k25_ragged_tiles", 2, 256, 72, 168, 25, pad=12),
 ]
 
 
@@ -83,6 +86,23 @@ def test_bn_block_forward_and_backward(cfg, mode):
     U.assert_close(chan(dbeta.cpu().numpy()), dbeta_ref, "f32", f"{cfg.name} dbeta")
     U.assert_close(U.to_host_f64(dx), dx_ref, dtype, f"{cfg.name} dx")
     U.assert_close(U.to_host_f64(dw), dw_ref, dtype, f"{cfg.name} dw", rms_bound=U.RMS_DW_BF16)
+
+
+def test_bn_forward_statistics_from_private_and_shared_tiles():
+    """1280 tiles on 256 CUs: every wavefront finishes a tile of its own and every workgroup one more with a split
+    reduction; both epilogues write their parts of the statistics.  Forward only, whole tensors."""
+    cfg = L("bn_1280_tiles", 20, 128, 512, 1280, 13, pad=6, residual=True)
+    dtype = "bf16"
+    inp = syn.make_inputs(cfg, dtype)
+    kw = U.geom_kw(cfg)
+    x, w, gd, bd, rd = (U.to_dev(inp, n, dtype) for n in ("x", "w", "scale", "shift", "residual"))
+    z, y, mean, invstd = nm.nm_conv1d_bn_fwd(x, w, gd, bd, rd, eps=EPS, relu=True, **kw)
+    zg = U.to_host_f64(z)
+    U.assert_close(zg, orc.block_fwd(inp["x"], inp["w"], None, None, None, False, **kw), dtype, "z")
+    y_ref, mean_ref, invstd_ref = bno.bn_train_fwd(zg, inp["scale"], inp["shift"], EPS, inp["residual"], True)
+    assert np.max(np.abs(chan(mean.cpu().numpy()) - mean_ref) * invstd_ref) <= 1e-5
+    U.assert_close(chan(invstd.cpu().numpy()), invstd_ref, "f32", "invstd")
+    U.assert_close(U.to_host_f64(y), y_ref, dtype, "y")
 
 
 def test_bn_backward_accumulates_and_is_deterministic():
