@@ -71,14 +71,14 @@ def kernel_names_for(cfg):
         if cfg.Cout <= 32 and cfg.Cin % 16 == 0 and cfg.T % 8 == 0:
             conv = "decoder_mfma_kernel<true>"
         else:
-            conv = pointwise(cfg.Cout) if cfg.Cout > 64 else "conv_gemm_kernel<5, 1, 0, false>"
+            conv = pointwise(cfg.Cout) if cfg.Cout > 64 else "conv_gemm_kernel<5, 1, 0, false, false>"
         if cfg.Cout <= 32 and cfg.T % 8 == 0:
             conv_d = "few_channels_gemm_kernel"
         else:
-            conv_d = pointwise(cfg.Cin) if cfg.Cin > 64 else "conv_gemm_kernel<5, 1, 0, false>"
+            conv_d = pointwise(cfg.Cin) if cfg.Cin > 64 else "conv_gemm_kernel<5, 1, 0, false, false>"
         wg = "wgrad_k1_kernel" if min(cfg.Cin, cfg.Cout) >= 64 and cfg.T % 8 == 0 else "wgrad_fast_kernel<1, 1>"
         return {"fwd": conv + " (forward)", "dgrad": conv_d + " (input gradient)", "wgrad": wg}
-    conv = f"conv_gemm_kernel<5, 1, {cfg.K}, false>"
+    conv = f"conv_gemm_kernel<5, 1, {cfg.K}, false, false>"
     wg = {17: "wgrad_shared_kernel<17, 1, false>", 11: "wgrad_shared_kernel<11, 1, false>",
           29: "wgrad_shared_kernel<15, 2, false>"}.get(cfg.K, "wgrad kernel")
     return {"fwd": conv + " (forward)", "dgrad": conv + " (input gradient)", "wgrad": wg}
