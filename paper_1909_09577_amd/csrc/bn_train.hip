@@ -258,8 +258,6 @@ bool vec8_ok(bool is_bf16, int T, std::initializer_list<const void *> ptrs)
     return true;
 }
 
-}  // namespace
-
 // parts of a channel's statistics: the groups of batch items of bn_stats_kernel, or one per (batch item, 160-step
 // time tile) when the convolution kernel writes them from its epilogue
 size_t bn_parts_cap(int B, int T)
@@ -267,6 +265,8 @@ size_t bn_parts_cap(int B, int T)
     const size_t tiles = (size_t)B * ((T + 159) / 160);
     return tiles > (size_t)batch_groups(B) ? tiles : (size_t)batch_groups(B);
 }
+
+}  // namespace
 
 size_t bn_fwd_scratch_bytes(int B, int C, int T)
 {
