@@ -338,6 +338,7 @@ def test_pure_gradients_without_epilogue_and_accumulate():
 
 @pytest.mark.parametrize("cfg", [
     L("acc_k1_proj", 2, 256, 384, 320, 1, relu=False),                   # a residual projection: the K=1 kernel
+    L("acc_k1_few_outputs", 2, 200, 29, 328, 1, affine=False, relu=False),  # the store-bound kernel does not accumulate: the GEMM kernel takes it
     L("acc_k11", 2, 72, 100, 336, 11, pad=5, residual=True),             # unrolled engine, ragged channel tiles
     L("acc_k5", 2, 64, 64, 176, 5, pad=2),                               # tap-pair engine
     L("acc_odd_len", 2, 40, 48, 333, 7, pad=3),                          # plain kernels
